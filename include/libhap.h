@@ -1,0 +1,205 @@
+/*
+ * libhap - per-device compute of HAP-style SPMD programs on one MI355X (gfx950).
+ *
+ * HAP (arXiv 2401.05965) shards every tensor of a training graph over m virtual
+ * devices with UNEVEN ratios B_1..B_m chosen by a linear program (Sec. 5.1), and
+ * each device executes its own slice of every instruction (Sec. 4.1, Fig.
+ * "semantics"; Sec. 6).  This library is that per-device work:
+ *
+ *   host   hap_shard_ratios      the LP of Eq. (opt_B)
+ *          hap_round_shards      integer sizes + ownership ranges (Sec. 5.1 rounding, Sec. 6 slicing)
+ *   device hap_sharded_linear_*  the three MatMul sharding rules of Fig. "semantics" + the replicated rule
+ *          hap_sharded_attn_*    softmax attention restricted to a head / batch slice
+ *          hap_sfb_grad          sufficient-factor gradient rebuild (Sec. 2.3.2, Fig. "sfb"(c))
+ *          hap_layernorm_*, hap_gelu_*, hap_add, hap_colsum   memory-bound row / element helpers
+ *
+ * Conventions
+ *   - activations X[tokens x in], weights W[in x out], all row-major with an explicit leading
+ *     dimension (elements);  Y = act(X W + b),  dX = dP W^T,  dW = X^T dP,  db = colsum(dP),
+ *     dP = dY * act'(preact).
+ *   - every function returns a hap_status (0 = OK); nothing throws or aborts.  Arguments are
+ *     validated on the host before any launch.  hap_last_error() gives a thread-local detail string.
+ *   - "device pointer" = memory of the current HIP device, owned by the caller, never freed or
+ *     resized here.  The library allocates no device memory: scratch comes in through (ws, ws_bytes),
+ *     sized by the matching hap_*_workspace() call; HAP_EWORKSPACE if too small.
+ *   - device calls are asynchronous on `stream` (a hipStream_t passed as void*, NULL = default stream).
+ *   - a shard of size 0 is legal (B_j >= 0 in Eq. (opt_B)): the call returns HAP_OK without launching.
+ *   - outputs never alias inputs unless stated.
+ */
+#ifndef LIBHAP_H
+#define LIBHAP_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  HAP_OK = 0,
+  HAP_EINVAL = 1,       /* NULL pointer, non-positive size, bad enum */
+  HAP_ESHAPE = 2,       /* offsets not monotone / not ending at the dimension, ld too small, granule mismatch */
+  HAP_EINFEASIBLE = 3,  /* LP has no feasible point (cannot happen for valid inputs) */
+  HAP_EUNBOUNDED = 4,   /* LP unbounded (negative cost coefficients) */
+  HAP_EWORKSPACE = 5,   /* ws NULL or ws_bytes below hap_*_workspace() */
+  HAP_EDEVICE = 6,      /* HIP launch failed */
+  HAP_EUNSUPPORTED = 7  /* valid request this build does not implement (e.g. one operand view >= 2 GiB) */
+} hap_status;
+
+const char* hap_strerror(int status);  /* static string */
+const char* hap_last_error(void);      /* thread-local; valid until the next libhap call on this thread */
+const char* hap_version(void);
+
+/* ------------------------------------------------------------------ host: ratios and ranges --- */
+
+/* One stage of the synthesized program (Sec. 3.2): a collective followed by computation.
+ *   compute time on device j:  (flops_sharded * B_j + flops_fixed) / speed_j
+ *   communication time:        comm_latency + comm_per_ratio * max_j B_j                         */
+typedef struct {
+  double flops_sharded;   /* flops of ops with a sharded dimension: scale with B_j (Sec. 3.2)      */
+  double flops_fixed;     /* flops of ops without one: every device does all of them               */
+  double comm_latency;    /* seconds                                                               */
+  double comm_per_ratio;  /* seconds for the whole tensor; the largest shard decides (Sec. 5.1)    */
+} hap_stage;
+
+/* Eq. (opt_B):  min_B sum_i [ comm_i(B) + max_j comp_ij(B_j) ]  s.t. sum_j B_j = 1, B >= 0.
+ * Solved as an LP in epigraph form by a dense two-phase simplex with Bland's rule (host, plain C).
+ * speed[m] > 0 (flops/s), st[n_stages] with non-negative fields; ratios[m] out; objective (seconds)
+ * out, may be NULL.  All host pointers.  m <= 256, n_stages <= 256.                              */
+int hap_shard_ratios(int m, const double* speed, int n_stages, const hap_stage* st,
+                     double* ratios, double* objective);
+
+/* The cost model itself (Sec. 3.2): t(B) for given ratios; host pointers. */
+int hap_iteration_time(int m, const double* speed, int n_stages, const hap_stage* st,
+                       const double* ratios, double* seconds);
+
+/* Sec. 5.1 rounding: sizes nearest to ratios[j]*dim_len, then +-1 on the shard whose size after the
+ * move is closest to its target until they sum to dim_len (ties: .5 up, lowest device first, never
+ * below 0).  Sizes are multiples of `granule` (>= 1, must divide dim_len).  offsets[j] = sum of the
+ * sizes before j, offsets[m] = dim_len: device j owns [offsets[j], offsets[j+1])  (Sec. 6).
+ * sizes[m] and offsets[m+1] are host output arrays.                                              */
+int hap_round_shards(int m, const double* ratios, int64_t dim_len, int64_t granule,
+                     int64_t* sizes, int64_t* offsets);
+
+/* ------------------------------------------------------------------ device: sharded linear --- */
+
+typedef enum { HAP_F32 = 0, HAP_BF16 = 1 } hap_dtype;
+
+/* Which MatMul rule of Fig. "semantics" the instruction follows (names: sharded axis of the layer). */
+typedef enum {
+  HAP_SHARD_BATCH = 0,      /* X rows sharded, W whole       -> Y rows sharded                     */
+  HAP_SHARD_FEATURE = 1,    /* X whole, W columns sharded    -> Y columns sharded                  */
+  HAP_SHARD_REDUCTION = 2,  /* X columns, W rows sharded     -> Y is a partial sum (to All-Reduce) */
+  HAP_REPLICATED = 3        /* everything whole on every device (rule added for SFB, Sec. 4.3)     */
+} hap_shard_mode;
+
+typedef enum { HAP_ACT_NONE = 0, HAP_ACT_GELU_ERF = 1 } hap_act;
+
+typedef struct {
+  int64_t tokens, in_features, out_features; /* UNSHARDED logical sizes                              */
+  int mode;                 /* hap_shard_mode                                                        */
+  int m;                    /* number of virtual devices                                             */
+  const int64_t* offsets;   /* host pointer, [m+1], from hap_round_shards over the sharded axis
+                               (tokens / out_features / in_features); ignored for HAP_REPLICATED   */
+  int io_dtype;             /* hap_dtype of X, W, bias, Y, preact, dY, dX.  Accumulation is fp32.   */
+  int act;                  /* hap_act, applied after bias; must be NONE in REDUCTION mode          */
+  int has_bias;             /* must be 0 in REDUCTION mode: bias belongs after the All-Reduce       */
+  int64_t ldx, ldw, ldy;    /* leading dimensions (elements) of the X-like, W-like, Y-like buffers  */
+  int operands_are_full;    /* 1: sharded tensors are passed whole; the library applies the range.
+                               0: sharded tensors are passed as the device's compact slice
+                                  (row 0 / column 0 of the buffer = first owned row / column).
+                               Tensors the mode does not shard are always whole.                    */
+} hap_linear_desc;
+
+/* Y_j (and optionally the pre-activation) of device `shard_index`.
+ *   BATCH:     Y[r_j,:]  = act(X[r_j,:] W + b)          X,Y(,preact) sharded on rows
+ *   FEATURE:   Y[:,c_j]  = act(X W[:,c_j] + b[c_j])     W,bias,Y(,preact) sharded on columns
+ *   REDUCTION: P_j       = X[:,k_j] W[k_j,:]            X sharded on columns, W on rows; Y whole [tokens x out]
+ * X, W, bias (NULL iff !has_bias), Y, preact (NULL = do not save) are device pointers.
+ * preact has Y's shape/ld and is required by the backward only when act != NONE.                  */
+int hap_sharded_linear_fwd(const hap_linear_desc* d, int shard_index, const void* X, const void* W,
+                           const void* bias, void* Y, void* preact, void* ws, size_t ws_bytes, void* stream);
+
+/* Gradients of device `shard_index`.  dY has Y's layout, dX has X's, dW has W's (dtype dW_dtype,
+ * leading dimension ldw), dbias has bias's layout but is always fp32.
+ *   BATCH:     dX[r_j,:] exact;  dW, dbias are the device's partial sums over its rows
+ *   FEATURE:   dX is a partial [tokens x in];  dW[:,c_j], dbias[c_j] exact
+ *   REDUCTION: dX[:,k_j], dW[k_j,:] exact;  dbias must be NULL
+ * Any of dX, dW, dbias may be NULL to skip it.  With act != NONE the call first forms
+ * dP = dY * act'(preact) in ws (see hap_linear_bwd_workspace).                                    */
+int hap_sharded_linear_bwd(const hap_linear_desc* d, int shard_index, const void* X, const void* W,
+                           const void* preact, const void* dY, void* dX, void* dW, int dW_dtype,
+                           float* dbias, void* ws, size_t ws_bytes, void* stream);
+
+size_t hap_linear_fwd_workspace(const hap_linear_desc* d, int shard_index);
+size_t hap_linear_bwd_workspace(const hap_linear_desc* d, int shard_index);
+
+/* ------------------------------------------------------------------ device: SFB rebuild --- */
+
+/* dW[in x out] (+)= sum_i X_i[0:rows_i,:]^T dY_i[0:rows_i,:]      (Sec. 2.3.2, Fig. "sfb"(c))
+ * One GEMM whose contracted axis is the concatenation of the m devices' gathered factors.
+ *   X, dY   host arrays of m device pointers; X_i is [cap_i x in_features] with leading dimension ldx,
+ *           dY_i is [cap_i x out_features] with ldy; cap_i >= rows_i (padded All-Gather layout) or
+ *           cap_i == rows_i (grouped-Broadcast layout).  Rows >= rows_i are never read.
+ *   rows    host array, rows_i >= 0 (0: that device contributes nothing)
+ *   dW      device, fp32, leading dimension lddw; accumulate = 0 overwrites, 1 adds to the contents
+ * m <= HAP_SFB_MAX_DEVICES.                                                                       */
+#define HAP_SFB_MAX_DEVICES 64
+int hap_sfb_grad(int m, const void* const* X, const void* const* dY, const int64_t* rows,
+                 int64_t in_features, int64_t out_features, int64_t ldx, int64_t ldy, int in_dtype,
+                 float* dW, int64_t lddw, int accumulate, void* ws, size_t ws_bytes, void* stream);
+size_t hap_sfb_workspace(int m, const int64_t* rows, int64_t in_features, int64_t out_features);
+
+/* ------------------------------------------------------------------ device: attention slice --- */
+
+/* Softmax attention per (batch, head): S = Q K^T / sqrt(head_dim), P = softmax_keys(S), O = P V;
+ * no mask, no dropout.  The tensors passed are WHOLE [batch, seq, heads, head_dim] views addressed by
+ * strides (elements; head_dim contiguous); the device computes only its heads (shard_over_heads = 1)
+ * or its batch entries (0), i.e. the index range [offsets[j], offsets[j+1]).  With m = 1 and
+ * offsets = {0, heads or batch} the whole tensor is computed (use this for compact slices).       */
+typedef struct {
+  int64_t batch, heads, seq, head_dim;     /* head_dim in {64, 128}                                   */
+  int shard_over_heads;
+  int m;
+  const int64_t* offsets;                  /* host, [m+1] over heads or batch                          */
+  int io_dtype;                            /* HAP_BF16                                                 */
+  int64_t stride_b, stride_s, stride_h;    /* shared by Q, K, V, O and their gradients                 */
+} hap_attn_desc;
+
+/* lse: device fp32 [batch x heads x seq] (whole-tensor indexing), log-sum-exp of each query row,
+ * written for the slice; needed by the backward.                                                  */
+int hap_sharded_attn_fwd(const hap_attn_desc* d, int shard_index, const void* Q, const void* K, const void* V,
+                         void* O, float* lse, void* ws, size_t ws_bytes, void* stream);
+int hap_sharded_attn_bwd(const hap_attn_desc* d, int shard_index, const void* Q, const void* K, const void* V,
+                         const void* O, const float* lse, const void* dO, void* dQ, void* dK, void* dV,
+                         void* ws, size_t ws_bytes, void* stream);
+size_t hap_attn_bwd_workspace(const hap_attn_desc* d, int shard_index);
+
+/* ------------------------------------------------------------------ device: row / element helpers --- */
+
+/* LayerNorm over the last axis, biased variance, eps = 1e-5.  x,y [rows x n] (ld = n), gamma/beta [n]
+ * in io_dtype; mean, rstd fp32 [rows] saved for the backward.                                      */
+int hap_layernorm_fwd(int64_t rows, int64_t n, int io_dtype, const void* x, const void* gamma, const void* beta,
+                      void* y, float* mean, float* rstd, void* stream);
+/* dx in io_dtype; dgamma, dbeta fp32 [n], overwritten.  ws from hap_layernorm_bwd_workspace.        */
+int hap_layernorm_bwd(int64_t rows, int64_t n, int io_dtype, const void* x, const void* gamma, const float* mean,
+                      const float* rstd, const void* dy, void* dx, float* dgamma, float* dbeta,
+                      void* ws, size_t ws_bytes, void* stream);
+size_t hap_layernorm_bwd_workspace(int64_t rows, int64_t n);
+
+/* out[r,c] = dy[r,c] * gelu'(preact[r,c])   (erf form)                                            */
+int hap_gelu_bwd(int64_t rows, int64_t cols, int io_dtype, const void* preact, int64_t ldp, const void* dy,
+                 int64_t lddy, void* out, int64_t ldo, void* stream);
+/* out = a + b (+ bias broadcast over rows if bias != NULL); out may alias a or b.                  */
+int hap_add(int64_t rows, int64_t cols, int io_dtype, const void* a, int64_t lda, const void* b, int64_t ldb,
+            const void* bias, void* out, int64_t ldo, void* stream);
+/* out[c] = sum_r a[r,c], fp32 out, overwritten.  ws from hap_colsum_workspace.                     */
+int hap_colsum(int64_t rows, int64_t cols, int io_dtype, const void* a, int64_t lda, float* out,
+               void* ws, size_t ws_bytes, void* stream);
+size_t hap_colsum_workspace(int64_t rows, int64_t cols);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LIBHAP_H */

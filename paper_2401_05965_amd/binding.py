@@ -1,0 +1,240 @@
+"""ctypes binding of libhap.so: argument marshalling only.
+
+Device buffers are torch tensors (any object with ``data_ptr()``) or raw integer addresses;
+the stream is torch's current HIP stream unless given.  Every wrapper raises HapError on a
+non-zero status and never falls back to another implementation: if the shared library has
+not been built, importing this module fails.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional, Sequence
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+lib_path = os.path.join(HERE, "libhap.so")
+
+F32, BF16 = 0, 1
+SHARD_BATCH, SHARD_FEATURE, SHARD_REDUCTION, REPLICATED = 0, 1, 2, 3
+ACT_NONE, ACT_GELU_ERF = 0, 1
+
+if not os.path.exists(lib_path):
+    raise ImportError(
+        f"{lib_path} is missing: build it with `python -m paper_2401_05965_amd.build` "
+        "(or __graft_entry__.build()); there is no fallback path")
+# PyTorch ships its own HIP runtime (same SONAME as the system one).  Two runtimes in one process do
+# not work, so torch's copy must already be mapped when libhap.so is loaded: the dynamic linker then
+# resolves libhap's libamdhip64.so.7 dependency to it, and both share devices, streams and memory.
+import torch  # noqa: E402,F401  (load order matters; no torch API is used by the library)
+
+lib = C.CDLL(lib_path)
+
+
+class HapError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        detail = lib.hap_last_error().decode()
+        super().__init__(f"{where}: {lib.hap_strerror(status).decode()} ({status}): {detail}")
+
+
+class Stage(C.Structure):
+    _fields_ = [("flops_sharded", C.c_double), ("flops_fixed", C.c_double),
+                ("comm_latency", C.c_double), ("comm_per_ratio", C.c_double)]
+
+
+class _LinearDesc(C.Structure):
+    _fields_ = [("tokens", C.c_int64), ("in_features", C.c_int64), ("out_features", C.c_int64),
+                ("mode", C.c_int), ("m", C.c_int), ("offsets", C.POINTER(C.c_int64)),
+                ("io_dtype", C.c_int), ("act", C.c_int), ("has_bias", C.c_int),
+                ("ldx", C.c_int64), ("ldw", C.c_int64), ("ldy", C.c_int64),
+                ("operands_are_full", C.c_int)]
+
+
+class _AttnDesc(C.Structure):
+    _fields_ = [("batch", C.c_int64), ("heads", C.c_int64), ("seq", C.c_int64), ("head_dim", C.c_int64),
+                ("shard_over_heads", C.c_int), ("m", C.c_int), ("offsets", C.POINTER(C.c_int64)),
+                ("io_dtype", C.c_int), ("stride_b", C.c_int64), ("stride_s", C.c_int64), ("stride_h", C.c_int64)]
+
+
+class LinearDesc:
+    """Python mirror of hap_linear_desc; keeps the offsets array alive."""
+
+    def __init__(self, tokens, in_features, out_features, mode, offsets: Optional[Sequence[int]], io_dtype,
+                 act=ACT_NONE, has_bias=False, ldx=None, ldw=None, ldy=None, operands_are_full=True, m=None):
+        offsets = list(offsets) if offsets is not None else None
+        self._offs = (C.c_int64 * len(offsets))(*offsets) if offsets is not None else None
+        self.m = (len(offsets) - 1) if (offsets is not None and m is None) else (m if m is not None else 1)
+        self.c = _LinearDesc(tokens, in_features, out_features, mode, self.m,
+                             C.cast(self._offs, C.POINTER(C.c_int64)) if self._offs is not None else None,
+                             io_dtype, act, int(bool(has_bias)),
+                             ldx if ldx is not None else in_features,
+                             ldw if ldw is not None else out_features,
+                             ldy if ldy is not None else out_features,
+                             int(bool(operands_are_full)))
+
+
+class AttnDesc:
+    def __init__(self, batch, heads, seq, head_dim, shard_over_heads, offsets, io_dtype=BF16,
+                 stride_b=None, stride_s=None, stride_h=None):
+        offsets = list(offsets)
+        self._offs = (C.c_int64 * len(offsets))(*offsets)
+        self.m = len(offsets) - 1
+        stride_h = head_dim if stride_h is None else stride_h
+        stride_s = heads * head_dim if stride_s is None else stride_s
+        stride_b = seq * stride_s if stride_b is None else stride_b
+        self.c = _AttnDesc(batch, heads, seq, head_dim, int(bool(shard_over_heads)), self.m,
+                           C.cast(self._offs, C.POINTER(C.c_int64)), io_dtype, stride_b, stride_s, stride_h)
+
+
+lib.hap_strerror.restype = C.c_char_p
+lib.hap_strerror.argtypes = [C.c_int]
+lib.hap_last_error.restype = C.c_char_p
+lib.hap_version.restype = C.c_char_p
+for _n in ("hap_linear_fwd_workspace", "hap_linear_bwd_workspace", "hap_sfb_workspace", "hap_attn_bwd_workspace",
+           "hap_layernorm_bwd_workspace", "hap_colsum_workspace"):
+    if hasattr(lib, _n):
+        getattr(lib, _n).restype = C.c_size_t
+
+
+def _ptr(t) -> C.c_void_p:
+    if t is None:
+        return C.c_void_p(None)
+    if isinstance(t, int):
+        return C.c_void_p(t)
+    return C.c_void_p(t.data_ptr())
+
+
+def _stream(stream) -> C.c_void_p:
+    if stream is None:
+        import torch
+        return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+    if isinstance(stream, int):
+        return C.c_void_p(stream)
+    return C.c_void_p(stream.cuda_stream)
+
+
+def _ws(ws):
+    if ws is None:
+        return C.c_void_p(None), C.c_size_t(0)
+    return C.c_void_p(ws.data_ptr()), C.c_size_t(ws.numel() * ws.element_size())
+
+
+def _check(status: int, where: str):
+    if status != 0:
+        raise HapError(status, where)
+
+
+def _stages(stages):
+    arr = (Stage * len(stages))()
+    for i, s in enumerate(stages):
+        arr[i] = s if isinstance(s, Stage) else Stage(*[float(v) for v in s])
+    return arr
+
+
+# ---------------------------------------------------------------- host
+
+def hap_shard_ratios(speed: Sequence[float], stages):
+    """stages: sequence of (flops_sharded, flops_fixed, comm_latency, comm_per_ratio). Returns (ratios, seconds)."""
+    m = len(speed)
+    sp = (C.c_double * m)(*[float(v) for v in speed])
+    out = (C.c_double * m)()
+    obj = C.c_double()
+    _check(lib.hap_shard_ratios(C.c_int(m), sp, C.c_int(len(stages)), _stages(stages), out, C.byref(obj)), "hap_shard_ratios")
+    return list(out), obj.value
+
+
+def hap_iteration_time(speed, stages, ratios) -> float:
+    m = len(speed)
+    sec = C.c_double()
+    _check(lib.hap_iteration_time(C.c_int(m), (C.c_double * m)(*map(float, speed)), C.c_int(len(stages)), _stages(stages),
+                                  (C.c_double * m)(*map(float, ratios)), C.byref(sec)), "hap_iteration_time")
+    return sec.value
+
+
+def hap_round_shards(ratios: Sequence[float], dim_len: int, granule: int = 1):
+    m = len(ratios)
+    sizes = (C.c_int64 * m)()
+    offs = (C.c_int64 * (m + 1))()
+    _check(lib.hap_round_shards(C.c_int(m), (C.c_double * m)(*map(float, ratios)), C.c_int64(dim_len), C.c_int64(granule),
+                                sizes, offs), "hap_round_shards")
+    return list(sizes), list(offs)
+
+
+# ---------------------------------------------------------------- device
+
+def hap_linear_bwd_workspace(desc: LinearDesc, shard_index: int) -> int:
+    return int(lib.hap_linear_bwd_workspace(C.byref(desc.c), C.c_int(shard_index)))
+
+
+def hap_sharded_linear_fwd(desc: LinearDesc, shard_index, X, W, bias, Y, preact=None, ws=None, stream=None):
+    wp, wb = _ws(ws)
+    _check(lib.hap_sharded_linear_fwd(C.byref(desc.c), C.c_int(shard_index), _ptr(X), _ptr(W), _ptr(bias), _ptr(Y),
+                                      _ptr(preact), wp, wb, _stream(stream)), "hap_sharded_linear_fwd")
+
+
+def hap_sharded_linear_bwd(desc: LinearDesc, shard_index, X, W, preact, dY, dX, dW, dW_dtype, dbias, ws=None, stream=None):
+    wp, wb = _ws(ws)
+    _check(lib.hap_sharded_linear_bwd(C.byref(desc.c), C.c_int(shard_index), _ptr(X), _ptr(W), _ptr(preact), _ptr(dY),
+                                      _ptr(dX), _ptr(dW), C.c_int(dW_dtype), _ptr(dbias), wp, wb, _stream(stream)),
+           "hap_sharded_linear_bwd")
+
+
+def hap_sfb_grad(Xs, dYs, rows, in_features, out_features, ldx, ldy, in_dtype, dW, lddw, accumulate=False, ws=None, stream=None):
+    m = len(rows)
+    xp = (C.c_void_p * m)(*[_ptr(t) for t in Xs])
+    yp = (C.c_void_p * m)(*[_ptr(t) for t in dYs])
+    wp, wb = _ws(ws)
+    _check(lib.hap_sfb_grad(C.c_int(m), xp, yp, (C.c_int64 * m)(*map(int, rows)), C.c_int64(in_features), C.c_int64(out_features),
+                            C.c_int64(ldx), C.c_int64(ldy), C.c_int(in_dtype), _ptr(dW), C.c_int64(lddw), C.c_int(int(accumulate)),
+                            wp, wb, _stream(stream)), "hap_sfb_grad")
+
+
+def hap_attn_bwd_workspace(desc: AttnDesc, shard_index: int) -> int:
+    return int(lib.hap_attn_bwd_workspace(C.byref(desc.c), C.c_int(shard_index)))
+
+
+def hap_sharded_attn_fwd(desc: AttnDesc, shard_index, Q, K, V, O, lse, ws=None, stream=None):
+    wp, wb = _ws(ws)
+    _check(lib.hap_sharded_attn_fwd(C.byref(desc.c), C.c_int(shard_index), _ptr(Q), _ptr(K), _ptr(V), _ptr(O), _ptr(lse),
+                                    wp, wb, _stream(stream)), "hap_sharded_attn_fwd")
+
+
+def hap_sharded_attn_bwd(desc: AttnDesc, shard_index, Q, K, V, O, lse, dO, dQ, dK, dV, ws=None, stream=None):
+    wp, wb = _ws(ws)
+    _check(lib.hap_sharded_attn_bwd(C.byref(desc.c), C.c_int(shard_index), _ptr(Q), _ptr(K), _ptr(V), _ptr(O), _ptr(lse),
+                                    _ptr(dO), _ptr(dQ), _ptr(dK), _ptr(dV), wp, wb, _stream(stream)), "hap_sharded_attn_bwd")
+
+
+def hap_layernorm_fwd(rows, n, io_dtype, x, gamma, beta, y, mean, rstd, stream=None):
+    _check(lib.hap_layernorm_fwd(C.c_int64(rows), C.c_int64(n), C.c_int(io_dtype), _ptr(x), _ptr(gamma), _ptr(beta), _ptr(y),
+                                 _ptr(mean), _ptr(rstd), _stream(stream)), "hap_layernorm_fwd")
+
+
+def hap_layernorm_bwd_workspace(rows, n) -> int:
+    return int(lib.hap_layernorm_bwd_workspace(C.c_int64(rows), C.c_int64(n)))
+
+
+def hap_layernorm_bwd(rows, n, io_dtype, x, gamma, mean, rstd, dy, dx, dgamma, dbeta, ws, stream=None):
+    wp, wb = _ws(ws)
+    _check(lib.hap_layernorm_bwd(C.c_int64(rows), C.c_int64(n), C.c_int(io_dtype), _ptr(x), _ptr(gamma), _ptr(mean), _ptr(rstd),
+                                 _ptr(dy), _ptr(dx), _ptr(dgamma), _ptr(dbeta), wp, wb, _stream(stream)), "hap_layernorm_bwd")
+
+
+def hap_gelu_bwd(rows, cols, io_dtype, preact, ldp, dy, lddy, out, ldo, stream=None):
+    _check(lib.hap_gelu_bwd(C.c_int64(rows), C.c_int64(cols), C.c_int(io_dtype), _ptr(preact), C.c_int64(ldp), _ptr(dy),
+                            C.c_int64(lddy), _ptr(out), C.c_int64(ldo), _stream(stream)), "hap_gelu_bwd")
+
+
+def hap_add(rows, cols, io_dtype, a, lda, b, ldb, bias, out, ldo, stream=None):
+    _check(lib.hap_add(C.c_int64(rows), C.c_int64(cols), C.c_int(io_dtype), _ptr(a), C.c_int64(lda), _ptr(b), C.c_int64(ldb),
+                       _ptr(bias), _ptr(out), C.c_int64(ldo), _stream(stream)), "hap_add")
+
+
+def hap_colsum_workspace(rows, cols) -> int:
+    return int(lib.hap_colsum_workspace(C.c_int64(rows), C.c_int64(cols)))
+
+
+def hap_colsum(rows, cols, io_dtype, a, lda, out, ws, stream=None):
+    wp, wb = _ws(ws)
+    _check(lib.hap_colsum(C.c_int64(rows), C.c_int64(cols), C.c_int(io_dtype), _ptr(a), C.c_int64(lda), _ptr(out), wp, wb,
+                          _stream(stream)), "hap_colsum")

@@ -1,0 +1,508 @@
+/*
+ * GEMM engine of libhap for gfx950 (CDNA4): bf16 / fp32 MFMA, LDS-tiled, ragged edges handled by
+ * predication instead of padding the problem.
+ *
+ * Data movement.  A tile of each operand is fetched as 16-byte chunks with raw buffer loads
+ * (an out-of-range chunk costs no memory access and reads as zero) and stored in LDS in the
+ * operand's own contiguous direction:
+ *   K-contiguous operand  -> LDS rows are m (or n), chunks run along k; MFMA fragments come from
+ *                            one 128-bit LDS read per lane;
+ *   M/N-contiguous operand-> LDS rows are k, chunks run along m (or n); fragments come from the
+ *                            transposing LDS read of gfx950 (ds_read_b64_tr_b16), which hands each
+ *                            lane 4 consecutive k of one column.
+ * 16-byte chunks are XOR-swizzled inside a row so both kinds of fragment read are bank-conflict free.
+ *
+ * Raggedness.  Shard ranges start at arbitrary elements (e.g. column 13443 of a bf16 matrix), so the
+ * launcher aligns every operand base DOWN to 16 bytes and passes the number of leading elements
+ * (skew) that do not belong to the shard.  Leading / trailing elements along k are zeroed in
+ * registers before they reach LDS; leading / trailing rows and columns of C are simply not stored.
+ */
+#include <hip/hip_runtime.h>
+
+#include <stdint.h>
+
+#include "hap_gemm.h"
+
+namespace {
+
+typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+typedef short s16x4_t __attribute__((ext_vector_type(4)));
+typedef float f32x16_t __attribute__((ext_vector_type(16)));
+typedef int i32x4_t __attribute__((ext_vector_type(4)));
+
+#define LDS_PTR(T, p) ((__attribute__((address_space(3))) T*)(p))
+
+constexpr unsigned kOobOffset = 0x80000000u;  // beyond any num_records we pass: reads as zero
+constexpr int kRsrcFlags = 0x00020000;        // raw buffer, 32-bit data format
+
+struct SegArg {
+  const void* a;   // aligned-down base of this segment's A view
+  const void* b;
+  int k;           // logical contracted length of the segment
+  unsigned a_bytes, b_bytes;  // valid extent from the aligned bases
+  int pad;
+};
+
+struct GemmArgs {
+  int M, N;            // logical extent of C
+  int skewM, skewN;    // physical columns preceding logical 0 in an M-/N-contiguous operand
+  int skewK;           // physical k preceding logical 0 in a K-contiguous operand
+  int nseg;
+  int tiles_m, tiles_n;
+  long long lda, ldb, ldc, ldp;
+  void* c;
+  void* preact;
+  const void* bias;
+  int act, accumulate;
+  SegArg seg[HAP_GEMM_MAX_SEG];
+};
+
+__device__ __forceinline__ float gelu_erf(float x) { return 0.5f * x * (1.0f + erff(x * 0.70710678118654752f)); }
+
+template <typename T> struct Elem;
+template <> struct Elem<__bf16> {
+  static constexpr int kStep = 16;  // k per MFMA (v_mfma_f32_32x32x16_bf16)
+};
+template <> struct Elem<float> {
+  static constexpr int kStep = 2;   // v_mfma_f32_32x32x2_f32
+};
+
+/* Swizzled position of 16-byte chunk c in LDS row `row`. */
+template <bool KC, int CPR>
+__device__ __forceinline__ int swz(int row, int c) {
+  if constexpr (KC) {
+    constexpr int RPS = CPR >= 8 ? 1 : 8 / CPR;      // rows per 128-byte bank sweep
+    constexpr int MASK = (CPR >= 8 ? 8 : CPR) - 1;
+    return c ^ ((row / RPS) & MASK);
+  } else {
+    return c ^ ((row & 3) << 1);
+  }
+}
+
+template <typename T> __device__ __forceinline__ void store_c(T* p, float v);
+template <> __device__ __forceinline__ void store_c<float>(float* p, float v) { *p = v; }
+template <> __device__ __forceinline__ void store_c<__bf16>(__bf16* p, float v) { *p = (__bf16)v; }
+template <typename T> __device__ __forceinline__ float load_s(const T* p);
+template <> __device__ __forceinline__ float load_s<float>(const float* p) { return *p; }
+template <> __device__ __forceinline__ float load_s<__bf16>(const __bf16* p) { return (float)*p; }
+
+/* Loads one operand tile's chunks owned by this thread into registers.
+ * KC:  rows = ROWS (m or n), chunk c covers k in [c*EPC, (c+1)*EPC)
+ * !KC: rows = BK (k), chunk c covers m (or n) in [c*EPC, ...)                                   */
+template <typename T, bool KC, int ROWS, int BK, int NT>
+struct TileLoader {
+  static constexpr int ES = sizeof(T);
+  static constexpr int EPC = 16 / ES;
+  static constexpr int LROWS = KC ? ROWS : BK;
+  static constexpr int CPR = (KC ? BK : ROWS) / EPC;
+  static constexpr int CPT = LROWS * CPR / NT;
+  static_assert(LROWS * CPR % NT == 0, "tile chunks must divide evenly over threads");
+
+  i32x4_t regs[CPT];
+
+  /* mn0: first physical row (KC) or column (!KC) of the tile in the MN direction.
+   * mn_lim: physical MN extent.  k0: first physical k of the tile; kskew/kend: logical k range in
+   * physical coordinates [kskew, kend).  ld in elements.                                        */
+  __device__ __forceinline__ void load(__amdgpu_buffer_rsrc_t rsrc, int tid, int mn0, int mn_lim, long long ld,
+                                       int k0, int kskew, int kend) {
+#pragma unroll
+    for (int i = 0; i < CPT; ++i) {
+      const int id = tid + i * NT;
+      const int row = id / CPR, c = id % CPR;
+      unsigned off;
+      if constexpr (KC) {
+        const int mn = mn0 + row, kp = k0 + c * EPC;
+        const bool ok = mn < mn_lim && kp < kend && kp + EPC > kskew;
+        off = ok ? (unsigned)(((long long)mn * ld + kp) * ES) : kOobOffset;
+      } else {
+        const int kl = k0 + row, mn = mn0 + c * EPC;
+        const bool ok = kl >= kskew && kl < kend && mn < mn_lim;
+        off = ok ? (unsigned)(((long long)(kl - kskew) * ld + mn) * ES) : kOobOffset;
+      }
+      regs[i] = __builtin_bit_cast(i32x4_t, __builtin_amdgcn_raw_buffer_load_b128(rsrc, off, 0, 0));
+    }
+  }
+
+  /* Zeroes elements outside [kskew, kend) of K-contiguous chunks (needed on a segment's first and
+   * last tile only; callers skip it elsewhere). */
+  __device__ __forceinline__ void mask_k(int tid, int k0, int kskew, int kend) {
+    if constexpr (KC) {
+#pragma unroll
+      for (int i = 0; i < CPT; ++i) {
+        const int id = tid + i * NT;
+        const int c = id % CPR;
+        const int kp = k0 + c * EPC;
+        if (kp < kskew || kp + EPC > kend) {
+          T v[EPC];
+          __builtin_memcpy(v, &regs[i], 16);
+#pragma unroll
+          for (int e = 0; e < EPC; ++e)
+            if (kp + e < kskew || kp + e >= kend) v[e] = (T)0.0f;
+          __builtin_memcpy(&regs[i], v, 16);
+        }
+      }
+    }
+  }
+
+  __device__ __forceinline__ void store(char* lds, int tid) {
+#pragma unroll
+    for (int i = 0; i < CPT; ++i) {
+      const int id = tid + i * NT;
+      const int row = id / CPR, c = id % CPR;
+      *reinterpret_cast<i32x4_t*>(lds + row * (CPR * 16) + swz<KC, CPR>(row, c) * 16) = regs[i];
+    }
+  }
+};
+
+/* MFMA operand fragment for a 32-row block starting at LDS row/column `mn` (multiple of 32) and
+ * k-step kk of the tile. */
+template <typename T, bool KC, int ROWS, int BK>
+struct Frag;
+
+template <bool KC, int ROWS, int BK>
+struct Frag<__bf16, KC, ROWS, BK> {
+  typedef bf16x8_t type;
+  static constexpr int CPR = (KC ? BK : ROWS) / 8;
+  static __device__ __forceinline__ type read(const char* lds, int mn, int kk, int lane) {
+    if constexpr (KC) {
+      const int row = mn + (lane & 31);
+      const int c = kk * 2 + (lane >> 5);
+      return __builtin_bit_cast(type, *reinterpret_cast<const i32x4_t*>(lds + row * (CPR * 16) + swz<true, CPR>(row, c) * 16));
+    } else {
+      const int g = lane >> 4, i = lane & 15;
+      const int col = mn + (g & 1) * 16 + (i & 3) * 4;
+      const int krow = kk * 16 + (g >> 1) * 8 + (i >> 2);
+      const int c = col >> 3, sub = (col & 7) * 2;
+      const char* p0 = lds + krow * (CPR * 16) + swz<false, CPR>(krow, c) * 16 + sub;
+      const char* p1 = lds + (krow + 4) * (CPR * 16) + swz<false, CPR>(krow + 4, c) * 16 + sub;
+      s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4_t, p0));
+      s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4_t, p1));
+      typedef short s16x8_t __attribute__((ext_vector_type(8)));
+      s16x8_t v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+      return __builtin_bit_cast(type, v);
+    }
+  }
+};
+
+template <bool KC, int ROWS, int BK>
+struct Frag<float, KC, ROWS, BK> {
+  typedef float type;
+  static constexpr int CPR = (KC ? BK : ROWS) / 4;
+  static __device__ __forceinline__ type read(const char* lds, int mn, int kk, int lane) {
+    if constexpr (KC) {
+      const int row = mn + (lane & 31);
+      const int k = kk * 2 + (lane >> 5);
+      return *reinterpret_cast<const float*>(lds + row * (CPR * 16) + swz<true, CPR>(row, k >> 2) * 16 + (k & 3) * 4);
+    } else {
+      const int krow = kk * 2 + (lane >> 5);
+      const int col = mn + (lane & 31);
+      return *reinterpret_cast<const float*>(lds + krow * (CPR * 16) + swz<false, CPR>(krow, col >> 2) * 16 + (col & 3) * 4);
+    }
+  }
+};
+
+__device__ __forceinline__ f32x16_t mfma(bf16x8_t a, bf16x8_t b, f32x16_t c) {
+  return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+}
+__device__ __forceinline__ f32x16_t mfma(float a, float b, f32x16_t c) {
+  return __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, c, 0, 0, 0);
+}
+
+/* Workgroup id -> tile, keeping the workgroups that share an XCD (ids congruent mod 8 are
+ * dispatched to the same die and L2) on a compact block of the tile grid. */
+__device__ __forceinline__ void tile_of_block(int bid, int nblocks, int tiles_m, int tiles_n, int* tm, int* tn) {
+  constexpr int XCDS = 8, GM = 4;
+  const int xcd = bid % XCDS, local = bid / XCDS;
+  const int q = nblocks / XCDS, r = nblocks % XCDS;
+  const int logical = xcd * q + (xcd < r ? xcd : r) + local;
+  const int per_group = GM * tiles_n;
+  const int group = logical / per_group, in_group = logical % per_group;
+  const int first_m = group * GM;
+  const int gsize = tiles_m - first_m < GM ? tiles_m - first_m : GM;
+  *tm = first_m + in_group % gsize;
+  *tn = in_group / gsize;
+}
+
+template <typename T, typename TC, bool AKC, bool BKC, int BM, int BN, int BK, int WGM, int WGN>
+__global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(const GemmArgs args) {
+  constexpr int NT = 64 * WGM * WGN;
+  constexpr int ES = sizeof(T);
+  constexpr int WTM = BM / WGM, WTN = BN / WGN;
+  constexpr int TM = WTM / 32, TN = WTN / 32;
+  constexpr int KSTEP = Elem<T>::kStep;
+  static_assert(WTM % 32 == 0 && WTN % 32 == 0 && BK % KSTEP == 0, "tile shape");
+
+  __shared__ __attribute__((aligned(16))) char lds_a[BM * BK * ES];
+  __shared__ __attribute__((aligned(16))) char lds_b[BN * BK * ES];
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm0 = (wave / WGN) * WTM, wn0 = (wave % WGN) * WTN;
+  int tm, tn;
+  tile_of_block(blockIdx.x, gridDim.x, args.tiles_m, args.tiles_n, &tm, &tn);
+  const int m0 = tm * BM, n0 = tn * BN;                 // physical tile origin
+  const int m_lim = args.skewM + args.M, n_lim = args.skewN + args.N;
+
+  TileLoader<T, AKC, BM, BK, NT> la;
+  TileLoader<T, BKC, BN, BK, NT> lb;
+
+  f32x16_t acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
+
+  // loader state runs one tile ahead of the compute
+  int seg = 0, k0 = 0;
+  int kend = args.skewK + args.seg[0].k;
+  __amdgpu_buffer_rsrc_t ra = __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(args.seg[0].a), 0, args.seg[0].a_bytes, kRsrcFlags);
+  __amdgpu_buffer_rsrc_t rb = __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(args.seg[0].b), 0, args.seg[0].b_bytes, kRsrcFlags);
+
+  auto fetch = [&]() {
+    la.load(ra, tid, m0, m_lim, args.lda, k0, args.skewK, kend);
+    lb.load(rb, tid, n0, n_lim, args.ldb, k0, args.skewK, kend);
+  };
+  auto commit = [&](int ck0, int ckend) {
+    if (ck0 < args.skewK || ck0 + BK > ckend) {
+      la.mask_k(tid, ck0, args.skewK, ckend);
+      lb.mask_k(tid, ck0, args.skewK, ckend);
+    }
+    la.store(lds_a, tid);
+    lb.store(lds_b, tid);
+  };
+
+  fetch();
+  while (true) {
+    const int ck0 = k0, ckend = kend;
+    // advance the loader to the next tile
+    k0 += BK;
+    bool more = true;
+    if (k0 >= kend) {
+      ++seg;
+      if (seg < args.nseg) {
+        k0 = 0;
+        kend = args.skewK + args.seg[seg].k;
+        ra = __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(args.seg[seg].a), 0, args.seg[seg].a_bytes, kRsrcFlags);
+        rb = __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(args.seg[seg].b), 0, args.seg[seg].b_bytes, kRsrcFlags);
+      } else {
+        more = false;
+      }
+    }
+    commit(ck0, ckend);
+    __syncthreads();
+    if (more) fetch();
+#pragma unroll
+    for (int kk = 0; kk < BK / KSTEP; ++kk) {
+      typename Frag<T, AKC, BM, BK>::type fa[TM];
+      typename Frag<T, BKC, BN, BK>::type fb[TN];
+#pragma unroll
+      for (int i = 0; i < TM; ++i) fa[i] = Frag<T, AKC, BM, BK>::read(lds_a, wm0 + i * 32, kk, lane);
+#pragma unroll
+      for (int j = 0; j < TN; ++j) fb[j] = Frag<T, BKC, BN, BK>::read(lds_b, wn0 + j * 32, kk, lane);
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j) acc[i][j] = mfma(fa[i], fb[j], acc[i][j]);
+    }
+    if (!more) break;
+    __syncthreads();
+  }
+
+  // epilogue: accumulator element e of lane l is row (e/4)*8 + (l/32)*4 + e%4, column l%32
+  TC* C = static_cast<TC*>(args.c);
+  TC* P = static_cast<TC*>(args.preact);
+  const T* bias = static_cast<const T*>(args.bias);
+#pragma unroll
+  for (int j = 0; j < TN; ++j) {
+    const int n = n0 + wn0 + j * 32 + (lane & 31) - args.skewN;
+    const bool n_ok = n >= 0 && n < args.N;
+    const float bv = (bias && n_ok) ? load_s<T>(bias + n) : 0.0f;
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        const int m = m0 + wm0 + i * 32 + (e >> 2) * 8 + (lane >> 5) * 4 + (e & 3) - args.skewM;
+        if (n_ok && m >= 0 && m < args.M) {
+          float v = acc[i][j][e] + bv;
+          if (P) store_c<TC>(P + (long long)m * args.ldp + n, v);
+          if (args.act == HAP_ACT_GELU_ERF) v = gelu_erf(v);
+          TC* dst = C + (long long)m * args.ldc + n;
+          if (args.accumulate) v += load_s<TC>(dst);
+          store_c<TC>(dst, v);
+        }
+      }
+    }
+  }
+}
+
+/* Scalar fallback for operand views the tiled kernel cannot address with aligned 16-byte chunks
+ * (leading dimension not a multiple of 16 bytes, or differently skewed K-contiguous operands). */
+struct GenericArgs {
+  int M, N, nseg;
+  long long lda, ldb, ldc, ldp;
+  int a_kcontig, b_kcontig;
+  void* c; void* preact; const void* bias;
+  int act, accumulate;
+  const void* a[HAP_GEMM_MAX_SEG];
+  const void* b[HAP_GEMM_MAX_SEG];
+  int k[HAP_GEMM_MAX_SEG];
+};
+
+template <typename T, typename TC>
+__global__ __launch_bounds__(256) void gemm_generic_kernel(const GenericArgs g) {
+  const int n = blockIdx.x * 16 + (threadIdx.x & 15);
+  const int m = blockIdx.y * 16 + (threadIdx.x >> 4);
+  if (m >= g.M || n >= g.N) return;
+  float acc = 0.0f;
+  for (int s = 0; s < g.nseg; ++s) {
+    const T* A = static_cast<const T*>(g.a[s]);
+    const T* B = static_cast<const T*>(g.b[s]);
+    for (int k = 0; k < g.k[s]; ++k) {
+      const float av = load_s<T>(g.a_kcontig ? A + (long long)m * g.lda + k : A + (long long)k * g.lda + m);
+      const float bv = load_s<T>(g.b_kcontig ? B + (long long)n * g.ldb + k : B + (long long)k * g.ldb + n);
+      acc = fmaf(av, bv, acc);
+    }
+  }
+  if (g.bias) acc += load_s<T>(static_cast<const T*>(g.bias) + n);
+  if (g.preact) store_c<TC>(static_cast<TC*>(g.preact) + (long long)m * g.ldp + n, acc);
+  if (g.act == HAP_ACT_GELU_ERF) acc = gelu_erf(acc);
+  TC* dst = static_cast<TC*>(g.c) + (long long)m * g.ldc + n;
+  if (g.accumulate) acc += load_s<TC>(dst);
+  store_c<TC>(dst, acc);
+}
+
+struct Plan {
+  bool tiled;
+  int skewM, skewN, skewK;
+  int bm, bn;       // tile
+  const char* name;
+};
+
+inline int esize(int dtype) { return dtype == HAP_BF16 ? 2 : 4; }
+
+/* Decides whether the aligned-chunk kernel can address the operands and with which skews. */
+Plan make_plan(const hap_gemm_problem* p) {
+  Plan pl = {false, 0, 0, 0, 0, 0, "generic"};
+  if (p->force_generic) return pl;
+  const int es = esize(p->in_dtype);
+  if ((p->lda * es) % 16 || (p->ldb * es) % 16) return pl;
+  int sa = -1, sb = -1;
+  for (int s = 0; s < p->nseg; ++s) {
+    if (p->k[s] == 0) continue;
+    const int xa = (int)(((uintptr_t)p->a[s] % 16) / es), xb = (int)(((uintptr_t)p->b[s] % 16) / es);
+    if (((uintptr_t)p->a[s] % es) || ((uintptr_t)p->b[s] % es)) return pl;
+    if (sa < 0) { sa = xa; sb = xb; }
+    else if (sa != xa || sb != xb) return pl;
+  }
+  if (sa < 0) { sa = sb = 0; }
+  if (p->a_kcontig && p->b_kcontig && sa != sb) return pl;
+  pl.skewK = p->a_kcontig ? sa : (p->b_kcontig ? sb : 0);
+  pl.skewM = p->a_kcontig ? 0 : sa;
+  pl.skewN = p->b_kcontig ? 0 : sb;
+  // operand views must stay below 2 GiB so 32-bit buffer offsets and the out-of-range marker work
+  for (int s = 0; s < p->nseg; ++s) {
+    const double ea = p->a_kcontig ? ((double)(p->M - 1) * p->lda + pl.skewK + p->k[s]) : ((double)(p->k[s] - 1) * p->lda + pl.skewM + p->M);
+    const double eb = p->b_kcontig ? ((double)(p->N - 1) * p->ldb + pl.skewK + p->k[s]) : ((double)(p->k[s] - 1) * p->ldb + pl.skewN + p->N);
+    if (ea * es >= 2147483000.0 || eb * es >= 2147483000.0) return pl;
+  }
+  pl.tiled = true;
+  if (p->in_dtype == HAP_F32) { pl.bm = pl.bn = 64; pl.name = "f32_64x64x16"; }
+  else if (p->M + pl.skewM > 128 && p->N + pl.skewN > 128) { pl.bm = pl.bn = 256; pl.name = "bf16_256x256x64"; }
+  else { pl.bm = pl.bn = 128; pl.name = "bf16_128x128x64"; }
+  return pl;
+}
+
+template <typename T, typename TC, bool AKC, bool BKC, int BM, int BN, int BK, int WGM, int WGN>
+int launch_tiled(const GemmArgs& a, hipStream_t st) {
+  const int grid = a.tiles_m * a.tiles_n;
+  hipLaunchKernelGGL((gemm_kernel<T, TC, AKC, BKC, BM, BN, BK, WGM, WGN>), dim3(grid), dim3(64 * WGM * WGN), 0, st, a);
+  const hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return hap_fail(HAP_EDEVICE, "gemm launch: %s", hipGetErrorString(e));
+  return HAP_OK;
+}
+
+template <typename T, typename TC, int BM, int BN, int BK, int WGM, int WGN>
+int dispatch_layout(const hap_gemm_problem* p, const GemmArgs& a, hipStream_t st) {
+  if (p->a_kcontig && p->b_kcontig) return launch_tiled<T, TC, true, true, BM, BN, BK, WGM, WGN>(a, st);
+  if (p->a_kcontig && !p->b_kcontig) return launch_tiled<T, TC, true, false, BM, BN, BK, WGM, WGN>(a, st);
+  if (!p->a_kcontig && !p->b_kcontig) return launch_tiled<T, TC, false, false, BM, BN, BK, WGM, WGN>(a, st);
+  return launch_tiled<T, TC, false, true, BM, BN, BK, WGM, WGN>(a, st);
+}
+
+template <typename T, typename TC>
+int dispatch_tile(const hap_gemm_problem* p, const Plan& pl, const GemmArgs& a, hipStream_t st) {
+  if constexpr (sizeof(T) == 4) {
+    return dispatch_layout<T, TC, 64, 64, 16, 2, 2>(p, a, st);
+  } else {
+    if (pl.bm == 256) return dispatch_layout<T, TC, 256, 256, 64, 2, 4>(p, a, st);
+    return dispatch_layout<T, TC, 128, 128, 64, 2, 2>(p, a, st);
+  }
+}
+
+}  // namespace
+
+const char* hap_gemm_variant(const hap_gemm_problem* p) { return make_plan(p).name; }
+
+int hap_gemm_run(const hap_gemm_problem* p, void* stream) {
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  if (p->M <= 0 || p->N <= 0) return HAP_OK;
+  if (p->M > 0x7fffffff || p->N > 0x7fffffff) return hap_fail(HAP_EUNSUPPORTED, "GEMM extent exceeds 2^31");
+  if (p->accumulate && p->c_dtype != HAP_F32) return hap_fail(HAP_EINVAL, "accumulate needs an fp32 output");
+  if (p->in_dtype == HAP_F32 && p->c_dtype != HAP_F32) return hap_fail(HAP_EUNSUPPORTED, "fp32 inputs need fp32 output");
+  const int es = esize(p->in_dtype);
+  const Plan pl = make_plan(p);
+
+  if (!pl.tiled) {
+    GenericArgs g;
+    g.M = (int)p->M; g.N = (int)p->N; g.nseg = 0;
+    g.lda = p->lda; g.ldb = p->ldb; g.ldc = p->ldc; g.ldp = p->ldp;
+    g.a_kcontig = p->a_kcontig; g.b_kcontig = p->b_kcontig;
+    g.c = p->c; g.preact = p->preact; g.bias = p->bias; g.act = p->act; g.accumulate = p->accumulate;
+    for (int s = 0; s < p->nseg; ++s) {
+      if (p->k[s] <= 0) continue;
+      if (p->k[s] > 0x7fffffff) return hap_fail(HAP_EUNSUPPORTED, "segment longer than 2^31");
+      g.a[g.nseg] = p->a[s]; g.b[g.nseg] = p->b[s]; g.k[g.nseg] = (int)p->k[s]; ++g.nseg;
+    }
+    dim3 grid((unsigned)((p->N + 15) / 16), (unsigned)((p->M + 15) / 16));
+    if (grid.y > 65535u) return hap_fail(HAP_EUNSUPPORTED, "generic GEMM fallback: too many rows");
+    if (p->in_dtype == HAP_BF16 && p->c_dtype == HAP_BF16) hipLaunchKernelGGL((gemm_generic_kernel<__bf16, __bf16>), grid, dim3(256), 0, st, g);
+    else if (p->in_dtype == HAP_BF16) hipLaunchKernelGGL((gemm_generic_kernel<__bf16, float>), grid, dim3(256), 0, st, g);
+    else hipLaunchKernelGGL((gemm_generic_kernel<float, float>), grid, dim3(256), 0, st, g);
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return hap_fail(HAP_EDEVICE, "generic gemm launch: %s", hipGetErrorString(e));
+    return HAP_OK;
+  }
+
+  GemmArgs a;
+  a.M = (int)p->M; a.N = (int)p->N;
+  a.skewM = pl.skewM; a.skewN = pl.skewN; a.skewK = pl.skewK;
+  a.lda = p->lda; a.ldb = p->ldb; a.ldc = p->ldc; a.ldp = p->ldp;
+  a.c = p->c; a.preact = p->preact; a.bias = p->bias; a.act = p->act; a.accumulate = p->accumulate;
+  a.tiles_m = (int)((p->M + pl.skewM + pl.bm - 1) / pl.bm);
+  a.tiles_n = (int)((p->N + pl.skewN + pl.bn - 1) / pl.bn);
+  a.nseg = 0;
+  for (int s = 0; s < p->nseg; ++s) {
+    if (p->k[s] <= 0) continue;
+    SegArg& sg = a.seg[a.nseg++];
+    const int skew_a = p->a_kcontig ? pl.skewK : pl.skewM, skew_b = p->b_kcontig ? pl.skewK : pl.skewN;
+    sg.a = static_cast<const char*>(p->a[s]) - (size_t)skew_a * es;
+    sg.b = static_cast<const char*>(p->b[s]) - (size_t)skew_b * es;
+    sg.k = (int)p->k[s];
+    const long long ea = p->a_kcontig ? ((p->M - 1) * p->lda + pl.skewK + p->k[s]) : ((p->k[s] - 1) * p->lda + pl.skewM + p->M);
+    const long long eb = p->b_kcontig ? ((p->N - 1) * p->ldb + pl.skewK + p->k[s]) : ((p->k[s] - 1) * p->ldb + pl.skewN + p->N);
+    // Extents are rounded up to whole 16-byte chunks: the hardware range check works per dword, and
+    // a chunk that starts inside the view must come back whole (its tail is discarded by the kernel).
+    // An aligned chunk never crosses a page, so the bytes past the view are still mapped memory.
+    sg.a_bytes = (unsigned)((ea * es + 15) / 16 * 16);
+    sg.b_bytes = (unsigned)((eb * es + 15) / 16 * 16);
+    sg.pad = 0;
+  }
+  if (a.nseg == 0) {   // empty contraction: the product is zero; run one empty segment so the epilogue still applies
+    a.nseg = 1;
+    a.seg[0].a = p->c; a.seg[0].b = p->c; a.seg[0].k = 0; a.seg[0].a_bytes = 0; a.seg[0].b_bytes = 0; a.seg[0].pad = 0;
+  }
+  if (p->in_dtype == HAP_BF16 && p->c_dtype == HAP_BF16) return dispatch_tile<__bf16, __bf16>(p, pl, a, st);
+  if (p->in_dtype == HAP_BF16) return dispatch_tile<__bf16, float>(p, pl, a, st);
+  return dispatch_tile<float, float>(p, pl, a, st);
+}

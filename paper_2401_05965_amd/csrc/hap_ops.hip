@@ -1,0 +1,352 @@
+/*
+ * Memory-bound row / element kernels of libhap: GeLU backward, residual / bias add, column sums
+ * (bias gradients), LayerNorm forward / backward.  The paper treats these as stock single-device
+ * operators; here they are the HBM-bound epilogues around the sharded GEMMs.  All arithmetic is
+ * fp32, I/O in the tensor dtype; reductions across a wavefront use 64-lane shuffles.
+ */
+#include <hip/hip_runtime.h>
+
+#include <stdint.h>
+
+#include "hap_internal.h"
+
+namespace {
+
+constexpr float kLnEps = 1e-5f;
+
+template <typename T> __device__ __forceinline__ float ld(const T* p);
+template <> __device__ __forceinline__ float ld<float>(const float* p) { return *p; }
+template <> __device__ __forceinline__ float ld<__bf16>(const __bf16* p) { return (float)*p; }
+template <typename T> __device__ __forceinline__ void st(T* p, float v);
+template <> __device__ __forceinline__ void st<float>(float* p, float v) { *p = v; }
+template <> __device__ __forceinline__ void st<__bf16>(__bf16* p, float v) { *p = (__bf16)v; }
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
+
+__device__ __forceinline__ float gelu_grad(float x) {
+  const float cdf = 0.5f * (1.0f + erff(x * 0.70710678118654752f));
+  const float pdf = 0.3989422804014327f * __expf(-0.5f * x * x);
+  return cdf + x * pdf;
+}
+
+/* Vector of V elements of T moved as one access when V > 1. */
+template <typename T, int V> struct Pack { T v[V]; } __attribute__((aligned(sizeof(T) * V)));
+
+/* out[r,c] = dy[r,c] * gelu'(pre[r,c]); V elements per thread along the row (V = 1 handles any alignment). */
+template <typename T, int V>
+__global__ __launch_bounds__(256) void gelu_bwd_kernel(int64_t rows, int64_t cols, const T* pre, int64_t ldp,
+                                                       const T* dy, int64_t lddy, T* out, int64_t ldo) {
+  const int64_t cv = (cols + V - 1) / V;
+  const int64_t total = rows * cv;
+  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (int64_t)gridDim.x * 256) {
+    const int64_t r = i / cv, c = (i % cv) * V;
+    Pack<T, V> p = *reinterpret_cast<const Pack<T, V>*>(pre + r * ldp + c);
+    Pack<T, V> g = *reinterpret_cast<const Pack<T, V>*>(dy + r * lddy + c);
+    Pack<T, V> o;
+#pragma unroll
+    for (int e = 0; e < V; ++e) o.v[e] = (T)((float)g.v[e] * gelu_grad((float)p.v[e]));
+    *reinterpret_cast<Pack<T, V>*>(out + r * ldo + c) = o;
+  }
+}
+
+template <typename T, int V>
+__global__ __launch_bounds__(256) void add_kernel(int64_t rows, int64_t cols, const T* a, int64_t lda, const T* b,
+                                                  int64_t ldb, const T* bias, T* out, int64_t ldo) {
+  const int64_t cv = (cols + V - 1) / V;
+  const int64_t total = rows * cv;
+  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (int64_t)gridDim.x * 256) {
+    const int64_t r = i / cv, c = (i % cv) * V;
+    Pack<T, V> x = *reinterpret_cast<const Pack<T, V>*>(a + r * lda + c);
+    Pack<T, V> y = *reinterpret_cast<const Pack<T, V>*>(b + r * ldb + c);
+    Pack<T, V> o;
+#pragma unroll
+    for (int e = 0; e < V; ++e) {
+      float v = (float)x.v[e] + (float)y.v[e];
+      if (bias) v += (float)bias[c + e];
+      o.v[e] = (T)v;
+    }
+    *reinterpret_cast<Pack<T, V>*>(out + r * ldo + c) = o;
+  }
+}
+
+/* Column sums, stage 1: block (bx, by) sums rows [by*rpb, (by+1)*rpb) of 64 columns starting at
+ * bx*64.  Lane l of a wave reads column l&63... each of the 4 waves strides over rows; the four
+ * waves' partials meet in LDS.  partial[by][col] is fp32. */
+template <typename T>
+__global__ __launch_bounds__(256) void colsum_partial_kernel(int64_t rows, int64_t cols, const T* a, int64_t lda,
+                                                             int64_t rpb, float* partial) {
+  __shared__ float red[4][64];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int64_t c = (int64_t)blockIdx.x * 64 + lane;
+  const int64_t r0 = (int64_t)blockIdx.y * rpb;
+  const int64_t r1 = r0 + rpb < rows ? r0 + rpb : rows;
+  float s = 0.0f;
+  if (c < cols)
+    for (int64_t r = r0 + wave; r < r1; r += 4) s += ld<T>(a + r * lda + c);
+  red[wave][lane] = s;
+  __syncthreads();
+  if (wave == 0 && c < cols) partial[(int64_t)blockIdx.y * cols + c] = red[0][lane] + red[1][lane] + red[2][lane] + red[3][lane];
+}
+
+/* Stage 2: out[c] = sum over nparts of partial[p][c]; one wave per 64 columns is plenty. */
+__global__ __launch_bounds__(256) void colsum_final_kernel(int64_t cols, int nparts, const float* partial, float* out) {
+  const int64_t c = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (c >= cols) return;
+  float s = 0.0f;
+  for (int p = 0; p < nparts; ++p) s += partial[(int64_t)p * cols + c];
+  out[c] = s;
+}
+
+/* LayerNorm forward: one wavefront per row, row kept in registers (n <= 64 * 8 * MAXV). */
+template <typename T, int PER>   // PER = elements per lane, row length n <= 64*PER, n % 1 == 0
+__global__ __launch_bounds__(256) void layernorm_fwd_kernel(int64_t rows, int n, const T* x, const T* gamma, const T* beta,
+                                                            T* y, float* mean, float* rstd) {
+  const int lane = threadIdx.x & 63;
+  const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (row >= rows) return;
+  const T* xr = x + row * n;
+  float v[PER];
+  float s = 0.0f;
+#pragma unroll
+  for (int i = 0; i < PER; ++i) {
+    const int c = i * 64 + lane;
+    v[i] = c < n ? ld<T>(xr + c) : 0.0f;
+    s += v[i];
+  }
+  const float mu = wave_sum(s) / (float)n;
+  float q = 0.0f;
+#pragma unroll
+  for (int i = 0; i < PER; ++i) {
+    const int c = i * 64 + lane;
+    const float d = c < n ? v[i] - mu : 0.0f;
+    q += d * d;
+  }
+  const float rs = rsqrtf(wave_sum(q) / (float)n + kLnEps);
+  T* yr = y + row * n;
+#pragma unroll
+  for (int i = 0; i < PER; ++i) {
+    const int c = i * 64 + lane;
+    if (c < n) st<T>(yr + c, (v[i] - mu) * rs * ld<T>(gamma + c) + ld<T>(beta + c));
+  }
+  if (lane == 0) { mean[row] = mu; rstd[row] = rs; }
+}
+
+/* LayerNorm backward.  Block = 4 waves, each wave walks rows (stride = 4*gridDim.x); per row it forms
+ * dx, and accumulates this block's share of dgamma / dbeta in registers; block partials go to
+ * ws[block][2][n] and a second kernel (colsum_final) folds them. */
+template <typename T, int PER>
+__global__ __launch_bounds__(256) void layernorm_bwd_kernel(int64_t rows, int n, const T* x, const T* gamma, const float* mean,
+                                                            const float* rstd, const T* dy, T* dx, float* part) {
+  __shared__ float red[2][4][64 * PER];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  float dg[PER], db[PER], gm[PER];
+#pragma unroll
+  for (int i = 0; i < PER; ++i) {
+    dg[i] = db[i] = 0.0f;
+    const int c = i * 64 + lane;
+    gm[i] = c < n ? ld<T>(gamma + c) : 0.0f;
+  }
+  for (int64_t row = (int64_t)blockIdx.x * 4 + wave; row < rows; row += (int64_t)gridDim.x * 4) {
+    const float mu = mean[row], rs = rstd[row];
+    float xh[PER], g[PER];
+    float s1 = 0.0f, s2 = 0.0f;
+#pragma unroll
+    for (int i = 0; i < PER; ++i) {
+      const int c = i * 64 + lane;
+      const bool ok = c < n;
+      const float xv = ok ? ld<T>(x + row * n + c) : 0.0f;
+      const float dv = ok ? ld<T>(dy + row * n + c) : 0.0f;
+      xh[i] = ok ? (xv - mu) * rs : 0.0f;
+      g[i] = dv * gm[i];
+      s1 += g[i];
+      s2 += g[i] * xh[i];
+      dg[i] += dv * xh[i];
+      db[i] += dv;
+    }
+    s1 = wave_sum(s1) / (float)n;
+    s2 = wave_sum(s2) / (float)n;
+#pragma unroll
+    for (int i = 0; i < PER; ++i) {
+      const int c = i * 64 + lane;
+      if (c < n) st<T>(dx + row * n + c, rs * (g[i] - s1 - xh[i] * s2));
+    }
+  }
+#pragma unroll
+  for (int i = 0; i < PER; ++i) { red[0][wave][i * 64 + lane] = dg[i]; red[1][wave][i * 64 + lane] = db[i]; }
+  __syncthreads();
+  for (int c = threadIdx.x; c < n; c += 256) {
+    part[((int64_t)blockIdx.x * 2 + 0) * n + c] = red[0][0][c] + red[0][1][c] + red[0][2][c] + red[0][3][c];
+    part[((int64_t)blockIdx.x * 2 + 1) * n + c] = red[1][0][c] + red[1][1][c] + red[1][2][c] + red[1][3][c];
+  }
+}
+
+/* Folds layernorm_bwd partials: part[block][2][n] -> dgamma[n], dbeta[n]. */
+__global__ __launch_bounds__(256) void layernorm_bwd_final_kernel(int n, int nblocks, const float* part, float* dgamma, float* dbeta) {
+  const int c = blockIdx.x * 256 + threadIdx.x;
+  if (c >= n) return;
+  float a = 0.0f, b = 0.0f;
+  for (int p = 0; p < nblocks; ++p) { a += part[((int64_t)p * 2 + 0) * n + c]; b += part[((int64_t)p * 2 + 1) * n + c]; }
+  dgamma[c] = a;
+  dbeta[c] = b;
+}
+
+inline int check_launch(const char* what) {
+  const hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return hap_fail(HAP_EDEVICE, "%s launch: %s", what, hipGetErrorString(e));
+  return HAP_OK;
+}
+
+inline bool aligned16(const void* p) { return ((uintptr_t)p % 16) == 0; }
+
+inline int grid_for(int64_t work_items) {
+  int64_t g = (work_items + 255) / 256;
+  if (g > 256 * 32) g = 256 * 32;   // grid-stride beyond 32 blocks per CU
+  return g < 1 ? 1 : (int)g;
+}
+
+constexpr int kLnBlocks = 1024;   // layernorm backward: blocks (= partial rows of dgamma/dbeta)
+constexpr int kColsumRowsPerBlock = 512;
+
+template <typename T>
+int gelu_bwd_t(int64_t rows, int64_t cols, const void* pre, int64_t ldp, const void* dy, int64_t lddy, void* out, int64_t ldo, hipStream_t s) {
+  constexpr int V = 16 / sizeof(T);
+  const bool vec = cols % V == 0 && ldp % V == 0 && lddy % V == 0 && ldo % V == 0 && aligned16(pre) && aligned16(dy) && aligned16(out);
+  if (vec) hipLaunchKernelGGL((gelu_bwd_kernel<T, V>), dim3(grid_for(rows * (cols / V))), dim3(256), 0, s, rows, cols, (const T*)pre, ldp, (const T*)dy, lddy, (T*)out, ldo);
+  else hipLaunchKernelGGL((gelu_bwd_kernel<T, 1>), dim3(grid_for(rows * cols)), dim3(256), 0, s, rows, cols, (const T*)pre, ldp, (const T*)dy, lddy, (T*)out, ldo);
+  return check_launch("gelu_bwd");
+}
+
+template <typename T>
+int add_t(int64_t rows, int64_t cols, const void* a, int64_t lda, const void* b, int64_t ldb, const void* bias, void* out, int64_t ldo, hipStream_t s) {
+  constexpr int V = 16 / sizeof(T);
+  const bool vec = cols % V == 0 && lda % V == 0 && ldb % V == 0 && ldo % V == 0 && aligned16(a) && aligned16(b) && aligned16(out);
+  if (vec) hipLaunchKernelGGL((add_kernel<T, V>), dim3(grid_for(rows * (cols / V))), dim3(256), 0, s, rows, cols, (const T*)a, lda, (const T*)b, ldb, (const T*)bias, (T*)out, ldo);
+  else hipLaunchKernelGGL((add_kernel<T, 1>), dim3(grid_for(rows * cols)), dim3(256), 0, s, rows, cols, (const T*)a, lda, (const T*)b, ldb, (const T*)bias, (T*)out, ldo);
+  return check_launch("add");
+}
+
+template <typename T>
+int layernorm_fwd_t(int64_t rows, int n, const void* x, const void* g, const void* b, void* y, float* mean, float* rstd, hipStream_t s) {
+  const dim3 grid((unsigned)((rows + 3) / 4));
+#define LN_FWD(PER) hipLaunchKernelGGL((layernorm_fwd_kernel<T, PER>), grid, dim3(256), 0, s, rows, n, (const T*)x, (const T*)g, (const T*)b, (T*)y, mean, rstd)
+  if (n <= 64 * 4) LN_FWD(4); else if (n <= 64 * 16) LN_FWD(16); else if (n <= 64 * 32) LN_FWD(32); else LN_FWD(64);
+#undef LN_FWD
+  return check_launch("layernorm_fwd");
+}
+
+template <typename T>
+int layernorm_bwd_t(int64_t rows, int n, const void* x, const void* g, const float* mean, const float* rstd, const void* dy,
+                    void* dx, float* dgamma, float* dbeta, float* part, hipStream_t s) {
+  const int nblocks = (int)((rows + 3) / 4 < kLnBlocks ? (rows + 3) / 4 : kLnBlocks);
+#define LN_BWD(PER) hipLaunchKernelGGL((layernorm_bwd_kernel<T, PER>), dim3(nblocks), dim3(256), 0, s, rows, n, (const T*)x, (const T*)g, mean, rstd, (const T*)dy, (T*)dx, part)
+  if (n <= 64 * 4) LN_BWD(4); else if (n <= 64 * 16) LN_BWD(16); else LN_BWD(32);
+#undef LN_BWD
+  int rc = check_launch("layernorm_bwd");
+  if (rc) return rc;
+  hipLaunchKernelGGL(layernorm_bwd_final_kernel, dim3((n + 255) / 256), dim3(256), 0, s, n, nblocks, part, dgamma, dbeta);
+  return check_launch("layernorm_bwd_final");
+}
+
+}  // namespace
+
+extern "C" {
+
+int hap_gelu_bwd(int64_t rows, int64_t cols, int io_dtype, const void* preact, int64_t ldp, const void* dy,
+                 int64_t lddy, void* out, int64_t ldo, void* stream) {
+  hap_clear_error();
+  if (rows < 0 || cols < 0) return hap_fail(HAP_EINVAL, "negative size");
+  if (rows == 0 || cols == 0) return HAP_OK;
+  if (!preact || !dy || !out) return hap_fail(HAP_EINVAL, "NULL pointer");
+  if (ldp < cols || lddy < cols || ldo < cols) return hap_fail(HAP_ESHAPE, "leading dimension below cols");
+  hipStream_t s = (hipStream_t)stream;
+  if (io_dtype == HAP_BF16) return gelu_bwd_t<__bf16>(rows, cols, preact, ldp, dy, lddy, out, ldo, s);
+  if (io_dtype == HAP_F32) return gelu_bwd_t<float>(rows, cols, preact, ldp, dy, lddy, out, ldo, s);
+  return hap_fail(HAP_EINVAL, "bad dtype %d", io_dtype);
+}
+
+int hap_add(int64_t rows, int64_t cols, int io_dtype, const void* a, int64_t lda, const void* b, int64_t ldb,
+            const void* bias, void* out, int64_t ldo, void* stream) {
+  hap_clear_error();
+  if (rows < 0 || cols < 0) return hap_fail(HAP_EINVAL, "negative size");
+  if (rows == 0 || cols == 0) return HAP_OK;
+  if (!a || !b || !out) return hap_fail(HAP_EINVAL, "NULL pointer");
+  if (lda < cols || ldb < cols || ldo < cols) return hap_fail(HAP_ESHAPE, "leading dimension below cols");
+  hipStream_t s = (hipStream_t)stream;
+  if (io_dtype == HAP_BF16) return add_t<__bf16>(rows, cols, a, lda, b, ldb, bias, out, ldo, s);
+  if (io_dtype == HAP_F32) return add_t<float>(rows, cols, a, lda, b, ldb, bias, out, ldo, s);
+  return hap_fail(HAP_EINVAL, "bad dtype %d", io_dtype);
+}
+
+size_t hap_colsum_workspace(int64_t rows, int64_t cols) {
+  if (rows <= 0 || cols <= 0) return 0;
+  const int64_t parts = (rows + kColsumRowsPerBlock - 1) / kColsumRowsPerBlock;
+  return (size_t)(parts * cols) * sizeof(float);
+}
+
+int hap_colsum(int64_t rows, int64_t cols, int io_dtype, const void* a, int64_t lda, float* out,
+               void* ws, size_t ws_bytes, void* stream) {
+  hap_clear_error();
+  if (rows < 0 || cols < 0) return hap_fail(HAP_EINVAL, "negative size");
+  if (cols == 0) return HAP_OK;
+  if (!out) return hap_fail(HAP_EINVAL, "NULL output");
+  hipStream_t s = (hipStream_t)stream;
+  if (rows == 0) {   // empty sum
+    hipLaunchKernelGGL(colsum_final_kernel, dim3((unsigned)((cols + 255) / 256)), dim3(256), 0, s, cols, 0, (const float*)out, out);
+    return check_launch("colsum");
+  }
+  if (!a) return hap_fail(HAP_EINVAL, "NULL input");
+  if (lda < cols) return hap_fail(HAP_ESHAPE, "leading dimension below cols");
+  if (io_dtype != HAP_BF16 && io_dtype != HAP_F32) return hap_fail(HAP_EINVAL, "bad dtype %d", io_dtype);
+  const size_t need = hap_colsum_workspace(rows, cols);
+  if (!ws || ws_bytes < need) return hap_fail(HAP_EWORKSPACE, "colsum needs %zu workspace bytes", need);
+  const int64_t parts = (rows + kColsumRowsPerBlock - 1) / kColsumRowsPerBlock;
+  if (parts > 65535) return hap_fail(HAP_EUNSUPPORTED, "colsum over more than 65535*512 rows");
+  const dim3 grid((unsigned)((cols + 63) / 64), (unsigned)parts);
+  if (io_dtype == HAP_BF16) hipLaunchKernelGGL((colsum_partial_kernel<__bf16>), grid, dim3(256), 0, s, rows, cols, (const __bf16*)a, lda, (int64_t)kColsumRowsPerBlock, (float*)ws);
+  else hipLaunchKernelGGL((colsum_partial_kernel<float>), grid, dim3(256), 0, s, rows, cols, (const float*)a, lda, (int64_t)kColsumRowsPerBlock, (float*)ws);
+  int rc = check_launch("colsum_partial");
+  if (rc) return rc;
+  hipLaunchKernelGGL(colsum_final_kernel, dim3((unsigned)((cols + 255) / 256)), dim3(256), 0, s, cols, (int)parts, (const float*)ws, out);
+  return check_launch("colsum_final");
+}
+
+int hap_layernorm_fwd(int64_t rows, int64_t n, int io_dtype, const void* x, const void* gamma, const void* beta,
+                      void* y, float* mean, float* rstd, void* stream) {
+  hap_clear_error();
+  if (rows < 0 || n < 1) return hap_fail(HAP_EINVAL, "bad size");
+  if (rows == 0) return HAP_OK;
+  if (!x || !gamma || !beta || !y || !mean || !rstd) return hap_fail(HAP_EINVAL, "NULL pointer");
+  if (n > 64 * 64) return hap_fail(HAP_EUNSUPPORTED, "layernorm row longer than 4096");
+  hipStream_t s = (hipStream_t)stream;
+  if (io_dtype == HAP_BF16) return layernorm_fwd_t<__bf16>(rows, (int)n, x, gamma, beta, y, mean, rstd, s);
+  if (io_dtype == HAP_F32) return layernorm_fwd_t<float>(rows, (int)n, x, gamma, beta, y, mean, rstd, s);
+  return hap_fail(HAP_EINVAL, "bad dtype %d", io_dtype);
+}
+
+size_t hap_layernorm_bwd_workspace(int64_t rows, int64_t n) {
+  if (rows <= 0 || n <= 0) return 0;
+  const int64_t nblocks = (rows + 3) / 4 < kLnBlocks ? (rows + 3) / 4 : kLnBlocks;
+  return (size_t)(nblocks * 2 * n) * sizeof(float);
+}
+
+int hap_layernorm_bwd(int64_t rows, int64_t n, int io_dtype, const void* x, const void* gamma, const float* mean,
+                      const float* rstd, const void* dy, void* dx, float* dgamma, float* dbeta,
+                      void* ws, size_t ws_bytes, void* stream) {
+  hap_clear_error();
+  if (rows < 0 || n < 1) return hap_fail(HAP_EINVAL, "bad size");
+  if (rows == 0) return HAP_OK;
+  if (!x || !gamma || !mean || !rstd || !dy || !dx || !dgamma || !dbeta) return hap_fail(HAP_EINVAL, "NULL pointer");
+  if (n > 64 * 32) return hap_fail(HAP_EUNSUPPORTED, "layernorm backward row longer than 2048");
+  const size_t need = hap_layernorm_bwd_workspace(rows, n);
+  if (!ws || ws_bytes < need) return hap_fail(HAP_EWORKSPACE, "layernorm_bwd needs %zu workspace bytes", need);
+  hipStream_t s = (hipStream_t)stream;
+  if (io_dtype == HAP_BF16) return layernorm_bwd_t<__bf16>(rows, (int)n, x, gamma, mean, rstd, dy, dx, dgamma, dbeta, (float*)ws, s);
+  if (io_dtype == HAP_F32) return layernorm_bwd_t<float>(rows, (int)n, x, gamma, mean, rstd, dy, dx, dgamma, dbeta, (float*)ws, s);
+  return hap_fail(HAP_EINVAL, "bad dtype %d", io_dtype);
+}
+
+}  // extern "C"

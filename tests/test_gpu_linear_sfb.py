@@ -1,0 +1,227 @@
+"""GPU parity: sharded linear fwd / bwd and SFB rebuild against the CPU oracle, through the C ABI.
+
+Tolerances (max|err| / max|ref| per output tensor): 1e-5 for fp32, 2e-2 for bf16 inputs with fp32
+accumulation; shard index ranges are compared bit-exactly.
+"""
+import numpy as np
+import pytest
+
+import hapgen
+from hapgen import TensorId as T
+from oracle import linear as olin, sfb as osfb, lp as olp, rounding as ornd
+
+pytestmark = pytest.mark.gpu
+
+from gpu_util import gen, empty, host, check, relerr, torch_mod  # noqa: E402
+
+
+@pytest.fixture(scope="module")
+def hap():
+    import paper_2401_05965_amd as h
+    return h
+
+
+DT = {"bf16": 1, "f32": 0}
+
+
+def run_linear_case(hap, dtype, tokens, in_f, out_f, mode, offsets, act, bias, full, dw_dtype=None, pad=0, seed=7):
+    """Runs every shard of one layer on the GPU and checks each against the oracle.  Returns max error."""
+    torch = torch_mod()
+    dw_dtype = dw_dtype or dtype
+    if mode == olin.REDUCTION:
+        bias = False          # bias is applied once, after the all-reduce of the partials
+    Xh, Xd = gen(seed, T.X, (tokens, in_f), 1.0, dtype)
+    Wh, Wd = gen(seed, T.W, (in_f, out_f), 0.05, dtype)
+    bh, bd = gen(seed, T.BIAS, (out_f,), 0.5, dtype) if bias else (None, None)
+    dYh, dYd = gen(seed, T.DY, (tokens, out_f), 1.0, dtype)
+    m = len(offsets) - 1
+    worst = 0.0
+    Yfull, prefull = olin.linear_fwd(Xh, Wh, bh, act)
+    dXsum = np.zeros_like(Xh); dWsum = np.zeros_like(Wh); dbsum = np.zeros(out_f)
+    Psum = np.zeros_like(Yfull)
+    for j in range(m):
+        lo, hi = offsets[j], offsets[j + 1]
+        n = hi - lo
+        Yo, preo = olin.sharded_linear_fwd(mode, offsets, j, Xh, Wh, bh, act)
+        # the oracle's backward takes the full-precision pre-activation; the device uses what it saved
+        dXo, dWo, dbo = olin.sharded_linear_bwd(mode, offsets, j, Xh, Wh, prefull if mode != olin.REDUCTION else None, dYh, act)
+        if full:
+            ldx, ldw, ldy = in_f, out_f, out_f
+            Xj, Wj, bj, dYj = Xd, Wd, bd, dYd
+            Yj = empty((tokens, out_f), dtype, 0); Pj = empty((tokens, out_f), dtype, 0) if act else None
+            dXj = empty((tokens, in_f), dtype, 0); dWj = empty((in_f, out_f), dw_dtype, 0); dbj = empty((out_f,), "f32", 0)
+        else:
+            # compact slices with padded leading dimensions (pad extra columns filled with NaN poison)
+            def compact(t, rows, cols, fill=float("nan")):
+                buf = empty((t.shape[0] if rows is None else rows.stop - rows.start, (cols.stop - cols.start if cols else t.shape[1]) + pad), dtype, fill)
+                src = t[rows if rows is not None else slice(None), cols if cols is not None else slice(None)]
+                buf[:, :src.shape[1]] = src
+                return buf
+            r = slice(lo, hi)
+            if mode == olin.BATCH:
+                Xj, Wj, bj, dYj = compact(Xd, r, None), compact(Wd, None, None), bd, compact(dYd, r, None)
+                shapeY, shapeX, shapeW = (n, out_f), (n, in_f), (in_f, out_f)
+            elif mode == olin.FEATURE:
+                Xj, Wj, dYj = compact(Xd, None, None), compact(Wd, None, r), compact(dYd, None, r)
+                bj = bd[lo:hi].clone() if bias else None
+                shapeY, shapeX, shapeW = (tokens, n), (tokens, in_f), (in_f, n)
+            elif mode == olin.REDUCTION:
+                Xj, Wj, bj, dYj = compact(Xd, None, r), compact(Wd, r, None), None, compact(dYd, None, None)
+                shapeY, shapeX, shapeW = (tokens, out_f), (tokens, n), (n, out_f)
+            else:
+                Xj, Wj, bj, dYj = compact(Xd, None, None), compact(Wd, None, None), bd, compact(dYd, None, None)
+                shapeY, shapeX, shapeW = (tokens, out_f), (tokens, in_f), (in_f, out_f)
+            ldx, ldw, ldy = shapeX[1] + pad, shapeW[1] + pad, shapeY[1] + pad
+            Yj = empty((shapeY[0], ldy), dtype, 0); Pj = empty((shapeY[0], ldy), dtype, 0) if act else None
+            dXj = empty((shapeX[0], ldx), dtype, 0); dWj = empty((shapeW[0], ldw), dw_dtype, 0)
+            dbj = empty((shapeY[1],), "f32", 0)
+        desc = hap.LinearDesc(tokens, in_f, out_f, mode, offsets, DT[dtype], act=int(act), has_bias=bias and mode != olin.REDUCTION,
+                              ldx=ldx, ldw=ldw, ldy=ldy, operands_are_full=full)
+        ws = empty((max(hap.hap_linear_bwd_workspace(desc, j), 16),), "u8")
+        hap.hap_sharded_linear_fwd(desc, j, Xj, Wj, bj if mode != olin.REDUCTION else None, Yj, Pj, None)
+        want_db = mode != olin.REDUCTION
+        hap.hap_sharded_linear_bwd(desc, j, Xj, Wj, Pj, dYj, dXj, dWj, DT[dw_dtype], dbj if want_db else None, ws)
+        Yg, dXg, dWg, dbg = host(Yj), host(dXj), host(dWj), host(dbj)
+        # carve the device's slice out of what came back
+        if full:
+            if mode == olin.BATCH:
+                Ys, dXs, dWs, dbs = Yg[lo:hi], dXg[lo:hi], dWg, dbg
+                assert not Yg[:lo].any() and not Yg[hi:].any(), "rows outside the shard were written"
+            elif mode == olin.FEATURE:
+                Ys, dXs, dWs, dbs = Yg[:, lo:hi], dXg, dWg[:, lo:hi], dbg[lo:hi]
+                assert not Yg[:, :lo].any() and not Yg[:, hi:].any(), "columns outside the shard were written"
+                assert not dWg[:, :lo].any() and not dWg[:, hi:].any()
+            elif mode == olin.REDUCTION:
+                Ys, dXs, dWs, dbs = Yg, dXg[:, lo:hi], dWg[lo:hi], None
+                assert not dXg[:, :lo].any() and not dXg[:, hi:].any()
+                assert not dWg[:lo].any() and not dWg[hi:].any()
+            else:
+                Ys, dXs, dWs, dbs = Yg, dXg, dWg, dbg
+        else:
+            Ys, dXs, dWs = Yg[:, :shapeY[1]], dXg[:, :shapeX[1]], dWg[:, :shapeW[1]]
+            dbs = dbg if want_db else None
+        if n == 0 and mode in (olin.BATCH, olin.FEATURE):
+            assert Ys.size == 0 or mode == olin.FEATURE
+        tag = f"{dtype} mode{mode} shard{j} full{int(full)}"
+        worst = max(worst, check(tag + " Y", Ys, Yo, dtype), check(tag + " dX", dXs, dXo, dtype), check(tag + " dW", dWs, dWo, dw_dtype if dw_dtype == "bf16" else dtype))
+        if want_db:
+            worst = max(worst, check(tag + " db", dbs, dbo, dtype))
+        if mode == olin.REDUCTION:
+            Psum += Ys
+        if mode == olin.FEATURE:
+            dXsum += dXs
+        if mode == olin.BATCH:
+            dWsum += dWs; dbsum += dbs
+    # the rules of Fig. "semantics": partials sum to the unsharded result
+    _, dWfull, dbfull = olin.linear_bwd(Xh, Wh, prefull, dYh, act)
+    dXfull = olin.linear_bwd(Xh, Wh, prefull, dYh, act)[0]
+    big = 4e-2 if dtype == "bf16" else 1e-5
+    if mode == olin.REDUCTION:
+        assert relerr(Psum, Yfull) <= big
+    if mode == olin.FEATURE:
+        assert relerr(dXsum, dXfull) <= big
+    if mode == olin.BATCH:
+        assert relerr(dWsum, dWfull) <= big and relerr(dbsum, dbfull) <= big
+    return worst
+
+
+def test_cfg1_fc_fp32_two_devices(hap):
+    """Single fully-connected layer, fp32, batch rows split by the LP ratios of speeds (1, 0.67)."""
+    w = hapgen.WORKLOADS["cfg1_fc_f32"]
+    d = w.dims
+    ratios, _ = hap.hap_shard_ratios(w.speeds, [(1.0, 0, 0, 0)])
+    oratios, _ = olp.shard_ratios(w.speeds, [(1.0, 0, 0, 0)])
+    assert np.allclose(ratios, oratios, atol=1e-12)
+    sizes, offs = hap.hap_round_shards(ratios, d["tokens"])
+    osizes, ooffs = ornd.round_shards(oratios, d["tokens"])
+    assert sizes == osizes == [38, 26] and offs == ooffs
+    # the workload's own scales: X ~ N(0,1), W ~ N(0,0.02), dY ~ N(0,1); seed 0
+    torch = torch_mod()
+    Xh, Xd = gen(0, T.X, (64, 1024), 1.0, "f32"); Wh, Wd = gen(0, T.W, (1024, 1024), 0.02, "f32"); dYh, dYd = gen(0, T.DY, (64, 1024), 1.0, "f32")
+    desc = hap.LinearDesc(64, 1024, 1024, hap.SHARD_BATCH, offs, hap.F32)
+    Y = empty((64, 1024), "f32", 0); dX = empty((64, 1024), "f32", 0)
+    Xs, dYs = [], []
+    for j in range(2):
+        dW = empty((1024, 1024), "f32", 0)
+        hap.hap_sharded_linear_fwd(desc, j, Xd, Wd, None, Y, None)
+        hap.hap_sharded_linear_bwd(desc, j, Xd, Wd, None, dYd, dX, dW, hap.F32, None)
+        _, dWo, _ = olin.sharded_linear_bwd(olin.BATCH, offs, j, Xh, Wh, None, dYh)
+        check(f"cfg1 dW_{j}", host(dW), dWo, "f32")
+        Xs.append(Xd[offs[j]:offs[j + 1]]); dYs.append(dYd[offs[j]:offs[j + 1]])
+    Yo, _ = olin.linear_fwd(Xh, Wh); dXo, dWo, _ = olin.linear_bwd(Xh, Wh, None, dYh)
+    check("cfg1 Y", host(Y), Yo, "f32"); check("cfg1 dX", host(dX), dXo, "f32")
+    # SFB rebuild from the two devices' gathered factors equals the all-reduced gradient
+    dW = empty((1024, 1024), "f32", float("nan"))
+    hap.hap_sfb_grad(Xs, dYs, sizes, 1024, 1024, 1024, 1024, hap.F32, dW, 1024)
+    check("cfg1 SFB dW", host(dW), osfb.sfb_grad([Xh[:38], Xh[38:]], [dYh[:38], dYh[38:]], sizes), "f32")
+    check("cfg1 SFB dW vs unsharded", host(dW), dWo, "f32")
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("mode", [0, 1, 2, 3])
+@pytest.mark.parametrize("full", [True, False])
+def test_linear_modes_ragged(hap, dtype, mode, full):
+    tokens, in_f, out_f = 300, 264, 520
+    dim = {0: tokens, 1: out_f, 2: in_f, 3: 1}[mode]
+    offsets = {0: [0, 131, 131, 257, 300], 1: [0, 137, 137, 391, 520], 2: [0, 99, 99, 200, 264], 3: [0, 1]}[mode]
+    assert offsets[-1] == dim
+    act = mode in (0, 1, 3)
+    run_linear_case(hap, dtype, tokens, in_f, out_f, mode, offsets, act=act, bias=True, full=full)
+
+
+def test_linear_unaligned_leading_dimensions_take_the_scalar_kernel(hap):
+    # compact slices whose leading dimension is not a multiple of 16 bytes
+    run_linear_case(hap, "bf16", 70, 50, 90, 1, [0, 37, 90], act=True, bias=True, full=False, pad=3)
+    run_linear_case(hap, "f32", 70, 50, 90, 2, [0, 21, 50], act=False, bias=False, full=False, pad=1)
+
+
+def test_linear_bf16_fp32_weight_gradient(hap):
+    run_linear_case(hap, "bf16", 515, 256, 384, 1, [0, 129, 384], act=True, bias=True, full=True, dw_dtype="f32")
+
+
+def test_index_ranges_bit_exact_through_identity(hap):
+    """An iota tensor pushed through an identity weight: each shard must reproduce exactly its own rows / columns."""
+    torch = torch_mod()
+    n = 160
+    ratios, _ = hap.hap_shard_ratios([1.0, 0.6, 0.35], [(1.0, 0, 0, 0)])
+    sizes, offs = hap.hap_round_shards(ratios, n)
+    assert (sizes, offs) == ornd.round_shards(olp.shard_ratios([1.0, 0.6, 0.35], [(1.0, 0, 0, 0)])[0], n)
+    iota = torch.arange(n * n, dtype=torch.float32, device="cuda").reshape(n, n) % 251   # exact in bf16
+    eye = torch.eye(n, dtype=torch.float32, device="cuda")
+    for dtype, td in (("f32", torch.float32), ("bf16", torch.bfloat16)):
+        X, W = iota.to(td), eye.to(td)
+        for mode in (0, 1):
+            desc = hap.LinearDesc(n, n, n, mode, offs, DT[dtype])
+            for j in range(3):
+                Y = empty((n, n), dtype, -1)
+                hap.hap_sharded_linear_fwd(desc, j, X, W, None, Y, None)
+                got = host(Y); ref = host(X)
+                mask = np.zeros((n, n), bool)
+                if mode == 0:
+                    mask[offs[j]:offs[j + 1], :] = True
+                else:
+                    mask[:, offs[j]:offs[j + 1]] = True
+                assert np.array_equal(got[mask], ref[mask]) and (got[~mask] == -1).all()
+
+
+def test_sfb_ragged_segments_padding_never_read(hap):
+    rows = [70, 0, 33, 128, 1]
+    cap, in_f, out_f = 128, 200, 328
+    Xh, Xd, dYh, dYd = [], [], [], []
+    for i in range(len(rows)):
+        a, b = gen(1, T.SFB_X + i, (cap, in_f), 1.0, "bf16"); Xh.append(a); Xd.append(b)
+        a, b = gen(1, T.SFB_DY + i, (cap, out_f), 1.0, "bf16"); dYh.append(a); dYd.append(b)
+        Xd[i][rows[i]:] = float("nan"); dYd[i][rows[i]:] = float("nan")     # poison the padded All-Gather rows
+    ref = osfb.sfb_grad(Xh, dYh, rows)
+    dW = empty((in_f, out_f), "f32", float("nan"))
+    hap.hap_sfb_grad(Xd, dYd, rows, in_f, out_f, in_f, out_f, hap.BF16, dW, out_f)
+    check("sfb", host(dW), ref, "bf16")
+    hap.hap_sfb_grad(Xd, dYd, rows, in_f, out_f, in_f, out_f, hap.BF16, dW, out_f, accumulate=True)
+    check("sfb accumulate", host(dW), 2 * ref, "bf16")
+    # grouped-Broadcast layout: compact factors (cap_i == rows_i), one device only -> plain X^T dY
+    dW1 = empty((in_f, out_f), "f32", 0)
+    hap.hap_sfb_grad([Xd[3]], [dYd[3]], [128], in_f, out_f, in_f, out_f, hap.BF16, dW1, out_f)
+    check("sfb m=1", host(dW1), Xh[3].T @ dYh[3], "bf16")
+    # all devices empty -> zeros
+    hap.hap_sfb_grad(Xd, dYd, [0] * 5, in_f, out_f, in_f, out_f, hap.BF16, dW1, out_f)
+    assert not host(dW1).any()
