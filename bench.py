@@ -1,0 +1,157 @@
+#!/usr/bin/env python3
+"""Benchmark of the HAP per-device hot path on one MI355X.
+
+One step = one pass of the path over one batch of synthetic input:
+  host   LP sharding ratios + integer rounding for the workload's device speeds,
+  device fwd + bwd of the largest and the smallest shard of the GPT-style MLP block
+         (hidden 4096, ffn 16384 sharded over 3 virtual devices with speeds 1 / 0.6 / 0.35, 8192 tokens, bf16),
+         and the sufficient-factor rebuild of dW1[4096 x 16384] from 8 devices' gathered factors
+         (token counts 512,512,384,384,256,256,128,128).
+Value = algorithmic TFLOP/s of the whole step (2*M*N*K per GEMM over valid rows / columns only).
+Prints ONE JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA peak
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (each virtual device's shard runs in turn on it); "
+              "--gpus N with N > 1 is not supported", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    import hapgen
+    from hapgen import TensorId as T
+    import paper_2401_05965_amd as hap
+    from paper_2401_05965_amd.programs import MlpShard, SfbRebuild
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(3)
+    dev = torch.device("cuda:0")
+
+    def dev_bf16(seed, tid, shape, sigma):
+        _, bits = hapgen.normal_bf16(seed, tid, shape, sigma)
+        return torch.from_numpy(bits.view(np.int16)).view(torch.bfloat16).to(dev)
+
+    w2 = hapgen.WORKLOADS["cfg2_mlp_bf16"]; w3 = hapgen.WORKLOADS["cfg3_sfb_bf16"]
+    Tn, h, F = w2.dims["tokens"], w2.dims["hidden"], w2.dims["ffn"]
+    t_setup = time.time()
+    X = dev_bf16(0, T.X, (Tn, h), 1.0)
+    W1 = dev_bf16(0, T.W, (h, F), 0.02); b1 = dev_bf16(0, T.BIAS, (F,), 0.02)
+    W2 = dev_bf16(0, T.W2, (F, h), 0.02)
+    dOut = dev_bf16(0, T.DY, (Tn, h), 1.0)
+    cap, rows = w3.dims["capacity"], w3.dims["rows"]
+    sX = [dev_bf16(0, T.SFB_X + i, (cap, w3.dims["in_features"]), 1.0) for i in range(len(rows))]
+    sdY = [dev_bf16(0, T.SFB_DY + i, (cap, w3.dims["out_features"]), 1.0) for i in range(len(rows))]
+    t_setup = time.time() - t_setup
+
+    stages = [(1.0, 0.0, 0.0, 0.0)]        # compute-only single stage: the ratios the workload's shard sizes come from
+
+    def host_part():
+        ratios, _ = hap.hap_shard_ratios(w2.speeds, stages)
+        return hap.hap_round_shards(ratios, F)
+
+    sizes, offsets = host_part()
+    assert sizes == [8402, 5041, 2941], sizes
+    shards = [MlpShard(Tn, h, F, offsets, j, X, W1, b1, W2, dOut) for j in (0, 2)]
+    sfb = SfbRebuild(sX, sdY, rows, w3.dims["in_features"], w3.dims["out_features"])
+    del W1, W2
+    step_flops = sum(sum(s.flops()) for s in shards) + sfb.flops()
+
+    stream = torch.cuda.current_stream()
+    marks = {}
+
+    def timer(label, fn):
+        a = torch.cuda.Event(enable_timing=True); b = torch.cuda.Event(enable_timing=True)
+        a.record(stream); fn(); b.record(stream)
+        marks.setdefault(label, []).append((a, b))
+
+    def step(tm=None):
+        host_part()
+        for s in shards:
+            s.forward(None if tm is None else (lambda l, f, s=s: tm(f"{l}[f={s.f}]", f)))
+            s.backward(None if tm is None else (lambda l, f, s=s: tm(f"{l}[f={s.f}]", f)))
+        sfb.run(tm)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step(timer)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ms = dt / args.steps * 1e3
+    value = step_flops / (dt / args.steps) / 1e12
+
+    # per-call durations measured with events on the launch stream inside the timed region
+    per = {k: sum(a.elapsed_time(b) for a, b in v) / len(v) for k, v in marks.items()}
+    big = shards[0]
+    gemm = 2.0 * big.T * big.h * big.f
+    call_flops = {f"fc1_fwd[f={big.f}]": gemm, f"fc2_fwd[f={big.f}]": gemm, "sfb_grad": sfb.flops()}
+    dom = f"fc1_fwd[f={big.f}]"                      # one launch of the dominant kernel (bf16 256x256x64 MFMA GEMM)
+    achieved = call_flops[dom] / (per[dom] * 1e-3) / 1e12
+    out = {
+        "metric": "TFLOP/s of sharded fwd+bwd + SFB dW at uneven ratios; % of MFMA peak",
+        "value": round(value, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms, 3), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "cfg2_mlp_bf16 shards 0 and 2 fwd+bwd + cfg3_sfb_bf16 rebuild", "tokens": Tn, "hidden": h, "ffn": F,
+                   "speeds": list(w2.speeds), "shard_sizes": sizes, "sfb_rows": list(rows), "step_gflop": round(step_flops / 1e9, 1),
+                   "pct_of_bf16_mfma_peak": round(100 * value / PEAK_BF16_TFLOPS, 2)},
+        "roofline": {"bound": "mfma", "kernel": "gemm_kernel<bf16,256x256x64> (" + dom + ")", "achieved": round(achieved, 1),
+                     "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_TFLOPS, 4), "traffic": None},
+        "calls_ms": {k: round(v, 4) for k, v in sorted(per.items())},
+        "calls_tflops": {k: round(call_flops[k] / (per[k] * 1e-3) / 1e12, 1) for k in call_flops},
+        "setup_s": round(t_setup, 1),
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(np, hapgen, T, w2, offsets)
+    print(json.dumps(out))
+
+
+def cpu_baseline(np, hapgen, T, w2, offsets):
+    """The oracle as it stands, timed on this host's cores on a bounded sample of the workload."""
+    from oracle import layers
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    except Exception:
+        cores = os.cpu_count()
+    h = w2.dims["hidden"]
+    lo, hi = offsets[2], offsets[3]
+    tok = 1024
+    f = hi - lo
+    X = hapgen.normal_bf16(0, T.X, (tok, h), 1.0)[0]
+    W1 = hapgen.normal_bf16(1, T.W, (h, f), 0.02)[0]; b1 = hapgen.normal_bf16(1, T.BIAS, (f,), 0.02)[0]
+    W2 = hapgen.normal_bf16(1, T.W2, (f, h), 0.02)[0]; dOut = hapgen.normal_bf16(0, T.DY, (tok, h), 1.0)[0]
+    t0 = time.perf_counter()
+    layers.mlp_block(X, W1, b1, W2, np.zeros(h), dOut)
+    dt = time.perf_counter() - t0
+    flops = 12.0 * tok * h * f
+    return {"value": round(flops / dt / 1e12, 4), "unit": "TFLOP/s", "cores": int(cores), "kind": "oracle",
+            "sample": f"oracle.layers.mlp_block fwd+bwd (float64 numpy) on {tok} of 8192 tokens of the smallest shard (ffn {f}): "
+                      f"{flops / 1e9:.0f} GFLOP in {dt:.1f} s"}
+
+
+if __name__ == "__main__":
+    main()
