@@ -1,0 +1,427 @@
+/*
+ * Softmax attention restricted to a device's head or batch slice, forward and backward, bf16 with
+ * fp32 softmax and accumulation, for gfx950.  Heads and batch entries are independent, so a
+ * slice is simply a sub-grid of (batch, head) pairs of the whole [batch, seq, heads, head_dim] tensors.
+ *
+ * All three kernels work on TRANSPOSED score tiles so that the probabilities never leave registers:
+ * an MFMA 32x32 accumulator holds, per lane, 16 rows of ONE column.  With scores laid out as
+ * [key][query] (forward, dQ) a lane owns one query, so the running max / sum of the online softmax
+ * are per-lane scalars (one cross-half shuffle finishes a row reduction) and the bf16-converted
+ * accumulator is directly the B operand of the next MFMA (O^T = V^T P^T).  The matching A operand is
+ * fetched from LDS with the transposing read, in the same permuted key order the accumulator has.
+ *
+ *   forward      per 32-query wave:  S^T = K Q^T,  online softmax,  O^T += V^T P^T
+ *   backward dQ  per 32-query wave:  S^T, dP^T = V dO^T, dS^T = P^T (dP^T - D),  dQ^T += K^T dS^T
+ *   backward dKV per 32-key wave:    S = Q K^T, dP = dO V^T, dS,  dV^T += dO^T P,  dK^T += Q^T dS
+ * D[q] = sum_d dO[q,d] O[q,d] comes from a small pre-pass.  No atomics, deterministic.
+ */
+#include <hip/hip_runtime.h>
+
+#include <stdint.h>
+
+#include "hap_internal.h"
+
+namespace {
+
+typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4_t __attribute__((ext_vector_type(4)));
+typedef short s16x4_t __attribute__((ext_vector_type(4)));
+typedef short s16x8_t __attribute__((ext_vector_type(8)));
+typedef float f32x16_t __attribute__((ext_vector_type(16)));
+typedef float f32x4_t __attribute__((ext_vector_type(4)));
+typedef int i32x4_t __attribute__((ext_vector_type(4)));
+
+#define LDS_PTR(T, p) ((__attribute__((address_space(3))) T*)(p))
+
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLn2 = 0.6931471805599453f;
+constexpr int kTile = 64;     // rows of a K/V (or Q/dO) tile staged in LDS
+constexpr int kWaves = 4;     // waves per workgroup, 32 rows of the outer axis each
+
+struct AttnArgs {
+  const __bf16 *q, *k, *v, *o, *dout;
+  __bf16 *out, *dq, *dk, *dv;
+  float* lse;        // [batch][heads][seq] whole-tensor indexing
+  float* dsum;       // same indexing as lse, workspace
+  long long stride_b, stride_s, stride_h;
+  int seq, heads;    // whole-tensor head count (for lse indexing)
+  int b0, h0;        // first batch entry / head of the slice
+  float scale;
+};
+
+/* 16-byte chunk c of LDS row `row` sits at chunk position c ^ f(row); f makes both the 128-bit row
+ * reads (32 consecutive rows, same chunk) and the transposing reads (4 consecutive rows) conflict free. */
+__device__ __forceinline__ int swz(int row, int c) { return c ^ (((row & 3) << 1) | ((row >> 2) & 1)); }
+
+template <int D>
+__device__ __forceinline__ void stage_tile(char* lds, const __bf16* base, long long stride_s, int row0, int seq, int tid) {
+  constexpr int CPR = D / 8;
+  constexpr int CPT = kTile * CPR / (64 * kWaves);
+#pragma unroll
+  for (int i = 0; i < CPT; ++i) {
+    const int id = tid + i * 64 * kWaves;
+    const int row = id / CPR, c = id % CPR;
+    i32x4_t v = {0, 0, 0, 0};
+    if (row0 + row < seq) v = *reinterpret_cast<const i32x4_t*>(base + (long long)(row0 + row) * stride_s + c * 8);
+    *reinterpret_cast<i32x4_t*>(lds + row * (D * 2) + swz(row, c) * 16) = v;
+  }
+}
+
+/* A operand, K-contiguous: rows of the tile are the MFMA M index, head_dim the contraction. */
+template <int D>
+__device__ __forceinline__ bf16x8_t frag_rows(const char* lds, int row_base, int ks, int lane) {
+  const int row = row_base + (lane & 31);
+  const int c = ks * 2 + (lane >> 5);
+  return __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const i32x4_t*>(lds + row * (D * 2) + swz(row, c) * 16));
+}
+
+/* A operand, transposed: MFMA M index = head_dim column (32 starting at col_base), contraction =
+ * tile rows in the accumulator's order: k-slot j of lane half h is row row_base + (j/4)*8 + h*4 + j%4. */
+template <int D>
+__device__ __forceinline__ bf16x8_t frag_cols(const char* lds, int row_base, int col_base, int lane) {
+  const int g = lane >> 4, i = lane & 15;
+  const int col = col_base + (g & 1) * 16 + (i & 3) * 4;
+  const int r0 = row_base + (g >> 1) * 4 + (i >> 2);
+  const int c = col >> 3, sub = (col & 7) * 2;
+  s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4_t, lds + r0 * (D * 2) + swz(r0, c) * 16 + sub));
+  s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4_t, lds + (r0 + 8) * (D * 2) + swz(r0 + 8, c) * 16 + sub));
+  return __builtin_bit_cast(bf16x8_t, (s16x8_t)__builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+}
+
+/* B operand kept in registers: row `row` of a [seq][D] matrix, lane = row, 8 contiguous d per k-step. */
+template <int D>
+__device__ __forceinline__ void load_row_frags(bf16x8_t (&f)[D / 16], const __bf16* base, long long stride_s, int row, int seq, int lane) {
+#pragma unroll
+  for (int ks = 0; ks < D / 16; ++ks) {
+    i32x4_t v = {0, 0, 0, 0};
+    if (row < seq) v = *reinterpret_cast<const i32x4_t*>(base + (long long)row * stride_s + ks * 16 + (lane >> 5) * 8);
+    f[ks] = __builtin_bit_cast(bf16x8_t, v);
+  }
+}
+
+__device__ __forceinline__ bf16x8_t pack8(const f32x16_t& a, int s) {
+  bf16x8_t r;
+#pragma unroll
+  for (int j = 0; j < 8; ++j) r[j] = (__bf16)a[8 * s + j];
+  return r;
+}
+
+__device__ __forceinline__ f32x16_t zero16() {
+  f32x16_t z;
+#pragma unroll
+  for (int e = 0; e < 16; ++e) z[e] = 0.0f;
+  return z;
+}
+
+__device__ __forceinline__ f32x16_t mfma(bf16x8_t a, bf16x8_t b, f32x16_t c) {
+  return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+}
+
+/* accumulator element e of lane l: row (e/4)*8 + (l/32)*4 + e%4 */
+__device__ __forceinline__ int acc_row(int e, int lane) { return (e >> 2) * 8 + (lane >> 5) * 4 + (e & 3); }
+
+/* Stores a transposed accumulator set acc[D/32] (rows = d, column = this lane's sequence row) to out[row][d]. */
+template <int D>
+__device__ __forceinline__ void store_rows(__bf16* base, long long stride_s, int row, int seq, const f32x16_t (&acc)[D / 32], float mul, int lane) {
+  if (row >= seq) return;
+  __bf16* p = base + (long long)row * stride_s;
+#pragma unroll
+  for (int dt = 0; dt < D / 32; ++dt)
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+      bf16x4_t v;
+#pragma unroll
+      for (int x = 0; x < 4; ++x) v[x] = (__bf16)(acc[dt][g * 4 + x] * mul);
+      *reinterpret_cast<bf16x4_t*>(p + dt * 32 + g * 8 + (lane >> 5) * 4) = v;
+    }
+}
+
+template <int D>
+__global__ __launch_bounds__(64 * kWaves) void attn_fwd_kernel(const AttnArgs a) {
+  __shared__ __attribute__((aligned(16))) char lds_k[kTile * D * 2];
+  __shared__ __attribute__((aligned(16))) char lds_v[kTile * D * 2];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int b = a.b0 + blockIdx.z, h = a.h0 + blockIdx.y;
+  const long long head_off = (long long)b * a.stride_b + (long long)h * a.stride_h;
+  const int q = blockIdx.x * (32 * kWaves) + wave * 32 + (lane & 31);
+  bf16x8_t qf[D / 16];
+  load_row_frags<D>(qf, a.q + head_off, a.stride_s, q, a.seq, lane);
+  f32x16_t o[D / 32];
+#pragma unroll
+  for (int dt = 0; dt < D / 32; ++dt) o[dt] = zero16();
+  float m_i = -INFINITY, l_i = 0.0f;
+  const float c = a.scale * kLog2e;
+  for (int kv0 = 0; kv0 < a.seq; kv0 += kTile) {
+    __syncthreads();
+    stage_tile<D>(lds_k, a.k + head_off, a.stride_s, kv0, a.seq, tid);
+    stage_tile<D>(lds_v, a.v + head_off, a.stride_s, kv0, a.seq, tid);
+    __syncthreads();
+    f32x16_t s[2];
+    float mx = -INFINITY;
+#pragma unroll
+    for (int sub = 0; sub < 2; ++sub) {
+      s[sub] = zero16();
+#pragma unroll
+      for (int ks = 0; ks < D / 16; ++ks) s[sub] = mfma(frag_rows<D>(lds_k, sub * 32, ks, lane), qf[ks], s[sub]);
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        const int key = kv0 + sub * 32 + acc_row(e, lane);
+        s[sub][e] = key < a.seq ? s[sub][e] * c : -INFINITY;
+        mx = fmaxf(mx, s[sub][e]);
+      }
+    }
+    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+    const float m_new = fmaxf(m_i, mx);          // finite: every tile holds at least one valid key
+    const float alpha = exp2f(m_i - m_new);
+    float rs = 0.0f;
+#pragma unroll
+    for (int sub = 0; sub < 2; ++sub)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        s[sub][e] = exp2f(s[sub][e] - m_new);
+        rs += s[sub][e];
+      }
+    rs += __shfl_xor(rs, 32, 64);
+    l_i = l_i * alpha + rs;
+    m_i = m_new;
+#pragma unroll
+    for (int dt = 0; dt < D / 32; ++dt)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) o[dt][e] *= alpha;
+#pragma unroll
+    for (int sub = 0; sub < 2; ++sub)
+#pragma unroll
+      for (int ss = 0; ss < 2; ++ss) {
+        const bf16x8_t p = pack8(s[sub], ss);
+#pragma unroll
+        for (int dt = 0; dt < D / 32; ++dt) o[dt] = mfma(frag_cols<D>(lds_v, sub * 32 + ss * 16, dt * 32, lane), p, o[dt]);
+      }
+  }
+  store_rows<D>(a.out + head_off, a.stride_s, q, a.seq, o, 1.0f / l_i, lane);
+  if (q < a.seq && lane < 32) a.lse[((long long)b * a.heads + h) * a.seq + q] = (m_i + log2f(l_i)) * kLn2;
+}
+
+/* D[q] = sum_d dO[q,d] * O[q,d]; one thread per (b, h, q) row. */
+template <int D>
+__global__ __launch_bounds__(256) void attn_dsum_kernel(const AttnArgs a) {
+  const int q = blockIdx.x * 256 + threadIdx.x;
+  if (q >= a.seq) return;
+  const int b = a.b0 + blockIdx.z, h = a.h0 + blockIdx.y;
+  const long long off = (long long)b * a.stride_b + (long long)h * a.stride_h + (long long)q * a.stride_s;
+  float acc = 0.0f;
+#pragma unroll
+  for (int c = 0; c < D / 8; ++c) {
+    const bf16x8_t x = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const i32x4_t*>(a.dout + off + c * 8));
+    const bf16x8_t y = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const i32x4_t*>(a.o + off + c * 8));
+#pragma unroll
+    for (int e = 0; e < 8; ++e) acc += (float)x[e] * (float)y[e];
+  }
+  a.dsum[((long long)b * a.heads + h) * a.seq + q] = acc;
+}
+
+template <int D>
+__global__ __launch_bounds__(64 * kWaves) void attn_bwd_dq_kernel(const AttnArgs a) {
+  __shared__ __attribute__((aligned(16))) char lds_k[kTile * D * 2];
+  __shared__ __attribute__((aligned(16))) char lds_v[kTile * D * 2];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int b = a.b0 + blockIdx.z, h = a.h0 + blockIdx.y;
+  const long long head_off = (long long)b * a.stride_b + (long long)h * a.stride_h;
+  const long long stat_off = ((long long)b * a.heads + h) * a.seq;
+  const int q = blockIdx.x * (32 * kWaves) + wave * 32 + (lane & 31);
+  bf16x8_t qf[D / 16], dof[D / 16];
+  load_row_frags<D>(qf, a.q + head_off, a.stride_s, q, a.seq, lane);
+  load_row_frags<D>(dof, a.dout + head_off, a.stride_s, q, a.seq, lane);
+  const float lse2 = q < a.seq ? a.lse[stat_off + q] * kLog2e : 0.0f;
+  const float dsum = q < a.seq ? a.dsum[stat_off + q] : 0.0f;
+  const float c = a.scale * kLog2e;
+  f32x16_t dq[D / 32];
+#pragma unroll
+  for (int dt = 0; dt < D / 32; ++dt) dq[dt] = zero16();
+  for (int kv0 = 0; kv0 < a.seq; kv0 += kTile) {
+    __syncthreads();
+    stage_tile<D>(lds_k, a.k + head_off, a.stride_s, kv0, a.seq, tid);
+    stage_tile<D>(lds_v, a.v + head_off, a.stride_s, kv0, a.seq, tid);
+    __syncthreads();
+#pragma unroll
+    for (int sub = 0; sub < 2; ++sub) {
+      f32x16_t s = zero16(), dp = zero16();
+#pragma unroll
+      for (int ks = 0; ks < D / 16; ++ks) {
+        s = mfma(frag_rows<D>(lds_k, sub * 32, ks, lane), qf[ks], s);
+        dp = mfma(frag_rows<D>(lds_v, sub * 32, ks, lane), dof[ks], dp);
+      }
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        const int key = kv0 + sub * 32 + acc_row(e, lane);
+        const float p = key < a.seq ? exp2f(s[e] * c - lse2) : 0.0f;
+        s[e] = p * (dp[e] - dsum);          // dS^T
+      }
+#pragma unroll
+      for (int ss = 0; ss < 2; ++ss) {
+        const bf16x8_t ds = pack8(s, ss);
+#pragma unroll
+        for (int dt = 0; dt < D / 32; ++dt) dq[dt] = mfma(frag_cols<D>(lds_k, sub * 32 + ss * 16, dt * 32, lane), ds, dq[dt]);
+      }
+    }
+  }
+  store_rows<D>(a.dq + head_off, a.stride_s, q, a.seq, dq, a.scale, lane);
+}
+
+template <int D>
+__global__ __launch_bounds__(64 * kWaves) void attn_bwd_dkv_kernel(const AttnArgs a) {
+  __shared__ __attribute__((aligned(16))) char lds_q[kTile * D * 2];
+  __shared__ __attribute__((aligned(16))) char lds_do[kTile * D * 2];
+  __shared__ float lds_lse[kTile], lds_dsum[kTile];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int b = a.b0 + blockIdx.z, h = a.h0 + blockIdx.y;
+  const long long head_off = (long long)b * a.stride_b + (long long)h * a.stride_h;
+  const long long stat_off = ((long long)b * a.heads + h) * a.seq;
+  const int key = blockIdx.x * (32 * kWaves) + wave * 32 + (lane & 31);
+  bf16x8_t kf[D / 16], vf[D / 16];
+  load_row_frags<D>(kf, a.k + head_off, a.stride_s, key, a.seq, lane);
+  load_row_frags<D>(vf, a.v + head_off, a.stride_s, key, a.seq, lane);
+  const bool key_ok = key < a.seq;
+  const float c = a.scale * kLog2e;
+  f32x16_t dk[D / 32], dv[D / 32];
+#pragma unroll
+  for (int dt = 0; dt < D / 32; ++dt) { dk[dt] = zero16(); dv[dt] = zero16(); }
+  for (int q0 = 0; q0 < a.seq; q0 += kTile) {
+    __syncthreads();
+    stage_tile<D>(lds_q, a.q + head_off, a.stride_s, q0, a.seq, tid);
+    stage_tile<D>(lds_do, a.dout + head_off, a.stride_s, q0, a.seq, tid);
+    if (tid < kTile) {
+      const bool ok = q0 + tid < a.seq;
+      lds_lse[tid] = ok ? a.lse[stat_off + q0 + tid] * kLog2e : 0.0f;
+      lds_dsum[tid] = ok ? a.dsum[stat_off + q0 + tid] : 0.0f;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int sub = 0; sub < 2; ++sub) {
+      f32x16_t s = zero16(), dp = zero16();
+#pragma unroll
+      for (int ks = 0; ks < D / 16; ++ks) {
+        s = mfma(frag_rows<D>(lds_q, sub * 32, ks, lane), kf[ks], s);
+        dp = mfma(frag_rows<D>(lds_do, sub * 32, ks, lane), vf[ks], dp);
+      }
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        const int ql = sub * 32 + acc_row(e, lane);
+        const bool ok = key_ok && q0 + ql < a.seq;
+        const float p = ok ? exp2f(s[e] * c - lds_lse[ql]) : 0.0f;
+        dp[e] = p * (dp[e] - lds_dsum[ql]);   // dS
+        s[e] = p;                             // P
+      }
+#pragma unroll
+      for (int ss = 0; ss < 2; ++ss) {
+        const bf16x8_t pf = pack8(s, ss), dsf = pack8(dp, ss);
+#pragma unroll
+        for (int dt = 0; dt < D / 32; ++dt) {
+          dv[dt] = mfma(frag_cols<D>(lds_do, sub * 32 + ss * 16, dt * 32, lane), pf, dv[dt]);
+          dk[dt] = mfma(frag_cols<D>(lds_q, sub * 32 + ss * 16, dt * 32, lane), dsf, dk[dt]);
+        }
+      }
+    }
+  }
+  store_rows<D>(a.dv + head_off, a.stride_s, key, a.seq, dv, 1.0f, lane);
+  store_rows<D>(a.dk + head_off, a.stride_s, key, a.seq, dk, a.scale, lane);
+}
+
+int resolve(const hap_attn_desc* d, int j, int* b0, int* nb, int* h0, int* nh) {
+  if (!d) return hap_fail(HAP_EINVAL, "descriptor is NULL");
+  if (d->batch < 1 || d->heads < 1 || d->seq < 1) return hap_fail(HAP_EINVAL, "bad attention sizes");
+  if (d->head_dim != 64 && d->head_dim != 128) return hap_fail(HAP_EUNSUPPORTED, "head_dim %lld (supported: 64, 128)", (long long)d->head_dim);
+  if (d->io_dtype != HAP_BF16) return hap_fail(HAP_EUNSUPPORTED, "attention supports bf16 only");
+  if (d->seq > 0x7fffffff / 2 || d->heads > 65535 || d->batch > 65535) return hap_fail(HAP_EUNSUPPORTED, "attention extent too large");
+  if (d->stride_s < d->head_dim || d->stride_h < d->head_dim) return hap_fail(HAP_ESHAPE, "strides overlap head_dim");
+  if (d->stride_s % 8 || d->stride_h % 8 || d->stride_b % 8) return hap_fail(HAP_EUNSUPPORTED, "strides must be multiples of 8 elements");
+  int64_t lo, hi;
+  const int rc = hap_shard_range(d->m, d->offsets, d->shard_over_heads ? d->heads : d->batch, j, &lo, &hi);
+  if (rc) return rc;
+  *b0 = 0; *nb = (int)d->batch; *h0 = 0; *nh = (int)d->heads;
+  if (d->shard_over_heads) { *h0 = (int)lo; *nh = (int)(hi - lo); }
+  else { *b0 = (int)lo; *nb = (int)(hi - lo); }
+  return HAP_OK;
+}
+
+int check_ptr(const void* p, const char* name) {
+  if (!p) return hap_fail(HAP_EINVAL, "%s is NULL", name);
+  if ((uintptr_t)p % 16) return hap_fail(HAP_EUNSUPPORTED, "%s must be 16-byte aligned", name);
+  return HAP_OK;
+}
+
+int launched(const char* what) {
+  const hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return hap_fail(HAP_EDEVICE, "%s launch: %s", what, hipGetErrorString(e));
+  return HAP_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int hap_sharded_attn_fwd(const hap_attn_desc* d, int shard_index, const void* Q, const void* K, const void* V,
+                         void* O, float* lse, void*, size_t, void* stream) {
+  hap_clear_error();
+  int b0, nb, h0, nh;
+  int rc = resolve(d, shard_index, &b0, &nb, &h0, &nh);
+  if (rc) return rc;
+  if (nb == 0 || nh == 0) return HAP_OK;
+  if ((rc = check_ptr(Q, "Q")) || (rc = check_ptr(K, "K")) || (rc = check_ptr(V, "V")) || (rc = check_ptr(O, "O"))) return rc;
+  if (!lse) return hap_fail(HAP_EINVAL, "lse is NULL");
+  AttnArgs a = {};
+  a.q = (const __bf16*)Q; a.k = (const __bf16*)K; a.v = (const __bf16*)V; a.out = (__bf16*)O; a.lse = lse;
+  a.stride_b = d->stride_b; a.stride_s = d->stride_s; a.stride_h = d->stride_h;
+  a.seq = (int)d->seq; a.heads = (int)d->heads; a.b0 = b0; a.h0 = h0;
+  a.scale = 1.0f / sqrtf((float)d->head_dim);
+  const dim3 grid((unsigned)((d->seq + 32 * kWaves - 1) / (32 * kWaves)), (unsigned)nh, (unsigned)nb);
+  hipStream_t s = (hipStream_t)stream;
+  if (d->head_dim == 128) hipLaunchKernelGGL(attn_fwd_kernel<128>, grid, dim3(64 * kWaves), 0, s, a);
+  else hipLaunchKernelGGL(attn_fwd_kernel<64>, grid, dim3(64 * kWaves), 0, s, a);
+  return launched("attn_fwd");
+}
+
+size_t hap_attn_bwd_workspace(const hap_attn_desc* d, int) {
+  if (!d || d->batch < 1 || d->heads < 1 || d->seq < 1) return 0;
+  return (size_t)(d->batch * d->heads * d->seq) * sizeof(float);
+}
+
+int hap_sharded_attn_bwd(const hap_attn_desc* d, int shard_index, const void* Q, const void* K, const void* V,
+                         const void* O, const float* lse, const void* dO, void* dQ, void* dK, void* dV,
+                         void* ws, size_t ws_bytes, void* stream) {
+  hap_clear_error();
+  int b0, nb, h0, nh;
+  int rc = resolve(d, shard_index, &b0, &nb, &h0, &nh);
+  if (rc) return rc;
+  if (nb == 0 || nh == 0) return HAP_OK;
+  if ((rc = check_ptr(Q, "Q")) || (rc = check_ptr(K, "K")) || (rc = check_ptr(V, "V")) || (rc = check_ptr(O, "O")) ||
+      (rc = check_ptr(dO, "dO")) || (rc = check_ptr(dQ, "dQ")) || (rc = check_ptr(dK, "dK")) || (rc = check_ptr(dV, "dV"))) return rc;
+  if (!lse) return hap_fail(HAP_EINVAL, "lse is NULL");
+  const size_t need = hap_attn_bwd_workspace(d, shard_index);
+  if (!ws || ws_bytes < need) return hap_fail(HAP_EWORKSPACE, "attn_bwd needs %zu workspace bytes", need);
+  AttnArgs a = {};
+  a.q = (const __bf16*)Q; a.k = (const __bf16*)K; a.v = (const __bf16*)V; a.o = (const __bf16*)O; a.dout = (const __bf16*)dO;
+  a.dq = (__bf16*)dQ; a.dk = (__bf16*)dK; a.dv = (__bf16*)dV;
+  a.lse = const_cast<float*>(lse); a.dsum = (float*)ws;
+  a.stride_b = d->stride_b; a.stride_s = d->stride_s; a.stride_h = d->stride_h;
+  a.seq = (int)d->seq; a.heads = (int)d->heads; a.b0 = b0; a.h0 = h0;
+  a.scale = 1.0f / sqrtf((float)d->head_dim);
+  hipStream_t s = (hipStream_t)stream;
+  const dim3 grid((unsigned)((d->seq + 32 * kWaves - 1) / (32 * kWaves)), (unsigned)nh, (unsigned)nb);
+  const dim3 grid_d((unsigned)((d->seq + 255) / 256), (unsigned)nh, (unsigned)nb);
+  if (d->head_dim == 128) {
+    hipLaunchKernelGGL(attn_dsum_kernel<128>, grid_d, dim3(256), 0, s, a);
+    if ((rc = launched("attn_dsum"))) return rc;
+    hipLaunchKernelGGL(attn_bwd_dkv_kernel<128>, grid, dim3(64 * kWaves), 0, s, a);
+    if ((rc = launched("attn_bwd_dkv"))) return rc;
+    hipLaunchKernelGGL(attn_bwd_dq_kernel<128>, grid, dim3(64 * kWaves), 0, s, a);
+  } else {
+    hipLaunchKernelGGL(attn_dsum_kernel<64>, grid_d, dim3(256), 0, s, a);
+    if ((rc = launched("attn_dsum"))) return rc;
+    hipLaunchKernelGGL(attn_bwd_dkv_kernel<64>, grid, dim3(64 * kWaves), 0, s, a);
+    if ((rc = launched("attn_bwd_dkv"))) return rc;
+    hipLaunchKernelGGL(attn_bwd_dq_kernel<64>, grid, dim3(64 * kWaves), 0, s, a);
+  }
+  return launched("attn_bwd_dq");
+}
+
+}  // extern "C"

@@ -1,0 +1,131 @@
+"""GPU parity: attention slice fwd / bwd and the row / element helpers against the CPU oracle."""
+import numpy as np
+import pytest
+
+import hapgen
+from hapgen import TensorId as T
+from oracle import attention as oatt, pointwise as opw
+
+pytestmark = pytest.mark.gpu
+
+from gpu_util import gen, empty, host, check, torch_mod  # noqa: E402
+
+
+@pytest.fixture(scope="module")
+def hap():
+    import paper_2401_05965_amd as h
+    return h
+
+
+def _bshd_to_bhsd(a, B, S, H, D):
+    return a.reshape(B, S, H, D).transpose(0, 2, 1, 3)
+
+
+@pytest.mark.parametrize("B,H,S,D,over_heads,offsets", [
+    (2, 5, 300, 128, True, [0, 2, 2, 5]),      # uneven head counts, one empty device; seq spans tiles + ragged tail
+    (5, 3, 197, 64, False, [0, 2, 3, 5]),      # ViT-like: batch slices, seq 197, head_dim 64
+    (1, 2, 64, 128, True, [0, 2]),             # exactly one tile
+    (1, 1, 1, 64, True, [0, 1]),               # degenerate: a single token attends to itself
+])
+def test_attention_slices_fwd_bwd(hap, B, H, S, D, over_heads, offsets):
+    torch = torch_mod()
+    shp = (B, S, H, D)
+    Qh, Qd = gen(3, T.Q, shp, 1.0, "bf16"); Kh, Kd = gen(3, T.K, shp, 1.0, "bf16")
+    Vh, Vd = gen(3, T.V, shp, 1.0, "bf16"); dOh, dOd = gen(3, T.DO, shp, 1.0, "bf16")
+    desc = hap.AttnDesc(B, H, S, D, over_heads, offsets)
+    O = empty(shp, "bf16", 0); lse = empty((B, H, S), "f32", 0)
+    dQ = empty(shp, "bf16", 0); dK = empty(shp, "bf16", 0); dV = empty(shp, "bf16", 0)
+    ws = empty((max(hap.hap_attn_bwd_workspace(desc, 0), 16),), "u8")
+    tr = lambda a: _bshd_to_bhsd(a, B, S, H, D)
+    Oo, lseo = oatt.attn_fwd(tr(Qh), tr(Kh), tr(Vh))
+    # backward oracle from exact O; the device uses its own bf16 O for D = rowsum(dO * O)
+    dQo, dKo, dVo = oatt.attn_bwd(tr(Qh), tr(Kh), tr(Vh), tr(dOh))
+    for j in range(len(offsets) - 1):
+        lo, hi = offsets[j], offsets[j + 1]
+        O.zero_(); lse.zero_(); dQ.zero_(); dK.zero_(); dV.zero_()
+        hap.hap_sharded_attn_fwd(desc, j, Qd, Kd, Vd, O, lse)
+        hap.hap_sharded_attn_bwd(desc, j, Qd, Kd, Vd, O, lse, dOd, dQ, dK, dV, ws)
+        got = {n: tr(host(t)) for n, t in (("O", O), ("dQ", dQ), ("dK", dK), ("dV", dV))}
+        got_lse = host(lse)
+        sl = (slice(None), slice(lo, hi)) if over_heads else (slice(lo, hi),)
+        mask = np.zeros((B, H), bool); mask[sl] = True
+        for n, ref in (("O", Oo), ("dQ", dQo), ("dK", dKo), ("dV", dVo)):
+            if hi > lo:
+                check(f"attn shard{j} {n}", got[n][sl], ref[sl], "bf16")
+            assert not got[n][~mask].any(), f"{n}: (batch, head) pairs outside the slice were written"
+        if hi > lo:
+            assert np.abs(got_lse[sl] - lseo[sl]).max() <= 2e-2
+        assert not got_lse[~mask].any()
+
+
+def test_attention_strided_qkv_views(hap):
+    """Q, K, V as column blocks of one [tokens x 3*heads*d] buffer (stride_s larger than heads*d)."""
+    torch = torch_mod()
+    B, H, S, D = 2, 3, 130, 64
+    w = 3 * H * D
+    allh, alld = gen(5, T.Q, (B * S, w), 1.0, "bf16")
+    dOh, dOd = gen(5, T.DO, (B, S, H, D), 1.0, "bf16")
+    desc = hap.AttnDesc(B, H, S, D, True, [0, 3], stride_b=S * w, stride_s=w, stride_h=D)
+    es = 2
+    base = alld.data_ptr()
+    Ostr = empty((B * S, w), "bf16", 0)
+    lse = empty((B, H, S), "f32", 0)
+    hap.hap_sharded_attn_fwd(desc, 0, base, base + H * D * es, base + 2 * H * D * es, Ostr.data_ptr(), lse)
+    q, k, v = (allh[:, i * H * D:(i + 1) * H * D].reshape(B, S, H, D).transpose(0, 2, 1, 3) for i in range(3))
+    Oo, _ = oatt.attn_fwd(q, k, v)
+    got = host(Ostr)[:, :H * D].reshape(B, S, H, D).transpose(0, 2, 1, 3)
+    check("strided O", got, Oo, "bf16")
+    assert not host(Ostr)[:, H * D:].any()
+
+
+def test_attention_argument_errors(hap):
+    torch = torch_mod()
+    t = empty((1, 8, 1, 64), "bf16", 0); lse = empty((8,), "f32", 0)
+    with pytest.raises(hap.HapError) as e:
+        hap.hap_sharded_attn_fwd(hap.AttnDesc(1, 1, 8, 96, True, [0, 1]), 0, t, t, t, t, lse)
+    assert e.value.status == 7
+    with pytest.raises(hap.HapError) as e:
+        hap.hap_sharded_attn_fwd(hap.AttnDesc(1, 1, 8, 64, True, [0, 2]), 0, t, t, t, t, lse)
+    assert e.value.status == 2
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("rows,n", [(37, 2048), (130, 1024), (5, 200)])
+def test_layernorm_fwd_bwd(hap, dtype, rows, n):
+    xh, xd = gen(2, T.X, (rows, n), 2.0, dtype)
+    gh, gd = gen(2, T.GAMMA, (n,), 0.3, dtype); gh = gh + 0  # gamma ~ N(0, .3): exercises the affine part
+    bh, bd = gen(2, T.BETA, (n,), 0.3, dtype)
+    dyh, dyd = gen(2, T.DY, (rows, n), 1.0, dtype)
+    y = empty((rows, n), dtype, 0); mean = empty((rows,), "f32", 0); rstd = empty((rows,), "f32", 0)
+    hap.hap_layernorm_fwd(rows, n, {"bf16": 1, "f32": 0}[dtype], xd, gd, bd, y, mean, rstd)
+    yo, muo, rso = opw.layernorm_fwd(xh, gh, bh)
+    check("ln y", host(y), yo, dtype)
+    assert np.abs(host(mean) - muo).max() <= 1e-4 * max(1, np.abs(muo).max())
+    assert np.abs(host(rstd) / rso - 1).max() <= 1e-4
+    dx = empty((rows, n), dtype, 0); dg = empty((n,), "f32", 0); db = empty((n,), "f32", 0)
+    ws = empty((max(hap.hap_layernorm_bwd_workspace(rows, n), 16),), "u8")
+    hap.hap_layernorm_bwd(rows, n, {"bf16": 1, "f32": 0}[dtype], xd, gd, mean, rstd, dyd, dx, dg, db, ws)
+    dxo, dgo, dbo = opw.layernorm_bwd(xh, gh, dyh)
+    check("ln dx", host(dx), dxo, dtype); check("ln dgamma", host(dg), dgo, dtype); check("ln dbeta", host(db), dbo, dtype)
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_gelu_bwd_add_colsum(hap, dtype):
+    torch = torch_mod()
+    io = {"bf16": 1, "f32": 0}[dtype]
+    for rows, cols, ld in [(300, 520, 520), (77, 137, 141), (1030, 64, 64)]:
+        ph, pd = gen(4, T.X, (rows, ld), 1.5, dtype); dyh, dyd = gen(4, T.DY, (rows, ld), 1.0, dtype)
+        out = empty((rows, ld), dtype, 0)
+        hap.hap_gelu_bwd(rows, cols, io, pd, ld, dyd, ld, out, ld)
+        check("gelu_bwd", host(out)[:, :cols], (dyh * opw.gelu_grad(ph))[:, :cols], dtype)
+        assert not host(out)[:, cols:].any()
+        bh, bd = gen(4, T.BIAS, (cols,), 1.0, dtype)
+        out.zero_()
+        hap.hap_add(rows, cols, io, pd, ld, dyd, ld, bd, out, ld)
+        check("add", host(out)[:, :cols], (ph + dyh)[:, :cols] + bh, dtype)
+        hap.hap_add(rows, cols, io, pd, ld, dyd, ld, None, pd, ld)           # in place, no bias
+        check("add in place", host(pd)[:, :cols], (ph + dyh)[:, :cols], dtype)
+        s = empty((cols,), "f32", float("nan"))
+        ws = empty((max(hap.hap_colsum_workspace(rows, cols), 16),), "u8")
+        hap.hap_colsum(rows, cols, io, dyd, ld, s, ws)
+        check("colsum", host(s), dyh[:, :cols].sum(0), dtype)
