@@ -164,7 +164,10 @@ typedef struct {
   int m;
   const int64_t* offsets;                  /* host, [m+1] over heads or batch                          */
   int io_dtype;                            /* HAP_BF16                                                 */
-  int64_t stride_b, stride_s, stride_h;    /* shared by Q, K, V, O and their gradients                 */
+  int64_t stride_b, stride_s, stride_h;    /* of Q, K, V and dQ, dK, dV                                */
+  int64_t o_stride_b, o_stride_s, o_stride_h; /* of O and dO; all three 0 = same as above (e.g. Q|K|V
+                                              are column blocks of one [tokens x 3*heads*d] buffer
+                                              while O is [tokens x heads*d])                        */
 } hap_attn_desc;
 
 /* lse: device fp32 [batch x heads x seq] (whole-tensor indexing), log-sum-exp of each query row,

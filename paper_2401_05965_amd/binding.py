@@ -53,7 +53,8 @@ class _LinearDesc(C.Structure):
 class _AttnDesc(C.Structure):
     _fields_ = [("batch", C.c_int64), ("heads", C.c_int64), ("seq", C.c_int64), ("head_dim", C.c_int64),
                 ("shard_over_heads", C.c_int), ("m", C.c_int), ("offsets", C.POINTER(C.c_int64)),
-                ("io_dtype", C.c_int), ("stride_b", C.c_int64), ("stride_s", C.c_int64), ("stride_h", C.c_int64)]
+                ("io_dtype", C.c_int), ("stride_b", C.c_int64), ("stride_s", C.c_int64), ("stride_h", C.c_int64),
+                ("o_stride_b", C.c_int64), ("o_stride_s", C.c_int64), ("o_stride_h", C.c_int64)]
 
 
 class LinearDesc:
@@ -75,7 +76,7 @@ class LinearDesc:
 
 class AttnDesc:
     def __init__(self, batch, heads, seq, head_dim, shard_over_heads, offsets, io_dtype=BF16,
-                 stride_b=None, stride_s=None, stride_h=None):
+                 stride_b=None, stride_s=None, stride_h=None, o_strides=None):
         offsets = list(offsets)
         self._offs = (C.c_int64 * len(offsets))(*offsets)
         self.m = len(offsets) - 1
@@ -83,7 +84,8 @@ class AttnDesc:
         stride_s = heads * head_dim if stride_s is None else stride_s
         stride_b = seq * stride_s if stride_b is None else stride_b
         self.c = _AttnDesc(batch, heads, seq, head_dim, int(bool(shard_over_heads)), self.m,
-                           C.cast(self._offs, C.POINTER(C.c_int64)), io_dtype, stride_b, stride_s, stride_h)
+                           C.cast(self._offs, C.POINTER(C.c_int64)), io_dtype, stride_b, stride_s, stride_h,
+                           *(o_strides if o_strides is not None else (0, 0, 0)))
 
 
 lib.hap_strerror.restype = C.c_char_p

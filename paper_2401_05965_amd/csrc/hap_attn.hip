@@ -43,7 +43,8 @@ struct AttnArgs {
   __bf16 *out, *dq, *dk, *dv;
   float* lse;        // [batch][heads][seq] whole-tensor indexing
   float* dsum;       // same indexing as lse, workspace
-  long long stride_b, stride_s, stride_h;
+  long long stride_b, stride_s, stride_h;      // Q, K, V and their gradients
+  long long ostride_b, ostride_s, ostride_h;   // O and dO
   int seq, heads;    // whole-tensor head count (for lse indexing)
   int b0, h0;        // first batch entry / head of the slice
   float scale;
@@ -197,7 +198,8 @@ __global__ __launch_bounds__(64 * kWaves) void attn_fwd_kernel(const AttnArgs a)
         for (int dt = 0; dt < D / 32; ++dt) o[dt] = mfma(frag_cols<D>(lds_v, sub * 32 + ss * 16, dt * 32, lane), p, o[dt]);
       }
   }
-  store_rows<D>(a.out + head_off, a.stride_s, q, a.seq, o, 1.0f / l_i, lane);
+  const long long ohead_off = (long long)b * a.ostride_b + (long long)h * a.ostride_h;
+  store_rows<D>(a.out + ohead_off, a.ostride_s, q, a.seq, o, 1.0f / l_i, lane);
   if (q < a.seq && lane < 32) a.lse[((long long)b * a.heads + h) * a.seq + q] = (m_i + log2f(l_i)) * kLn2;
 }
 
@@ -207,7 +209,7 @@ __global__ __launch_bounds__(256) void attn_dsum_kernel(const AttnArgs a) {
   const int q = blockIdx.x * 256 + threadIdx.x;
   if (q >= a.seq) return;
   const int b = a.b0 + blockIdx.z, h = a.h0 + blockIdx.y;
-  const long long off = (long long)b * a.stride_b + (long long)h * a.stride_h + (long long)q * a.stride_s;
+  const long long off = (long long)b * a.ostride_b + (long long)h * a.ostride_h + (long long)q * a.ostride_s;
   float acc = 0.0f;
 #pragma unroll
   for (int c = 0; c < D / 8; ++c) {
@@ -230,7 +232,8 @@ __global__ __launch_bounds__(64 * kWaves) void attn_bwd_dq_kernel(const AttnArgs
   const int q = blockIdx.x * (32 * kWaves) + wave * 32 + (lane & 31);
   bf16x8_t qf[D / 16], dof[D / 16];
   load_row_frags<D>(qf, a.q + head_off, a.stride_s, q, a.seq, lane);
-  load_row_frags<D>(dof, a.dout + head_off, a.stride_s, q, a.seq, lane);
+  const long long ohead_off = (long long)b * a.ostride_b + (long long)h * a.ostride_h;
+  load_row_frags<D>(dof, a.dout + ohead_off, a.ostride_s, q, a.seq, lane);
   const float lse2 = q < a.seq ? a.lse[stat_off + q] * kLog2e : 0.0f;
   const float dsum = q < a.seq ? a.dsum[stat_off + q] : 0.0f;
   const float c = a.scale * kLog2e;
@@ -276,6 +279,7 @@ __global__ __launch_bounds__(64 * kWaves) void attn_bwd_dkv_kernel(const AttnArg
   const int b = a.b0 + blockIdx.z, h = a.h0 + blockIdx.y;
   const long long head_off = (long long)b * a.stride_b + (long long)h * a.stride_h;
   const long long stat_off = ((long long)b * a.heads + h) * a.seq;
+  const long long ohead_off = (long long)b * a.ostride_b + (long long)h * a.ostride_h;
   const int key = blockIdx.x * (32 * kWaves) + wave * 32 + (lane & 31);
   bf16x8_t kf[D / 16], vf[D / 16];
   load_row_frags<D>(kf, a.k + head_off, a.stride_s, key, a.seq, lane);
@@ -288,7 +292,7 @@ __global__ __launch_bounds__(64 * kWaves) void attn_bwd_dkv_kernel(const AttnArg
   for (int q0 = 0; q0 < a.seq; q0 += kTile) {
     __syncthreads();
     stage_tile<D>(lds_q, a.q + head_off, a.stride_s, q0, a.seq, tid);
-    stage_tile<D>(lds_do, a.dout + head_off, a.stride_s, q0, a.seq, tid);
+    stage_tile<D>(lds_do, a.dout + ohead_off, a.ostride_s, q0, a.seq, tid);
     if (tid < kTile) {
       const bool ok = q0 + tid < a.seq;
       lds_lse[tid] = ok ? a.lse[stat_off + q0 + tid] * kLog2e : 0.0f;
@@ -334,6 +338,10 @@ int resolve(const hap_attn_desc* d, int j, int* b0, int* nb, int* h0, int* nh) {
   if (d->seq > 0x7fffffff / 2 || d->heads > 65535 || d->batch > 65535) return hap_fail(HAP_EUNSUPPORTED, "attention extent too large");
   if (d->stride_s < d->head_dim || d->stride_h < d->head_dim) return hap_fail(HAP_ESHAPE, "strides overlap head_dim");
   if (d->stride_s % 8 || d->stride_h % 8 || d->stride_b % 8) return hap_fail(HAP_EUNSUPPORTED, "strides must be multiples of 8 elements");
+  if (d->o_stride_s || d->o_stride_h || d->o_stride_b) {
+    if (d->o_stride_s < d->head_dim || d->o_stride_h < d->head_dim) return hap_fail(HAP_ESHAPE, "O strides overlap head_dim");
+    if (d->o_stride_s % 8 || d->o_stride_h % 8 || d->o_stride_b % 8) return hap_fail(HAP_EUNSUPPORTED, "strides must be multiples of 8 elements");
+  }
   int64_t lo, hi;
   const int rc = hap_shard_range(d->m, d->offsets, d->shard_over_heads ? d->heads : d->batch, j, &lo, &hi);
   if (rc) return rc;
@@ -371,6 +379,8 @@ int hap_sharded_attn_fwd(const hap_attn_desc* d, int shard_index, const void* Q,
   AttnArgs a = {};
   a.q = (const __bf16*)Q; a.k = (const __bf16*)K; a.v = (const __bf16*)V; a.out = (__bf16*)O; a.lse = lse;
   a.stride_b = d->stride_b; a.stride_s = d->stride_s; a.stride_h = d->stride_h;
+  const bool own_o = d->o_stride_s || d->o_stride_h || d->o_stride_b;
+  a.ostride_b = own_o ? d->o_stride_b : d->stride_b; a.ostride_s = own_o ? d->o_stride_s : d->stride_s; a.ostride_h = own_o ? d->o_stride_h : d->stride_h;
   a.seq = (int)d->seq; a.heads = (int)d->heads; a.b0 = b0; a.h0 = h0;
   a.scale = 1.0f / sqrtf((float)d->head_dim);
   const dim3 grid((unsigned)((d->seq + 32 * kWaves - 1) / (32 * kWaves)), (unsigned)nh, (unsigned)nb);
@@ -403,6 +413,8 @@ int hap_sharded_attn_bwd(const hap_attn_desc* d, int shard_index, const void* Q,
   a.dq = (__bf16*)dQ; a.dk = (__bf16*)dK; a.dv = (__bf16*)dV;
   a.lse = const_cast<float*>(lse); a.dsum = (float*)ws;
   a.stride_b = d->stride_b; a.stride_s = d->stride_s; a.stride_h = d->stride_h;
+  const bool own_o = d->o_stride_s || d->o_stride_h || d->o_stride_b;
+  a.ostride_b = own_o ? d->o_stride_b : d->stride_b; a.ostride_s = own_o ? d->o_stride_s : d->stride_s; a.ostride_h = own_o ? d->o_stride_h : d->stride_h;
   a.seq = (int)d->seq; a.heads = (int)d->heads; a.b0 = b0; a.h0 = h0;
   a.scale = 1.0f / sqrtf((float)d->head_dim);
   hipStream_t s = (hipStream_t)stream;

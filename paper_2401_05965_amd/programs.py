@@ -95,3 +95,222 @@ class SfbRebuild:
     def run(self, timer=None):
         _call(timer, "sfb_grad", lambda: hap.hap_sfb_grad(self.Xs, self.dYs, self.rows, self.inf, self.outf, self.Xs[0].stride(0),
                                                           self.dYs[0].stride(0), self.dtype, self.dW, self.outf))
+
+
+def _zeros(shape, dtype, dev):
+    return torch.zeros(shape, dtype=dtype, device=dev)
+
+
+class EncoderShard:
+    """Device j's instructions of one pre-LayerNorm Transformer encoder layer.
+
+        x1 = x + Attn(LN1(x)) Wo + bo ;   y = x1 + gelu(LN2(x1) W1 + b1) W2 + b2
+
+    Two sharding styles share the instruction list:
+      "tensor": heads and the ffn axis are sharded (feature rule for Wq/Wk/Wv/W1, reduction rule
+                for Wo/W2); tokens are whole; the Wo and W2 products are partial sums that the
+                caller all-reduces (here: adds up over the virtual devices) before the residual.
+      "data":   the batch is sharded (batch rule everywhere); weights are whole; outputs are exact
+                row slices and the weight gradients are partial sums over the batch.
+    The device keeps its Wq|Wk|Wv slices side by side in one [hidden x 3*heads_j*d] buffer so the
+    three projections (and their backward) run as single GEMMs.
+    """
+
+    def __init__(self, style, j, B, S, hidden, heads, d, ffn, head_offsets, ffn_offsets, batch_offsets, params, dtype=torch.bfloat16):
+        assert style in ("tensor", "data")
+        self.style, self.j = style, j
+        dev = params["Wq"].device
+        self.S, self.hidden, self.d = S, hidden, d
+        if style == "tensor":
+            h0, h1 = head_offsets[j], head_offsets[j + 1]
+            f0, f1 = ffn_offsets[j], ffn_offsets[j + 1]
+            self.B, self.b0 = B, 0
+        else:
+            h0, h1, f0, f1 = 0, heads, 0, ffn
+            self.b0 = batch_offsets[j]; self.B = batch_offsets[j + 1] - batch_offsets[j]
+        self.nh, self.f = h1 - h0, f1 - f0
+        self.hd = hd = self.nh * d
+        self.N = N = self.B * S
+        self.ldf = ldf = max(_pad8(self.f), 8)
+        io = self.io = hap.BF16
+        c0, c1 = h0 * d, h1 * d
+        self.Wqkv = torch.cat([params[n][:, c0:c1] for n in ("Wq", "Wk", "Wv")], dim=1).contiguous() if hd else _zeros((hidden, 8), dtype, dev)
+        self.bqkv = torch.cat([params[n][c0:c1] for n in ("bq", "bk", "bv")]).contiguous() if hd else _zeros((8,), dtype, dev)
+        self.Wo = params["Wo"][c0:c1].contiguous() if hd else _zeros((8, hidden), dtype, dev)
+        self.W1 = _zeros((hidden, ldf), dtype, dev); self.W1[:, :self.f] = params["W1"][:, f0:f1]
+        self.b1 = params["b1"][f0:f1].contiguous() if self.f else _zeros((8,), dtype, dev)
+        self.W2 = params["W2"][f0:f1].contiguous() if self.f else _zeros((8, hidden), dtype, dev)
+        self.g1, self.be1, self.g2, self.be2 = params["g1"], params["be1"], params["g2"], params["be2"]
+        # activations saved for the backward
+        z = lambda *s: _zeros(s, dtype, dev)
+        zf = lambda *s: _zeros(s, torch.float32, dev)
+        self.ln1, self.ln2 = z(N, hidden), z(N, hidden)
+        self.mean1, self.rstd1, self.mean2, self.rstd2 = zf(N), zf(N), zf(N), zf(N)
+        self.qkv, self.o = z(N, max(3 * hd, 8)), z(N, max(hd, 8))
+        self.lse = zf(self.B, max(self.nh, 1), S)
+        self.attn_part, self.mlp_part = z(N, hidden), z(N, hidden)
+        self.H, self.pre = z(N, ldf), z(N, ldf)
+        # gradients
+        self.dH, self.dln2_part, self.dln1_part = z(N, ldf), z(N, hidden), z(N, hidden)
+        self.do, self.dqkv = z(N, max(hd, 8)), z(N, max(3 * hd, 8))
+        self.dx1_ln, self.dx_ln = z(N, hidden), z(N, hidden)
+        self.dWqkv, self.dWo = z(hidden, max(3 * hd, 8)), z(max(hd, 1), hidden)
+        self.dW1, self.dW2 = z(hidden, ldf), z(max(self.f, 1), hidden)
+        self.dbqkv, self.db1 = zf(max(3 * hd, 1)), zf(max(self.f, 1))
+        self.dg1, self.dbe1, self.dg2, self.dbe2 = zf(hidden), zf(hidden), zf(hidden), zf(hidden)
+        L = hap.LinearDesc
+        one = [0, 1]
+        self.d_qkv = L(N, hidden, max(3 * hd, 1), hap.REPLICATED, one, io, has_bias=True, ldx=hidden, ldw=max(3 * hd, 8), ldy=max(3 * hd, 8), m=1)
+        self.d_wo = L(N, max(hd, 1), hidden, hap.REPLICATED, one, io, ldx=max(hd, 8), ldw=hidden, ldy=hidden, m=1)
+        self.d_fc1 = L(N, hidden, max(self.f, 1), hap.REPLICATED, one, io, act=hap.ACT_GELU_ERF, has_bias=True, ldx=hidden, ldw=ldf, ldy=ldf, m=1)
+        self.d_fc2 = L(N, max(self.f, 1), hidden, hap.REPLICATED, one, io, ldx=ldf, ldw=hidden, ldy=hidden, m=1)
+        # Q|K|V are column blocks of the [N x 3hd] projection output; O and dO are [N x hd]
+        self.d_attn = hap.AttnDesc(self.B, max(self.nh, 1), S, d, True, [0, max(self.nh, 1)], stride_b=S * 3 * hd, stride_s=3 * hd, stride_h=d,
+                                   o_strides=(S * hd, hd, d)) if hd else None
+        nws = max([hap.hap_linear_bwd_workspace(x, 0) for x in (self.d_qkv, self.d_wo, self.d_fc1, self.d_fc2)] +
+                  [hap.hap_layernorm_bwd_workspace(N, hidden), hap.hap_colsum_workspace(N, hidden),
+                   hap.hap_attn_bwd_workspace(self.d_attn, 0) if hd else 0, 256])
+        self.ws = torch.empty((nws,), dtype=torch.uint8, device=dev)
+
+    # ---- token rows of this device inside whole [tokens x hidden] tensors
+    def rows(self, t):
+        return t[self.b0 * self.S:(self.b0 + self.B) * self.S]
+
+    def flops(self):
+        """Algorithmic flops (fwd, bwd): GEMMs 2*M*N*K, attention 4*S^2*d per (batch, head); backward = 2x forward."""
+        g = 2.0 * self.N * self.hidden * (3 * self.hd) + 2.0 * self.N * self.hd * self.hidden + 4.0 * self.N * self.hidden * self.f
+        a = 4.0 * self.B * self.nh * self.S * self.S * self.d
+        return g + a, 2 * (g + a)
+
+    def attn_forward(self, x, timer=None):
+        """x: this device's token rows [N x hidden].  Leaves the Wo product in attn_part."""
+        N, hd, io = self.N, self.hd, self.io
+        _call(timer, "ln1_fwd", lambda: hap.hap_layernorm_fwd(N, self.hidden, io, x, self.g1, self.be1, self.ln1, self.mean1, self.rstd1))
+        if hd == 0:
+            self.attn_part.zero_()
+            return
+        _call(timer, "qkv_fwd", lambda: hap.hap_sharded_linear_fwd(self.d_qkv, 0, self.ln1, self.Wqkv, self.bqkv, self.qkv, None))
+        q = self.qkv.data_ptr()
+        _call(timer, "attn_fwd", lambda: hap.hap_sharded_attn_fwd(self.d_attn, 0, q, q + hd * 2, q + 2 * hd * 2, self.o, self.lse))
+        _call(timer, "wo_fwd", lambda: hap.hap_sharded_linear_fwd(self.d_wo, 0, self.o, self.Wo, None, self.attn_part, None))
+
+    def mlp_forward(self, x1, timer=None):
+        N, io = self.N, self.io
+        _call(timer, "ln2_fwd", lambda: hap.hap_layernorm_fwd(N, self.hidden, io, x1, self.g2, self.be2, self.ln2, self.mean2, self.rstd2))
+        if self.f == 0:
+            self.mlp_part.zero_()
+            return
+        _call(timer, "fc1_fwd", lambda: hap.hap_sharded_linear_fwd(self.d_fc1, 0, self.ln2, self.W1, self.b1, self.H, self.pre))
+        _call(timer, "fc2_fwd", lambda: hap.hap_sharded_linear_fwd(self.d_fc2, 0, self.H, self.W2, None, self.mlp_part, None))
+
+    def mlp_backward(self, dy, timer=None):
+        """dy: gradient of the layer output on this device's rows.  Leaves the fc1 bwd-data product in dln2_part."""
+        if self.f == 0:
+            self.dln2_part.zero_()
+            return
+        _call(timer, "fc2_bwd", lambda: hap.hap_sharded_linear_bwd(self.d_fc2, 0, self.H, self.W2, None, dy, self.dH, self.dW2, self.io, None, self.ws))
+        _call(timer, "fc1_bwd", lambda: hap.hap_sharded_linear_bwd(self.d_fc1, 0, self.ln2, self.W1, self.pre, self.dH, self.dln2_part, self.dW1, self.io, self.db1, self.ws))
+
+    def ln2_backward(self, x1, dln2, timer=None):
+        _call(timer, "ln2_bwd", lambda: hap.hap_layernorm_bwd(self.N, self.hidden, self.io, x1, self.g2, self.mean2, self.rstd2, dln2, self.dx1_ln,
+                                                              self.dg2, self.dbe2, self.ws))
+
+    def attn_backward(self, dx1, timer=None):
+        """dx1: gradient at the residual stream after attention.  Leaves the QKV bwd-data product in dln1_part."""
+        hd = self.hd
+        if hd == 0:
+            self.dln1_part.zero_()
+            return
+        _call(timer, "wo_bwd", lambda: hap.hap_sharded_linear_bwd(self.d_wo, 0, self.o, self.Wo, None, dx1, self.do, self.dWo, self.io, None, self.ws))
+        q, dq = self.qkv.data_ptr(), self.dqkv.data_ptr()
+        _call(timer, "attn_bwd", lambda: hap.hap_sharded_attn_bwd(self.d_attn, 0, q, q + hd * 2, q + 2 * hd * 2, self.o, self.lse, self.do,
+                                                                  dq, dq + hd * 2, dq + 2 * hd * 2, self.ws))
+        _call(timer, "qkv_bwd", lambda: hap.hap_sharded_linear_bwd(self.d_qkv, 0, self.ln1, self.Wqkv, None, self.dqkv, self.dln1_part, self.dWqkv,
+                                                                   self.io, self.dbqkv, self.ws))
+
+    def ln1_backward(self, x, dln1, timer=None):
+        _call(timer, "ln1_bwd", lambda: hap.hap_layernorm_bwd(self.N, self.hidden, self.io, x, self.g1, self.mean1, self.rstd1, dln1, self.dx_ln,
+                                                              self.dg1, self.dbe1, self.ws))
+
+
+class EncoderLayerProgram:
+    """All virtual devices' EncoderShards run in turn on the one GPU.
+
+    What a cluster would do with collectives between stages is done here with sums over the
+    devices' partial results (hap_add): the All-Reduce of the Wo / W2 products in the forward and
+    of the bwd-data products in the backward ("tensor" style).  In "data" style a device's rows
+    never meet another device's, so no sums are needed (weight gradients stay per-device partials).
+    """
+
+    def __init__(self, style, B, S, hidden, heads, d, ffn, head_offsets, ffn_offsets, batch_offsets, params, x, dy):
+        self.style, self.hidden, self.S = style, hidden, S
+        self.params, self.x, self.dy = params, x, dy
+        m = (len(head_offsets) if style == "tensor" else len(batch_offsets)) - 1
+        self.shards = [EncoderShard(style, j, B, S, hidden, heads, d, ffn, head_offsets, ffn_offsets, batch_offsets, params) for j in range(m)]
+        N = B * S
+        self.N = N
+        z = lambda: torch.zeros((N, hidden), dtype=x.dtype, device=x.device)
+        self.x1, self.y, self.dx1, self.dx, self.red = z(), z(), z(), z(), z()
+        self.db2 = torch.zeros((hidden,), dtype=torch.float32, device=x.device)
+        self.dbo = torch.zeros((hidden,), dtype=torch.float32, device=x.device)
+        self.ws = torch.empty((max(hap.hap_colsum_workspace(N, hidden), 256),), dtype=torch.uint8, device=x.device)
+
+    def _add(self, n, a, b, bias, out):
+        hap.hap_add(n, self.hidden, hap.BF16, a, self.hidden, b, self.hidden, bias, out, self.hidden)
+
+    def _reduce(self, parts, out):
+        """out = sum of the devices' partial tensors (the All-Reduce)."""
+        if len(parts) == 1:
+            out.copy_(parts[0]); return
+        self._add(self.N, parts[0], parts[1], None, out)
+        for p in parts[2:]:
+            self._add(self.N, out, p, None, out)
+
+    def forward(self):
+        p, N = self.params, self.N
+        if self.style == "tensor":
+            for s in self.shards:
+                s.attn_forward(self.x)
+            self._reduce([s.attn_part for s in self.shards], self.red)
+            self._add(N, self.x, self.red, p["bo"], self.x1)
+            for s in self.shards:
+                s.mlp_forward(self.x1)
+            self._reduce([s.mlp_part for s in self.shards], self.red)
+            self._add(N, self.x1, self.red, p["b2"], self.y)
+        else:
+            for s in self.shards:
+                if s.N == 0:
+                    continue
+                xr, x1r, yr = s.rows(self.x), s.rows(self.x1), s.rows(self.y)
+                s.attn_forward(xr)
+                self._add(s.N, xr, s.attn_part, p["bo"], x1r)
+                s.mlp_forward(x1r)
+                self._add(s.N, x1r, s.mlp_part, p["b2"], yr)
+
+    def backward(self):
+        N = self.N
+        if self.style == "tensor":
+            s0 = self.shards[0]
+            for s in self.shards:
+                s.mlp_backward(self.dy)
+            self._reduce([s.dln2_part for s in self.shards], self.red)
+            s0.ln2_backward(self.x1, self.red)                       # replicated: every device computes the same
+            self._add(N, self.dy, s0.dx1_ln, None, self.dx1)
+            for s in self.shards:
+                s.attn_backward(self.dx1)
+            self._reduce([s.dln1_part for s in self.shards], self.red)
+            s0.ln1_backward(self.x, self.red)
+            self._add(N, self.dx1, s0.dx_ln, None, self.dx)
+        else:
+            for s in self.shards:
+                if s.N == 0:
+                    continue
+                xr, x1r, dyr, dx1r, dxr = (s.rows(t) for t in (self.x, self.x1, self.dy, self.dx1, self.dx))
+                s.mlp_backward(dyr)
+                s.ln2_backward(x1r, s.dln2_part)
+                self._add(s.N, dyr, s.dx1_ln, None, dx1r)
+                s.attn_backward(dx1r)
+                s.ln1_backward(xr, s.dln1_part)
+                self._add(s.N, dx1r, s.dx_ln, None, dxr)
+        hap.hap_colsum(N, self.hidden, hap.BF16, self.dy, self.hidden, self.db2, self.ws)
+        hap.hap_colsum(N, self.hidden, hap.BF16, self.dx1, self.hidden, self.dbo, self.ws)
