@@ -20,10 +20,12 @@
 #include <hip/hip_runtime.h>
 
 #include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
 
 #include "hap_gemm.h"
 
-namespace {
+namespace hap_gemm_detail {
 
 typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
 typedef short s16x4_t __attribute__((ext_vector_type(4)));
@@ -49,13 +51,42 @@ struct GemmArgs {
   int skewK;           // physical k preceding logical 0 in a K-contiguous operand
   int nseg;
   int tiles_m, tiles_n;
+  int vec_store;       // C (and preact) rows are 16-byte addressable: whole-chunk stores allowed
+  int ntiles;          // K tiles over all segments at the direct-to-LDS kernel's BK (0 for the staged kernel)
   long long lda, ldb, ldc, ldp;
   void* c;
   void* preact;
   const void* bias;
   int act, accumulate;
+#ifdef HAP_EXP_TRACE
+  void* trace;
+#endif
   SegArg seg[HAP_GEMM_MAX_SEG];
 };
+
+/* Values that are the same in every lane but that the compiler cannot prove uniform (they depend on
+ * a table entry picked by a loop-carried index) are pinned to scalar registers; otherwise every
+ * buffer instruction using them is wrapped in a per-lane "waterfall" loop. */
+__device__ __forceinline__ int uni(int v) { return __builtin_amdgcn_readfirstlane(v); }
+__device__ __forceinline__ const void* uni(const void* p) {
+  const unsigned long long v = reinterpret_cast<unsigned long long>(p);
+  const unsigned lo = __builtin_amdgcn_readfirstlane((unsigned)v), hi = __builtin_amdgcn_readfirstlane((unsigned)(v >> 32));
+  return reinterpret_cast<const void*>(((unsigned long long)hi << 32) | lo);
+}
+
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* base, unsigned bytes) {
+  return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(uni(base)), 0, uni((int)bytes), kRsrcFlags);
+}
+
+/* One wave-wide direct load: lane l's 16 bytes at (voff + soff) of the buffer land at lds + 16*l.
+ * `lds` must be wave-uniform.  The host pass of hipcc has no such builtin, hence the guard. */
+__device__ __forceinline__ void dma16(__amdgpu_buffer_rsrc_t rsrc, char* lds, unsigned voff, unsigned soff) {
+#if defined(__HIP_DEVICE_COMPILE__)
+  __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, LDS_PTR(void, lds), 16, voff, soff, 0, 0);
+#else
+  (void)rsrc; (void)lds; (void)voff; (void)soff;
+#endif
+}
 
 __device__ __forceinline__ float gelu_erf(float x) { return 0.5f * x * (1.0f + erff(x * 0.70710678118654752f)); }
 
@@ -67,15 +98,23 @@ template <> struct Elem<float> {
   static constexpr int kStep = 2;   // v_mfma_f32_32x32x2_f32
 };
 
-/* Swizzled position of 16-byte chunk c in LDS row `row`. */
+/* Swizzled position of 16-byte chunk c in LDS row `row`.  The LDS of gfx950 serves 256 bytes per clock
+ * (64 banks x 4 bytes): a 128-bit read is conflict free when every 16 consecutive lanes cover 16
+ * different chunk positions modulo 256 bytes, a transposing 64-bit read when every 32 lanes do.
+ *   K-contiguous tile: 16 lanes read the same logical chunk of 16 consecutive rows -> XOR the chunk
+ *     index with the row's index inside its 256-byte group.
+ *   M/N-contiguous tile (rows are 512 bytes or more): 32 lanes read 64 contiguous bytes of each of 4
+ *     consecutive rows -> XOR bits 2..3 of the chunk index with row & 3.                              */
 template <bool KC, int CPR>
 __device__ __forceinline__ int swz(int row, int c) {
   if constexpr (KC) {
-    constexpr int RPS = CPR >= 8 ? 1 : 8 / CPR;      // rows per 128-byte bank sweep
-    constexpr int MASK = (CPR >= 8 ? 8 : CPR) - 1;
+    constexpr int RPS = CPR >= 16 ? 1 : 16 / CPR;    // rows per 256-byte bank sweep
+    constexpr int MASK = (CPR >= 16 ? 16 : CPR) - 1;
     return c ^ ((row / RPS) & MASK);
   } else {
-    return c ^ ((row & 3) << 1);
+    static_assert(CPR >= 8, "M/N-contiguous tiles need rows of at least 128 bytes");
+    if constexpr (CPR >= 16) return c ^ ((row & 3) << 2);
+    else return c ^ ((row & 3) << 1);
   }
 }
 
@@ -223,6 +262,37 @@ __device__ __forceinline__ void tile_of_block(int bid, int nblocks, int tiles_m,
   *tn = in_group / gsize;
 }
 
+/* Writes a wave's TM x TN accumulator tiles.  Accumulator element e of lane l is row
+ * (e/4)*8 + (l/32)*4 + e%4, column l%32 of its 32x32 tile.  (row0, col0): physical origin of the
+ * wave tile; rows / columns outside the logical extent are dropped. */
+template <typename T, typename TC, int TM, int TN>
+__device__ __forceinline__ void epilogue(const GemmArgs& args, f32x16_t (&acc)[TM][TN], int row0, int col0, int lane) {
+  TC* C = static_cast<TC*>(args.c);
+  TC* P = static_cast<TC*>(args.preact);
+  const T* bias = static_cast<const T*>(args.bias);
+#pragma unroll
+  for (int j = 0; j < TN; ++j) {
+    const int n = col0 + j * 32 + (lane & 31) - args.skewN;
+    const bool n_ok = n >= 0 && n < args.N;
+    const float bv = (bias && n_ok) ? load_s<T>(bias + n) : 0.0f;
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        const int m = row0 + i * 32 + (e >> 2) * 8 + (lane >> 5) * 4 + (e & 3) - args.skewM;
+        if (n_ok && m >= 0 && m < args.M) {
+          float v = acc[i][j][e] + bv;
+          if (P) store_c<TC>(P + (long long)m * args.ldp + n, v);
+          if (args.act == HAP_ACT_GELU_ERF) v = gelu_erf(v);
+          TC* dst = C + (long long)m * args.ldc + n;
+          if (args.accumulate) v += load_s<TC>(dst);
+          store_c<TC>(dst, v);
+        }
+      }
+    }
+  }
+}
+
 template <typename T, typename TC, bool AKC, bool BKC, int BM, int BN, int BK, int WGM, int WGN>
 __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(const GemmArgs args) {
   constexpr int NT = 64 * WGM * WGN;
@@ -256,8 +326,8 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(const GemmArgs arg
   // loader state runs one tile ahead of the compute
   int seg = 0, k0 = 0;
   int kend = args.skewK + args.seg[0].k;
-  __amdgpu_buffer_rsrc_t ra = __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(args.seg[0].a), 0, args.seg[0].a_bytes, kRsrcFlags);
-  __amdgpu_buffer_rsrc_t rb = __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(args.seg[0].b), 0, args.seg[0].b_bytes, kRsrcFlags);
+  __amdgpu_buffer_rsrc_t ra = make_rsrc(args.seg[0].a, args.seg[0].a_bytes);
+  __amdgpu_buffer_rsrc_t rb = make_rsrc(args.seg[0].b, args.seg[0].b_bytes);
 
   auto fetch = [&]() {
     la.load(ra, tid, m0, m_lim, args.lda, k0, args.skewK, kend);
@@ -282,9 +352,10 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(const GemmArgs arg
       ++seg;
       if (seg < args.nseg) {
         k0 = 0;
-        kend = args.skewK + args.seg[seg].k;
-        ra = __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(args.seg[seg].a), 0, args.seg[seg].a_bytes, kRsrcFlags);
-        rb = __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(args.seg[seg].b), 0, args.seg[seg].b_bytes, kRsrcFlags);
+        seg = uni(seg);
+        kend = uni(args.skewK + args.seg[seg].k);
+        ra = make_rsrc(args.seg[seg].a, args.seg[seg].a_bytes);
+        rb = make_rsrc(args.seg[seg].b, args.seg[seg].b_bytes);
       } else {
         more = false;
       }
@@ -309,31 +380,461 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(const GemmArgs arg
     __syncthreads();
   }
 
-  // epilogue: accumulator element e of lane l is row (e/4)*8 + (l/32)*4 + e%4, column l%32
+  epilogue<T, TC, TM, TN>(args, acc, m0 + wm0, n0 + wn0, lane);
+}
+
+/* Epilogue of the direct-to-LDS kernels.  Their accumulators are TRANSPOSED tiles (the MFMA is fed
+ * B-fragment first), so element e of lane l belongs to output row l%32 and columns
+ * (e/4)*8 + (l/32)*4 + e%4: four consecutive columns per register quad.  Each wave passes one
+ * 32-row block at a time through a private LDS patch and writes it out as whole 16-byte chunks,
+ * eight (bf16) or four (fp32) lanes per 128-byte line, instead of 2-byte scattered stores.
+ * Bias, activation, the optional pre-activation copy and fp32 accumulation are applied on the way.
+ * Falls back to element stores where the destination is not 16-byte addressable or at ragged ends. */
+template <typename TC> struct Vec16;
+template <> struct Vec16<__bf16> { typedef __bf16 type __attribute__((ext_vector_type(8))); };
+template <> struct Vec16<float> { typedef float type __attribute__((ext_vector_type(4))); };
+
+template <typename T, typename TC, int TM, int TN>
+__device__ __forceinline__ void epilogue_transposed(const GemmArgs& args, f32x16_t (&acc)[TM][TN], int row0, int col0, int lane, char* patch) {
+  constexpr int ES = sizeof(TC);
+  constexpr int EPC = 16 / ES;
+  constexpr int COLS = TN * 32;
+  constexpr int ROWB = COLS * ES + 16;            // padded row of the LDS patch
+  constexpr int CH = COLS * ES / 16;              // 16-byte chunks per row
+  typedef typename Vec16<TC>::type vec_t;
   TC* C = static_cast<TC*>(args.c);
   TC* P = static_cast<TC*>(args.preact);
   const T* bias = static_cast<const T*>(args.bias);
+  const int h = lane >> 5, ml = lane & 31;
+  const bool vec_ok = args.vec_store != 0;
 #pragma unroll
-  for (int j = 0; j < TN; ++j) {
-    const int n = n0 + wn0 + j * 32 + (lane & 31) - args.skewN;
-    const bool n_ok = n >= 0 && n < args.N;
-    const float bv = (bias && n_ok) ? load_s<T>(bias + n) : 0.0f;
+  for (int i = 0; i < TM; ++i) {
 #pragma unroll
-    for (int i = 0; i < TM; ++i) {
+    for (int pass = 0; pass < 2; ++pass) {
+      if (pass == 0 && !P) continue;
+      TC* dst_base = pass == 0 ? P : C;
+      const long long ldd = pass == 0 ? args.ldp : args.ldc;
+      // registers -> LDS patch [32 rows][COLS]
 #pragma unroll
-      for (int e = 0; e < 16; ++e) {
-        const int m = m0 + wm0 + i * 32 + (e >> 2) * 8 + (lane >> 5) * 4 + (e & 3) - args.skewM;
-        if (n_ok && m >= 0 && m < args.M) {
-          float v = acc[i][j][e] + bv;
-          if (P) store_c<TC>(P + (long long)m * args.ldp + n, v);
-          if (args.act == HAP_ACT_GELU_ERF) v = gelu_erf(v);
-          TC* dst = C + (long long)m * args.ldc + n;
-          if (args.accumulate) v += load_s<TC>(dst);
-          store_c<TC>(dst, v);
+      for (int j = 0; j < TN; ++j)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          const int cl = j * 32 + g * 8 + h * 4;            // first of 4 consecutive columns
+          TC v[4];
+#pragma unroll
+          for (int x = 0; x < 4; ++x) {
+            float f = acc[i][j][g * 4 + x];
+            if (bias) {
+              const int n = col0 + cl + x - args.skewN;
+              f += (n >= 0 && n < args.N) ? load_s<T>(bias + n) : 0.0f;
+            }
+            if (pass == 1 && args.act == HAP_ACT_GELU_ERF) f = gelu_erf(f);
+            v[x] = (TC)f;
+          }
+          __builtin_memcpy(patch + ml * ROWB + cl * ES, v, 4 * ES);
+        }
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+      __builtin_amdgcn_wave_barrier();
+      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+      // LDS patch -> global, 16 bytes per lane
+#pragma unroll
+      for (int it = 0; it < 32 * CH / 64; ++it) {
+        const int idx = it * 64 + lane;
+        const int r = idx / CH, c = idx % CH;
+        const int m = row0 + i * 32 + r - args.skewM;
+        const int n = col0 + c * EPC - args.skewN;
+        if (m < 0 || m >= args.M || n >= args.N || n + EPC <= 0) continue;
+        vec_t val = *reinterpret_cast<const vec_t*>(patch + r * ROWB + c * 16);
+        TC* dst = dst_base + (long long)m * ldd + n;
+        if (vec_ok && n >= 0 && n + EPC <= args.N) {
+          if (pass == 1 && args.accumulate) {
+            const vec_t old = *reinterpret_cast<const vec_t*>(dst);
+#pragma unroll
+            for (int x = 0; x < EPC; ++x) val[x] = (TC)((float)val[x] + (float)old[x]);
+          }
+          *reinterpret_cast<vec_t*>(dst) = val;
+        } else {
+#pragma unroll
+          for (int x = 0; x < EPC; ++x)
+            if (n + x >= 0 && n + x < args.N) {
+              float f = (float)val[x];
+              if (pass == 1 && args.accumulate) f += load_s<TC>(dst + x);
+              store_c<TC>(dst + x, f);
+            }
+        }
+      }
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+      __builtin_amdgcn_wave_barrier();
+      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    }
+  }
+}
+
+/* ---------------------------------------------------------------------------------------------
+ * bf16 main kernel: global -> LDS by buffer loads that write LDS directly (no register staging),
+ * STAGES-deep ring of tiles, one barrier per tile.
+ *
+ * A wave-wide direct load writes 64 lanes x 16 bytes to CONSECUTIVE LDS bytes, so the XOR swizzle is
+ * applied on the global side: the lane that fills LDS chunk position p of a row fetches the chunk
+ * whose swizzled position is p.  Interior tiles use precomputed per-lane offsets plus one scalar
+ * offset per tile; the first / last tile of a segment recompute validity per chunk and, for
+ * K-contiguous operands, zero the elements outside the logical k range in LDS once the data landed.
+ * ------------------------------------------------------------------------------------------- */
+template <bool KC, int ROWS, int BK, int NT>
+struct DmaLoader {
+  static constexpr int EPC = 8;
+  static constexpr int LROWS = KC ? ROWS : BK;
+  static constexpr int CPR = (KC ? BK : ROWS) / EPC;
+  static constexpr int CPT = LROWS * CPR / NT;
+  static constexpr int TILE_BYTES = ROWS * BK * 2;
+  static_assert(LROWS * CPR % NT == 0, "tile chunks must divide evenly over threads");
+
+  unsigned base[CPT];   // byte offset of this lane's chunk for k0 = 0, or the out-of-range marker
+
+  /* LDS position id -> (row, logical chunk) */
+  static __device__ __forceinline__ void where(int id, int* row, int* c) {
+    *row = id / CPR;
+    *c = swz<KC, CPR>(*row, id % CPR);
+  }
+
+  __device__ __forceinline__ void init(int tid, int mn0, int mn_lim, long long ld) {
+#pragma unroll
+    for (int i = 0; i < CPT; ++i) {
+      int row, c;
+      where(tid + i * NT, &row, &c);
+      if constexpr (KC) {
+        const int mn = mn0 + row;
+        base[i] = mn < mn_lim ? (unsigned)(((long long)mn * ld + c * EPC) * 2) : kOobOffset;
+      } else {
+        const int mn = mn0 + c * EPC;
+        base[i] = mn < mn_lim ? (unsigned)(((long long)row * ld + mn) * 2) : kOobOffset;
+      }
+    }
+  }
+
+  /* Byte offset of a tile starting at physical k0: k0 elements along a row (KC) or (k0 - kskew) rows. */
+  static __device__ __forceinline__ unsigned tile_offset(int k0, int kskew, long long ld) {
+    if constexpr (KC) return (unsigned)k0 * 2u;
+    else return (unsigned)((long long)(k0 - kskew) * ld * 2);
+  }
+
+  /* Interior tile: every k of the tile is inside the logical range; soff = tile_offset() >= 0 goes in
+   * the instruction's scalar offset. */
+  __device__ __forceinline__ void issue(__amdgpu_buffer_rsrc_t rsrc, char* lds, int tid, unsigned soff) const {
+    const int wave_first = (tid & ~63);
+#pragma unroll
+    for (int i = 0; i < CPT; ++i) dma16(rsrc, lds + (wave_first + i * NT) * 16, base[i], soff);
+  }
+
+  /* Edge tile: validity along k decided per chunk; the tile offset (which may be "negative" for the
+   * rows a skewed first tile does not use) is added per lane so valid chunks get an exact offset. */
+  __device__ __forceinline__ void issue_edge(__amdgpu_buffer_rsrc_t rsrc, char* lds, int tid, unsigned toff, int k0, int kskew, int kend) const {
+    const int wave_first = (tid & ~63);
+#pragma unroll
+    for (int i = 0; i < CPT; ++i) {
+      int row, c;
+      where(tid + i * NT, &row, &c);
+      bool ok;
+      if constexpr (KC) { const int kp = k0 + c * EPC; ok = kp < kend && kp + EPC > kskew; }
+      else { const int kl = k0 + row; ok = kl >= kskew && kl < kend; }
+      ok = ok && base[i] != kOobOffset;
+      dma16(rsrc, lds + (wave_first + i * NT) * 16, ok ? base[i] + toff : kOobOffset, 0);
+    }
+  }
+
+  /* After the edge tile landed: zero elements outside [kskew, kend) in this thread's own chunks. */
+  __device__ __forceinline__ void fixup(char* lds, int tid, int k0, int kskew, int kend) const {
+    if constexpr (KC) {
+#pragma unroll
+      for (int i = 0; i < CPT; ++i) {
+        int row, c;
+        where(tid + i * NT, &row, &c);
+        const int kp = k0 + c * EPC;
+        if (kp < kend && kp + EPC > kskew && (kp < kskew || kp + EPC > kend)) {
+          i32x4_t* q = reinterpret_cast<i32x4_t*>(lds + (tid + i * NT) * 16);
+          bf16x8_t v = __builtin_bit_cast(bf16x8_t, *q);
+#pragma unroll
+          for (int e = 0; e < EPC; ++e)
+            if (kp + e < kskew || kp + e >= kend) v[e] = (__bf16)0.0f;
+          *q = __builtin_bit_cast(i32x4_t, v);
         }
       }
     }
   }
+};
+
+template <typename TC, bool AKC, bool BKC, int BM, int BN, int BK, int WGM, int WGN, int STAGES>
+__global__ __launch_bounds__(64 * WGM * WGN) void gemm_dma_kernel(const GemmArgs args) {
+  typedef __bf16 T;
+  constexpr int NT = 64 * WGM * WGN;
+  constexpr int WTM = BM / WGM, WTN = BN / WGN;
+  constexpr int TM = WTM / 32, TN = WTN / 32;
+  constexpr int A_BYTES = BM * BK * 2, B_BYTES = BN * BK * 2, STAGE_BYTES = A_BYTES + B_BYTES;
+  typedef DmaLoader<AKC, BM, BK, NT> LA;
+  typedef DmaLoader<BKC, BN, BK, NT> LB;
+  constexpr int LOADS_PER_TILE = LA::CPT + LB::CPT;
+
+  extern __shared__ __attribute__((aligned(16))) char smem[];
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm0 = (wave / WGN) * WTM, wn0 = (wave % WGN) * WTN;
+  int tm, tn;
+  tile_of_block(blockIdx.x, gridDim.x, args.tiles_m, args.tiles_n, &tm, &tn);
+  const int m0 = tm * BM, n0 = tn * BN;
+  const int m_lim = args.skewM + args.M, n_lim = args.skewN + args.N;
+
+  LA la; LB lb;
+  la.init(tid, m0, m_lim, args.lda);
+  lb.init(tid, n0, n_lim, args.ldb);
+
+  f32x16_t acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
+
+  // producer state (runs STAGES-1 tiles ahead of the consumer)
+  int pseg = 0, pk0 = 0, pkend = args.skewK + args.seg[0].k, pslot = 0;
+  __amdgpu_buffer_rsrc_t ra = make_rsrc(args.seg[0].a, args.seg[0].a_bytes);
+  __amdgpu_buffer_rsrc_t rb = make_rsrc(args.seg[0].b, args.seg[0].b_bytes);
+  // consumer state: k range of the tile being consumed (for the edge fix-up)
+  int cseg = 0, ck0 = 0, ckend = pkend, cslot = 0;
+  const int ntiles = args.ntiles;
+
+  for (int t = -(STAGES - 1); t < ntiles; ++t) {
+    char* sa = smem + cslot * STAGE_BYTES;
+    char* sb = sa + A_BYTES;
+#ifdef HAP_EXP_TRACE
+    long long ts0 = __builtin_readcyclecounter(), ts1 = 0, ts2 = 0, ts3 = 0;
+#endif
+    if (t >= 0) {
+      // tile t must have landed; up to STAGES-2 newer tiles may stay in flight
+      if (STAGES > 2 && t + STAGES - 2 < ntiles) asm volatile("s_waitcnt vmcnt(%0)" ::"n"((STAGES - 2) * LOADS_PER_TILE) : "memory");
+      else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+      if (ck0 < args.skewK || ck0 + BK > ckend) {
+        la.fixup(sa, tid, ck0, args.skewK, ckend);
+        lb.fixup(sb, tid, ck0, args.skewK, ckend);
+      }
+      ck0 += BK;
+      if (ck0 >= ckend && cseg + 1 < args.nseg) { ++cseg; ck0 = 0; ckend = args.skewK + args.seg[cseg].k; }
+#ifdef HAP_EXP_TRACE
+      ts1 = __builtin_readcyclecounter();
+#endif
+      __syncthreads();          // tile visible to all waves; every wave is done with the slot refilled below
+#ifdef HAP_EXP_TRACE
+      ts2 = __builtin_readcyclecounter();
+#endif
+    }
+    if (t + STAGES - 1 < ntiles) {
+      char* pa = smem + pslot * STAGE_BYTES;
+      char* pb = pa + A_BYTES;
+      const bool edge = pk0 < args.skewK || pk0 + BK > pkend;
+      const unsigned soa = LA::tile_offset(pk0, args.skewK, args.lda);
+      const unsigned sob = LB::tile_offset(pk0, args.skewK, args.ldb);
+      if (!edge) {
+        la.issue(ra, pa, tid, soa);
+        lb.issue(rb, pb, tid, sob);
+      } else {
+        la.issue_edge(ra, pa, tid, soa, pk0, args.skewK, pkend);
+        lb.issue_edge(rb, pb, tid, sob, pk0, args.skewK, pkend);
+      }
+      pslot = pslot + 1 == STAGES ? 0 : pslot + 1;
+      pk0 += BK;
+      if (pk0 >= pkend && pseg + 1 < args.nseg) {
+        pseg = uni(pseg + 1);
+        pk0 = 0;
+        pkend = uni(args.skewK + args.seg[pseg].k);
+        ra = make_rsrc(args.seg[pseg].a, args.seg[pseg].a_bytes);
+        rb = make_rsrc(args.seg[pseg].b, args.seg[pseg].b_bytes);
+      }
+    }
+    if (t >= 0) {
+#pragma unroll
+      for (int kk = 0; kk < BK / 16; ++kk) {
+        bf16x8_t fa[TM], fb[TN];
+#pragma unroll
+        for (int i = 0; i < TM; ++i) fa[i] = Frag<T, AKC, BM, BK>::read(sa, wm0 + i * 32, kk, lane);
+#pragma unroll
+        for (int j = 0; j < TN; ++j) fb[j] = Frag<T, BKC, BN, BK>::read(sb, wn0 + j * 32, kk, lane);
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+          for (int j = 0; j < TN; ++j) acc[i][j] = mfma(fb[j], fa[i], acc[i][j]);
+      }
+      cslot = cslot + 1 == STAGES ? 0 : cslot + 1;
+    }
+#ifdef HAP_EXP_TRACE
+    ts3 = __builtin_readcyclecounter();
+    if (blockIdx.x == 8 && lane == 0 && t >= 0 && t < 64) {
+      long long* tr = reinterpret_cast<long long*>(args.trace) + (wave * 64 + t) * 4;
+      tr[0] = ts0; tr[1] = ts1; tr[2] = ts2; tr[3] = ts3;
+    }
+#endif
+  }
+
+#ifdef HAP_EXP_TRACE
+  long long te0 = __builtin_readcyclecounter();
+#endif
+  __syncthreads();   // every wave is done reading the ring: reuse it as per-wave store patches
+  epilogue_transposed<T, TC, TM, TN>(args, acc, m0 + wm0, n0 + wn0, lane, smem + wave * (32 * (TN * 32 * (int)sizeof(TC) + 16)));
+#ifdef HAP_EXP_TRACE
+  if (blockIdx.x == 8 && lane == 0) { long long* tr = reinterpret_cast<long long*>(args.trace) + 8 * 64 * 4 + wave * 2; tr[0] = te0; tr[1] = __builtin_readcyclecounter(); }
+#endif
+}
+
+/* ---------------------------------------------------------------------------------------------
+ * Software-pipelined form of the direct-to-LDS kernel (STAGES >= 3).
+ *
+ * MFMA fragments are double-buffered in registers: while the MFMAs of k-step kk run, the LDS reads
+ * of k-step kk+1 are already in flight - across tile boundaries too, because the one barrier per
+ * tile sits BEFORE the last k-step of the current tile, where it (a) publishes tile t+1, which was
+ * requested STAGES-1 tiles ago, and (b) proves that every wave has left tile t-1, whose ring slot is
+ * then refilled with tile t+STAGES-1.
+ * ------------------------------------------------------------------------------------------- */
+template <typename TC, bool AKC, bool BKC, int BM, int BN, int BK, int WGM, int WGN, int STAGES>
+__global__ __launch_bounds__(64 * WGM * WGN) void gemm_pipe_kernel(const GemmArgs args) {
+  typedef __bf16 T;
+  static_assert(STAGES >= 3, "needs a free ring slot while two tiles are live");
+  constexpr int NT = 64 * WGM * WGN;
+  constexpr int WTM = BM / WGM, WTN = BN / WGN;
+  constexpr int TM = WTM / 32, TN = WTN / 32;
+  constexpr int KK = BK / 16;
+  static_assert(KK % 2 == 0, "fragment double buffer parity must repeat per tile");
+  constexpr int A_BYTES = BM * BK * 2, B_BYTES = BN * BK * 2, STAGE_BYTES = A_BYTES + B_BYTES;
+  typedef DmaLoader<AKC, BM, BK, NT> LA;
+  typedef DmaLoader<BKC, BN, BK, NT> LB;
+  constexpr int LOADS_PER_TILE = LA::CPT + LB::CPT;
+  typedef Frag<T, AKC, BM, BK> FA;
+  typedef Frag<T, BKC, BN, BK> FB;
+
+  extern __shared__ __attribute__((aligned(16))) char smem[];
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm0 = (wave / WGN) * WTM, wn0 = (wave % WGN) * WTN;
+  int tm, tn;
+  tile_of_block(blockIdx.x, gridDim.x, args.tiles_m, args.tiles_n, &tm, &tn);
+  const int m0 = tm * BM, n0 = tn * BN;
+  const int m_lim = args.skewM + args.M, n_lim = args.skewN + args.N;
+
+  LA la; LB lb;
+  la.init(tid, m0, m_lim, args.lda);
+  lb.init(tid, n0, n_lim, args.ldb);
+
+  f32x16_t acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
+
+  int pseg = 0, pk0 = 0, pkend = args.skewK + args.seg[0].k, pslot = 0;
+  int cseg = 0, ck0 = 0, ckend = pkend;     // k range of the NEXT tile to be published
+  const int ntiles = args.ntiles;
+
+#define HAP_PRODUCE()                                                                            \
+  do {                                                                                           \
+    pslot = uni(pslot); pk0 = uni(pk0); pkend = uni(pkend); pseg = uni(pseg);                    \
+    char* pa = smem + pslot * STAGE_BYTES;                                                       \
+    char* pb = pa + A_BYTES;                                                                     \
+    const __amdgpu_buffer_rsrc_t ra = make_rsrc(args.seg[pseg].a, args.seg[pseg].a_bytes);       \
+    const __amdgpu_buffer_rsrc_t rb = make_rsrc(args.seg[pseg].b, args.seg[pseg].b_bytes);       \
+    const bool edge = pk0 < args.skewK || pk0 + BK > pkend;                                      \
+    const unsigned soa = (unsigned)uni((int)LA::tile_offset(pk0, args.skewK, args.lda));         \
+    const unsigned sob = (unsigned)uni((int)LB::tile_offset(pk0, args.skewK, args.ldb));         \
+    if (!edge) { la.issue(ra, pa, tid, soa); lb.issue(rb, pb, tid, sob); }                       \
+    else { la.issue_edge(ra, pa, tid, soa, pk0, args.skewK, pkend); lb.issue_edge(rb, pb, tid, sob, pk0, args.skewK, pkend); } \
+    pslot = pslot + 1 == STAGES ? 0 : pslot + 1;                                                 \
+    pk0 += BK;                                                                                   \
+    if (pk0 >= pkend && pseg + 1 < args.nseg) {                                                  \
+      pseg = uni(pseg + 1); pk0 = 0; pkend = uni(args.skewK + args.seg[pseg].k);                  \
+    }                                                                                            \
+  } while (0)
+
+  /* Waits until the oldest outstanding tile has landed, patches its k edges, publishes it.  NEWER:
+   * tiles requested after it that may stay in flight when the ring is full (`steady`). */
+#define HAP_PUBLISH(slot_ptr, steady, NEWER)                                                     \
+  do {                                                                                           \
+    ck0 = uni(ck0); ckend = uni(ckend); cseg = uni(cseg);                                        \
+    if ((NEWER) > 0 && (steady)) asm volatile("s_waitcnt vmcnt(%0)" ::"n"((NEWER) * LOADS_PER_TILE) : "memory"); \
+    else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");                                        \
+    if (ck0 < args.skewK || ck0 + BK > ckend) {                                                  \
+      la.fixup(slot_ptr, tid, ck0, args.skewK, ckend);                                           \
+      lb.fixup(slot_ptr + A_BYTES, tid, ck0, args.skewK, ckend);                                 \
+    }                                                                                            \
+    ck0 += BK;                                                                                   \
+    if (ck0 >= ckend && cseg + 1 < args.nseg) { cseg = uni(cseg + 1); ck0 = 0; ckend = uni(args.skewK + args.seg[cseg].k); } \
+    __syncthreads();                                                                             \
+  } while (0)
+
+  // prologue: request STAGES-1 tiles, publish tile 0, fetch its first fragments
+  int requested = 0;
+#pragma unroll
+  for (int s = 0; s < STAGES - 1; ++s)
+    if (requested < ntiles) { HAP_PRODUCE(); ++requested; }
+  HAP_PUBLISH(smem, requested == STAGES - 1, STAGES - 2);
+
+  bf16x8_t fa[2][TM], fb[2][TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i) fa[0][i] = FA::read(smem, wm0 + i * 32, 0, lane);
+#pragma unroll
+  for (int j = 0; j < TN; ++j) fb[0][j] = FB::read(smem + A_BYTES, wn0 + j * 32, 0, lane);
+
+  // Steady state: every tile but the last has a successor to publish and prefetch, so the loop body is
+  // straight-line (no join points that would make the compiler wait for the prefetched fragments early).
+  int cslot = 0;
+  for (int t = 0; t + 1 < ntiles; ++t) {
+    char* sa = smem + cslot * STAGE_BYTES;
+    const int nslot = cslot + 1 == STAGES ? 0 : cslot + 1;
+    char* na = smem + nslot * STAGE_BYTES;
+#pragma unroll
+    for (int kk = 0; kk < KK; ++kk) {
+      const int cur = kk & 1, nxt = cur ^ 1;
+      if (kk == KK - 1) {
+        // tile t+1 was requested STAGES-1 tiles ago; tiles t+2 .. requested-1 may stay in flight
+        HAP_PUBLISH(na, requested - (t + 2) >= STAGES - 3, STAGES - 3);
+        if (requested < ntiles) { HAP_PRODUCE(); ++requested; }
+#pragma unroll
+        for (int i = 0; i < TM; ++i) fa[nxt][i] = FA::read(na, wm0 + i * 32, 0, lane);
+#pragma unroll
+        for (int j = 0; j < TN; ++j) fb[nxt][j] = FB::read(na + A_BYTES, wn0 + j * 32, 0, lane);
+      } else {
+#pragma unroll
+        for (int i = 0; i < TM; ++i) fa[nxt][i] = FA::read(sa, wm0 + i * 32, kk + 1, lane);
+#pragma unroll
+        for (int j = 0; j < TN; ++j) fb[nxt][j] = FB::read(sa + A_BYTES, wn0 + j * 32, kk + 1, lane);
+      }
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j) acc[i][j] = mfma(fb[cur][j], fa[cur][i], acc[i][j]);
+    }
+    cslot = nslot;
+  }
+  {  // last tile: nothing left to publish
+    char* sa = smem + cslot * STAGE_BYTES;
+#pragma unroll
+    for (int kk = 0; kk < KK; ++kk) {
+      const int cur = kk & 1, nxt = cur ^ 1;
+      if (kk + 1 < KK) {
+#pragma unroll
+        for (int i = 0; i < TM; ++i) fa[nxt][i] = FA::read(sa, wm0 + i * 32, kk + 1, lane);
+#pragma unroll
+        for (int j = 0; j < TN; ++j) fb[nxt][j] = FB::read(sa + A_BYTES, wn0 + j * 32, kk + 1, lane);
+      }
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j) acc[i][j] = mfma(fb[cur][j], fa[cur][i], acc[i][j]);
+    }
+  }
+#undef HAP_PRODUCE
+#undef HAP_PUBLISH
+
+  __syncthreads();   // every wave is done reading the ring: reuse it as per-wave store patches
+  epilogue_transposed<T, TC, TM, TN>(args, acc, m0 + wm0, n0 + wn0, lane, smem + wave * (32 * (TN * 32 * (int)sizeof(TC) + 16)));
 }
 
 /* Scalar fallback for operand views the tiled kernel cannot address with aligned 16-byte chunks
@@ -372,18 +873,37 @@ __global__ __launch_bounds__(256) void gemm_generic_kernel(const GenericArgs g) 
   store_c<TC>(dst, acc);
 }
 
+/* Kernel variant for large bf16 problems; HAP_GEMM_KERNEL=staged|dma2|pipe4|pipe3 overrides the default (tuning aid). */
+int dma_variant() {
+  static int v = -1;
+  if (v < 0) {
+    const char* e = getenv("HAP_GEMM_KERNEL");
+    v = 1;
+    if (e) {
+      if (!strcmp(e, "staged")) v = 0;
+      else if (!strcmp(e, "dma2")) v = 1;
+      else if (!strcmp(e, "pipe4")) v = 2;
+      else if (!strcmp(e, "pipe3")) v = 3;
+      else if (!strcmp(e, "dma2w4")) v = 4;
+      else if (!strcmp(e, "pipe4w4")) v = 5;
+    }
+  }
+  return v;
+}
+
 struct Plan {
   bool tiled;
   int skewM, skewN, skewK;
   int bm, bn;       // tile
   const char* name;
+  int dma;          // 0: register-staged kernel; else direct-to-LDS kernel variant (1: 2 stages x BK 64, 2: 4 x 32, 3: 3 x 32)
 };
 
 inline int esize(int dtype) { return dtype == HAP_BF16 ? 2 : 4; }
 
 /* Decides whether the aligned-chunk kernel can address the operands and with which skews. */
 Plan make_plan(const hap_gemm_problem* p) {
-  Plan pl = {false, 0, 0, 0, 0, 0, "generic"};
+  Plan pl = {false, 0, 0, 0, 0, 0, "generic", 0};
   if (p->force_generic) return pl;
   const int es = esize(p->in_dtype);
   if ((p->lda * es) % 16 || (p->ldb * es) % 16) return pl;
@@ -408,7 +928,13 @@ Plan make_plan(const hap_gemm_problem* p) {
   }
   pl.tiled = true;
   if (p->in_dtype == HAP_F32) { pl.bm = pl.bn = 64; pl.name = "f32_64x64x16"; }
-  else if (p->M + pl.skewM > 128 && p->N + pl.skewN > 128) { pl.bm = pl.bn = 256; pl.name = "bf16_256x256x64"; }
+  else if (p->M + pl.skewM > 128 && p->N + pl.skewN > 128) {
+    pl.bm = pl.bn = 256;
+    pl.dma = dma_variant();
+    static const char* names[] = {"bf16_256x256x64_staged", "bf16_256x256x64_dma2", "bf16_256x256x32_pipe4", "bf16_256x256x32_pipe3",
+                                  "bf16_256x256x64_dma2_4waves", "bf16_256x256x32_pipe4_4waves"};
+    pl.name = names[pl.dma];
+  }
   else { pl.bm = pl.bn = 128; pl.name = "bf16_128x128x64"; }
   return pl;
 }
@@ -420,6 +946,56 @@ int launch_tiled(const GemmArgs& a, hipStream_t st) {
   const hipError_t e = hipGetLastError();
   if (e != hipSuccess) return hap_fail(HAP_EDEVICE, "gemm launch: %s", hipGetErrorString(e));
   return HAP_OK;
+}
+
+template <typename TC, bool AKC, bool BKC, int BK, int STAGES, int WGM = 2, int WGN = 4>
+int launch_dma(const GemmArgs& a, hipStream_t st) {
+  constexpr int BM = 256, BN = 256;
+  constexpr size_t smem = (size_t)STAGES * (BM + BN) * BK * 2;
+  static bool configured = false;     // benign race: the attribute call is idempotent
+  if (!configured) {
+    const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_dma_kernel<TC, AKC, BKC, BM, BN, BK, WGM, WGN, STAGES>),
+                                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+    if (e != hipSuccess) return hap_fail(HAP_EDEVICE, "cannot reserve %zu bytes of LDS: %s", smem, hipGetErrorString(e));
+    configured = true;
+  }
+  hipLaunchKernelGGL((gemm_dma_kernel<TC, AKC, BKC, BM, BN, BK, WGM, WGN, STAGES>), dim3(a.tiles_m * a.tiles_n), dim3(64 * WGM * WGN), smem, st, a);
+  const hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return hap_fail(HAP_EDEVICE, "gemm launch: %s", hipGetErrorString(e));
+  return HAP_OK;
+}
+
+template <typename TC, bool AKC, bool BKC, int BK, int STAGES, int WGM = 2, int WGN = 4>
+int launch_pipe(const GemmArgs& a, hipStream_t st) {
+  constexpr int BM = 256, BN = 256;
+  constexpr size_t smem = (size_t)STAGES * (BM + BN) * BK * 2;
+  static bool configured = false;     // benign race: the attribute call is idempotent
+  if (!configured) {
+    const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_pipe_kernel<TC, AKC, BKC, BM, BN, BK, WGM, WGN, STAGES>),
+                                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+    if (e != hipSuccess) return hap_fail(HAP_EDEVICE, "cannot reserve %zu bytes of LDS: %s", smem, hipGetErrorString(e));
+    configured = true;
+  }
+  hipLaunchKernelGGL((gemm_pipe_kernel<TC, AKC, BKC, BM, BN, BK, WGM, WGN, STAGES>), dim3(a.tiles_m * a.tiles_n), dim3(64 * WGM * WGN), smem, st, a);
+  const hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return hap_fail(HAP_EDEVICE, "gemm launch: %s", hipGetErrorString(e));
+  return HAP_OK;
+}
+
+template <typename TC, int BK, int STAGES, int WGM = 2, int WGN = 4>
+int dispatch_pipe(const hap_gemm_problem* p, const GemmArgs& a, hipStream_t st) {
+  if (p->a_kcontig && p->b_kcontig) return launch_pipe<TC, true, true, BK, STAGES, WGM, WGN>(a, st);
+  if (p->a_kcontig && !p->b_kcontig) return launch_pipe<TC, true, false, BK, STAGES, WGM, WGN>(a, st);
+  if (!p->a_kcontig && !p->b_kcontig) return launch_pipe<TC, false, false, BK, STAGES, WGM, WGN>(a, st);
+  return launch_pipe<TC, false, true, BK, STAGES, WGM, WGN>(a, st);
+}
+
+template <typename TC, int BK, int STAGES, int WGM = 2, int WGN = 4>
+int dispatch_dma(const hap_gemm_problem* p, const GemmArgs& a, hipStream_t st) {
+  if (p->a_kcontig && p->b_kcontig) return launch_dma<TC, true, true, BK, STAGES, WGM, WGN>(a, st);
+  if (p->a_kcontig && !p->b_kcontig) return launch_dma<TC, true, false, BK, STAGES, WGM, WGN>(a, st);
+  if (!p->a_kcontig && !p->b_kcontig) return launch_dma<TC, false, false, BK, STAGES, WGM, WGN>(a, st);
+  return launch_dma<TC, false, true, BK, STAGES, WGM, WGN>(a, st);
 }
 
 template <typename T, typename TC, int BM, int BN, int BK, int WGM, int WGN>
@@ -435,13 +1011,23 @@ int dispatch_tile(const hap_gemm_problem* p, const Plan& pl, const GemmArgs& a, 
   if constexpr (sizeof(T) == 4) {
     return dispatch_layout<T, TC, 64, 64, 16, 2, 2>(p, a, st);
   } else {
+    if (pl.bm == 256 && pl.dma == 4) return dispatch_dma<TC, 64, 2, 2, 2>(p, a, st);
+    if (pl.bm == 256 && pl.dma == 5) return dispatch_pipe<TC, 32, 4, 2, 2>(p, a, st);
+    if (pl.bm == 256 && pl.dma == 1) return dispatch_dma<TC, 64, 2>(p, a, st);
+    if (pl.bm == 256 && pl.dma == 2) return dispatch_pipe<TC, 32, 4>(p, a, st);
+    if (pl.bm == 256 && pl.dma == 3) return dispatch_pipe<TC, 32, 3>(p, a, st);
     if (pl.bm == 256) return dispatch_layout<T, TC, 256, 256, 64, 2, 4>(p, a, st);
     return dispatch_layout<T, TC, 128, 128, 64, 2, 2>(p, a, st);
   }
 }
 
-}  // namespace
+}  // namespace hap_gemm_detail
 
+using namespace hap_gemm_detail;
+
+#ifdef HAP_EXP_TRACE
+void* g_trace = nullptr;
+#endif
 const char* hap_gemm_variant(const hap_gemm_problem* p) { return make_plan(p).name; }
 
 int hap_gemm_run(const hap_gemm_problem* p, void* stream) {
@@ -501,6 +1087,20 @@ int hap_gemm_run(const hap_gemm_problem* p, void* stream) {
   if (a.nseg == 0) {   // empty contraction: the product is zero; run one empty segment so the epilogue still applies
     a.nseg = 1;
     a.seg[0].a = p->c; a.seg[0].b = p->c; a.seg[0].k = 0; a.seg[0].a_bytes = 0; a.seg[0].b_bytes = 0; a.seg[0].pad = 0;
+  }
+#ifdef HAP_EXP_TRACE
+  a.trace = g_trace;
+#endif
+  {
+    const int ces = esize(p->c_dtype), cepc = 16 / ces;
+    a.vec_store = pl.skewN == 0 && ((uintptr_t)p->c % 16) == 0 && p->ldc % cepc == 0 &&
+                  (!p->preact || (((uintptr_t)p->preact % 16) == 0 && p->ldp % cepc == 0));
+  }
+  a.ntiles = 0;
+  if (pl.dma) {
+    const int bk = (pl.dma == 1 || pl.dma == 4) ? 64 : 32;
+    for (int s = 0; s < a.nseg; ++s) a.ntiles += (pl.skewK + a.seg[s].k + bk - 1) / bk;
+    if (a.ntiles == 0) a.ntiles = 1;     // empty contraction still runs one (all-zero) tile
   }
   if (p->in_dtype == HAP_BF16 && p->c_dtype == HAP_BF16) return dispatch_tile<__bf16, __bf16>(p, pl, a, st);
   if (p->in_dtype == HAP_BF16) return dispatch_tile<__bf16, float>(p, pl, a, st);
