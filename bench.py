@@ -30,6 +30,8 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="only run a plain 256 MiB device copy 10 times (reference for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (each virtual device's shard runs in turn on it); "
@@ -47,6 +49,13 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(3)
     dev = torch.device("cuda:0")
+    if args.copy_calibration:
+        src = torch.ones((1 << 26,), dtype=torch.float32, device=dev); dst = torch.empty_like(src)
+        for _ in range(10):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_bytes_each_way": src.numel() * 4, "launches": 10}))
+        return
 
     def dev_bf16(seed, tid, shape, sigma):
         _, bits = hapgen.normal_bf16(seed, tid, shape, sigma)
@@ -130,27 +139,32 @@ def main():
 
 
 def cpu_baseline(np, hapgen, T, w2, offsets):
-    """The oracle as it stands, timed on this host's cores on a bounded sample of the workload."""
-    from oracle import layers
+    """The oracle as it stands, timed on this host's cores on a bounded sample of the workload:
+    the smallest shard's MLP fwd+bwd over all tokens plus the SFB rebuild (about a quarter of a step)."""
+    from oracle import layers, sfb
     try:
         from threadpoolctl import threadpool_info
         cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
     except Exception:
         cores = os.cpu_count()
-    h = w2.dims["hidden"]
+    w3 = hapgen.WORKLOADS["cfg3_sfb_bf16"]
+    h, tok = w2.dims["hidden"], w2.dims["tokens"]
     lo, hi = offsets[2], offsets[3]
-    tok = 1024
     f = hi - lo
     X = hapgen.normal_bf16(0, T.X, (tok, h), 1.0)[0]
     W1 = hapgen.normal_bf16(1, T.W, (h, f), 0.02)[0]; b1 = hapgen.normal_bf16(1, T.BIAS, (f,), 0.02)[0]
     W2 = hapgen.normal_bf16(1, T.W2, (f, h), 0.02)[0]; dOut = hapgen.normal_bf16(0, T.DY, (tok, h), 1.0)[0]
+    rows, cap = w3.dims["rows"], w3.dims["capacity"]
+    sX = [hapgen.normal_bf16(0, T.SFB_X + i, (cap, w3.dims["in_features"]), 1.0)[0] for i in range(len(rows))]
+    sdY = [hapgen.normal_bf16(0, T.SFB_DY + i, (cap, w3.dims["out_features"]), 1.0)[0] for i in range(len(rows))]
     t0 = time.perf_counter()
     layers.mlp_block(X, W1, b1, W2, np.zeros(h), dOut)
+    sfb.sfb_grad(sX, sdY, rows)
     dt = time.perf_counter() - t0
-    flops = 12.0 * tok * h * f
+    flops = 12.0 * tok * h * f + 2.0 * w3.dims["in_features"] * w3.dims["out_features"] * sum(rows)
     return {"value": round(flops / dt / 1e12, 4), "unit": "TFLOP/s", "cores": int(cores), "kind": "oracle",
-            "sample": f"oracle.layers.mlp_block fwd+bwd (float64 numpy) on {tok} of 8192 tokens of the smallest shard (ffn {f}): "
-                      f"{flops / 1e9:.0f} GFLOP in {dt:.1f} s"}
+            "sample": f"oracle (float64 numpy): MLP fwd+bwd of the smallest shard (ffn {f}) over all {tok} tokens + SFB rebuild: "
+                      f"{flops / 1e9:.0f} of the step's GFLOP in {dt:.1f} s"}
 
 
 if __name__ == "__main__":

@@ -58,9 +58,6 @@ struct GemmArgs {
   void* preact;
   const void* bias;
   int act, accumulate;
-#ifdef HAP_EXP_TRACE
-  void* trace;
-#endif
   SegArg seg[HAP_GEMM_MAX_SEG];
 };
 
@@ -433,9 +430,10 @@ __device__ __forceinline__ void epilogue_transposed(const GemmArgs& args, f32x16
           }
           __builtin_memcpy(patch + ml * ROWB + cl * ES, v, 4 * ES);
         }
-      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+      // Order the patch accesses of this wave only: LDS operations of a wave execute in order, so a
+      // wait on the LDS counter is enough (a fence would also drain the global stores in flight).
+      asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
       __builtin_amdgcn_wave_barrier();
-      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
       // LDS patch -> global, 16 bytes per lane
 #pragma unroll
       for (int it = 0; it < 32 * CH / 64; ++it) {
@@ -463,9 +461,10 @@ __device__ __forceinline__ void epilogue_transposed(const GemmArgs& args, f32x16
             }
         }
       }
-      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+      // Order the patch accesses of this wave only: LDS operations of a wave execute in order, so a
+      // wait on the LDS counter is enough (a fence would also drain the global stores in flight).
+      asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
       __builtin_amdgcn_wave_barrier();
-      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
     }
   }
 }
@@ -606,9 +605,6 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_dma_kernel(const GemmArgs
   for (int t = -(STAGES - 1); t < ntiles; ++t) {
     char* sa = smem + cslot * STAGE_BYTES;
     char* sb = sa + A_BYTES;
-#ifdef HAP_EXP_TRACE
-    long long ts0 = __builtin_readcyclecounter(), ts1 = 0, ts2 = 0, ts3 = 0;
-#endif
     if (t >= 0) {
       // tile t must have landed; up to STAGES-2 newer tiles may stay in flight
       if (STAGES > 2 && t + STAGES - 2 < ntiles) asm volatile("s_waitcnt vmcnt(%0)" ::"n"((STAGES - 2) * LOADS_PER_TILE) : "memory");
@@ -619,13 +615,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_dma_kernel(const GemmArgs
       }
       ck0 += BK;
       if (ck0 >= ckend && cseg + 1 < args.nseg) { ++cseg; ck0 = 0; ckend = args.skewK + args.seg[cseg].k; }
-#ifdef HAP_EXP_TRACE
-      ts1 = __builtin_readcyclecounter();
-#endif
       __syncthreads();          // tile visible to all waves; every wave is done with the slot refilled below
-#ifdef HAP_EXP_TRACE
-      ts2 = __builtin_readcyclecounter();
-#endif
     }
     if (t + STAGES - 1 < ntiles) {
       char* pa = smem + pslot * STAGE_BYTES;
@@ -665,23 +655,10 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_dma_kernel(const GemmArgs
       }
       cslot = cslot + 1 == STAGES ? 0 : cslot + 1;
     }
-#ifdef HAP_EXP_TRACE
-    ts3 = __builtin_readcyclecounter();
-    if (blockIdx.x == 8 && lane == 0 && t >= 0 && t < 64) {
-      long long* tr = reinterpret_cast<long long*>(args.trace) + (wave * 64 + t) * 4;
-      tr[0] = ts0; tr[1] = ts1; tr[2] = ts2; tr[3] = ts3;
-    }
-#endif
   }
 
-#ifdef HAP_EXP_TRACE
-  long long te0 = __builtin_readcyclecounter();
-#endif
   __syncthreads();   // every wave is done reading the ring: reuse it as per-wave store patches
   epilogue_transposed<T, TC, TM, TN>(args, acc, m0 + wm0, n0 + wn0, lane, smem + wave * (32 * (TN * 32 * (int)sizeof(TC) + 16)));
-#ifdef HAP_EXP_TRACE
-  if (blockIdx.x == 8 && lane == 0) { long long* tr = reinterpret_cast<long long*>(args.trace) + 8 * 64 * 4 + wave * 2; tr[0] = te0; tr[1] = __builtin_readcyclecounter(); }
-#endif
 }
 
 /* ---------------------------------------------------------------------------------------------
@@ -1025,9 +1002,6 @@ int dispatch_tile(const hap_gemm_problem* p, const Plan& pl, const GemmArgs& a, 
 
 using namespace hap_gemm_detail;
 
-#ifdef HAP_EXP_TRACE
-void* g_trace = nullptr;
-#endif
 const char* hap_gemm_variant(const hap_gemm_problem* p) { return make_plan(p).name; }
 
 int hap_gemm_run(const hap_gemm_problem* p, void* stream) {
@@ -1088,9 +1062,6 @@ int hap_gemm_run(const hap_gemm_problem* p, void* stream) {
     a.nseg = 1;
     a.seg[0].a = p->c; a.seg[0].b = p->c; a.seg[0].k = 0; a.seg[0].a_bytes = 0; a.seg[0].b_bytes = 0; a.seg[0].pad = 0;
   }
-#ifdef HAP_EXP_TRACE
-  a.trace = g_trace;
-#endif
   {
     const int ces = esize(p->c_dtype), cepc = 16 / ces;
     a.vec_store = pl.skewN == 0 && ((uintptr_t)p->c % 16) == 0 && p->ldc % cepc == 0 &&
