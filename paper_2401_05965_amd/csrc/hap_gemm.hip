@@ -525,6 +525,16 @@ struct DmaLoader {
     for (int i = 0; i < CPT; ++i) dma16(rsrc, lds + (wave_first + i * NT) * 16, base[i], soff);
   }
 
+  /* The loads i of an interior tile with i % nparts == part.  A tile's loads are spread between the
+   * MFMA groups of the previous tile: issued back to back they fill the memory queue and the wave
+   * blocks on it instead of feeding the matrix unit.  `part` and `nparts` fold at compile time. */
+  __device__ __forceinline__ void issue_part(__amdgpu_buffer_rsrc_t rsrc, char* lds, int tid, unsigned soff, int part, int nparts) const {
+    const int wave_first = (tid & ~63);
+#pragma unroll
+    for (int i = 0; i < CPT; ++i)
+      if (i % nparts == part) dma16(rsrc, lds + (wave_first + i * NT) * 16, base[i], soff);
+  }
+
   /* Edge tile: validity along k decided per chunk; the tile offset (which may be "negative" for the
    * rows a skewed first tile does not use) is added per lane so valid chunks get an exact offset. */
   __device__ __forceinline__ void issue_edge(__amdgpu_buffer_rsrc_t rsrc, char* lds, int tid, unsigned toff, int k0, int kskew, int kend) const {
@@ -601,214 +611,84 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_dma_kernel(const GemmArgs
   // consumer state: k range of the tile being consumed (for the edge fix-up)
   int cseg = 0, ck0 = 0, ckend = pkend, cslot = 0;
   const int ntiles = args.ntiles;
-
-  for (int t = -(STAGES - 1); t < ntiles; ++t) {
-    char* sa = smem + cslot * STAGE_BYTES;
-    char* sb = sa + A_BYTES;
-    if (t >= 0) {
-      // tile t must have landed; up to STAGES-2 newer tiles may stay in flight
-      if (STAGES > 2 && t + STAGES - 2 < ntiles) asm volatile("s_waitcnt vmcnt(%0)" ::"n"((STAGES - 2) * LOADS_PER_TILE) : "memory");
-      else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-      if (ck0 < args.skewK || ck0 + BK > ckend) {
-        la.fixup(sa, tid, ck0, args.skewK, ckend);
-        lb.fixup(sb, tid, ck0, args.skewK, ckend);
-      }
-      ck0 += BK;
-      if (ck0 >= ckend && cseg + 1 < args.nseg) { ++cseg; ck0 = 0; ckend = args.skewK + args.seg[cseg].k; }
-      __syncthreads();          // tile visible to all waves; every wave is done with the slot refilled below
-    }
-    if (t + STAGES - 1 < ntiles) {
-      char* pa = smem + pslot * STAGE_BYTES;
-      char* pb = pa + A_BYTES;
-      const bool edge = pk0 < args.skewK || pk0 + BK > pkend;
-      const unsigned soa = LA::tile_offset(pk0, args.skewK, args.lda);
-      const unsigned sob = LB::tile_offset(pk0, args.skewK, args.ldb);
-      if (!edge) {
-        la.issue(ra, pa, tid, soa);
-        lb.issue(rb, pb, tid, sob);
-      } else {
-        la.issue_edge(ra, pa, tid, soa, pk0, args.skewK, pkend);
-        lb.issue_edge(rb, pb, tid, sob, pk0, args.skewK, pkend);
-      }
-      pslot = pslot + 1 == STAGES ? 0 : pslot + 1;
-      pk0 += BK;
-      if (pk0 >= pkend && pseg + 1 < args.nseg) {
-        pseg = uni(pseg + 1);
-        pk0 = 0;
-        pkend = uni(args.skewK + args.seg[pseg].k);
-        ra = make_rsrc(args.seg[pseg].a, args.seg[pseg].a_bytes);
-        rb = make_rsrc(args.seg[pseg].b, args.seg[pseg].b_bytes);
-      }
-    }
-    if (t >= 0) {
-#pragma unroll
-      for (int kk = 0; kk < BK / 16; ++kk) {
-        bf16x8_t fa[TM], fb[TN];
-#pragma unroll
-        for (int i = 0; i < TM; ++i) fa[i] = Frag<T, AKC, BM, BK>::read(sa, wm0 + i * 32, kk, lane);
-#pragma unroll
-        for (int j = 0; j < TN; ++j) fb[j] = Frag<T, BKC, BN, BK>::read(sb, wn0 + j * 32, kk, lane);
-#pragma unroll
-        for (int i = 0; i < TM; ++i)
-#pragma unroll
-          for (int j = 0; j < TN; ++j) acc[i][j] = mfma(fb[j], fa[i], acc[i][j]);
-      }
-      cslot = cslot + 1 == STAGES ? 0 : cslot + 1;
-    }
-  }
-
-  __syncthreads();   // every wave is done reading the ring: reuse it as per-wave store patches
-  epilogue_transposed<T, TC, TM, TN>(args, acc, m0 + wm0, n0 + wn0, lane, smem + wave * (32 * (TN * 32 * (int)sizeof(TC) + 16)));
-}
-
-/* ---------------------------------------------------------------------------------------------
- * Software-pipelined form of the direct-to-LDS kernel (STAGES >= 3).
- *
- * MFMA fragments are double-buffered in registers: while the MFMAs of k-step kk run, the LDS reads
- * of k-step kk+1 are already in flight - across tile boundaries too, because the one barrier per
- * tile sits BEFORE the last k-step of the current tile, where it (a) publishes tile t+1, which was
- * requested STAGES-1 tiles ago, and (b) proves that every wave has left tile t-1, whose ring slot is
- * then refilled with tile t+STAGES-1.
- * ------------------------------------------------------------------------------------------- */
-template <typename TC, bool AKC, bool BKC, int BM, int BN, int BK, int WGM, int WGN, int STAGES>
-__global__ __launch_bounds__(64 * WGM * WGN) void gemm_pipe_kernel(const GemmArgs args) {
-  typedef __bf16 T;
-  static_assert(STAGES >= 3, "needs a free ring slot while two tiles are live");
-  constexpr int NT = 64 * WGM * WGN;
-  constexpr int WTM = BM / WGM, WTN = BN / WGN;
-  constexpr int TM = WTM / 32, TN = WTN / 32;
   constexpr int KK = BK / 16;
-  static_assert(KK % 2 == 0, "fragment double buffer parity must repeat per tile");
-  constexpr int A_BYTES = BM * BK * 2, B_BYTES = BN * BK * 2, STAGE_BYTES = A_BYTES + B_BYTES;
-  typedef DmaLoader<AKC, BM, BK, NT> LA;
-  typedef DmaLoader<BKC, BN, BK, NT> LB;
-  constexpr int LOADS_PER_TILE = LA::CPT + LB::CPT;
-  typedef Frag<T, AKC, BM, BK> FA;
-  typedef Frag<T, BKC, BN, BK> FB;
+  constexpr int MF = TM * TN;                       // MFMAs per k-step
 
-  extern __shared__ __attribute__((aligned(16))) char smem[];
+  auto advance_producer = [&]() {
+    pslot = pslot + 1 == STAGES ? 0 : pslot + 1;
+    pk0 += BK;
+    if (pk0 >= pkend && pseg + 1 < args.nseg) {
+      pseg = uni(pseg + 1);
+      pk0 = 0;
+      pkend = uni(args.skewK + args.seg[pseg].k);
+      ra = make_rsrc(args.seg[pseg].a, args.seg[pseg].a_bytes);
+      rb = make_rsrc(args.seg[pseg].b, args.seg[pseg].b_bytes);
+    }
+  };
 
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int wm0 = (wave / WGN) * WTM, wn0 = (wave % WGN) * WTN;
-  int tm, tn;
-  tile_of_block(blockIdx.x, gridDim.x, args.tiles_m, args.tiles_n, &tm, &tn);
-  const int m0 = tm * BM, n0 = tn * BN;
-  const int m_lim = args.skewM + args.M, n_lim = args.skewN + args.N;
-
-  LA la; LB lb;
-  la.init(tid, m0, m_lim, args.lda);
-  lb.init(tid, n0, n_lim, args.ldb);
-
-  f32x16_t acc[TM][TN];
-#pragma unroll
-  for (int i = 0; i < TM; ++i)
-#pragma unroll
-    for (int j = 0; j < TN; ++j)
-#pragma unroll
-      for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
-
-  int pseg = 0, pk0 = 0, pkend = args.skewK + args.seg[0].k, pslot = 0;
-  int cseg = 0, ck0 = 0, ckend = pkend;     // k range of the NEXT tile to be published
-  const int ntiles = args.ntiles;
-
-#define HAP_PRODUCE()                                                                            \
-  do {                                                                                           \
-    pslot = uni(pslot); pk0 = uni(pk0); pkend = uni(pkend); pseg = uni(pseg);                    \
-    char* pa = smem + pslot * STAGE_BYTES;                                                       \
-    char* pb = pa + A_BYTES;                                                                     \
-    const __amdgpu_buffer_rsrc_t ra = make_rsrc(args.seg[pseg].a, args.seg[pseg].a_bytes);       \
-    const __amdgpu_buffer_rsrc_t rb = make_rsrc(args.seg[pseg].b, args.seg[pseg].b_bytes);       \
-    const bool edge = pk0 < args.skewK || pk0 + BK > pkend;                                      \
-    const unsigned soa = (unsigned)uni((int)LA::tile_offset(pk0, args.skewK, args.lda));         \
-    const unsigned sob = (unsigned)uni((int)LB::tile_offset(pk0, args.skewK, args.ldb));         \
-    if (!edge) { la.issue(ra, pa, tid, soa); lb.issue(rb, pb, tid, sob); }                       \
-    else { la.issue_edge(ra, pa, tid, soa, pk0, args.skewK, pkend); lb.issue_edge(rb, pb, tid, sob, pk0, args.skewK, pkend); } \
-    pslot = pslot + 1 == STAGES ? 0 : pslot + 1;                                                 \
-    pk0 += BK;                                                                                   \
-    if (pk0 >= pkend && pseg + 1 < args.nseg) {                                                  \
-      pseg = uni(pseg + 1); pk0 = 0; pkend = uni(args.skewK + args.seg[pseg].k);                  \
-    }                                                                                            \
-  } while (0)
-
-  /* Waits until the oldest outstanding tile has landed, patches its k edges, publishes it.  NEWER:
-   * tiles requested after it that may stay in flight when the ring is full (`steady`). */
-#define HAP_PUBLISH(slot_ptr, steady, NEWER)                                                     \
-  do {                                                                                           \
-    ck0 = uni(ck0); ckend = uni(ckend); cseg = uni(cseg);                                        \
-    if ((NEWER) > 0 && (steady)) asm volatile("s_waitcnt vmcnt(%0)" ::"n"((NEWER) * LOADS_PER_TILE) : "memory"); \
-    else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");                                        \
-    if (ck0 < args.skewK || ck0 + BK > ckend) {                                                  \
-      la.fixup(slot_ptr, tid, ck0, args.skewK, ckend);                                           \
-      lb.fixup(slot_ptr + A_BYTES, tid, ck0, args.skewK, ckend);                                 \
-    }                                                                                            \
-    ck0 += BK;                                                                                   \
-    if (ck0 >= ckend && cseg + 1 < args.nseg) { cseg = uni(cseg + 1); ck0 = 0; ckend = uni(args.skewK + args.seg[cseg].k); } \
-    __syncthreads();                                                                             \
-  } while (0)
-
-  // prologue: request STAGES-1 tiles, publish tile 0, fetch its first fragments
-  int requested = 0;
+  // prologue: request the first STAGES-1 tiles
 #pragma unroll
   for (int s = 0; s < STAGES - 1; ++s)
-    if (requested < ntiles) { HAP_PRODUCE(); ++requested; }
-  HAP_PUBLISH(smem, requested == STAGES - 1, STAGES - 2);
-
-  bf16x8_t fa[2][TM], fb[2][TN];
-#pragma unroll
-  for (int i = 0; i < TM; ++i) fa[0][i] = FA::read(smem, wm0 + i * 32, 0, lane);
-#pragma unroll
-  for (int j = 0; j < TN; ++j) fb[0][j] = FB::read(smem + A_BYTES, wn0 + j * 32, 0, lane);
-
-  // Steady state: every tile but the last has a successor to publish and prefetch, so the loop body is
-  // straight-line (no join points that would make the compiler wait for the prefetched fragments early).
-  int cslot = 0;
-  for (int t = 0; t + 1 < ntiles; ++t) {
-    char* sa = smem + cslot * STAGE_BYTES;
-    const int nslot = cslot + 1 == STAGES ? 0 : cslot + 1;
-    char* na = smem + nslot * STAGE_BYTES;
-#pragma unroll
-    for (int kk = 0; kk < KK; ++kk) {
-      const int cur = kk & 1, nxt = cur ^ 1;
-      if (kk == KK - 1) {
-        // tile t+1 was requested STAGES-1 tiles ago; tiles t+2 .. requested-1 may stay in flight
-        HAP_PUBLISH(na, requested - (t + 2) >= STAGES - 3, STAGES - 3);
-        if (requested < ntiles) { HAP_PRODUCE(); ++requested; }
-#pragma unroll
-        for (int i = 0; i < TM; ++i) fa[nxt][i] = FA::read(na, wm0 + i * 32, 0, lane);
-#pragma unroll
-        for (int j = 0; j < TN; ++j) fb[nxt][j] = FB::read(na + A_BYTES, wn0 + j * 32, 0, lane);
-      } else {
-#pragma unroll
-        for (int i = 0; i < TM; ++i) fa[nxt][i] = FA::read(sa, wm0 + i * 32, kk + 1, lane);
-#pragma unroll
-        for (int j = 0; j < TN; ++j) fb[nxt][j] = FB::read(sa + A_BYTES, wn0 + j * 32, kk + 1, lane);
-      }
-#pragma unroll
-      for (int i = 0; i < TM; ++i)
-#pragma unroll
-        for (int j = 0; j < TN; ++j) acc[i][j] = mfma(fb[cur][j], fa[cur][i], acc[i][j]);
+    if (s < ntiles) {
+      char* pa = smem + pslot * STAGE_BYTES;
+      la.issue_edge(ra, pa, tid, LA::tile_offset(pk0, args.skewK, args.lda), pk0, args.skewK, pkend);
+      lb.issue_edge(rb, pa + A_BYTES, tid, LB::tile_offset(pk0, args.skewK, args.ldb), pk0, args.skewK, pkend);
+      advance_producer();
     }
-    cslot = nslot;
-  }
-  {  // last tile: nothing left to publish
+
+  for (int t = 0; t < ntiles; ++t) {
     char* sa = smem + cslot * STAGE_BYTES;
+    char* sb = sa + A_BYTES;
+    // tile t must have landed; up to STAGES-2 newer tiles may stay in flight
+    if (STAGES > 2 && t + STAGES - 2 < ntiles) asm volatile("s_waitcnt vmcnt(%0)" ::"n"((STAGES - 2) * LOADS_PER_TILE) : "memory");
+    else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    if (ck0 < args.skewK || ck0 + BK > ckend) {
+      la.fixup(sa, tid, ck0, args.skewK, ckend);
+      lb.fixup(sb, tid, ck0, args.skewK, ckend);
+    }
+    ck0 += BK;
+    if (ck0 >= ckend && cseg + 1 < args.nseg) { cseg = uni(cseg + 1); ck0 = 0; ckend = uni(args.skewK + args.seg[cseg].k); }
+    __syncthreads();          // tile visible to all waves; every wave is done with the slot refilled below
+
+    // the next request goes out in pieces between the MFMA groups of this tile (interior tiles), or
+    // at once (first / last tile of a segment, where validity is decided per chunk)
+    const bool produce = t + STAGES - 1 < ntiles;
+    const bool edge = pk0 < args.skewK || pk0 + BK > pkend;
+    char* pa = smem + pslot * STAGE_BYTES;
+    char* pb = pa + A_BYTES;
+    const unsigned soa = LA::tile_offset(pk0, args.skewK, args.lda);
+    const unsigned sob = LB::tile_offset(pk0, args.skewK, args.ldb);
+    if (produce && edge) {
+      la.issue_edge(ra, pa, tid, soa, pk0, args.skewK, pkend);
+      lb.issue_edge(rb, pb, tid, sob, pk0, args.skewK, pkend);
+    }
+    const bool spread = produce && !edge;
+
+    // fragments of k-step kk+1 are fetched while the MFMAs of k-step kk run
+    bf16x8_t fa[2][TM], fb[2][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i) fa[0][i] = Frag<T, AKC, BM, BK>::read(sa, wm0 + i * 32, 0, lane);
+#pragma unroll
+    for (int j = 0; j < TN; ++j) fb[0][j] = Frag<T, BKC, BN, BK>::read(sb, wn0 + j * 32, 0, lane);
 #pragma unroll
     for (int kk = 0; kk < KK; ++kk) {
       const int cur = kk & 1, nxt = cur ^ 1;
       if (kk + 1 < KK) {
 #pragma unroll
-        for (int i = 0; i < TM; ++i) fa[nxt][i] = FA::read(sa, wm0 + i * 32, kk + 1, lane);
+        for (int i = 0; i < TM; ++i) fa[nxt][i] = Frag<T, AKC, BM, BK>::read(sa, wm0 + i * 32, kk + 1, lane);
 #pragma unroll
-        for (int j = 0; j < TN; ++j) fb[nxt][j] = FB::read(sa + A_BYTES, wn0 + j * 32, kk + 1, lane);
+        for (int j = 0; j < TN; ++j) fb[nxt][j] = Frag<T, BKC, BN, BK>::read(sb, wn0 + j * 32, kk + 1, lane);
       }
 #pragma unroll
-      for (int i = 0; i < TM; ++i)
+      for (int x = 0; x < MF / 2; ++x) acc[x / TN][x % TN] = mfma(fb[cur][x % TN], fa[cur][x / TN], acc[x / TN][x % TN]);
+      if (spread) la.issue_part(ra, pa, tid, soa, kk, KK);
 #pragma unroll
-        for (int j = 0; j < TN; ++j) acc[i][j] = mfma(fb[cur][j], fa[cur][i], acc[i][j]);
+      for (int x = MF / 2; x < MF; ++x) acc[x / TN][x % TN] = mfma(fb[cur][x % TN], fa[cur][x / TN], acc[x / TN][x % TN]);
+      if (spread) lb.issue_part(rb, pb, tid, sob, kk, KK);
     }
+    if (produce) advance_producer();
+    cslot = cslot + 1 == STAGES ? 0 : cslot + 1;
   }
-#undef HAP_PRODUCE
-#undef HAP_PUBLISH
 
   __syncthreads();   // every wave is done reading the ring: reuse it as per-wave store patches
   epilogue_transposed<T, TC, TM, TN>(args, acc, m0 + wm0, n0 + wn0, lane, smem + wave * (32 * (TN * 32 * (int)sizeof(TC) + 16)));
@@ -850,7 +730,7 @@ __global__ __launch_bounds__(256) void gemm_generic_kernel(const GenericArgs g) 
   store_c<TC>(dst, acc);
 }
 
-/* Kernel variant for large bf16 problems; HAP_GEMM_KERNEL=staged|dma2|pipe4|pipe3 overrides the default (tuning aid). */
+/* Kernel variant for large bf16 problems; HAP_GEMM_KERNEL=staged|dma2|dma4 overrides the default (tuning aid). */
 int dma_variant() {
   static int v = -1;
   if (v < 0) {
@@ -859,10 +739,7 @@ int dma_variant() {
     if (e) {
       if (!strcmp(e, "staged")) v = 0;
       else if (!strcmp(e, "dma2")) v = 1;
-      else if (!strcmp(e, "pipe4")) v = 2;
-      else if (!strcmp(e, "pipe3")) v = 3;
-      else if (!strcmp(e, "dma2w4")) v = 4;
-      else if (!strcmp(e, "pipe4w4")) v = 5;
+      else if (!strcmp(e, "dma4")) v = 2;
     }
   }
   return v;
@@ -873,7 +750,7 @@ struct Plan {
   int skewM, skewN, skewK;
   int bm, bn;       // tile
   const char* name;
-  int dma;          // 0: register-staged kernel; else direct-to-LDS kernel variant (1: 2 stages x BK 64, 2: 4 x 32, 3: 3 x 32)
+  int dma;          // 0: register-staged kernel; else direct-to-LDS kernel variant (1: 2 stages x BK 64, 2: 4 stages x BK 32)
 };
 
 inline int esize(int dtype) { return dtype == HAP_BF16 ? 2 : 4; }
@@ -908,8 +785,7 @@ Plan make_plan(const hap_gemm_problem* p) {
   else if (p->M + pl.skewM > 128 && p->N + pl.skewN > 128) {
     pl.bm = pl.bn = 256;
     pl.dma = dma_variant();
-    static const char* names[] = {"bf16_256x256x64_staged", "bf16_256x256x64_dma2", "bf16_256x256x32_pipe4", "bf16_256x256x32_pipe3",
-                                  "bf16_256x256x64_dma2_4waves", "bf16_256x256x32_pipe4_4waves"};
+    static const char* names[] = {"bf16_256x256x64_staged", "bf16_256x256x64_dma2", "bf16_256x256x32_dma4"};
     pl.name = names[pl.dma];
   }
   else { pl.bm = pl.bn = 128; pl.name = "bf16_128x128x64"; }
@@ -942,31 +818,6 @@ int launch_dma(const GemmArgs& a, hipStream_t st) {
   return HAP_OK;
 }
 
-template <typename TC, bool AKC, bool BKC, int BK, int STAGES, int WGM = 2, int WGN = 4>
-int launch_pipe(const GemmArgs& a, hipStream_t st) {
-  constexpr int BM = 256, BN = 256;
-  constexpr size_t smem = (size_t)STAGES * (BM + BN) * BK * 2;
-  static bool configured = false;     // benign race: the attribute call is idempotent
-  if (!configured) {
-    const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_pipe_kernel<TC, AKC, BKC, BM, BN, BK, WGM, WGN, STAGES>),
-                                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
-    if (e != hipSuccess) return hap_fail(HAP_EDEVICE, "cannot reserve %zu bytes of LDS: %s", smem, hipGetErrorString(e));
-    configured = true;
-  }
-  hipLaunchKernelGGL((gemm_pipe_kernel<TC, AKC, BKC, BM, BN, BK, WGM, WGN, STAGES>), dim3(a.tiles_m * a.tiles_n), dim3(64 * WGM * WGN), smem, st, a);
-  const hipError_t e = hipGetLastError();
-  if (e != hipSuccess) return hap_fail(HAP_EDEVICE, "gemm launch: %s", hipGetErrorString(e));
-  return HAP_OK;
-}
-
-template <typename TC, int BK, int STAGES, int WGM = 2, int WGN = 4>
-int dispatch_pipe(const hap_gemm_problem* p, const GemmArgs& a, hipStream_t st) {
-  if (p->a_kcontig && p->b_kcontig) return launch_pipe<TC, true, true, BK, STAGES, WGM, WGN>(a, st);
-  if (p->a_kcontig && !p->b_kcontig) return launch_pipe<TC, true, false, BK, STAGES, WGM, WGN>(a, st);
-  if (!p->a_kcontig && !p->b_kcontig) return launch_pipe<TC, false, false, BK, STAGES, WGM, WGN>(a, st);
-  return launch_pipe<TC, false, true, BK, STAGES, WGM, WGN>(a, st);
-}
-
 template <typename TC, int BK, int STAGES, int WGM = 2, int WGN = 4>
 int dispatch_dma(const hap_gemm_problem* p, const GemmArgs& a, hipStream_t st) {
   if (p->a_kcontig && p->b_kcontig) return launch_dma<TC, true, true, BK, STAGES, WGM, WGN>(a, st);
@@ -988,11 +839,8 @@ int dispatch_tile(const hap_gemm_problem* p, const Plan& pl, const GemmArgs& a, 
   if constexpr (sizeof(T) == 4) {
     return dispatch_layout<T, TC, 64, 64, 16, 2, 2>(p, a, st);
   } else {
-    if (pl.bm == 256 && pl.dma == 4) return dispatch_dma<TC, 64, 2, 2, 2>(p, a, st);
-    if (pl.bm == 256 && pl.dma == 5) return dispatch_pipe<TC, 32, 4, 2, 2>(p, a, st);
     if (pl.bm == 256 && pl.dma == 1) return dispatch_dma<TC, 64, 2>(p, a, st);
-    if (pl.bm == 256 && pl.dma == 2) return dispatch_pipe<TC, 32, 4>(p, a, st);
-    if (pl.bm == 256 && pl.dma == 3) return dispatch_pipe<TC, 32, 3>(p, a, st);
+    if (pl.bm == 256 && pl.dma == 2) return dispatch_dma<TC, 32, 4>(p, a, st);
     if (pl.bm == 256) return dispatch_layout<T, TC, 256, 256, 64, 2, 4>(p, a, st);
     return dispatch_layout<T, TC, 128, 128, 64, 2, 2>(p, a, st);
   }
@@ -1069,7 +917,7 @@ int hap_gemm_run(const hap_gemm_problem* p, void* stream) {
   }
   a.ntiles = 0;
   if (pl.dma) {
-    const int bk = (pl.dma == 1 || pl.dma == 4) ? 64 : 32;
+    const int bk = pl.dma == 1 ? 64 : 32;
     for (int s = 0; s < a.nseg; ++s) a.ntiles += (pl.skewK + a.seg[s].k + bk - 1) / bk;
     if (a.ntiles == 0) a.ntiles = 1;     // empty contraction still runs one (all-zero) tile
   }
