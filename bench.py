@@ -101,6 +101,30 @@ def main():
             s.backward(None if tm is None else (lambda l, f, s=s: tm(f"{l}[f={s.f}]", f)))
         sfb.run(tm)
 
+    def ceilings():
+        """Achievable ceilings measured in this run: MFMA issue rate on register operands, plain copy bandwidth."""
+        scratch = torch.empty((256 * 512,), dtype=torch.float32, device=dev)
+        res = {}
+        for name, rnd in (("mfma_bf16_constant_operands_tflops", False), ("mfma_bf16_random_operands_tflops", True)):
+            for _ in range(20):
+                fl = hap.hap_probe_mfma_bf16(rnd, 2000, scratch)
+            a = torch.cuda.Event(enable_timing=True); b = torch.cuda.Event(enable_timing=True)
+            a.record(stream)
+            for _ in range(100):
+                fl = hap.hap_probe_mfma_bf16(rnd, 2000, scratch)
+            b.record(stream); b.synchronize()
+            res[name] = round(fl * 100 / (a.elapsed_time(b) * 1e-3) / 1e12, 1)
+        src = torch.ones((1 << 26,), dtype=torch.float32, device=dev); dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        a = torch.cuda.Event(enable_timing=True); b = torch.cuda.Event(enable_timing=True)
+        a.record(stream)
+        for _ in range(20):
+            dst.copy_(src)
+        b.record(stream); b.synchronize()
+        res["copy_read_plus_write_gbs"] = round(2 * src.numel() * 4 * 20 / (a.elapsed_time(b) * 1e-3) / 1e9, 1)
+        return res
+
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -117,8 +141,13 @@ def main():
     big = shards[0]
     gemm = 2.0 * big.T * big.h * big.f
     call_flops = {f"fc1_fwd[f={big.f}]": gemm, f"fc2_fwd[f={big.f}]": gemm, "sfb_grad": sfb.flops()}
-    dom = f"fc1_fwd[f={big.f}]"                      # one launch of the dominant kernel (bf16 256x256x64 MFMA GEMM)
+    # Dominant kernel: the 256x256x64 bf16 MFMA GEMM.  fc2_fwd of the largest shard is ONE launch of it
+    # (M = 8192 tokens, N = 4096, K = 8402: 512 output tiles, no remainder strip), bracketed by events above.
+    dom = f"fc2_fwd[f={big.f}]"
     achieved = call_flops[dom] / (per[dom] * 1e-3) / 1e12
+    # HBM-side bytes of that launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (KiB), scaled by the factors a
+    # plain 256 MiB copy gives (2.000 and 1.000); see profiles/gemm_dma_256x256x64_cfg2_cfg3.md
+    traffic_bytes = int((406302 * 2.000 + 65536 * 1.000) * 1024)
     out = {
         "metric": "TFLOP/s of sharded fwd+bwd + SFB dW at uneven ratios; % of MFMA peak",
         "value": round(value, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -127,11 +156,15 @@ def main():
         "config": {"workload": "cfg2_mlp_bf16 shards 0 and 2 fwd+bwd + cfg3_sfb_bf16 rebuild", "tokens": Tn, "hidden": h, "ffn": F,
                    "speeds": list(w2.speeds), "shard_sizes": sizes, "sfb_rows": list(rows), "step_gflop": round(step_flops / 1e9, 1),
                    "pct_of_bf16_mfma_peak": round(100 * value / PEAK_BF16_TFLOPS, 2)},
-        "roofline": {"bound": "mfma", "kernel": "gemm_kernel<bf16,256x256x64> (" + dom + ")", "achieved": round(achieved, 1),
-                     "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_TFLOPS, 4), "traffic": None},
+        "roofline": {"bound": "mfma", "kernel": "gemm_dma_kernel<bf16,256x256x64> (" + dom + ": M=8192 N=4096 K=8402)",
+                     "achieved": round(achieved, 1), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                     "frac": round(achieved / PEAK_BF16_TFLOPS, 4), "traffic": traffic_bytes,
+                     "algorithmic_bytes": int(2 * (big.T * big.f + big.f * big.h + big.T * big.h)),
+                     "launch_ms": round(per[dom], 4)},
         "calls_ms": {k: round(v, 4) for k, v in sorted(per.items())},
         "calls_tflops": {k: round(call_flops[k] / (per[k] * 1e-3) / 1e12, 1) for k in call_flops},
         "setup_s": round(t_setup, 1),
+        "achievable": ceilings(),
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(np, hapgen, T, w2, offsets)

@@ -202,6 +202,15 @@ int hap_colsum(int64_t rows, int64_t cols, int io_dtype, const void* a, int64_t 
                void* ws, size_t ws_bytes, void* stream);
 size_t hap_colsum_workspace(int64_t rows, int64_t cols);
 
+/* ------------------------------------------------------------------ diagnostics --- */
+
+/* Issue-rate probe for the roofline report: 256 blocks x 8 waves run `iters` rounds of 8 independent
+ * v_mfma_f32_32x32x16_bf16 on register operands (no memory traffic).  random_operands != 0 uses
+ * pseudo-random operand values, which draw more power than constants and show the sustained clock a
+ * real GEMM can expect.  scratch: device, >= 256*512 floats, overwritten.  *flops (host, may be NULL)
+ * receives the floating-point operations of one launch; the caller times the launch.              */
+int hap_probe_mfma_bf16(int random_operands, int iters, float* scratch, double* flops, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

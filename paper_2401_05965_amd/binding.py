@@ -240,3 +240,11 @@ def hap_colsum(rows, cols, io_dtype, a, lda, out, ws, stream=None):
     wp, wb = _ws(ws)
     _check(lib.hap_colsum(C.c_int64(rows), C.c_int64(cols), C.c_int(io_dtype), _ptr(a), C.c_int64(lda), _ptr(out), wp, wb,
                           _stream(stream)), "hap_colsum")
+
+
+def hap_probe_mfma_bf16(random_operands: bool, iters: int, scratch, stream=None) -> float:
+    """Launches the MFMA issue-rate probe; returns the flops of the launch (the caller times it)."""
+    fl = C.c_double()
+    _check(lib.hap_probe_mfma_bf16(C.c_int(int(bool(random_operands))), C.c_int(iters), _ptr(scratch), C.byref(fl), _stream(stream)),
+           "hap_probe_mfma_bf16")
+    return fl.value

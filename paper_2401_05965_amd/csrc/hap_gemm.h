@@ -33,6 +33,7 @@ struct hap_gemm_problem {
   void* preact; int64_t ldp;           /* optional copy of (product + bias) in c_dtype            */
   int act;                             /* hap_act                                                 */
   int force_generic;                   /* testing aid: take the scalar fallback kernel            */
+  int tile;                            /* 0: engine chooses (and may split the problem); 128 / 256: fixed output tile */
 };
 
 /* Validates nothing beyond what the kernels need (callers validate user input); returns hap_status. */

@@ -730,7 +730,7 @@ __global__ __launch_bounds__(256) void gemm_generic_kernel(const GenericArgs g) 
   store_c<TC>(dst, acc);
 }
 
-/* Kernel variant for large bf16 problems; HAP_GEMM_KERNEL=staged|dma2|dma4 overrides the default (tuning aid). */
+/* Kernel variant for large bf16 problems; HAP_GEMM_KERNEL=staged|dma2 overrides the default (tuning aid). */
 int dma_variant() {
   static int v = -1;
   if (v < 0) {
@@ -739,7 +739,6 @@ int dma_variant() {
     if (e) {
       if (!strcmp(e, "staged")) v = 0;
       else if (!strcmp(e, "dma2")) v = 1;
-      else if (!strcmp(e, "dma4")) v = 2;
     }
   }
   return v;
@@ -750,7 +749,7 @@ struct Plan {
   int skewM, skewN, skewK;
   int bm, bn;       // tile
   const char* name;
-  int dma;          // 0: register-staged kernel; else direct-to-LDS kernel variant (1: 2 stages x BK 64, 2: 4 stages x BK 32)
+  int dma;          // 0: register-staged kernel; 1: direct-to-LDS kernel (2 stages x BK 64)
 };
 
 inline int esize(int dtype) { return dtype == HAP_BF16 ? 2 : 4; }
@@ -782,13 +781,13 @@ Plan make_plan(const hap_gemm_problem* p) {
   }
   pl.tiled = true;
   if (p->in_dtype == HAP_F32) { pl.bm = pl.bn = 64; pl.name = "f32_64x64x16"; }
-  else if (p->M + pl.skewM > 128 && p->N + pl.skewN > 128) {
-    pl.bm = pl.bn = 256;
+  else {
+    const bool big = p->tile ? p->tile == 256 : (p->M + pl.skewM > 128 && p->N + pl.skewN > 128);
+    pl.bm = pl.bn = big ? 256 : 128;
     pl.dma = dma_variant();
-    static const char* names[] = {"bf16_256x256x64_staged", "bf16_256x256x64_dma2", "bf16_256x256x32_dma4"};
-    pl.name = names[pl.dma];
+    static const char* names[2][2] = {{"bf16_128x128x64_staged", "bf16_128x128x64_dma2"}, {"bf16_256x256x64_staged", "bf16_256x256x64_dma2"}};
+    pl.name = names[big][pl.dma];
   }
-  else { pl.bm = pl.bn = 128; pl.name = "bf16_128x128x64"; }
   return pl;
 }
 
@@ -801,9 +800,8 @@ int launch_tiled(const GemmArgs& a, hipStream_t st) {
   return HAP_OK;
 }
 
-template <typename TC, bool AKC, bool BKC, int BK, int STAGES, int WGM = 2, int WGN = 4>
+template <typename TC, bool AKC, bool BKC, int BM, int BN, int BK, int STAGES, int WGM, int WGN>
 int launch_dma(const GemmArgs& a, hipStream_t st) {
-  constexpr int BM = 256, BN = 256;
   constexpr size_t smem = (size_t)STAGES * (BM + BN) * BK * 2;
   static bool configured = false;     // benign race: the attribute call is idempotent
   if (!configured) {
@@ -818,12 +816,12 @@ int launch_dma(const GemmArgs& a, hipStream_t st) {
   return HAP_OK;
 }
 
-template <typename TC, int BK, int STAGES, int WGM = 2, int WGN = 4>
+template <typename TC, int BM, int BN, int BK, int STAGES, int WGM, int WGN>
 int dispatch_dma(const hap_gemm_problem* p, const GemmArgs& a, hipStream_t st) {
-  if (p->a_kcontig && p->b_kcontig) return launch_dma<TC, true, true, BK, STAGES, WGM, WGN>(a, st);
-  if (p->a_kcontig && !p->b_kcontig) return launch_dma<TC, true, false, BK, STAGES, WGM, WGN>(a, st);
-  if (!p->a_kcontig && !p->b_kcontig) return launch_dma<TC, false, false, BK, STAGES, WGM, WGN>(a, st);
-  return launch_dma<TC, false, true, BK, STAGES, WGM, WGN>(a, st);
+  if (p->a_kcontig && p->b_kcontig) return launch_dma<TC, true, true, BM, BN, BK, STAGES, WGM, WGN>(a, st);
+  if (p->a_kcontig && !p->b_kcontig) return launch_dma<TC, true, false, BM, BN, BK, STAGES, WGM, WGN>(a, st);
+  if (!p->a_kcontig && !p->b_kcontig) return launch_dma<TC, false, false, BM, BN, BK, STAGES, WGM, WGN>(a, st);
+  return launch_dma<TC, false, true, BM, BN, BK, STAGES, WGM, WGN>(a, st);
 }
 
 template <typename T, typename TC, int BM, int BN, int BK, int WGM, int WGN>
@@ -839,8 +837,8 @@ int dispatch_tile(const hap_gemm_problem* p, const Plan& pl, const GemmArgs& a, 
   if constexpr (sizeof(T) == 4) {
     return dispatch_layout<T, TC, 64, 64, 16, 2, 2>(p, a, st);
   } else {
-    if (pl.bm == 256 && pl.dma == 1) return dispatch_dma<TC, 64, 2>(p, a, st);
-    if (pl.bm == 256 && pl.dma == 2) return dispatch_dma<TC, 32, 4>(p, a, st);
+    if (pl.bm == 256 && pl.dma == 1) return dispatch_dma<TC, 256, 256, 64, 2, 2, 4>(p, a, st);
+    if (pl.bm == 128 && pl.dma == 1) return dispatch_dma<TC, 128, 128, 64, 2, 2, 2>(p, a, st);
     if (pl.bm == 256) return dispatch_layout<T, TC, 256, 256, 64, 2, 4>(p, a, st);
     return dispatch_layout<T, TC, 128, 128, 64, 2, 2>(p, a, st);
   }
@@ -852,6 +850,87 @@ using namespace hap_gemm_detail;
 
 const char* hap_gemm_variant(const hap_gemm_problem* p) { return make_plan(p).name; }
 
+namespace {
+
+constexpr int kCUs = 256;
+
+/* Relative time of n output tiles of 128x128 (one 256x256 tile on one CU = 1): a small tile does a
+ * quarter of the work at lower efficiency, and two of them share a CU. */
+double small_tiles_time(long long n) {
+  if (n <= 0) return 0.0;
+  if (n <= kCUs) return 0.3;
+  return 0.6 * (double)((n + 2 * kCUs - 1) / (2 * kCUs));
+}
+
+inline long long cdiv(long long a, long long b) { return (a + b - 1) / b; }
+
+/* The sub-problem of p over logical rows [m_lo, m_hi) and columns [n_lo, n_hi). */
+hap_gemm_problem sub_problem(const hap_gemm_problem* p, int64_t m_lo, int64_t m_hi, int64_t n_lo, int64_t n_hi, int tile) {
+  hap_gemm_problem q = *p;
+  const int es = esize(p->in_dtype), ces = esize(p->c_dtype);
+  q.M = m_hi - m_lo; q.N = n_hi - n_lo; q.tile = tile;
+  for (int s = 0; s < p->nseg; ++s) {
+    q.a[s] = static_cast<const char*>(p->a[s]) + (p->a_kcontig ? m_lo * p->lda : m_lo) * es;
+    q.b[s] = static_cast<const char*>(p->b[s]) + (p->b_kcontig ? n_lo * p->ldb : n_lo) * es;
+  }
+  q.c = static_cast<char*>(p->c) + (m_lo * p->ldc + n_lo) * ces;
+  if (p->preact) q.preact = static_cast<char*>(p->preact) + (m_lo * p->ldp + n_lo) * ces;
+  if (p->bias) q.bias = static_cast<const char*>(p->bias) + n_lo * es;
+  return q;
+}
+
+}  // namespace
+
+/* 256x256 tiles on 256 CUs quantise badly: 33 tile columns of 32 rows are 4.1 rounds of work that take
+ * 5.  The engine therefore cuts the output into a part whose big tiles fill whole rounds and a
+ * remainder strip computed with 128x128 tiles, when its cost model says that is faster. */
+static int run_auto_tiled(const hap_gemm_problem* p, const Plan& pl, void* stream) {
+  const long long Mp = p->M + pl.skewM, Np = p->N + pl.skewN;
+  const long long tm = cdiv(Mp, 256), tn = cdiv(Np, 256);
+  const long long sm = cdiv(Mp, 128), sn = cdiv(Np, 128);
+  double best = (double)cdiv(tm * tn, kCUs);
+  int choice = 0;                 // 0: all big, 1: all small, 2: split columns, 3: split rows
+  long long cut = 0;
+  const double all_small = small_tiles_time(sm * sn);
+  if (all_small < best - 1e-9) { best = all_small; choice = 1; }
+  for (long long c = tn - 1; c >= 1; --c)
+    if ((tm * c) % kCUs == 0) {
+      const double t = (double)(tm * c / kCUs) + small_tiles_time(sm * cdiv(Np - c * 256, 128));
+      if (t < best - 1e-9) { best = t; choice = 2; cut = c; }
+      break;
+    }
+  for (long long r = tm - 1; r >= 1; --r)
+    if ((tn * r) % kCUs == 0) {
+      const double t = (double)(tn * r / kCUs) + small_tiles_time(sn * cdiv(Mp - r * 256, 128));
+      if (t < best - 1e-9) { best = t; choice = 3; cut = r; }
+      break;
+    }
+  hap_gemm_problem q;
+  int rc;
+  switch (choice) {
+    case 1:
+      q = sub_problem(p, 0, p->M, 0, p->N, 128);
+      return hap_gemm_run(&q, stream);
+    case 2: {
+      const int64_t n_cut = cut * 256 - pl.skewN;
+      q = sub_problem(p, 0, p->M, 0, n_cut, 256);
+      if ((rc = hap_gemm_run(&q, stream))) return rc;
+      q = sub_problem(p, 0, p->M, n_cut, p->N, 128);
+      return hap_gemm_run(&q, stream);
+    }
+    case 3: {
+      const int64_t m_cut = cut * 256 - pl.skewM;
+      q = sub_problem(p, 0, m_cut, 0, p->N, 256);
+      if ((rc = hap_gemm_run(&q, stream))) return rc;
+      q = sub_problem(p, m_cut, p->M, 0, p->N, 128);
+      return hap_gemm_run(&q, stream);
+    }
+    default:
+      q = sub_problem(p, 0, p->M, 0, p->N, 256);
+      return hap_gemm_run(&q, stream);
+  }
+}
+
 int hap_gemm_run(const hap_gemm_problem* p, void* stream) {
   hipStream_t st = static_cast<hipStream_t>(stream);
   if (p->M <= 0 || p->N <= 0) return HAP_OK;
@@ -860,6 +939,10 @@ int hap_gemm_run(const hap_gemm_problem* p, void* stream) {
   if (p->in_dtype == HAP_F32 && p->c_dtype != HAP_F32) return hap_fail(HAP_EUNSUPPORTED, "fp32 inputs need fp32 output");
   const int es = esize(p->in_dtype);
   const Plan pl = make_plan(p);
+  static const bool split_ok = !(getenv("HAP_GEMM_SPLIT") && !strcmp(getenv("HAP_GEMM_SPLIT"), "0"));   // tuning aid
+  static const int forced_tile = getenv("HAP_GEMM_TILE") ? atoi(getenv("HAP_GEMM_TILE")) : 0;             // tuning aid
+  if (forced_tile && p->tile == 0 && pl.tiled && pl.dma) { hap_gemm_problem q = *p; q.tile = forced_tile; return hap_gemm_run(&q, stream); }
+  if (pl.tiled && pl.dma && p->tile == 0 && pl.bm == 256 && split_ok) return run_auto_tiled(p, pl, stream);
 
   if (!pl.tiled) {
     GenericArgs g;
@@ -917,7 +1000,7 @@ int hap_gemm_run(const hap_gemm_problem* p, void* stream) {
   }
   a.ntiles = 0;
   if (pl.dma) {
-    const int bk = pl.dma == 1 ? 64 : 32;
+    const int bk = 64;
     for (int s = 0; s < a.nseg; ++s) a.ntiles += (pl.skewK + a.seg[s].k + bk - 1) / bk;
     if (a.ntiles == 0) a.ntiles = 1;     // empty contraction still runs one (all-zero) tile
   }

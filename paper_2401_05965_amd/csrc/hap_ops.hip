@@ -73,9 +73,9 @@ __global__ __launch_bounds__(256) void add_kernel(int64_t rows, int64_t cols, co
   }
 }
 
-/* Column sums, stage 1: block (bx, by) sums rows [by*rpb, (by+1)*rpb) of 64 columns starting at
- * bx*64.  Lane l of a wave reads column l&63... each of the 4 waves strides over rows; the four
- * waves' partials meet in LDS.  partial[by][col] is fp32. */
+/* Column sums, stage 1: block (bx, by) sums rows [by*rpb, (by+1)*rpb) of the 64 columns starting at
+ * bx*64.  Lanes run along the columns (coalesced rows), the 4 waves stride over the rows and their
+ * partials meet in LDS.  partial[by][col] is fp32. */
 template <typename T>
 __global__ __launch_bounds__(256) void colsum_partial_kernel(int64_t rows, int64_t cols, const T* a, int64_t lda,
                                                              int64_t rpb, float* partial) {
@@ -194,6 +194,33 @@ __global__ __launch_bounds__(256) void layernorm_bwd_final_kernel(int n, int nbl
   dbeta[c] = b;
 }
 
+/* Register-resident MFMA loop: 8 independent 32x32x16 bf16 accumulators per wave, 8 waves per block,
+ * one block per CU.  With `random` the operands are pseudo-random in [-1, 1) (switching activity of a
+ * real GEMM, which lowers the sustained clock), else constants. */
+typedef __bf16 probe_bf16x8 __attribute__((ext_vector_type(8)));
+typedef float probe_f32x16 __attribute__((ext_vector_type(16)));
+__global__ __launch_bounds__(512) void mfma_probe_kernel(float* out, int random, int iters) {
+  probe_bf16x8 a[4], b[2];
+  unsigned s = (blockIdx.x * 512u + threadIdx.x) * 2654435761u + 12345u;
+  for (int q = 0; q < 6; ++q)
+    for (int i = 0; i < 8; ++i) {
+      s = s * 1664525u + 1013904223u;
+      const float v = random ? (float)((int)((s >> 8) % 2001u) - 1000) * 0.001f : 0.5f;
+      if (q < 4) a[q][i] = (__bf16)v; else b[q - 4][i] = (__bf16)v;
+    }
+  probe_f32x16 c[8];
+  for (int j = 0; j < 8; ++j)
+    for (int e = 0; e < 16; ++e) c[j][e] = 0.0f;
+  for (int it = 0; it < iters; ++it) {
+#pragma unroll
+    for (int j = 0; j < 8; ++j) c[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[j / 2], b[j % 2], c[j], 0, 0, 0);
+  }
+  float t = 0.0f;
+  for (int j = 0; j < 8; ++j)
+    for (int e = 0; e < 16; ++e) t += c[j][e];
+  out[blockIdx.x * 512 + threadIdx.x] = t;
+}
+
 inline int check_launch(const char* what) {
   const hipError_t e = hipGetLastError();
   if (e != hipSuccess) return hap_fail(HAP_EDEVICE, "%s launch: %s", what, hipGetErrorString(e));
@@ -254,6 +281,14 @@ int layernorm_bwd_t(int64_t rows, int n, const void* x, const void* g, const flo
 }  // namespace
 
 extern "C" {
+
+int hap_probe_mfma_bf16(int random_operands, int iters, float* scratch, double* flops, void* stream) {
+  hap_clear_error();
+  if (!scratch || iters < 1) return hap_fail(HAP_EINVAL, "scratch is NULL or iters < 1");
+  hipLaunchKernelGGL(mfma_probe_kernel, dim3(256), dim3(512), 0, (hipStream_t)stream, scratch, random_operands, iters);
+  if (flops) *flops = 2.0 * 32 * 32 * 16 * 8.0 * (double)iters * 8.0 * 256.0;
+  return check_launch("mfma_probe");
+}
 
 int hap_gelu_bwd(int64_t rows, int64_t cols, int io_dtype, const void* preact, int64_t ldp, const void* dy,
                  int64_t lddy, void* out, int64_t ldo, void* stream) {
