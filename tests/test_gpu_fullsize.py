@@ -1,0 +1,101 @@
+"""GPU parity at the benchmark's full sizes, in the launch configuration bench.py times (compact shard
+slices, same programs), on sampled outputs the oracle can compute one by one from the original inputs:
+token rows are independent in the forward and in bwd-data, weight-gradient columns / rows are
+independent of each other, so any sample of them is an exact sub-problem of the definition."""
+import numpy as np
+import pytest
+
+import hapgen
+from hapgen import TensorId as T
+from oracle import pointwise as opw, lp as olp, rounding as ornd
+
+pytestmark = pytest.mark.gpu
+
+from gpu_util import gen, host, check, torch_mod  # noqa: E402
+
+
+@pytest.fixture(scope="module")
+def hap():
+    import paper_2401_05965_amd as h
+    return h
+
+
+@pytest.fixture(scope="module")
+def cfg2(hap):
+    w = hapgen.WORKLOADS["cfg2_mlp_bf16"]
+    Tn, h, F = w.dims["tokens"], w.dims["hidden"], w.dims["ffn"]
+    d = {}
+    d["Xh"], d["X"] = gen(0, T.X, (Tn, h), 1.0, "bf16")
+    d["W1h"], d["W1"] = gen(0, T.W, (h, F), 0.02, "bf16")
+    d["b1h"], d["b1"] = gen(0, T.BIAS, (F,), 0.02, "bf16")
+    d["W2h"], d["W2"] = gen(0, T.W2, (F, h), 0.02, "bf16")
+    d["dOh"], d["dO"] = gen(0, T.DY, (Tn, h), 1.0, "bf16")
+    ratios, _ = hap.hap_shard_ratios(w.speeds, [(1.0, 0, 0, 0)])
+    sizes, offs = hap.hap_round_shards(ratios, F)
+    assert (sizes, offs) == ornd.round_shards(olp.shard_ratios(w.speeds, [(1.0, 0, 0, 0)])[0], F)
+    assert sizes == [8402, 5041, 2941]
+    d["offs"] = offs
+    d["dims"] = (Tn, h, F)
+    return d
+
+
+@pytest.mark.parametrize("j", [0, 2])
+def test_cfg2_mlp_shard_full_size_sampled(hap, cfg2, j):
+    from paper_2401_05965_amd.programs import MlpShard
+    Tn, h, F = cfg2["dims"]
+    offs = cfg2["offs"]
+    lo, hi = offs[j], offs[j + 1]
+    f = hi - lo
+    s = MlpShard(Tn, h, F, offs, j, cfg2["X"], cfg2["W1"], cfg2["b1"], cfg2["W2"], cfg2["dO"])
+    s.forward(); s.backward()
+    rng = np.random.default_rng(j)
+    rows = np.unique(np.concatenate([[0, 255, 256, Tn - 1], rng.integers(0, Tn, 28)]))
+    X, dO = cfg2["Xh"], cfg2["dOh"]
+    W1, b1, W2 = cfg2["W1h"][:, lo:hi], cfg2["b1h"][lo:hi], cfg2["W2h"][lo:hi]
+    # sampled token rows: forward and bwd-data are row-wise
+    pre = X[rows] @ W1 + b1
+    H = opw.gelu(pre)
+    check("H rows", host(s.H[rows])[:, :f], H, "bf16")
+    check("pre rows", host(s.pre[rows])[:, :f], pre, "bf16")
+    check("P rows", host(s.P[rows]), H @ W2, "bf16")
+    dH = dO[rows] @ W2.T
+    check("dH rows", host(s.dH[rows])[:, :f], dH, "bf16")
+    check("dX rows", host(s.dX[rows]), (dH * opw.gelu_grad(pre)) @ W1.T, "bf16")
+    # sampled ffn columns (first, last, tile edges, random): weight gradients are column-wise in the ffn index
+    cols = np.unique(np.concatenate([[0, 255, 256, f - 1, (f // 256) * 256 % f], rng.integers(0, f, 11)]))
+    pre_c = X @ W1[:, cols] + b1[cols]
+    dP_c = (dO @ W2[cols].T) * opw.gelu_grad(pre_c)
+    check("dW1 cols", host(s.dW1)[:, cols], X.T @ dP_c, "bf16")
+    check("db1 cols", host(s.db1)[cols], dP_c.sum(0), "bf16")
+    check("dW2 rows", host(s.dW2)[cols], opw.gelu(pre_c).T @ dO, "bf16")
+    # padding columns of the compact buffers stay untouched (they were zero-initialised)
+    assert not host(s.H)[:, f:].any() and not host(s.dW1)[:, f:].any()
+
+
+def test_cfg3_sfb_full_size_sampled(hap):
+    from paper_2401_05965_amd.programs import SfbRebuild
+    w = hapgen.WORKLOADS["cfg3_sfb_bf16"]
+    inf, outf, cap, rows = w.dims["in_features"], w.dims["out_features"], w.dims["capacity"], w.dims["rows"]
+    Xh, Xd, Yh, Yd = [], [], [], []
+    for i in range(len(rows)):
+        a, b = gen(0, T.SFB_X + i, (cap, inf), 1.0, "bf16"); Xh.append(a); Xd.append(b)
+        a, b = gen(0, T.SFB_DY + i, (cap, outf), 1.0, "bf16"); Yh.append(a); Yd.append(b)
+        Xd[i][rows[i]:] = float("nan"); Yd[i][rows[i]:] = float("nan")      # padding rows of the padded All-Gather layout
+    prog = SfbRebuild(Xd, Yd, rows, inf, outf)
+    prog.dW.fill_(float("nan"))
+    prog.run()
+    got = host(prog.dW)
+    assert np.isfinite(got).all()
+    rng = np.random.default_rng(3)
+    ri = np.unique(np.concatenate([[0, 255, 256, inf - 1], rng.integers(0, inf, 12)]))
+    ref = sum(Xh[i][:rows[i]][:, ri].T @ Yh[i][:rows[i]] for i in range(len(rows)))
+    check("sfb dW rows", got[ri], ref, "bf16")
+    ci = np.unique(np.concatenate([[0, 255, 256, outf - 1], rng.integers(0, outf, 12)]))
+    ref = sum(Xh[i][:rows[i]].T @ Yh[i][:rows[i]][:, ci] for i in range(len(rows)))
+    check("sfb dW cols", got[:, ci], ref, "bf16")
+    # property that holds at any size: the rebuild equals the sum of per-device local gradients (Fig. sfb(b) vs (c))
+    torch = torch_mod()
+    naive = torch.zeros_like(prog.dW)
+    for i in range(len(rows)):
+        hap.hap_sfb_grad([Xd[i]], [Yd[i]], [rows[i]], inf, outf, inf, outf, hap.BF16, naive, outf, accumulate=True)
+    assert np.abs(host(naive) - got).max() <= 1e-3 * np.abs(got).max()
