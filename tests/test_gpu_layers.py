@@ -70,7 +70,7 @@ def test_mlp_block_ffn_sharded_three_devices(hap):
 
 def _check_layer(hap, style, B, S, hidden, heads, d, ffn, speeds):
     from paper_2401_05965_amd.programs import EncoderLayerProgram
-    ph, pd = make_params(1, hidden, ffn, 0.05)
+    ph, pd = make_params(1, hidden, ffn, 0.05 if hidden < 1024 else 0.02)
     xh, xd = gen(1, T.X, (B * S, hidden), 1.0, "bf16"); dyh, dyd = gen(1, T.DY, (B * S, hidden), 1.0, "bf16")
     _, hoffs = ratios_offsets(hap, speeds, heads)
     _, foffs = ratios_offsets(hap, speeds, ffn)
@@ -154,3 +154,17 @@ def test_vit_mlp_sfb_weight_gradients(hap):
     dW2 = empty((ffn, hidden), "f32", float("nan"))
     hap.hap_sfb_grad(dPs, Xs, rows, ffn, hidden, ffn, hidden, hap.BF16, dW2, hidden)
     check("sfb dW2", host(dW2), dPh.T @ Xh, "bf16")
+
+
+def test_cfg4_encoder_layer_full_widths(hap):
+    """cfg4 with its real widths (hidden 2048, 16 heads x 128 -> 5,5,3,3 heads, ffn 8192 -> 2731,2731,1365,1365, seq 1024)
+    and a reduced batch (2 of 16) so the float64 single-device oracle finishes in seconds."""
+    w = hapgen.WORKLOADS["cfg4_encoder_bf16"]; d = w.dims
+    _check_layer(hap, "tensor", B=2, S=d["seq"], hidden=d["hidden"], heads=d["heads"], d=d["head_dim"], ffn=d["ffn"], speeds=w.speeds)
+
+
+def test_cfg5_vit_layer_full_widths(hap):
+    """cfg5 with its real widths (hidden 1024, 16 heads x 64, 197 tokens, ffn 4096) and batch 26 of 256
+    (5 devices -> 8,6,6,3,3 samples)."""
+    w = hapgen.WORKLOADS["cfg5_vit_bf16"]; d = w.dims
+    _check_layer(hap, "data", B=26, S=d["seq"], hidden=d["hidden"], heads=d["heads"], d=d["head_dim"], ffn=d["ffn"], speeds=w.speeds)
