@@ -132,6 +132,10 @@ int hap_sharded_linear_bwd(const hap_linear_desc* d, int shard_index, const void
                            const void* preact, const void* dY, void* dX, void* dW, int dW_dtype,
                            float* dbias, void* ws, size_t ws_bytes, void* stream);
 
+/* Workspace sizes.  The forward needs none; what hap_linear_fwd_workspace() reports (and the last 64 MiB of what
+ * hap_linear_bwd_workspace() / hap_sfb_workspace() report) is OPTIONAL scratch that lets the GEMM engine split the
+ * contracted axis over idle compute units when an output has too few tiles to fill the chip.  With a smaller
+ * buffer, or ws = NULL in the forward / SFB calls, results are the same and only that optimisation is skipped.  */
 size_t hap_linear_fwd_workspace(const hap_linear_desc* d, int shard_index);
 size_t hap_linear_bwd_workspace(const hap_linear_desc* d, int shard_index);
 

@@ -191,6 +191,10 @@ def hap_sfb_grad(Xs, dYs, rows, in_features, out_features, ldx, ldy, in_dtype, d
                             wp, wb, _stream(stream)), "hap_sfb_grad")
 
 
+def hap_sfb_workspace(m, rows, in_features, out_features) -> int:
+    return int(lib.hap_sfb_workspace(C.c_int(m), (C.c_int64 * m)(*map(int, rows)), C.c_int64(in_features), C.c_int64(out_features)))
+
+
 def hap_attn_bwd_workspace(desc: AttnDesc, shard_index: int) -> int:
     return int(lib.hap_attn_bwd_workspace(C.byref(desc.c), C.c_int(shard_index)))
 

@@ -12,6 +12,7 @@
 #ifndef HAP_GEMM_H
 #define HAP_GEMM_H
 
+#include <stddef.h>
 #include <stdint.h>
 
 #include "hap_internal.h"
@@ -33,6 +34,7 @@ struct hap_gemm_problem {
   void* preact; int64_t ldp;           /* optional copy of (product + bias) in c_dtype            */
   int act;                             /* hap_act                                                 */
   int force_generic;                   /* testing aid: take the scalar fallback kernel            */
+  void* ws; size_t ws_bytes;           /* optional device scratch for split-K partial tiles (NULL: never split K)   */
   int tile;                            /* 0: engine chooses (and may split the problem); 128 / 256: fixed output tile */
 };
 
@@ -41,5 +43,8 @@ int hap_gemm_run(const hap_gemm_problem* p, void* stream);
 
 /* Name of the kernel variant the launcher would choose, for reports. */
 const char* hap_gemm_variant(const hap_gemm_problem* p);
+
+/* Scratch that lets every problem split K as far as the engine would like to (an upper bound). */
+#define HAP_GEMM_WS_BYTES ((size_t)64 << 20)
 
 #endif

@@ -34,6 +34,7 @@ typedef int i32x4_t __attribute__((ext_vector_type(4)));
 
 #define LDS_PTR(T, p) ((__attribute__((address_space(3))) T*)(p))
 
+constexpr int kCUs = 256;                     // compute units of MI355X
 constexpr unsigned kOobOffset = 0x80000000u;  // beyond any num_records we pass: reads as zero
 constexpr int kRsrcFlags = 0x00020000;        // raw buffer, 32-bit data format
 
@@ -52,6 +53,8 @@ struct GemmArgs {
   int nseg;
   int tiles_m, tiles_n;
   int vec_store;       // C (and preact) rows are 16-byte addressable: whole-chunk stores allowed
+  int ksplit;          // >1: each output tile is computed by ksplit workgroups over disjoint K-tile ranges, fp32 partials go to `partial`
+  float* partial;      // [tiles][ksplit][BM][BN] fp32 workspace when ksplit > 1
   int ntiles;          // K tiles over all segments at the direct-to-LDS kernel's BK (0 for the staged kernel)
   long long lda, ldb, ldc, ldp;
   void* c;
@@ -587,8 +590,10 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_dma_kernel(const GemmArgs
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm0 = (wave / WGN) * WTM, wn0 = (wave % WGN) * WTN;
+  // With split-K, ksplit consecutive workgroups share an output tile and take consecutive K-tile ranges.
+  const int ksplit = args.ksplit, out_tile = blockIdx.x / ksplit, split = blockIdx.x - out_tile * ksplit;
   int tm, tn;
-  tile_of_block(blockIdx.x, gridDim.x, args.tiles_m, args.tiles_n, &tm, &tn);
+  tile_of_block(out_tile, gridDim.x / ksplit, args.tiles_m, args.tiles_n, &tm, &tn);
   const int m0 = tm * BM, n0 = tn * BN;
   const int m_lim = args.skewM + args.M, n_lim = args.skewN + args.N;
 
@@ -604,13 +609,22 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_dma_kernel(const GemmArgs
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
 
+  // this workgroup's range [first, first + ntiles) of the K tiles of all segments laid end to end
+  const int first = (int)((long long)args.ntiles * split / ksplit);
+  const int ntiles = (int)((long long)args.ntiles * (split + 1) / ksplit) - first;
+  int seg0 = 0, skip = first;
+  while (seg0 + 1 < args.nseg) {
+    const int in_seg = (args.skewK + args.seg[seg0].k + BK - 1) / BK;
+    if (skip < in_seg) break;
+    skip -= in_seg;
+    seg0 = uni(seg0 + 1);
+  }
   // producer state (runs STAGES-1 tiles ahead of the consumer)
-  int pseg = 0, pk0 = 0, pkend = args.skewK + args.seg[0].k, pslot = 0;
-  __amdgpu_buffer_rsrc_t ra = make_rsrc(args.seg[0].a, args.seg[0].a_bytes);
-  __amdgpu_buffer_rsrc_t rb = make_rsrc(args.seg[0].b, args.seg[0].b_bytes);
+  int pseg = seg0, pk0 = skip * BK, pkend = uni(args.skewK + args.seg[seg0].k), pslot = 0;
+  __amdgpu_buffer_rsrc_t ra = make_rsrc(args.seg[seg0].a, args.seg[seg0].a_bytes);
+  __amdgpu_buffer_rsrc_t rb = make_rsrc(args.seg[seg0].b, args.seg[seg0].b_bytes);
   // consumer state: k range of the tile being consumed (for the edge fix-up)
-  int cseg = 0, ck0 = 0, ckend = pkend, cslot = 0;
-  const int ntiles = args.ntiles;
+  int cseg = seg0, ck0 = pk0, ckend = pkend, cslot = 0;
   constexpr int KK = BK / 16;
   constexpr int MF = TM * TN;                       // MFMAs per k-step
 
@@ -691,7 +705,51 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_dma_kernel(const GemmArgs
   }
 
   __syncthreads();   // every wave is done reading the ring: reuse it as per-wave store patches
+  if (ksplit > 1) {
+    // raw fp32 partial tile [BM][BN]; bias, activation and the real store happen in the reduction kernel
+    GemmArgs pa = args;
+    pa.c = args.partial + ((long long)out_tile * ksplit + split) * (BM * BN);
+    pa.ldc = BN; pa.M = BM; pa.N = BN; pa.skewM = 0; pa.skewN = 0;
+    pa.preact = nullptr; pa.bias = nullptr; pa.act = HAP_ACT_NONE; pa.accumulate = 0; pa.vec_store = 1;
+    epilogue_transposed<T, float, TM, TN>(pa, acc, wm0, wn0, lane, smem + wave * (32 * (TN * 32 * 4 + 16)));
+    return;
+  }
   epilogue_transposed<T, TC, TM, TN>(args, acc, m0 + wm0, n0 + wn0, lane, smem + wave * (32 * (TN * 32 * (int)sizeof(TC) + 16)));
+}
+
+/* Split-K reduction: sums the ksplit fp32 partial tiles of every output tile and applies what the
+ * one-pass epilogue would have (bias, pre-activation copy, activation, accumulation, conversion),
+ * storing only the logical rows / columns.  One thread per 4 consecutive columns. */
+template <typename T, typename TC, int BM, int BN>
+__global__ __launch_bounds__(256) void splitk_reduce_kernel(const GemmArgs args, int out_tiles) {
+  constexpr int QPT = BM * BN / 4;                 // column quads per tile
+  const long long gid = (long long)blockIdx.x * 256 + threadIdx.x;
+  const int tile = (int)(gid / QPT), q = (int)(gid % QPT);
+  if (tile >= out_tiles) return;
+  int tm, tn;
+  tile_of_block(tile, out_tiles, args.tiles_m, args.tiles_n, &tm, &tn);
+  const int r = q / (BN / 4), c4 = (q % (BN / 4)) * 4;
+  const int m = tm * BM + r - args.skewM, n = tn * BN + c4 - args.skewN;
+  if (m < 0 || m >= args.M || n >= args.N || n + 4 <= 0) return;
+  typedef float f32x4_t __attribute__((ext_vector_type(4)));
+  f32x4_t sum = {0.0f, 0.0f, 0.0f, 0.0f};
+  const float* p = args.partial + (long long)tile * args.ksplit * (BM * BN) + r * BN + c4;
+  for (int s = 0; s < args.ksplit; ++s) sum += *reinterpret_cast<const f32x4_t*>(p + (long long)s * (BM * BN));
+  TC* C = static_cast<TC*>(args.c);
+  TC* P = static_cast<TC*>(args.preact);
+  const T* bias = static_cast<const T*>(args.bias);
+#pragma unroll
+  for (int x = 0; x < 4; ++x) {
+    const int nn = n + x;
+    if (nn < 0 || nn >= args.N) continue;
+    float v = sum[x];
+    if (bias) v += load_s<T>(bias + nn);
+    if (P) store_c<TC>(P + (long long)m * args.ldp + nn, v);
+    if (args.act == HAP_ACT_GELU_ERF) v = gelu_erf(v);
+    TC* dst = C + (long long)m * args.ldc + nn;
+    if (args.accumulate) v += load_s<TC>(dst);
+    store_c<TC>(dst, v);
+  }
 }
 
 /* Scalar fallback for operand views the tiled kernel cannot address with aligned 16-byte chunks
@@ -810,9 +868,16 @@ int launch_dma(const GemmArgs& a, hipStream_t st) {
     if (e != hipSuccess) return hap_fail(HAP_EDEVICE, "cannot reserve %zu bytes of LDS: %s", smem, hipGetErrorString(e));
     configured = true;
   }
-  hipLaunchKernelGGL((gemm_dma_kernel<TC, AKC, BKC, BM, BN, BK, WGM, WGN, STAGES>), dim3(a.tiles_m * a.tiles_n), dim3(64 * WGM * WGN), smem, st, a);
-  const hipError_t e = hipGetLastError();
+  const int out_tiles = a.tiles_m * a.tiles_n;
+  hipLaunchKernelGGL((gemm_dma_kernel<TC, AKC, BKC, BM, BN, BK, WGM, WGN, STAGES>), dim3(out_tiles * a.ksplit), dim3(64 * WGM * WGN), smem, st, a);
+  hipError_t e = hipGetLastError();
   if (e != hipSuccess) return hap_fail(HAP_EDEVICE, "gemm launch: %s", hipGetErrorString(e));
+  if (a.ksplit > 1) {
+    const long long threads = (long long)out_tiles * (BM * BN / 4);
+    hipLaunchKernelGGL((splitk_reduce_kernel<__bf16, TC, BM, BN>), dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, st, a, out_tiles);
+    e = hipGetLastError();
+    if (e != hipSuccess) return hap_fail(HAP_EDEVICE, "split-K reduce launch: %s", hipGetErrorString(e));
+  }
   return HAP_OK;
 }
 
@@ -852,8 +917,6 @@ const char* hap_gemm_variant(const hap_gemm_problem* p) { return make_plan(p).na
 
 namespace {
 
-constexpr int kCUs = 256;
-
 /* Relative time of n output tiles of 128x128 (one 256x256 tile on one CU = 1): a small tile does a
  * quarter of the work at lower efficiency, and two of them share a CU. */
 double small_tiles_time(long long n) {
@@ -888,21 +951,42 @@ static int run_auto_tiled(const hap_gemm_problem* p, const Plan& pl, void* strea
   const long long Mp = p->M + pl.skewM, Np = p->N + pl.skewN;
   const long long tm = cdiv(Mp, 256), tn = cdiv(Np, 256);
   const long long sm = cdiv(Mp, 128), sn = cdiv(Np, 128);
+  // A remainder strip of r big tiles can also stay on big tiles with its K range split over the idle CUs
+  // (needs workspace); that costs about a third of a round for the partial-tile traffic plus 1/g rounds.
+  const bool can_split_k = p->ws && p->ws_bytes >= (size_t)8 << 20;
+  auto strip_time = [&](long long big_tiles, long long small_tiles, int* tile) {
+    double t = small_tiles_time(small_tiles);
+    *tile = 128;
+    if (can_split_k && big_tiles * 2 <= kCUs) {
+      const double ts = 0.35 + 1.0 / (double)(kCUs / big_tiles);
+      if (ts < t) { t = ts; *tile = 256; }
+    }
+    return t;
+  };
   double best = (double)cdiv(tm * tn, kCUs);
   int choice = 0;                 // 0: all big, 1: all small, 2: split columns, 3: split rows
+  int strip_tile = 128;
   long long cut = 0;
-  const double all_small = small_tiles_time(sm * sn);
-  if (all_small < best - 1e-9) { best = all_small; choice = 1; }
+  if (tm * tn < kCUs) {           // cannot fill the chip: small tiles, or big tiles with split-K (chosen at launch)
+    int tl;
+    const double t = strip_time(tm * tn, sm * sn, &tl);
+    if (t < best - 1e-9) { best = t; choice = tl == 128 ? 1 : 0; }
+  } else {
+    const double all_small = small_tiles_time(sm * sn);
+    if (all_small < best - 1e-9) { best = all_small; choice = 1; }
+  }
   for (long long c = tn - 1; c >= 1; --c)
     if ((tm * c) % kCUs == 0) {
-      const double t = (double)(tm * c / kCUs) + small_tiles_time(sm * cdiv(Np - c * 256, 128));
-      if (t < best - 1e-9) { best = t; choice = 2; cut = c; }
+      int tl;
+      const double t = (double)(tm * c / kCUs) + strip_time(tm * (tn - c), sm * cdiv(Np - c * 256, 128), &tl);
+      if (t < best - 1e-9) { best = t; choice = 2; cut = c; strip_tile = tl; }
       break;
     }
   for (long long r = tm - 1; r >= 1; --r)
     if ((tn * r) % kCUs == 0) {
-      const double t = (double)(tn * r / kCUs) + small_tiles_time(sn * cdiv(Mp - r * 256, 128));
-      if (t < best - 1e-9) { best = t; choice = 3; cut = r; }
+      int tl;
+      const double t = (double)(tn * r / kCUs) + strip_time(tn * (tm - r), sn * cdiv(Mp - r * 256, 128), &tl);
+      if (t < best - 1e-9) { best = t; choice = 3; cut = r; strip_tile = tl; }
       break;
     }
   hap_gemm_problem q;
@@ -915,14 +999,14 @@ static int run_auto_tiled(const hap_gemm_problem* p, const Plan& pl, void* strea
       const int64_t n_cut = cut * 256 - pl.skewN;
       q = sub_problem(p, 0, p->M, 0, n_cut, 256);
       if ((rc = hap_gemm_run(&q, stream))) return rc;
-      q = sub_problem(p, 0, p->M, n_cut, p->N, 128);
+      q = sub_problem(p, 0, p->M, n_cut, p->N, strip_tile);
       return hap_gemm_run(&q, stream);
     }
     case 3: {
       const int64_t m_cut = cut * 256 - pl.skewM;
       q = sub_problem(p, 0, m_cut, 0, p->N, 256);
       if ((rc = hap_gemm_run(&q, stream))) return rc;
-      q = sub_problem(p, m_cut, p->M, 0, p->N, 128);
+      q = sub_problem(p, m_cut, p->M, 0, p->N, strip_tile);
       return hap_gemm_run(&q, stream);
     }
     default:
@@ -999,10 +1083,25 @@ int hap_gemm_run(const hap_gemm_problem* p, void* stream) {
                   (!p->preact || (((uintptr_t)p->preact % 16) == 0 && p->ldp % cepc == 0));
   }
   a.ntiles = 0;
+  a.ksplit = 1;
+  a.partial = nullptr;
   if (pl.dma) {
     const int bk = 64;
     for (int s = 0; s < a.nseg; ++s) a.ntiles += (pl.skewK + a.seg[s].k + bk - 1) / bk;
     if (a.ntiles == 0) a.ntiles = 1;     // empty contraction still runs one (all-zero) tile
+    // Split-K when the output tiles cannot occupy the chip: spread each tile's K range over the idle CUs,
+    // keeping at least 4 K tiles per workgroup, as far as the caller's workspace allows.
+    const long long out_tiles = (long long)a.tiles_m * a.tiles_n;
+    const long long slots = pl.bm == 256 ? kCUs : 2 * kCUs;
+    long long g = slots / out_tiles;
+    if (g > a.ntiles / 4) g = a.ntiles / 4;
+    if (g > 16) g = 16;
+    const size_t per_split = (size_t)out_tiles * pl.bm * pl.bn * sizeof(float);
+    if (g >= 2 && p->ws && per_split * 2 <= p->ws_bytes) {
+      if (per_split * (size_t)g > p->ws_bytes) g = (long long)(p->ws_bytes / per_split);
+      a.ksplit = (int)g;
+      a.partial = static_cast<float*>(p->ws);
+    }
   }
   if (p->in_dtype == HAP_BF16 && p->c_dtype == HAP_BF16) return dispatch_tile<__bf16, __bf16>(p, pl, a, st);
   if (p->in_dtype == HAP_BF16) return dispatch_tile<__bf16, float>(p, pl, a, st);

@@ -89,20 +89,26 @@ inline char* at(void* p, int64_t elems, int es) { return static_cast<char*>(p) +
 
 extern "C" {
 
-size_t hap_linear_fwd_workspace(const hap_linear_desc*, int) { return 0; }
+size_t hap_linear_fwd_workspace(const hap_linear_desc*, int) { return HAP_GEMM_WS_BYTES; }   // optional: split-K partial tiles
 
-size_t hap_linear_bwd_workspace(const hap_linear_desc* d, int shard_index) {
+static size_t required_bwd_bytes(const hap_linear_desc* d, int shard_index) {
   View v;
   if (resolve(d, shard_index, &v) != HAP_OK) return 0;
   size_t need = 0;
   if (d->act != HAP_ACT_NONE) need += (size_t)(v.tok_n * (round_up(v.out_n, 8) + 8)) * esize(d->io_dtype);
   need = (size_t)round_up((int64_t)need, 256);
-  need += hap_colsum_workspace(v.tok_n, v.out_n);
+  need += (size_t)round_up((int64_t)hap_colsum_workspace(v.tok_n, v.out_n), 256);
   return need;
 }
 
+/* required_bwd_bytes(): the part that must be there (dP and column-sum scratch); the rest of what
+ * hap_linear_bwd_workspace() reports is optional split-K scratch for the GEMM engine. */
+size_t hap_linear_bwd_workspace(const hap_linear_desc* d, int shard_index) {
+  return required_bwd_bytes(d, shard_index) + HAP_GEMM_WS_BYTES;
+}
+
 int hap_sharded_linear_fwd(const hap_linear_desc* d, int shard_index, const void* X, const void* W,
-                           const void* bias, void* Y, void* preact, void*, size_t, void* stream) {
+                           const void* bias, void* Y, void* preact, void* ws, size_t ws_bytes, void* stream) {
   hap_clear_error();
   View v;
   int rc = resolve(d, shard_index, &v);
@@ -122,6 +128,7 @@ int hap_sharded_linear_fwd(const hap_linear_desc* d, int shard_index, const void
   p.bias = bias ? at(bias, o.b, es) : NULL;
   p.preact = preact ? at(preact, o.y, es) : NULL; p.ldp = d->ldy;
   p.act = d->act;
+  p.ws = ws; p.ws_bytes = ws ? ws_bytes : 0;
   return hap_gemm_run(&p, stream);
 }
 
@@ -141,7 +148,7 @@ int hap_sharded_linear_bwd(const hap_linear_desc* d, int shard_index, const void
   if (dW && d->io_dtype == HAP_F32 && dW_dtype != HAP_F32) return hap_fail(HAP_EINVAL, "fp32 layer needs fp32 dW");
   if (dbias && d->mode == HAP_SHARD_REDUCTION) return hap_fail(HAP_EINVAL, "dbias is not defined for a reduction-sharded partial");
   if (d->act != HAP_ACT_NONE && !preact && has_dp) return hap_fail(HAP_EINVAL, "activation backward needs the saved pre-activation");
-  const size_t need = hap_linear_bwd_workspace(d, shard_index);
+  const size_t need = required_bwd_bytes(d, shard_index);
   if (need && (d->act != HAP_ACT_NONE || dbias) && (!ws || ws_bytes < need))
     return hap_fail(HAP_EWORKSPACE, "linear_bwd needs %zu workspace bytes", need);
   // Empty shards need no special case: a product with an empty output is skipped by the engine and
@@ -164,6 +171,11 @@ int hap_sharded_linear_bwd(const hap_linear_desc* d, int shard_index, const void
     dP = dst;
     wsp += round_up((int64_t)((size_t)(v.tok_n * lddp) * es), 256);
   }
+  // [dP][column-sum scratch][optional split-K scratch for the GEMM engine]
+  char* colsum_ws = wsp;
+  char* gemm_ws = colsum_ws + round_up((int64_t)hap_colsum_workspace(v.tok_n, v.out_n), 256);
+  const size_t used = ws ? (size_t)(gemm_ws - static_cast<char*>(ws)) : 0;
+  const size_t gemm_ws_bytes = (ws && ws_bytes > used) ? ws_bytes - used : 0;
   if (dX) {
     hap_gemm_problem p = {};
     p.M = v.tok_n; p.N = v.in_n;
@@ -172,6 +184,7 @@ int hap_sharded_linear_bwd(const hap_linear_desc* d, int shard_index, const void
     p.b[0] = at(W, o.w, es); p.ldb = d->ldw; p.b_kcontig = 1;   // B(k = out, n = in) = W[n*ldw + k]
     p.in_dtype = d->io_dtype;
     p.c = at(dX, o.x, es); p.ldc = d->ldx; p.c_dtype = d->io_dtype;
+    p.ws = gemm_ws_bytes ? gemm_ws : NULL; p.ws_bytes = gemm_ws_bytes;
     rc = hap_gemm_run(&p, stream);
     if (rc) return rc;
   }
@@ -184,21 +197,22 @@ int hap_sharded_linear_bwd(const hap_linear_desc* d, int shard_index, const void
     p.b[0] = dP; p.ldb = lddp; p.b_kcontig = 0;
     p.in_dtype = d->io_dtype;
     p.c = at(dW, o.w, wes); p.ldc = d->ldw; p.c_dtype = dW_dtype;
+    p.ws = gemm_ws_bytes ? gemm_ws : NULL; p.ws_bytes = gemm_ws_bytes;
     rc = hap_gemm_run(&p, stream);
     if (rc) return rc;
   }
   if (dbias) {
-    rc = hap_colsum(v.tok_n, v.out_n, d->io_dtype, dP, lddp, dbias + o.b, wsp, hap_colsum_workspace(v.tok_n, v.out_n), stream);
+    rc = hap_colsum(v.tok_n, v.out_n, d->io_dtype, dP, lddp, dbias + o.b, colsum_ws, hap_colsum_workspace(v.tok_n, v.out_n), stream);
     if (rc) return rc;
   }
   return HAP_OK;
 }
 
-size_t hap_sfb_workspace(int, const int64_t*, int64_t, int64_t) { return 0; }
+size_t hap_sfb_workspace(int, const int64_t*, int64_t, int64_t) { return HAP_GEMM_WS_BYTES; }   // optional: split-K partial tiles
 
 int hap_sfb_grad(int m, const void* const* X, const void* const* dY, const int64_t* rows,
                  int64_t in_features, int64_t out_features, int64_t ldx, int64_t ldy, int in_dtype,
-                 float* dW, int64_t lddw, int accumulate, void*, size_t, void* stream) {
+                 float* dW, int64_t lddw, int accumulate, void* ws, size_t ws_bytes, void* stream) {
   hap_clear_error();
   if (m < 1 || m > HAP_SFB_MAX_DEVICES) return hap_fail(HAP_EINVAL, "m = %d outside [1, %d]", m, HAP_SFB_MAX_DEVICES);
   if (!X || !dY || !rows || !dW) return hap_fail(HAP_EINVAL, "NULL argument");
@@ -218,6 +232,7 @@ int hap_sfb_grad(int m, const void* const* X, const void* const* dY, const int64
   p.in_dtype = in_dtype;
   p.c = dW; p.ldc = lddw; p.c_dtype = HAP_F32;
   p.accumulate = accumulate ? 1 : 0;
+  p.ws = ws; p.ws_bytes = ws ? ws_bytes : 0;
   return hap_gemm_run(&p, stream);
 }
 

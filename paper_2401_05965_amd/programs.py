@@ -58,7 +58,7 @@ class MlpShard:
         self.fc2 = hap.LinearDesc(tokens, ffn, hidden, hap.SHARD_REDUCTION, offsets, io, ldx=ld, ldw=hidden, ldy=hidden,
                                   operands_are_full=False)
         nws = max(hap.hap_linear_bwd_workspace(self.fc1, j), hap.hap_linear_bwd_workspace(self.fc2, j), 256)
-        self.ws = torch.empty((nws,), dtype=torch.uint8, device=dev)
+        self.ws = torch.empty((nws,), dtype=torch.uint8, device=dev)      # also serves the forward's optional split-K scratch
 
     def flops(self):
         """Algorithmic flops of (fwd, bwd): 2 GEMMs forward, 4 backward, 2*M*N*K each."""
@@ -67,8 +67,8 @@ class MlpShard:
 
     def forward(self, timer=None):
         j = self.j
-        _call(timer, "fc1_fwd", lambda: hap.hap_sharded_linear_fwd(self.fc1, j, self.X, self.W1, self.b1, self.H, self.pre))
-        _call(timer, "fc2_fwd", lambda: hap.hap_sharded_linear_fwd(self.fc2, j, self.H, self.W2, None, self.P, None))
+        _call(timer, "fc1_fwd", lambda: hap.hap_sharded_linear_fwd(self.fc1, j, self.X, self.W1, self.b1, self.H, self.pre, self.ws))
+        _call(timer, "fc2_fwd", lambda: hap.hap_sharded_linear_fwd(self.fc2, j, self.H, self.W2, None, self.P, None, self.ws))
 
     def backward(self, timer=None):
         j = self.j
@@ -88,13 +88,14 @@ class SfbRebuild:
         self.inf, self.outf = in_features, out_features
         self.dW = torch.zeros((in_features, out_features), dtype=torch.float32, device=Xs[0].device)
         self.dtype = hap.BF16 if Xs[0].dtype == torch.bfloat16 else hap.F32
+        self.ws = torch.empty((hap.hap_sfb_workspace(len(self.rows), self.rows, in_features, out_features),), dtype=torch.uint8, device=Xs[0].device)
 
     def flops(self):
         return 2.0 * self.inf * self.outf * sum(self.rows)
 
     def run(self, timer=None):
         _call(timer, "sfb_grad", lambda: hap.hap_sfb_grad(self.Xs, self.dYs, self.rows, self.inf, self.outf, self.Xs[0].stride(0),
-                                                          self.dYs[0].stride(0), self.dtype, self.dW, self.outf))
+                                                          self.dYs[0].stride(0), self.dtype, self.dW, self.outf, ws=self.ws))
 
 
 def _zeros(shape, dtype, dev):
@@ -189,10 +190,10 @@ class EncoderShard:
         if hd == 0:
             self.attn_part.zero_()
             return
-        _call(timer, "qkv_fwd", lambda: hap.hap_sharded_linear_fwd(self.d_qkv, 0, self.ln1, self.Wqkv, self.bqkv, self.qkv, None))
+        _call(timer, "qkv_fwd", lambda: hap.hap_sharded_linear_fwd(self.d_qkv, 0, self.ln1, self.Wqkv, self.bqkv, self.qkv, None, self.ws))
         q = self.qkv.data_ptr()
         _call(timer, "attn_fwd", lambda: hap.hap_sharded_attn_fwd(self.d_attn, 0, q, q + hd * 2, q + 2 * hd * 2, self.o, self.lse))
-        _call(timer, "wo_fwd", lambda: hap.hap_sharded_linear_fwd(self.d_wo, 0, self.o, self.Wo, None, self.attn_part, None))
+        _call(timer, "wo_fwd", lambda: hap.hap_sharded_linear_fwd(self.d_wo, 0, self.o, self.Wo, None, self.attn_part, None, self.ws))
 
     def mlp_forward(self, x1, timer=None):
         N, io = self.N, self.io
@@ -200,8 +201,8 @@ class EncoderShard:
         if self.f == 0:
             self.mlp_part.zero_()
             return
-        _call(timer, "fc1_fwd", lambda: hap.hap_sharded_linear_fwd(self.d_fc1, 0, self.ln2, self.W1, self.b1, self.H, self.pre))
-        _call(timer, "fc2_fwd", lambda: hap.hap_sharded_linear_fwd(self.d_fc2, 0, self.H, self.W2, None, self.mlp_part, None))
+        _call(timer, "fc1_fwd", lambda: hap.hap_sharded_linear_fwd(self.d_fc1, 0, self.ln2, self.W1, self.b1, self.H, self.pre, self.ws))
+        _call(timer, "fc2_fwd", lambda: hap.hap_sharded_linear_fwd(self.d_fc2, 0, self.H, self.W2, None, self.mlp_part, None, self.ws))
 
     def mlp_backward(self, dy, timer=None):
         """dy: gradient of the layer output on this device's rows.  Leaves the fc1 bwd-data product in dln2_part."""

@@ -225,3 +225,41 @@ def test_sfb_ragged_segments_padding_never_read(hap):
     # all devices empty -> zeros
     hap.hap_sfb_grad(Xd, dYd, [0] * 5, in_f, out_f, in_f, out_f, hap.BF16, dW1, out_f)
     assert not host(dW1).any()
+
+
+def test_sfb_split_k_over_segment_boundaries(hap):
+    """With workspace the engine splits the contracted axis over idle compute units; the split points fall
+    inside and between the devices' ragged segments.  Result must equal the one-pass result."""
+    rows = [300, 0, 77, 512, 130]
+    cap, in_f, out_f = 512, 264, 392
+    Xh, Xd, dYh, dYd = [], [], [], []
+    for i in range(len(rows)):
+        a, b = gen(9, T.SFB_X + i, (cap, in_f), 1.0, "bf16"); Xh.append(a); Xd.append(b)
+        a, b = gen(9, T.SFB_DY + i, (cap, out_f), 1.0, "bf16"); dYh.append(a); dYd.append(b)
+        Xd[i][rows[i]:] = float("nan"); dYd[i][rows[i]:] = float("nan")
+    ref = osfb.sfb_grad(Xh, dYh, rows)
+    ws = empty((hap.hap_sfb_workspace(len(rows), rows, in_f, out_f),), "u8")
+    dW = empty((in_f, out_f), "f32", float("nan"))
+    hap.hap_sfb_grad(Xd, dYd, rows, in_f, out_f, in_f, out_f, hap.BF16, dW, out_f, ws=ws)
+    check("sfb split-k", host(dW), ref, "bf16")
+    dW1 = empty((in_f, out_f), "f32", float("nan"))
+    hap.hap_sfb_grad(Xd, dYd, rows, in_f, out_f, in_f, out_f, hap.BF16, dW1, out_f)
+    assert np.abs(host(dW1) - host(dW)).max() <= 1e-5 * np.abs(ref).max()      # fp32 partial sums, different order only
+    hap.hap_sfb_grad(Xd, dYd, rows, in_f, out_f, in_f, out_f, hap.BF16, dW, out_f, accumulate=True, ws=ws)
+    check("sfb split-k accumulate", host(dW), 2 * ref, "bf16")
+
+
+def test_linear_split_k_with_bias_gelu_and_ragged_view(hap):
+    """Deep contraction, few output tiles, bias + GeLU + saved pre-activation, misaligned column range:
+    the forward goes through split-K when given workspace."""
+    tokens, in_f, out_f = 200, 1024, 520
+    offs = [0, 137, 391, 520]
+    Xh, Xd = gen(5, T.X, (tokens, in_f), 1.0, "bf16"); Wh, Wd = gen(5, T.W, (in_f, out_f), 0.05, "bf16")
+    bh, bd = gen(5, T.BIAS, (out_f,), 0.5, "bf16")
+    desc = hap.LinearDesc(tokens, in_f, out_f, hap.SHARD_FEATURE, offs, hap.BF16, act=hap.ACT_GELU_ERF, has_bias=True)
+    ws = empty((hap.lib.hap_linear_fwd_workspace(None, 0),), "u8")
+    Yo, preo = olin.linear_fwd(Xh, Wh, bh, True)
+    Y = empty((tokens, out_f), "bf16", 0); P = empty((tokens, out_f), "bf16", 0)
+    for j in range(3):
+        hap.hap_sharded_linear_fwd(desc, j, Xd, Wd, bd, Y, P, ws)
+    check("split-k Y", host(Y), Yo, "bf16"); check("split-k preact", host(P), preo, "bf16")
