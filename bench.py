@@ -125,6 +125,47 @@ def main():
         res["copy_read_plus_write_gbs"] = round(2 * src.numel() * 4 * 20 / (a.elapsed_time(b) * 1e-3) / 1e9, 1)
         return res
 
+    def other_rows():
+        """Throughput of the path's remaining kernels (attention slice, row / element ops) at config 4's shard-0 shapes
+        (16 x 5 heads x 1024 x 128; 16384 x 2048 rows), measured in this run; not part of `value`."""
+        B, S, nh, dh, hid = 16, 1024, 5, 128, 2048
+        N = B * S
+        res = {}
+
+        def timeit(fn, n=10):
+            for _ in range(2):
+                fn()
+            a = torch.cuda.Event(enable_timing=True); b = torch.cuda.Event(enable_timing=True)
+            a.record(stream)
+            for _ in range(n):
+                fn()
+            b.record(stream); b.synchronize()
+            return a.elapsed_time(b) / n * 1e-3
+
+        qkv = dev_bf16(1, T.Q, (N, 3 * nh * dh), 1.0); dqkv = torch.zeros_like(qkv)
+        o = torch.zeros((N, nh * dh), dtype=torch.bfloat16, device=dev); do = dev_bf16(1, T.DO, (N, nh * dh), 1.0)
+        lse = torch.zeros((B, nh, S), dtype=torch.float32, device=dev)
+        ad = hap.AttnDesc(B, nh, S, dh, True, [0, nh], stride_b=S * 3 * nh * dh, stride_s=3 * nh * dh, stride_h=dh, o_strides=(S * nh * dh, nh * dh, dh))
+        aws = torch.empty((hap.hap_attn_bwd_workspace(ad, 0),), dtype=torch.uint8, device=dev)
+        q = qkv.data_ptr(); dq = dqkv.data_ptr(); hd2 = nh * dh * 2
+        fl = 4.0 * B * nh * S * S * dh
+        t = timeit(lambda: hap.hap_sharded_attn_fwd(ad, 0, q, q + hd2, q + 2 * hd2, o, lse))
+        res["attn_fwd_tflops"] = round(fl / t / 1e12, 1)
+        t = timeit(lambda: hap.hap_sharded_attn_bwd(ad, 0, q, q + hd2, q + 2 * hd2, o, lse, do, dq, dq + hd2, dq + 2 * hd2, aws))
+        res["attn_bwd_tflops_2x_fwd_flops"] = round(2 * fl / t / 1e12, 1)
+        x = dev_bf16(1, T.X, (N, hid), 1.0); y = torch.zeros_like(x); dy = dev_bf16(1, T.DY, (N, hid), 1.0)
+        g = torch.ones((hid,), dtype=torch.bfloat16, device=dev); be = torch.zeros_like(g)
+        mean = torch.zeros((N,), dtype=torch.float32, device=dev); rstd = torch.zeros_like(mean)
+        dg = torch.zeros((hid,), dtype=torch.float32, device=dev); dbe = torch.zeros_like(dg)
+        lws = torch.empty((max(hap.hap_layernorm_bwd_workspace(N, hid), hap.hap_colsum_workspace(N, hid)),), dtype=torch.uint8, device=dev)
+        nb = N * hid * 2
+        t = timeit(lambda: hap.hap_layernorm_fwd(N, hid, hap.BF16, x, g, be, y, mean, rstd)); res["layernorm_fwd_gbs"] = round(2 * nb / t / 1e9)
+        t = timeit(lambda: hap.hap_layernorm_bwd(N, hid, hap.BF16, x, g, mean, rstd, dy, y, dg, dbe, lws)); res["layernorm_bwd_gbs"] = round(3 * nb / t / 1e9)
+        t = timeit(lambda: hap.hap_gelu_bwd(N, hid, hap.BF16, x, hid, dy, hid, y, hid)); res["gelu_bwd_gbs"] = round(3 * nb / t / 1e9)
+        t = timeit(lambda: hap.hap_add(N, hid, hap.BF16, x, hid, dy, hid, g, y, hid)); res["add_bias_gbs"] = round(3 * nb / t / 1e9)
+        t = timeit(lambda: hap.hap_colsum(N, hid, hap.BF16, dy, hid, dg, lws)); res["colsum_gbs"] = round(nb / t / 1e9)
+        return res
+
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -165,6 +206,7 @@ def main():
         "calls_tflops": {k: round(call_flops[k] / (per[k] * 1e-3) / 1e12, 1) for k in call_flops},
         "setup_s": round(t_setup, 1),
         "achievable": ceilings(),
+        "other_rows_cfg4_shapes": other_rows(),
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(np, hapgen, T, w2, offsets)

@@ -186,7 +186,8 @@ size_t hap_attn_bwd_workspace(const hap_attn_desc* d, int shard_index);
 /* ------------------------------------------------------------------ device: row / element helpers --- */
 
 /* LayerNorm over the last axis, biased variance, eps = 1e-5.  x,y [rows x n] (ld = n), gamma/beta [n]
- * in io_dtype; mean, rstd fp32 [rows] saved for the backward.                                      */
+ * in io_dtype; mean, rstd fp32 [rows] saved for the backward.  n <= 2048 (HAP_EUNSUPPORTED beyond);
+ * 16-byte aligned pointers with n a multiple of 16 / sizeof(element) take the vector path.          */
 int hap_layernorm_fwd(int64_t rows, int64_t n, int io_dtype, const void* x, const void* gamma, const void* beta,
                       void* y, float* mean, float* rstd, void* stream);
 /* dx in io_dtype; dgamma, dbeta fp32 [n], overwritten.  ws from hap_layernorm_bwd_workspace.        */

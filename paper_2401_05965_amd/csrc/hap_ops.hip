@@ -8,6 +8,8 @@
 
 #include <stdint.h>
 
+#include <type_traits>
+
 #include "hap_internal.h"
 
 namespace {
@@ -73,125 +75,193 @@ __global__ __launch_bounds__(256) void add_kernel(int64_t rows, int64_t cols, co
   }
 }
 
-/* Column sums, stage 1: block (bx, by) sums rows [by*rpb, (by+1)*rpb) of the 64 columns starting at
- * bx*64.  Lanes run along the columns (coalesced rows), the 4 waves stride over the rows and their
- * partials meet in LDS.  partial[by][col] is fp32. */
-template <typename T>
-__global__ __launch_bounds__(256) void colsum_partial_kernel(int64_t rows, int64_t cols, const T* a, int64_t lda,
+/* Column sums, stage 1: block (bx, by) sums rows [by*rpb, (by+1)*rpb) of the 64*V columns starting at
+ * bx*64*V - skew.  `a` is the caller's pointer moved down by `skew` elements to a multiple of V
+ * elements, so each lane reads one aligned V-element chunk per row (a chunk is read only when it
+ * holds at least one wanted column).  The 4 waves stride over the rows, four rows in flight each, and
+ * their partials meet in LDS.  partial[by][col] is fp32. */
+template <typename T, int V>
+__global__ __launch_bounds__(256) void colsum_partial_kernel(int64_t rows, int64_t cols, const T* a, int64_t lda, int skew,
                                                              int64_t rpb, float* partial) {
-  __shared__ float red[4][64];
+  __shared__ float red[4][64 * V];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int64_t c = (int64_t)blockIdx.x * 64 + lane;
+  const int64_t c0 = ((int64_t)blockIdx.x * 64 + lane) * V - skew;
   const int64_t r0 = (int64_t)blockIdx.y * rpb;
   const int64_t r1 = r0 + rpb < rows ? r0 + rpb : rows;
-  float s = 0.0f;
-  if (c < cols)
-    for (int64_t r = r0 + wave; r < r1; r += 4) s += ld<T>(a + r * lda + c);
-  red[wave][lane] = s;
+  float s[V];
+#pragma unroll
+  for (int e = 0; e < V; ++e) s[e] = 0.0f;
+  if (c0 + V > 0 && c0 < cols) {
+    const T* p = a + c0 + skew;
+    int64_t r = r0 + wave;
+    for (; r + 12 < r1; r += 16) {
+      Pack<T, V> q[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) q[u] = *reinterpret_cast<const Pack<T, V>*>(p + (r + 4 * u) * lda);
+#pragma unroll
+      for (int u = 0; u < 4; ++u)
+#pragma unroll
+        for (int e = 0; e < V; ++e) s[e] += (float)q[u].v[e];
+    }
+    for (; r < r1; r += 4) {
+      const Pack<T, V> q = *reinterpret_cast<const Pack<T, V>*>(p + r * lda);
+#pragma unroll
+      for (int e = 0; e < V; ++e) s[e] += (float)q.v[e];
+    }
+  }
+#pragma unroll
+  for (int e = 0; e < V; ++e) red[wave][lane * V + e] = s[e];
   __syncthreads();
-  if (wave == 0 && c < cols) partial[(int64_t)blockIdx.y * cols + c] = red[0][lane] + red[1][lane] + red[2][lane] + red[3][lane];
+  for (int i = threadIdx.x; i < 64 * V; i += 256) {
+    const int64_t c = (int64_t)blockIdx.x * 64 * V + i - skew;
+    if (c >= 0 && c < cols) partial[(int64_t)blockIdx.y * cols + c] = red[0][i] + red[1][i] + red[2][i] + red[3][i];
+  }
 }
 
-/* Stage 2: out[c] = sum over nparts of partial[p][c]; one wave per 64 columns is plenty. */
+/* Stage 2: out[c] = sum over nparts of partial[p][c].  A block owns 16 columns; its 16 thread groups
+ * walk the partial rows 16 apart and meet in LDS. */
 __global__ __launch_bounds__(256) void colsum_final_kernel(int64_t cols, int nparts, const float* partial, float* out) {
-  const int64_t c = (int64_t)blockIdx.x * 256 + threadIdx.x;
-  if (c >= cols) return;
-  float s = 0.0f;
-  for (int p = 0; p < nparts; ++p) s += partial[(int64_t)p * cols + c];
-  out[c] = s;
+  __shared__ float red[16][17];
+  const int tx = threadIdx.x & 15, ty = threadIdx.x >> 4;
+  const int64_t c = (int64_t)blockIdx.x * 16 + tx;
+  float a = 0.0f;
+  if (c < cols)
+    for (int p = ty; p < nparts; p += 16) a += partial[(int64_t)p * cols + c];
+  red[ty][tx] = a;
+  __syncthreads();
+  if (ty == 0 && c < cols) {
+    float t = 0.0f;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) t += red[r][tx];
+    out[c] = t;
+  }
 }
 
-/* LayerNorm forward: one wavefront per row, row kept in registers (n <= 64 * 8 * MAXV). */
-template <typename T, int PER>   // PER = elements per lane, row length n <= 64*PER, n % 1 == 0
+/* LayerNorm kernels: one wavefront per row, the row held in registers as NCH chunks of V elements per
+ * lane (chunk index i*64 + lane, so a wave reads 64*V contiguous elements per access: 16-byte accesses
+ * when V = 16 / sizeof(T)).  Row length n <= 64 * V * NCH; n % V == 0 when V > 1. */
+template <typename T, int V, int NCH>
 __global__ __launch_bounds__(256) void layernorm_fwd_kernel(int64_t rows, int n, const T* x, const T* gamma, const T* beta,
                                                             T* y, float* mean, float* rstd) {
   const int lane = threadIdx.x & 63;
   const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
   if (row >= rows) return;
   const T* xr = x + row * n;
-  float v[PER];
+  float v[NCH][V];
   float s = 0.0f;
 #pragma unroll
-  for (int i = 0; i < PER; ++i) {
-    const int c = i * 64 + lane;
-    v[i] = c < n ? ld<T>(xr + c) : 0.0f;
-    s += v[i];
+  for (int i = 0; i < NCH; ++i) {
+    const int c = (i * 64 + lane) * V;
+    Pack<T, V> p;
+    if (c < n) p = *reinterpret_cast<const Pack<T, V>*>(xr + c);
+#pragma unroll
+    for (int e = 0; e < V; ++e) { v[i][e] = c < n ? (float)p.v[e] : 0.0f; s += v[i][e]; }
   }
   const float mu = wave_sum(s) / (float)n;
   float q = 0.0f;
 #pragma unroll
-  for (int i = 0; i < PER; ++i) {
-    const int c = i * 64 + lane;
-    const float d = c < n ? v[i] - mu : 0.0f;
-    q += d * d;
+  for (int i = 0; i < NCH; ++i) {
+    const int c = (i * 64 + lane) * V;
+#pragma unroll
+    for (int e = 0; e < V; ++e) { const float d = c < n ? v[i][e] - mu : 0.0f; q += d * d; }
   }
   const float rs = rsqrtf(wave_sum(q) / (float)n + kLnEps);
   T* yr = y + row * n;
 #pragma unroll
-  for (int i = 0; i < PER; ++i) {
-    const int c = i * 64 + lane;
-    if (c < n) st<T>(yr + c, (v[i] - mu) * rs * ld<T>(gamma + c) + ld<T>(beta + c));
+  for (int i = 0; i < NCH; ++i) {
+    const int c = (i * 64 + lane) * V;
+    if (c < n) {
+      const Pack<T, V> g = *reinterpret_cast<const Pack<T, V>*>(gamma + c);
+      const Pack<T, V> b = *reinterpret_cast<const Pack<T, V>*>(beta + c);
+      Pack<T, V> o;
+#pragma unroll
+      for (int e = 0; e < V; ++e) o.v[e] = (T)((v[i][e] - mu) * rs * (float)g.v[e] + (float)b.v[e]);
+      *reinterpret_cast<Pack<T, V>*>(yr + c) = o;
+    }
   }
   if (lane == 0) { mean[row] = mu; rstd[row] = rs; }
 }
 
-/* LayerNorm backward.  Block = 4 waves, each wave walks rows (stride = 4*gridDim.x); per row it forms
- * dx, and accumulates this block's share of dgamma / dbeta in registers; block partials go to
- * ws[block][2][n] and a second kernel (colsum_final) folds them. */
-template <typename T, int PER>
+/* LayerNorm backward.  Block = 4 waves, each wave walks rows (stride 4*gridDim.x); per row it forms dx
+ * and adds the row's contribution to its lanes' dgamma / dbeta accumulators; the four waves' sums meet
+ * in LDS and go to part[block][2][n]; layernorm_bwd_final_kernel folds the blocks. */
+template <typename T, int V, int NCH>
 __global__ __launch_bounds__(256) void layernorm_bwd_kernel(int64_t rows, int n, const T* x, const T* gamma, const float* mean,
                                                             const float* rstd, const T* dy, T* dx, float* part) {
-  __shared__ float red[2][4][64 * PER];
+  __shared__ float red[4][64 * V * NCH];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  float dg[PER], db[PER], gm[PER];
+  float dg[NCH][V], db[NCH][V];
+  Pack<T, V> gm[NCH];
 #pragma unroll
-  for (int i = 0; i < PER; ++i) {
-    dg[i] = db[i] = 0.0f;
-    const int c = i * 64 + lane;
-    gm[i] = c < n ? ld<T>(gamma + c) : 0.0f;
+  for (int i = 0; i < NCH; ++i) {
+    const int c = (i * 64 + lane) * V;
+    if (c < n) gm[i] = *reinterpret_cast<const Pack<T, V>*>(gamma + c);
+#pragma unroll
+    for (int e = 0; e < V; ++e) { dg[i][e] = 0.0f; db[i][e] = 0.0f; if (c >= n) gm[i].v[e] = (T)0.0f; }
   }
   for (int64_t row = (int64_t)blockIdx.x * 4 + wave; row < rows; row += (int64_t)gridDim.x * 4) {
     const float mu = mean[row], rs = rstd[row];
-    float xh[PER], g[PER];
+    float xh[NCH][V], g[NCH][V];
     float s1 = 0.0f, s2 = 0.0f;
 #pragma unroll
-    for (int i = 0; i < PER; ++i) {
-      const int c = i * 64 + lane;
-      const bool ok = c < n;
-      const float xv = ok ? ld<T>(x + row * n + c) : 0.0f;
-      const float dv = ok ? ld<T>(dy + row * n + c) : 0.0f;
-      xh[i] = ok ? (xv - mu) * rs : 0.0f;
-      g[i] = dv * gm[i];
-      s1 += g[i];
-      s2 += g[i] * xh[i];
-      dg[i] += dv * xh[i];
-      db[i] += dv;
+    for (int i = 0; i < NCH; ++i) {
+      const int c = (i * 64 + lane) * V;
+      Pack<T, V> px, pd;
+      if (c < n) { px = *reinterpret_cast<const Pack<T, V>*>(x + row * n + c); pd = *reinterpret_cast<const Pack<T, V>*>(dy + row * n + c); }
+#pragma unroll
+      for (int e = 0; e < V; ++e) {
+        const float dv = c < n ? (float)pd.v[e] : 0.0f;
+        xh[i][e] = c < n ? ((float)px.v[e] - mu) * rs : 0.0f;
+        g[i][e] = dv * (float)gm[i].v[e];
+        s1 += g[i][e];
+        s2 += g[i][e] * xh[i][e];
+        dg[i][e] += dv * xh[i][e];
+        db[i][e] += dv;
+      }
     }
     s1 = wave_sum(s1) / (float)n;
     s2 = wave_sum(s2) / (float)n;
 #pragma unroll
-    for (int i = 0; i < PER; ++i) {
-      const int c = i * 64 + lane;
-      if (c < n) st<T>(dx + row * n + c, rs * (g[i] - s1 - xh[i] * s2));
+    for (int i = 0; i < NCH; ++i) {
+      const int c = (i * 64 + lane) * V;
+      if (c < n) {
+        Pack<T, V> o;
+#pragma unroll
+        for (int e = 0; e < V; ++e) o.v[e] = (T)(rs * (g[i][e] - s1 - xh[i][e] * s2));
+        *reinterpret_cast<Pack<T, V>*>(dx + row * n + c) = o;
+      }
     }
   }
 #pragma unroll
-  for (int i = 0; i < PER; ++i) { red[0][wave][i * 64 + lane] = dg[i]; red[1][wave][i * 64 + lane] = db[i]; }
-  __syncthreads();
-  for (int c = threadIdx.x; c < n; c += 256) {
-    part[((int64_t)blockIdx.x * 2 + 0) * n + c] = red[0][0][c] + red[0][1][c] + red[0][2][c] + red[0][3][c];
-    part[((int64_t)blockIdx.x * 2 + 1) * n + c] = red[1][0][c] + red[1][1][c] + red[1][2][c] + red[1][3][c];
+  for (int pass = 0; pass < 2; ++pass) {
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < NCH; ++i)
+#pragma unroll
+      for (int e = 0; e < V; ++e) red[wave][(i * 64 + lane) * V + e] = pass == 0 ? dg[i][e] : db[i][e];
+    __syncthreads();
+    for (int c = threadIdx.x; c < n; c += 256)
+      part[((int64_t)blockIdx.x * 2 + pass) * n + c] = red[0][c] + red[1][c] + red[2][c] + red[3][c];
   }
 }
 
-/* Folds layernorm_bwd partials: part[block][2][n] -> dgamma[n], dbeta[n]. */
+/* Folds layernorm_bwd partials: part[block][2][n] -> dgamma[n] (blockIdx.y = 0), dbeta[n] (1).  A block
+ * owns 16 columns; its 16 thread groups walk the partial rows 16 apart and meet in LDS. */
 __global__ __launch_bounds__(256) void layernorm_bwd_final_kernel(int n, int nblocks, const float* part, float* dgamma, float* dbeta) {
-  const int c = blockIdx.x * 256 + threadIdx.x;
-  if (c >= n) return;
-  float a = 0.0f, b = 0.0f;
-  for (int p = 0; p < nblocks; ++p) { a += part[((int64_t)p * 2 + 0) * n + c]; b += part[((int64_t)p * 2 + 1) * n + c]; }
-  dgamma[c] = a;
-  dbeta[c] = b;
+  __shared__ float red[16][17];
+  const int tx = threadIdx.x & 15, ty = threadIdx.x >> 4;
+  const int c = blockIdx.x * 16 + tx;
+  float a = 0.0f;
+  if (c < n)
+    for (int p = ty; p < nblocks; p += 16) a += part[((int64_t)p * 2 + blockIdx.y) * n + c];
+  red[ty][tx] = a;
+  __syncthreads();
+  if (ty == 0 && c < n) {
+    float t = 0.0f;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) t += red[r][tx];
+    (blockIdx.y == 0 ? dgamma : dbeta)[c] = t;
+  }
 }
 
 /* Register-resident MFMA loop: 8 independent 32x32x16 bf16 accumulators per wave, 8 waves per block,
@@ -235,8 +305,8 @@ inline int grid_for(int64_t work_items) {
   return g < 1 ? 1 : (int)g;
 }
 
-constexpr int kLnBlocks = 1024;   // layernorm backward: blocks (= partial rows of dgamma/dbeta)
-constexpr int kColsumRowsPerBlock = 512;
+constexpr int kLnBlocks = 512;    // layernorm backward: blocks (= partial rows of dgamma/dbeta)
+constexpr int kColsumRowsPerBlock = 64;
 
 template <typename T>
 int gelu_bwd_t(int64_t rows, int64_t cols, const void* pre, int64_t ldp, const void* dy, int64_t lddy, void* out, int64_t ldo, hipStream_t s) {
@@ -256,12 +326,33 @@ int add_t(int64_t rows, int64_t cols, const void* a, int64_t lda, const void* b,
   return check_launch("add");
 }
 
+/* Picks the access width and chunk count: 16-byte chunks when the row length and the pointers allow. */
+template <typename T, typename F>
+bool ln_dispatch(int n, bool vec_ok, F&& launch) {
+  constexpr int VV = 16 / sizeof(T);
+  if (vec_ok && n % VV == 0) {
+    const int chunks = (n / VV + 63) / 64;
+    if (chunks <= 1) { launch(std::integral_constant<int, VV>(), std::integral_constant<int, 1>()); return true; }
+    if (chunks <= 2) { launch(std::integral_constant<int, VV>(), std::integral_constant<int, 2>()); return true; }
+    if (chunks <= 4) { launch(std::integral_constant<int, VV>(), std::integral_constant<int, 4>()); return true; }
+    if (chunks <= 8) { launch(std::integral_constant<int, VV>(), std::integral_constant<int, 8>()); return true; }
+  }
+  const int chunks = (n + 63) / 64;
+  if (chunks <= 4) { launch(std::integral_constant<int, 1>(), std::integral_constant<int, 4>()); return true; }
+  if (chunks <= 16) { launch(std::integral_constant<int, 1>(), std::integral_constant<int, 16>()); return true; }
+  if (chunks <= 32) { launch(std::integral_constant<int, 1>(), std::integral_constant<int, 32>()); return true; }
+  return false;
+}
+
 template <typename T>
 int layernorm_fwd_t(int64_t rows, int n, const void* x, const void* g, const void* b, void* y, float* mean, float* rstd, hipStream_t s) {
   const dim3 grid((unsigned)((rows + 3) / 4));
-#define LN_FWD(PER) hipLaunchKernelGGL((layernorm_fwd_kernel<T, PER>), grid, dim3(256), 0, s, rows, n, (const T*)x, (const T*)g, (const T*)b, (T*)y, mean, rstd)
-  if (n <= 64 * 4) LN_FWD(4); else if (n <= 64 * 16) LN_FWD(16); else if (n <= 64 * 32) LN_FWD(32); else LN_FWD(64);
-#undef LN_FWD
+  const bool vec_ok = aligned16(x) && aligned16(y) && aligned16(g) && aligned16(b);
+  const bool ok = ln_dispatch<T>(n, vec_ok, [&](auto v, auto nch) {
+    hipLaunchKernelGGL((layernorm_fwd_kernel<T, decltype(v)::value, decltype(nch)::value>), grid, dim3(256), 0, s, rows, n, (const T*)x, (const T*)g,
+                       (const T*)b, (T*)y, mean, rstd);
+  });
+  if (!ok) return hap_fail(HAP_EUNSUPPORTED, "layernorm row of %d elements is too long for this layout", n);
   return check_launch("layernorm_fwd");
 }
 
@@ -269,12 +360,15 @@ template <typename T>
 int layernorm_bwd_t(int64_t rows, int n, const void* x, const void* g, const float* mean, const float* rstd, const void* dy,
                     void* dx, float* dgamma, float* dbeta, float* part, hipStream_t s) {
   const int nblocks = (int)((rows + 3) / 4 < kLnBlocks ? (rows + 3) / 4 : kLnBlocks);
-#define LN_BWD(PER) hipLaunchKernelGGL((layernorm_bwd_kernel<T, PER>), dim3(nblocks), dim3(256), 0, s, rows, n, (const T*)x, (const T*)g, mean, rstd, (const T*)dy, (T*)dx, part)
-  if (n <= 64 * 4) LN_BWD(4); else if (n <= 64 * 16) LN_BWD(16); else LN_BWD(32);
-#undef LN_BWD
+  const bool vec_ok = aligned16(x) && aligned16(dy) && aligned16(dx) && aligned16(g);
+  const bool ok = ln_dispatch<T>(n, vec_ok, [&](auto v, auto nch) {
+    hipLaunchKernelGGL((layernorm_bwd_kernel<T, decltype(v)::value, decltype(nch)::value>), dim3(nblocks), dim3(256), 0, s, rows, n, (const T*)x,
+                       (const T*)g, mean, rstd, (const T*)dy, (T*)dx, part);
+  });
+  if (!ok) return hap_fail(HAP_EUNSUPPORTED, "layernorm row of %d elements is too long for this layout", n);
   int rc = check_launch("layernorm_bwd");
   if (rc) return rc;
-  hipLaunchKernelGGL(layernorm_bwd_final_kernel, dim3((n + 255) / 256), dim3(256), 0, s, n, nblocks, part, dgamma, dbeta);
+  hipLaunchKernelGGL(layernorm_bwd_final_kernel, dim3((n + 15) / 16, 2), dim3(256), 0, s, n, nblocks, part, dgamma, dbeta);
   return check_launch("layernorm_bwd_final");
 }
 
@@ -330,7 +424,7 @@ int hap_colsum(int64_t rows, int64_t cols, int io_dtype, const void* a, int64_t 
   if (!out) return hap_fail(HAP_EINVAL, "NULL output");
   hipStream_t s = (hipStream_t)stream;
   if (rows == 0) {   // empty sum
-    hipLaunchKernelGGL(colsum_final_kernel, dim3((unsigned)((cols + 255) / 256)), dim3(256), 0, s, cols, 0, (const float*)out, out);
+    hipLaunchKernelGGL(colsum_final_kernel, dim3((unsigned)((cols + 15) / 16)), dim3(256), 0, s, cols, 0, (const float*)out, out);
     return check_launch("colsum");
   }
   if (!a) return hap_fail(HAP_EINVAL, "NULL input");
@@ -339,13 +433,24 @@ int hap_colsum(int64_t rows, int64_t cols, int io_dtype, const void* a, int64_t 
   const size_t need = hap_colsum_workspace(rows, cols);
   if (!ws || ws_bytes < need) return hap_fail(HAP_EWORKSPACE, "colsum needs %zu workspace bytes", need);
   const int64_t parts = (rows + kColsumRowsPerBlock - 1) / kColsumRowsPerBlock;
-  if (parts > 65535) return hap_fail(HAP_EUNSUPPORTED, "colsum over more than 65535*512 rows");
-  const dim3 grid((unsigned)((cols + 63) / 64), (unsigned)parts);
-  if (io_dtype == HAP_BF16) hipLaunchKernelGGL((colsum_partial_kernel<__bf16>), grid, dim3(256), 0, s, rows, cols, (const __bf16*)a, lda, (int64_t)kColsumRowsPerBlock, (float*)ws);
-  else hipLaunchKernelGGL((colsum_partial_kernel<float>), grid, dim3(256), 0, s, rows, cols, (const float*)a, lda, (int64_t)kColsumRowsPerBlock, (float*)ws);
+  if (parts > 65535) return hap_fail(HAP_EUNSUPPORTED, "colsum over more than 65535 * 64 rows");
+  const int esz = io_dtype == HAP_BF16 ? 2 : 4, V = 16 / esz;
+  const bool vec = (uintptr_t)a % esz == 0 && lda % V == 0;
+  const int skew = vec ? (int)(((uintptr_t)a % 16) / esz) : 0;
+  const char* base = static_cast<const char*>(a) - (size_t)skew * esz;
+  const int64_t per_block = vec ? 64 * V : 64;
+  const dim3 grid((unsigned)((cols + skew + per_block - 1) / per_block), (unsigned)parts);
+  const int64_t rpb = kColsumRowsPerBlock;
+  if (io_dtype == HAP_BF16) {
+    if (vec) hipLaunchKernelGGL((colsum_partial_kernel<__bf16, 8>), grid, dim3(256), 0, s, rows, cols, (const __bf16*)base, lda, skew, rpb, (float*)ws);
+    else hipLaunchKernelGGL((colsum_partial_kernel<__bf16, 1>), grid, dim3(256), 0, s, rows, cols, (const __bf16*)a, lda, 0, rpb, (float*)ws);
+  } else {
+    if (vec) hipLaunchKernelGGL((colsum_partial_kernel<float, 4>), grid, dim3(256), 0, s, rows, cols, (const float*)base, lda, skew, rpb, (float*)ws);
+    else hipLaunchKernelGGL((colsum_partial_kernel<float, 1>), grid, dim3(256), 0, s, rows, cols, (const float*)a, lda, 0, rpb, (float*)ws);
+  }
   int rc = check_launch("colsum_partial");
   if (rc) return rc;
-  hipLaunchKernelGGL(colsum_final_kernel, dim3((unsigned)((cols + 255) / 256)), dim3(256), 0, s, cols, (int)parts, (const float*)ws, out);
+  hipLaunchKernelGGL(colsum_final_kernel, dim3((unsigned)((cols + 15) / 16)), dim3(256), 0, s, cols, (int)parts, (const float*)ws, out);
   return check_launch("colsum_final");
 }
 
@@ -355,7 +460,6 @@ int hap_layernorm_fwd(int64_t rows, int64_t n, int io_dtype, const void* x, cons
   if (rows < 0 || n < 1) return hap_fail(HAP_EINVAL, "bad size");
   if (rows == 0) return HAP_OK;
   if (!x || !gamma || !beta || !y || !mean || !rstd) return hap_fail(HAP_EINVAL, "NULL pointer");
-  if (n > 64 * 64) return hap_fail(HAP_EUNSUPPORTED, "layernorm row longer than 4096");
   hipStream_t s = (hipStream_t)stream;
   if (io_dtype == HAP_BF16) return layernorm_fwd_t<__bf16>(rows, (int)n, x, gamma, beta, y, mean, rstd, s);
   if (io_dtype == HAP_F32) return layernorm_fwd_t<float>(rows, (int)n, x, gamma, beta, y, mean, rstd, s);
@@ -375,7 +479,6 @@ int hap_layernorm_bwd(int64_t rows, int64_t n, int io_dtype, const void* x, cons
   if (rows < 0 || n < 1) return hap_fail(HAP_EINVAL, "bad size");
   if (rows == 0) return HAP_OK;
   if (!x || !gamma || !mean || !rstd || !dy || !dx || !dgamma || !dbeta) return hap_fail(HAP_EINVAL, "NULL pointer");
-  if (n > 64 * 32) return hap_fail(HAP_EUNSUPPORTED, "layernorm backward row longer than 2048");
   const size_t need = hap_layernorm_bwd_workspace(rows, n);
   if (!ws || ws_bytes < need) return hap_fail(HAP_EWORKSPACE, "layernorm_bwd needs %zu workspace bytes", need);
   hipStream_t s = (hipStream_t)stream;

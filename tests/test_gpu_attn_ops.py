@@ -90,7 +90,7 @@ def test_attention_argument_errors(hap):
 
 
 @pytest.mark.parametrize("dtype", ["bf16", "f32"])
-@pytest.mark.parametrize("rows,n", [(37, 2048), (130, 1024), (5, 200)])
+@pytest.mark.parametrize("rows,n", [(37, 2048), (130, 1024), (5, 200), (4099, 768), (9, 201), (3, 8), (21, 1992), (6, 2047)])
 def test_layernorm_fwd_bwd(hap, dtype, rows, n):
     xh, xd = gen(2, T.X, (rows, n), 2.0, dtype)
     gh, gd = gen(2, T.GAMMA, (n,), 0.3, dtype); gh = gh + 0  # gamma ~ N(0, .3): exercises the affine part
@@ -129,3 +129,16 @@ def test_gelu_bwd_add_colsum(hap, dtype):
         ws = empty((max(hap.hap_colsum_workspace(rows, cols), 16),), "u8")
         hap.hap_colsum(rows, cols, io, dyd, ld, s, ws)
         check("colsum", host(s), dyh[:, :cols].sum(0), dtype)
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_colsum_unaligned_base(hap, dtype):
+    """Column sums of a view that starts 3 elements into an aligned buffer (vector path with a skew)."""
+    io = {"bf16": 1, "f32": 0}[dtype]; esz = {"bf16": 2, "f32": 4}[dtype]
+    rows, ld = 333, 1024
+    ah, ad = gen(5, T.DY, (rows + 1, ld), 1.0, dtype)
+    for off, cols in [(3, 1000), (5, 1019), (1, 7), (8, 520)]:
+        s = empty((cols,), "f32", float("nan"))
+        ws = empty((max(hap.hap_colsum_workspace(rows, cols), 16),), "u8")
+        hap.hap_colsum(rows, cols, io, ad.data_ptr() + off * esz, ld, s, ws)
+        check("colsum skew", host(s), ah[:rows, off:off + cols].sum(0), dtype)
