@@ -152,7 +152,7 @@ def main():
         t = timeit(lambda: hap.hap_sharded_attn_fwd(ad, 0, q, q + hd2, q + 2 * hd2, o, lse))
         res["attn_fwd_tflops"] = round(fl / t / 1e12, 1)
         t = timeit(lambda: hap.hap_sharded_attn_bwd(ad, 0, q, q + hd2, q + 2 * hd2, o, lse, do, dq, dq + hd2, dq + 2 * hd2, aws))
-        res["attn_bwd_tflops_2x_fwd_flops"] = round(2 * fl / t / 1e12, 1)
+        res["attn_bwd_tflops_2.5x_fwd_flops"] = round(2.5 * fl / t / 1e12, 1)
         x = dev_bf16(1, T.X, (N, hid), 1.0); y = torch.zeros_like(x); dy = dev_bf16(1, T.DY, (N, hid), 1.0)
         g = torch.ones((hid,), dtype=torch.bfloat16, device=dev); be = torch.zeros_like(g)
         mean = torch.zeros((N,), dtype=torch.float32, device=dev); rstd = torch.zeros_like(mean)

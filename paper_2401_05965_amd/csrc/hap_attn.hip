@@ -54,20 +54,6 @@ struct AttnArgs {
  * reads (32 consecutive rows, same chunk) and the transposing reads (4 consecutive rows) conflict free. */
 __device__ __forceinline__ int swz(int row, int c) { return c ^ (((row & 3) << 1) | ((row >> 2) & 1)); }
 
-template <int D>
-__device__ __forceinline__ void stage_tile(char* lds, const __bf16* base, long long stride_s, int row0, int seq, int tid) {
-  constexpr int CPR = D / 8;
-  constexpr int CPT = kTile * CPR / (64 * kWaves);
-#pragma unroll
-  for (int i = 0; i < CPT; ++i) {
-    const int id = tid + i * 64 * kWaves;
-    const int row = id / CPR, c = id % CPR;
-    i32x4_t v = {0, 0, 0, 0};
-    if (row0 + row < seq) v = *reinterpret_cast<const i32x4_t*>(base + (long long)(row0 + row) * stride_s + c * 8);
-    *reinterpret_cast<i32x4_t*>(lds + row * (D * 2) + swz(row, c) * 16) = v;
-  }
-}
-
 /* A operand, K-contiguous: rows of the tile are the MFMA M index, head_dim the contraction. */
 template <int D>
 __device__ __forceinline__ bf16x8_t frag_rows(const char* lds, int row_base, int ks, int lane) {
@@ -137,58 +123,116 @@ __device__ __forceinline__ void store_rows(__bf16* base, long long stride_s, int
     }
 }
 
+/* Register-staged copy of a [kTile x D] tile: load issues the global loads (rows past the end repeat
+ * the last row: the kernels give them zero weight), store_tile writes them to LDS later, so a whole tile of compute hides the load latency. */
 template <int D>
-__global__ __launch_bounds__(64 * kWaves) void attn_fwd_kernel(const AttnArgs a) {
-  __shared__ __attribute__((aligned(16))) char lds_k[kTile * D * 2];
-  __shared__ __attribute__((aligned(16))) char lds_v[kTile * D * 2];
+struct TileRegs {
+  static constexpr int CPR = D / 8;
+  static constexpr int CPT = kTile * CPR / (64 * kWaves);
+  i32x4_t v[CPT];
+  __device__ __forceinline__ void load(const __bf16* base, long long stride_s, int row0, int seq, int tid) {
+#pragma unroll
+    for (int i = 0; i < CPT; ++i) {
+      const int id = tid + i * 64 * kWaves;
+      const int row = id / CPR, c = id % CPR;
+      const int r = row0 + row < seq ? row0 + row : seq - 1;
+      v[i] = *reinterpret_cast<const i32x4_t*>(base + (long long)r * stride_s + c * 8);
+    }
+  }
+  __device__ __forceinline__ void store(char* lds, int tid) const {
+#pragma unroll
+    for (int i = 0; i < CPT; ++i) {
+      const int id = tid + i * 64 * kWaves;
+      const int row = id / CPR, c = id % CPR;
+      *reinterpret_cast<i32x4_t*>(lds + row * (D * 2) + swz(row, c) * 16) = v[i];
+    }
+  }
+};
+
+/* Largest growth of a row's running maximum (log2 units) that is absorbed without rescaling the
+ * accumulators: probabilities are then at most 2^kLazy times larger than with the exact maximum, far
+ * inside fp32 / bf16 range, and the final division by the row sum is unaffected. */
+constexpr float kLazy = 8.0f;
+
+template <int D>
+__global__ __launch_bounds__(64 * kWaves, 2) void attn_fwd_kernel(const AttnArgs a) {
+  constexpr int kTileBytes = kTile * D * 2;
+  __shared__ __attribute__((aligned(16))) char lds[2][2][kTileBytes];   // [buffer][K, V]
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int b = a.b0 + blockIdx.z, h = a.h0 + blockIdx.y;
   const long long head_off = (long long)b * a.stride_b + (long long)h * a.stride_h;
   const int q = blockIdx.x * (32 * kWaves) + wave * 32 + (lane & 31);
+  const __bf16* kbase = a.k + head_off;
+  const __bf16* vbase = a.v + head_off;
   bf16x8_t qf[D / 16];
   load_row_frags<D>(qf, a.q + head_off, a.stride_s, q, a.seq, lane);
   f32x16_t o[D / 32];
 #pragma unroll
   for (int dt = 0; dt < D / 32; ++dt) o[dt] = zero16();
-  float m_i = -INFINITY, l_i = 0.0f;
+  float m_ref = -INFINITY, l_i = 0.0f;    // m_ref: reference maximum of the exponent (scaled, log2 units)
   const float c = a.scale * kLog2e;
-  for (int kv0 = 0; kv0 < a.seq; kv0 += kTile) {
-    __syncthreads();
-    stage_tile<D>(lds_k, a.k + head_off, a.stride_s, kv0, a.seq, tid);
-    stage_tile<D>(lds_v, a.v + head_off, a.stride_s, kv0, a.seq, tid);
-    __syncthreads();
+  const int ntiles = (a.seq + kTile - 1) / kTile;
+  TileRegs<D> kr, vr;
+  kr.load(kbase, a.stride_s, 0, a.seq, tid);
+  vr.load(vbase, a.stride_s, 0, a.seq, tid);
+  kr.store(lds[0][0], tid);
+  vr.store(lds[0][1], tid);
+  if (ntiles > 1) {
+    kr.load(kbase, a.stride_s, kTile, a.seq, tid);
+    vr.load(vbase, a.stride_s, kTile, a.seq, tid);
+  }
+  __syncthreads();
+  for (int t = 0; t < ntiles; ++t) {
+    const int kv0 = t * kTile;
+    const char* lds_k = lds[t & 1][0];
+    const char* lds_v = lds[t & 1][1];
+    if (t + 1 < ntiles) {     // the other buffer was last read in iteration t-1, before the barrier
+      kr.store(lds[(t + 1) & 1][0], tid);
+      vr.store(lds[(t + 1) & 1][1], tid);
+      if (t + 2 < ntiles) {
+        kr.load(kbase, a.stride_s, kv0 + 2 * kTile, a.seq, tid);
+        vr.load(vbase, a.stride_s, kv0 + 2 * kTile, a.seq, tid);
+      }
+    }
     f32x16_t s[2];
-    float mx = -INFINITY;
 #pragma unroll
     for (int sub = 0; sub < 2; ++sub) {
       s[sub] = zero16();
 #pragma unroll
       for (int ks = 0; ks < D / 16; ++ks) s[sub] = mfma(frag_rows<D>(lds_k, sub * 32, ks, lane), qf[ks], s[sub]);
-#pragma unroll
-      for (int e = 0; e < 16; ++e) {
-        const int key = kv0 + sub * 32 + acc_row(e, lane);
-        s[sub][e] = key < a.seq ? s[sub][e] * c : -INFINITY;
-        mx = fmaxf(mx, s[sub][e]);
-      }
     }
-    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-    const float m_new = fmaxf(m_i, mx);          // finite: every tile holds at least one valid key
-    const float alpha = exp2f(m_i - m_new);
+    if (kv0 + kTile > a.seq) {   // ragged last tile: keys past the end drop out
+#pragma unroll
+      for (int sub = 0; sub < 2; ++sub)
+#pragma unroll
+        for (int e = 0; e < 16; ++e)
+          if (kv0 + sub * 32 + acc_row(e, lane) >= a.seq) s[sub][e] = -INFINITY;
+    }
+    float mx = -INFINITY;
+#pragma unroll
+    for (int sub = 0; sub < 2; ++sub)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) mx = fmaxf(mx, s[sub][e]);
+    mx = fmaxf(mx, __shfl_xor(mx, 32, 64)) * c;   // finite: every tile holds at least one valid key
+    if (__any(mx > m_ref + kLazy)) {
+      const float m_new = fmaxf(m_ref, mx);
+      const float alpha = __builtin_amdgcn_exp2f(m_ref - m_new);
+      l_i *= alpha;
+#pragma unroll
+      for (int dt = 0; dt < D / 32; ++dt)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) o[dt][e] *= alpha;
+      m_ref = m_new;
+    }
     float rs = 0.0f;
 #pragma unroll
     for (int sub = 0; sub < 2; ++sub)
 #pragma unroll
       for (int e = 0; e < 16; ++e) {
-        s[sub][e] = exp2f(s[sub][e] - m_new);
+        s[sub][e] = __builtin_amdgcn_exp2f(fmaf(s[sub][e], c, -m_ref));
         rs += s[sub][e];
       }
-    rs += __shfl_xor(rs, 32, 64);
-    l_i = l_i * alpha + rs;
-    m_i = m_new;
-#pragma unroll
-    for (int dt = 0; dt < D / 32; ++dt)
-#pragma unroll
-      for (int e = 0; e < 16; ++e) o[dt][e] *= alpha;
+    l_i += rs;      // this lane's half of the row; the halves meet after the loop
 #pragma unroll
     for (int sub = 0; sub < 2; ++sub)
 #pragma unroll
@@ -197,10 +241,12 @@ __global__ __launch_bounds__(64 * kWaves) void attn_fwd_kernel(const AttnArgs a)
 #pragma unroll
         for (int dt = 0; dt < D / 32; ++dt) o[dt] = mfma(frag_cols<D>(lds_v, sub * 32 + ss * 16, dt * 32, lane), p, o[dt]);
       }
+    __syncthreads();
   }
+  l_i += __shfl_xor(l_i, 32, 64);
   const long long ohead_off = (long long)b * a.ostride_b + (long long)h * a.ostride_h;
   store_rows<D>(a.out + ohead_off, a.ostride_s, q, a.seq, o, 1.0f / l_i, lane);
-  if (q < a.seq && lane < 32) a.lse[((long long)b * a.heads + h) * a.seq + q] = (m_i + log2f(l_i)) * kLn2;
+  if (q < a.seq && lane < 32) a.lse[((long long)b * a.heads + h) * a.seq + q] = (m_ref + log2f(l_i)) * kLn2;
 }
 
 /* D[q] = sum_d dO[q,d] * O[q,d]; one thread per (b, h, q) row. */
@@ -222,14 +268,16 @@ __global__ __launch_bounds__(256) void attn_dsum_kernel(const AttnArgs a) {
 }
 
 template <int D>
-__global__ __launch_bounds__(64 * kWaves) void attn_bwd_dq_kernel(const AttnArgs a) {
-  __shared__ __attribute__((aligned(16))) char lds_k[kTile * D * 2];
-  __shared__ __attribute__((aligned(16))) char lds_v[kTile * D * 2];
+__global__ __launch_bounds__(64 * kWaves, 2) void attn_bwd_dq_kernel(const AttnArgs a) {
+  constexpr int kTileBytes = kTile * D * 2;
+  __shared__ __attribute__((aligned(16))) char lds[2][2][kTileBytes];   // [buffer][K, V]
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int b = a.b0 + blockIdx.z, h = a.h0 + blockIdx.y;
   const long long head_off = (long long)b * a.stride_b + (long long)h * a.stride_h;
   const long long stat_off = ((long long)b * a.heads + h) * a.seq;
   const int q = blockIdx.x * (32 * kWaves) + wave * 32 + (lane & 31);
+  const __bf16* kbase = a.k + head_off;
+  const __bf16* vbase = a.v + head_off;
   bf16x8_t qf[D / 16], dof[D / 16];
   load_row_frags<D>(qf, a.q + head_off, a.stride_s, q, a.seq, lane);
   const long long ohead_off = (long long)b * a.ostride_b + (long long)h * a.ostride_h;
@@ -240,11 +288,30 @@ __global__ __launch_bounds__(64 * kWaves) void attn_bwd_dq_kernel(const AttnArgs
   f32x16_t dq[D / 32];
 #pragma unroll
   for (int dt = 0; dt < D / 32; ++dt) dq[dt] = zero16();
-  for (int kv0 = 0; kv0 < a.seq; kv0 += kTile) {
-    __syncthreads();
-    stage_tile<D>(lds_k, a.k + head_off, a.stride_s, kv0, a.seq, tid);
-    stage_tile<D>(lds_v, a.v + head_off, a.stride_s, kv0, a.seq, tid);
-    __syncthreads();
+  const int ntiles = (a.seq + kTile - 1) / kTile;
+  TileRegs<D> kr, vr;
+  kr.load(kbase, a.stride_s, 0, a.seq, tid);
+  vr.load(vbase, a.stride_s, 0, a.seq, tid);
+  kr.store(lds[0][0], tid);
+  vr.store(lds[0][1], tid);
+  if (ntiles > 1) {
+    kr.load(kbase, a.stride_s, kTile, a.seq, tid);
+    vr.load(vbase, a.stride_s, kTile, a.seq, tid);
+  }
+  __syncthreads();
+  for (int t = 0; t < ntiles; ++t) {
+    const int kv0 = t * kTile;
+    const char* lds_k = lds[t & 1][0];
+    const char* lds_v = lds[t & 1][1];
+    if (t + 1 < ntiles) {     // the other buffer was last read in iteration t-1, before the barrier
+      kr.store(lds[(t + 1) & 1][0], tid);
+      vr.store(lds[(t + 1) & 1][1], tid);
+      if (t + 2 < ntiles) {
+        kr.load(kbase, a.stride_s, kv0 + 2 * kTile, a.seq, tid);
+        vr.load(vbase, a.stride_s, kv0 + 2 * kTile, a.seq, tid);
+      }
+    }
+    const bool ragged = kv0 + kTile > a.seq;
 #pragma unroll
     for (int sub = 0; sub < 2; ++sub) {
       f32x16_t s = zero16(), dp = zero16();
@@ -255,9 +322,13 @@ __global__ __launch_bounds__(64 * kWaves) void attn_bwd_dq_kernel(const AttnArgs
       }
 #pragma unroll
       for (int e = 0; e < 16; ++e) {
-        const int key = kv0 + sub * 32 + acc_row(e, lane);
-        const float p = key < a.seq ? exp2f(s[e] * c - lse2) : 0.0f;
+        const float p = __builtin_amdgcn_exp2f(fmaf(s[e], c, -lse2));
         s[e] = p * (dp[e] - dsum);          // dS^T
+      }
+      if (ragged) {     // keys past the end (their rows repeat the last key) carry no gradient
+#pragma unroll
+        for (int e = 0; e < 16; ++e)
+          if (kv0 + sub * 32 + acc_row(e, lane) >= a.seq) s[e] = 0.0f;
       }
 #pragma unroll
       for (int ss = 0; ss < 2; ++ss) {
@@ -266,39 +337,74 @@ __global__ __launch_bounds__(64 * kWaves) void attn_bwd_dq_kernel(const AttnArgs
         for (int dt = 0; dt < D / 32; ++dt) dq[dt] = mfma(frag_cols<D>(lds_k, sub * 32 + ss * 16, dt * 32, lane), ds, dq[dt]);
       }
     }
+    __syncthreads();
   }
   store_rows<D>(a.dq + head_off, a.stride_s, q, a.seq, dq, a.scale, lane);
 }
 
 template <int D>
 __global__ __launch_bounds__(64 * kWaves) void attn_bwd_dkv_kernel(const AttnArgs a) {
-  __shared__ __attribute__((aligned(16))) char lds_q[kTile * D * 2];
-  __shared__ __attribute__((aligned(16))) char lds_do[kTile * D * 2];
-  __shared__ float lds_lse[kTile], lds_dsum[kTile];
+  constexpr int kTileBytes = kTile * D * 2;
+  __shared__ __attribute__((aligned(16))) char lds[2][2][kTileBytes];   // [buffer][Q, dO]
+  __shared__ float lds_stat[2][2][kTile];                                // [buffer][lse * log2(e), D]
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int b = a.b0 + blockIdx.z, h = a.h0 + blockIdx.y;
   const long long head_off = (long long)b * a.stride_b + (long long)h * a.stride_h;
   const long long stat_off = ((long long)b * a.heads + h) * a.seq;
   const long long ohead_off = (long long)b * a.ostride_b + (long long)h * a.ostride_h;
   const int key = blockIdx.x * (32 * kWaves) + wave * 32 + (lane & 31);
+  const __bf16* qbase = a.q + head_off;
+  const __bf16* dobase = a.dout + ohead_off;
+  // rows of keys past the end read as zero; whatever they accumulate is never stored
   bf16x8_t kf[D / 16], vf[D / 16];
   load_row_frags<D>(kf, a.k + head_off, a.stride_s, key, a.seq, lane);
   load_row_frags<D>(vf, a.v + head_off, a.stride_s, key, a.seq, lane);
-  const bool key_ok = key < a.seq;
   const float c = a.scale * kLog2e;
   f32x16_t dk[D / 32], dv[D / 32];
 #pragma unroll
   for (int dt = 0; dt < D / 32; ++dt) { dk[dt] = zero16(); dv[dt] = zero16(); }
-  for (int q0 = 0; q0 < a.seq; q0 += kTile) {
-    __syncthreads();
-    stage_tile<D>(lds_q, a.q + head_off, a.stride_s, q0, a.seq, tid);
-    stage_tile<D>(lds_do, a.dout + ohead_off, a.ostride_s, q0, a.seq, tid);
+  const int ntiles = (a.seq + kTile - 1) / kTile;
+  TileRegs<D> qr, dor;
+  float st_l = 0.0f, st_d = 0.0f;
+  auto load_stats = [&](int q0) {
     if (tid < kTile) {
-      const bool ok = q0 + tid < a.seq;
-      lds_lse[tid] = ok ? a.lse[stat_off + q0 + tid] * kLog2e : 0.0f;
-      lds_dsum[tid] = ok ? a.dsum[stat_off + q0 + tid] : 0.0f;
+      const int r = q0 + tid < a.seq ? q0 + tid : a.seq - 1;
+      st_l = a.lse[stat_off + r] * kLog2e;
+      st_d = a.dsum[stat_off + r];
     }
-    __syncthreads();
+  };
+  auto store_stats = [&](int buf) {
+    if (tid < kTile) { lds_stat[buf][0][tid] = st_l; lds_stat[buf][1][tid] = st_d; }
+  };
+  qr.load(qbase, a.stride_s, 0, a.seq, tid);
+  dor.load(dobase, a.ostride_s, 0, a.seq, tid);
+  load_stats(0);
+  qr.store(lds[0][0], tid);
+  dor.store(lds[0][1], tid);
+  store_stats(0);
+  if (ntiles > 1) {
+    qr.load(qbase, a.stride_s, kTile, a.seq, tid);
+    dor.load(dobase, a.ostride_s, kTile, a.seq, tid);
+    load_stats(kTile);
+  }
+  __syncthreads();
+  for (int t = 0; t < ntiles; ++t) {
+    const int q0 = t * kTile;
+    const char* lds_q = lds[t & 1][0];
+    const char* lds_do = lds[t & 1][1];
+    const float* lds_lse = lds_stat[t & 1][0];
+    const float* lds_dsum = lds_stat[t & 1][1];
+    if (t + 1 < ntiles) {     // the other buffer was last read in iteration t-1, before the barrier
+      qr.store(lds[(t + 1) & 1][0], tid);
+      dor.store(lds[(t + 1) & 1][1], tid);
+      store_stats((t + 1) & 1);
+      if (t + 2 < ntiles) {
+        qr.load(qbase, a.stride_s, q0 + 2 * kTile, a.seq, tid);
+        dor.load(dobase, a.ostride_s, q0 + 2 * kTile, a.seq, tid);
+        load_stats(q0 + 2 * kTile);
+      }
+    }
+    const bool ragged = q0 + kTile > a.seq;
 #pragma unroll
     for (int sub = 0; sub < 2; ++sub) {
       f32x16_t s = zero16(), dp = zero16();
@@ -308,12 +414,22 @@ __global__ __launch_bounds__(64 * kWaves) void attn_bwd_dkv_kernel(const AttnArg
         dp = mfma(frag_rows<D>(lds_do, sub * 32, ks, lane), vf[ks], dp);
       }
 #pragma unroll
-      for (int e = 0; e < 16; ++e) {
-        const int ql = sub * 32 + acc_row(e, lane);
-        const bool ok = key_ok && q0 + ql < a.seq;
-        const float p = ok ? exp2f(s[e] * c - lds_lse[ql]) : 0.0f;
-        dp[e] = p * (dp[e] - lds_dsum[ql]);   // dS
-        s[e] = p;                             // P
+      for (int g = 0; g < 4; ++g) {
+        const int ql = sub * 32 + g * 8 + (lane >> 5) * 4;
+        const f32x4_t l4 = *reinterpret_cast<const f32x4_t*>(lds_lse + ql);
+        const f32x4_t d4 = *reinterpret_cast<const f32x4_t*>(lds_dsum + ql);
+#pragma unroll
+        for (int x = 0; x < 4; ++x) {
+          const int e = g * 4 + x;
+          const float p = __builtin_amdgcn_exp2f(fmaf(s[e], c, -l4[x]));
+          dp[e] = p * (dp[e] - d4[x]);   // dS
+          s[e] = p;                       // P
+        }
+      }
+      if (ragged) {     // queries past the end (their rows repeat the last query) contribute nothing
+#pragma unroll
+        for (int e = 0; e < 16; ++e)
+          if (q0 + sub * 32 + acc_row(e, lane) >= a.seq) { s[e] = 0.0f; dp[e] = 0.0f; }
       }
 #pragma unroll
       for (int ss = 0; ss < 2; ++ss) {
@@ -325,6 +441,7 @@ __global__ __launch_bounds__(64 * kWaves) void attn_bwd_dkv_kernel(const AttnArg
         }
       }
     }
+    __syncthreads();
   }
   store_rows<D>(a.dv + head_off, a.stride_s, key, a.seq, dv, 1.0f, lane);
   store_rows<D>(a.dk + head_off, a.stride_s, key, a.seq, dk, a.scale, lane);
