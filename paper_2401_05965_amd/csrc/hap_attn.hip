@@ -19,6 +19,9 @@
 
 #include <stdint.h>
 
+#include <type_traits>
+#include <utility>
+
 #include "hap_internal.h"
 
 namespace {
@@ -30,6 +33,12 @@ typedef short s16x8_t __attribute__((ext_vector_type(8)));
 typedef float f32x16_t __attribute__((ext_vector_type(16)));
 typedef float f32x4_t __attribute__((ext_vector_type(4)));
 typedef int i32x4_t __attribute__((ext_vector_type(4)));
+
+template <typename F, int... I>
+__device__ __forceinline__ void static_for_impl(F&& f, std::integer_sequence<int, I...>) { (f(std::integral_constant<int, I>{}), ...); }
+/* f(std::integral_constant<int, 0>), ..., f(<N-1>) in order: a loop whose index is a constant in every pass. */
+template <int N, typename F>
+__device__ __forceinline__ void static_for(F&& f) { static_for_impl(f, std::make_integer_sequence<int, N>{}); }
 
 #define LDS_PTR(T, p) ((__attribute__((address_space(3))) T*)(p))
 
@@ -43,6 +52,7 @@ struct AttnArgs {
   __bf16 *out, *dq, *dk, *dv;
   float* lse;        // [batch][heads][seq] whole-tensor indexing
   float* dsum;       // same indexing as lse, workspace
+  float* lse2;       // lse * log2(e), workspace
   long long stride_b, stride_s, stride_h;      // Q, K, V and their gradients
   long long ostride_b, ostride_s, ostride_h;   // O and dO
   int seq, heads;    // whole-tensor head count (for lse indexing)
@@ -50,16 +60,22 @@ struct AttnArgs {
   float scale;
 };
 
-/* 16-byte chunk c of LDS row `row` sits at chunk position c ^ f(row); f makes both the 128-bit row
- * reads (32 consecutive rows, same chunk) and the transposing reads (4 consecutive rows) conflict free. */
-__device__ __forceinline__ int swz(int row, int c) { return c ^ (((row & 3) << 1) | ((row >> 2) & 1)); }
+/* 16-byte chunk c of LDS row `row` (a row is D bf16) sits at chunk position c ^ f(row).  LDS serves 64
+ * four-byte banks per clock: a 128-bit row read is served 16 lanes (16 consecutive rows, one chunk) at
+ * a time, a transposing 64-bit read 32 lanes (4 consecutive rows x 4 consecutive chunks) at a time; f
+ * spreads both over all 64 banks. */
+template <int D>
+__device__ __forceinline__ int swz(int row, int c) {
+  if constexpr (D == 128) return c ^ (((row & 3) << 2) | ((row >> 2) & 3));
+  else return c ^ ((((row >> 1) & 1) << 2) | ((row >> 2) & 3));
+}
 
 /* A operand, K-contiguous: rows of the tile are the MFMA M index, head_dim the contraction. */
 template <int D>
 __device__ __forceinline__ bf16x8_t frag_rows(const char* lds, int row_base, int ks, int lane) {
   const int row = row_base + (lane & 31);
   const int c = ks * 2 + (lane >> 5);
-  return __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const i32x4_t*>(lds + row * (D * 2) + swz(row, c) * 16));
+  return __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const i32x4_t*>(lds + row * (D * 2) + swz<D>(row, c) * 16));
 }
 
 /* A operand, transposed: MFMA M index = head_dim column (32 starting at col_base), contraction =
@@ -70,8 +86,8 @@ __device__ __forceinline__ bf16x8_t frag_cols(const char* lds, int row_base, int
   const int col = col_base + (g & 1) * 16 + (i & 3) * 4;
   const int r0 = row_base + (g >> 1) * 4 + (i >> 2);
   const int c = col >> 3, sub = (col & 7) * 2;
-  s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4_t, lds + r0 * (D * 2) + swz(r0, c) * 16 + sub));
-  s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4_t, lds + (r0 + 8) * (D * 2) + swz(r0 + 8, c) * 16 + sub));
+  s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4_t, lds + r0 * (D * 2) + swz<D>(r0, c) * 16 + sub));
+  s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4_t, lds + (r0 + 8) * (D * 2) + swz<D>(r0 + 8, c) * 16 + sub));
   return __builtin_bit_cast(bf16x8_t, (s16x8_t)__builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
 }
 
@@ -123,31 +139,68 @@ __device__ __forceinline__ void store_rows(__bf16* base, long long stride_s, int
     }
 }
 
-/* Register-staged copy of a [kTile x D] tile: load issues the global loads (rows past the end repeat
- * the last row: the kernels give them zero weight), store_tile writes them to LDS later, so a whole tile of compute hides the load latency. */
+__device__ __forceinline__ int uni(int v) { return __builtin_amdgcn_readfirstlane(v); }
+
+/* Buffer descriptor over `bytes` bytes at `base` (wave-uniform): loads past the end return zero. */
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* base, unsigned bytes) {
+  const uintptr_t u = (uintptr_t)base;
+  const uintptr_t v = ((uintptr_t)(unsigned)uni((int)(u >> 32)) << 32) | (unsigned)uni((int)(u & 0xffffffffu));
+  return __builtin_amdgcn_make_buffer_rsrc((void*)v, 0, uni((int)bytes), 0x00020000);
+}
+
+/* One wave-wide direct load to LDS: lane l's 16 (4) bytes at byte offset voff + soff of the buffer land
+ * at lds + 16*l (4*l).  `lds` must be wave-uniform.  The host pass of hipcc lacks the builtin. */
+__device__ __forceinline__ void dma16(__amdgpu_buffer_rsrc_t rsrc, char* lds, unsigned voff, unsigned soff) {
+#if defined(__HIP_DEVICE_COMPILE__)
+  __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, LDS_PTR(void, lds), 16, voff, soff, 0, 0);
+#else
+  (void)rsrc; (void)lds; (void)voff; (void)soff;
+#endif
+}
+__device__ __forceinline__ void dma4(__amdgpu_buffer_rsrc_t rsrc, char* lds, unsigned voff, unsigned soff) {
+#if defined(__HIP_DEVICE_COMPILE__)
+  __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, LDS_PTR(void, lds), 4, voff, soff, 0, 0);
+#else
+  (void)rsrc; (void)lds; (void)voff; (void)soff;
+#endif
+}
+
+/* Rows [row0, row0 + kTile) of a [seq x D] matrix (row stride in bytes given at init) go straight from
+ * global memory to the swizzled LDS tile, no registers in between; the descriptor ends with row
+ * seq - 1, so rows past the end arrive as zeros.  The loads are asynchronous: the caller waits for
+ * vmcnt(0) and a barrier before any wave reads the tile. */
 template <int D>
-struct TileRegs {
+struct TileDma {
   static constexpr int CPR = D / 8;
   static constexpr int CPT = kTile * CPR / (64 * kWaves);
-  i32x4_t v[CPT];
-  __device__ __forceinline__ void load(const __bf16* base, long long stride_s, int row0, int seq, int tid) {
+  unsigned voff[CPT];
+  unsigned stride_bytes;
+  __device__ __forceinline__ void init(long long stride_s, int tid) {
+    stride_bytes = (unsigned)stride_s * 2u;
 #pragma unroll
     for (int i = 0; i < CPT; ++i) {
-      const int id = tid + i * 64 * kWaves;
-      const int row = id / CPR, c = id % CPR;
-      const int r = row0 + row < seq ? row0 + row : seq - 1;
-      v[i] = *reinterpret_cast<const i32x4_t*>(base + (long long)r * stride_s + c * 8);
+      const int id = tid + i * 64 * kWaves;       // 16-byte slot of the LDS tile this lane fills
+      const int row = id / CPR, pos = id % CPR;
+      voff[i] = (unsigned)row * stride_bytes + (unsigned)swz<D>(row, pos) * 16u;   // the chunk that belongs there
     }
   }
-  __device__ __forceinline__ void store(char* lds, int tid) const {
+  __device__ __forceinline__ void issue(__amdgpu_buffer_rsrc_t rsrc, char* lds_tile, int row0, int tid) const {
+    const int wave_first = uni(tid & ~63);
+    const unsigned soff = (unsigned)uni(row0) * (unsigned)uni((int)stride_bytes);
 #pragma unroll
-    for (int i = 0; i < CPT; ++i) {
-      const int id = tid + i * 64 * kWaves;
-      const int row = id / CPR, c = id % CPR;
-      *reinterpret_cast<i32x4_t*>(lds + row * (D * 2) + swz(row, c) * 16) = v[i];
-    }
+    for (int i = 0; i < CPT; ++i) dma16(rsrc, lds_tile + (wave_first + i * 64 * kWaves) * 16, voff[i], soff);
   }
 };
+
+template <int D>
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t tile_rsrc(const __bf16* base, int seq, long long stride_s) {
+  return make_rsrc(base, (unsigned)(((long long)(seq - 1) * stride_s + D) * 2));
+}
+
+__device__ __forceinline__ void wait_tiles_and_sync() {
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  __syncthreads();
+}
 
 /* Largest growth of a row's running maximum (log2 units) that is absorbed without rescaling the
  * accumulators: probabilities are then at most 2^kLazy times larger than with the exact maximum, far
@@ -172,27 +225,19 @@ __global__ __launch_bounds__(64 * kWaves, 2) void attn_fwd_kernel(const AttnArgs
   float m_ref = -INFINITY, l_i = 0.0f;    // m_ref: reference maximum of the exponent (scaled, log2 units)
   const float c = a.scale * kLog2e;
   const int ntiles = (a.seq + kTile - 1) / kTile;
-  TileRegs<D> kr, vr;
-  kr.load(kbase, a.stride_s, 0, a.seq, tid);
-  vr.load(vbase, a.stride_s, 0, a.seq, tid);
-  kr.store(lds[0][0], tid);
-  vr.store(lds[0][1], tid);
-  if (ntiles > 1) {
-    kr.load(kbase, a.stride_s, kTile, a.seq, tid);
-    vr.load(vbase, a.stride_s, kTile, a.seq, tid);
-  }
-  __syncthreads();
+  const __amdgpu_buffer_rsrc_t rk = tile_rsrc<D>(kbase, a.seq, a.stride_s), rv = tile_rsrc<D>(vbase, a.seq, a.stride_s);
+  TileDma<D> td;
+  td.init(a.stride_s, tid);
+  td.issue(rk, lds[0][0], 0, tid);
+  td.issue(rv, lds[0][1], 0, tid);
+  wait_tiles_and_sync();
   for (int t = 0; t < ntiles; ++t) {
     const int kv0 = t * kTile;
     const char* lds_k = lds[t & 1][0];
     const char* lds_v = lds[t & 1][1];
     if (t + 1 < ntiles) {     // the other buffer was last read in iteration t-1, before the barrier
-      kr.store(lds[(t + 1) & 1][0], tid);
-      vr.store(lds[(t + 1) & 1][1], tid);
-      if (t + 2 < ntiles) {
-        kr.load(kbase, a.stride_s, kv0 + 2 * kTile, a.seq, tid);
-        vr.load(vbase, a.stride_s, kv0 + 2 * kTile, a.seq, tid);
-      }
+      td.issue(rk, lds[(t + 1) & 1][0], kv0 + kTile, tid);
+      td.issue(rv, lds[(t + 1) & 1][1], kv0 + kTile, tid);
     }
     f32x16_t s[2];
 #pragma unroll
@@ -241,7 +286,7 @@ __global__ __launch_bounds__(64 * kWaves, 2) void attn_fwd_kernel(const AttnArgs
 #pragma unroll
         for (int dt = 0; dt < D / 32; ++dt) o[dt] = mfma(frag_cols<D>(lds_v, sub * 32 + ss * 16, dt * 32, lane), p, o[dt]);
       }
-    __syncthreads();
+    wait_tiles_and_sync();
   }
   l_i += __shfl_xor(l_i, 32, 64);
   const long long ohead_off = (long long)b * a.ostride_b + (long long)h * a.ostride_h;
@@ -249,22 +294,28 @@ __global__ __launch_bounds__(64 * kWaves, 2) void attn_fwd_kernel(const AttnArgs
   if (q < a.seq && lane < 32) a.lse[((long long)b * a.heads + h) * a.seq + q] = (m_ref + log2f(l_i)) * kLn2;
 }
 
-/* D[q] = sum_d dO[q,d] * O[q,d]; one thread per (b, h, q) row. */
+/* D[q] = sum_d dO[q,d] * O[q,d] and lse[q] * log2(e); D/8 adjacent lanes share a (b, h, q) row, 16 bytes
+ * of it each. */
 template <int D>
 __global__ __launch_bounds__(256) void attn_dsum_kernel(const AttnArgs a) {
-  const int q = blockIdx.x * 256 + threadIdx.x;
-  if (q >= a.seq) return;
+  constexpr int LPR = D / 8;                       // lanes per row
+  const int q = blockIdx.x * (256 / LPR) + threadIdx.x / LPR, c = threadIdx.x % LPR;
   const int b = a.b0 + blockIdx.z, h = a.h0 + blockIdx.y;
-  const long long off = (long long)b * a.ostride_b + (long long)h * a.ostride_h + (long long)q * a.ostride_s;
   float acc = 0.0f;
-#pragma unroll
-  for (int c = 0; c < D / 8; ++c) {
-    const bf16x8_t x = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const i32x4_t*>(a.dout + off + c * 8));
-    const bf16x8_t y = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const i32x4_t*>(a.o + off + c * 8));
+  if (q < a.seq) {
+    const long long off = (long long)b * a.ostride_b + (long long)h * a.ostride_h + (long long)q * a.ostride_s + c * 8;
+    const bf16x8_t x = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const i32x4_t*>(a.dout + off));
+    const bf16x8_t y = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const i32x4_t*>(a.o + off));
 #pragma unroll
     for (int e = 0; e < 8; ++e) acc += (float)x[e] * (float)y[e];
   }
-  a.dsum[((long long)b * a.heads + h) * a.seq + q] = acc;
+#pragma unroll
+  for (int sh = LPR / 2; sh >= 1; sh >>= 1) acc += __shfl_xor(acc, sh, 64);
+  if (q < a.seq && c == 0) {
+    const long long at = ((long long)b * a.heads + h) * a.seq + q;
+    a.dsum[at] = acc;
+    a.lse2[at] = a.lse[at] * kLog2e;
+  }
 }
 
 template <int D>
@@ -282,36 +333,27 @@ __global__ __launch_bounds__(64 * kWaves, 2) void attn_bwd_dq_kernel(const AttnA
   load_row_frags<D>(qf, a.q + head_off, a.stride_s, q, a.seq, lane);
   const long long ohead_off = (long long)b * a.ostride_b + (long long)h * a.ostride_h;
   load_row_frags<D>(dof, a.dout + ohead_off, a.ostride_s, q, a.seq, lane);
-  const float lse2 = q < a.seq ? a.lse[stat_off + q] * kLog2e : 0.0f;
+  const float lse2 = q < a.seq ? a.lse2[stat_off + q] : 0.0f;
   const float dsum = q < a.seq ? a.dsum[stat_off + q] : 0.0f;
   const float c = a.scale * kLog2e;
   f32x16_t dq[D / 32];
 #pragma unroll
   for (int dt = 0; dt < D / 32; ++dt) dq[dt] = zero16();
   const int ntiles = (a.seq + kTile - 1) / kTile;
-  TileRegs<D> kr, vr;
-  kr.load(kbase, a.stride_s, 0, a.seq, tid);
-  vr.load(vbase, a.stride_s, 0, a.seq, tid);
-  kr.store(lds[0][0], tid);
-  vr.store(lds[0][1], tid);
-  if (ntiles > 1) {
-    kr.load(kbase, a.stride_s, kTile, a.seq, tid);
-    vr.load(vbase, a.stride_s, kTile, a.seq, tid);
-  }
-  __syncthreads();
+  const __amdgpu_buffer_rsrc_t rk = tile_rsrc<D>(kbase, a.seq, a.stride_s), rv = tile_rsrc<D>(vbase, a.seq, a.stride_s);
+  TileDma<D> td;
+  td.init(a.stride_s, tid);
+  td.issue(rk, lds[0][0], 0, tid);
+  td.issue(rv, lds[0][1], 0, tid);
+  wait_tiles_and_sync();
   for (int t = 0; t < ntiles; ++t) {
     const int kv0 = t * kTile;
     const char* lds_k = lds[t & 1][0];
     const char* lds_v = lds[t & 1][1];
     if (t + 1 < ntiles) {     // the other buffer was last read in iteration t-1, before the barrier
-      kr.store(lds[(t + 1) & 1][0], tid);
-      vr.store(lds[(t + 1) & 1][1], tid);
-      if (t + 2 < ntiles) {
-        kr.load(kbase, a.stride_s, kv0 + 2 * kTile, a.seq, tid);
-        vr.load(vbase, a.stride_s, kv0 + 2 * kTile, a.seq, tid);
-      }
+      td.issue(rk, lds[(t + 1) & 1][0], kv0 + kTile, tid);
+      td.issue(rv, lds[(t + 1) & 1][1], kv0 + kTile, tid);
     }
-    const bool ragged = kv0 + kTile > a.seq;
 #pragma unroll
     for (int sub = 0; sub < 2; ++sub) {
       f32x16_t s = zero16(), dp = zero16();
@@ -325,11 +367,7 @@ __global__ __launch_bounds__(64 * kWaves, 2) void attn_bwd_dq_kernel(const AttnA
         const float p = __builtin_amdgcn_exp2f(fmaf(s[e], c, -lse2));
         s[e] = p * (dp[e] - dsum);          // dS^T
       }
-      if (ragged) {     // keys past the end (their rows repeat the last key) carry no gradient
-#pragma unroll
-        for (int e = 0; e < 16; ++e)
-          if (kv0 + sub * 32 + acc_row(e, lane) >= a.seq) s[e] = 0.0f;
-      }
+      // keys past the end: their K rows are zero in LDS, so whatever dS holds there adds nothing to dQ
 #pragma unroll
       for (int ss = 0; ss < 2; ++ss) {
         const bf16x8_t ds = pack8(s, ss);
@@ -337,7 +375,7 @@ __global__ __launch_bounds__(64 * kWaves, 2) void attn_bwd_dq_kernel(const AttnA
         for (int dt = 0; dt < D / 32; ++dt) dq[dt] = mfma(frag_cols<D>(lds_k, sub * 32 + ss * 16, dt * 32, lane), ds, dq[dt]);
       }
     }
-    __syncthreads();
+    wait_tiles_and_sync();
   }
   store_rows<D>(a.dq + head_off, a.stride_s, q, a.seq, dq, a.scale, lane);
 }
@@ -346,7 +384,7 @@ template <int D>
 __global__ __launch_bounds__(64 * kWaves) void attn_bwd_dkv_kernel(const AttnArgs a) {
   constexpr int kTileBytes = kTile * D * 2;
   __shared__ __attribute__((aligned(16))) char lds[2][2][kTileBytes];   // [buffer][Q, dO]
-  __shared__ float lds_stat[2][2][kTile];                                // [buffer][lse * log2(e), D]
+  __shared__ __attribute__((aligned(16))) float lds_stat[2][2][kTile];   // [buffer][lse * log2(e), D]
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int b = a.b0 + blockIdx.z, h = a.h0 + blockIdx.y;
   const long long head_off = (long long)b * a.stride_b + (long long)h * a.stride_h;
@@ -364,84 +402,90 @@ __global__ __launch_bounds__(64 * kWaves) void attn_bwd_dkv_kernel(const AttnArg
 #pragma unroll
   for (int dt = 0; dt < D / 32; ++dt) { dk[dt] = zero16(); dv[dt] = zero16(); }
   const int ntiles = (a.seq + kTile - 1) / kTile;
-  TileRegs<D> qr, dor;
-  float st_l = 0.0f, st_d = 0.0f;
-  auto load_stats = [&](int q0) {
-    if (tid < kTile) {
-      const int r = q0 + tid < a.seq ? q0 + tid : a.seq - 1;
-      st_l = a.lse[stat_off + r] * kLog2e;
-      st_d = a.dsum[stat_off + r];
+  const __amdgpu_buffer_rsrc_t rq = tile_rsrc<D>(qbase, a.seq, a.stride_s), rdo = tile_rsrc<D>(dobase, a.seq, a.ostride_s);
+  const __amdgpu_buffer_rsrc_t rl = make_rsrc(a.lse2 + stat_off, (unsigned)a.seq * 4u), rd = make_rsrc(a.dsum + stat_off, (unsigned)a.seq * 4u);
+  TileDma<D> tq, tdo;
+  tq.init(a.stride_s, tid);
+  tdo.init(a.ostride_s, tid);
+  // Queries past the end arrive as zeros everywhere (Q, dO, lse, D): P = 1 there but dO = 0 and dS = 0,
+  // so they add nothing to dV or dK.
+  auto issue_tile = [&](int buf, int q0) {
+    tq.issue(rq, lds[buf][0], q0, tid);
+    tdo.issue(rdo, lds[buf][1], q0, tid);
+    if (wave == 0) {
+      dma4(rl, reinterpret_cast<char*>(lds_stat[buf][0]), (unsigned)lane * 4u, (unsigned)uni(q0) * 4u);
+      dma4(rd, reinterpret_cast<char*>(lds_stat[buf][1]), (unsigned)lane * 4u, (unsigned)uni(q0) * 4u);
     }
   };
-  auto store_stats = [&](int buf) {
-    if (tid < kTile) { lds_stat[buf][0][tid] = st_l; lds_stat[buf][1][tid] = st_d; }
-  };
-  qr.load(qbase, a.stride_s, 0, a.seq, tid);
-  dor.load(dobase, a.ostride_s, 0, a.seq, tid);
-  load_stats(0);
-  qr.store(lds[0][0], tid);
-  dor.store(lds[0][1], tid);
-  store_stats(0);
-  if (ntiles > 1) {
-    qr.load(qbase, a.stride_s, kTile, a.seq, tid);
-    dor.load(dobase, a.ostride_s, kTile, a.seq, tid);
-    load_stats(kTile);
-  }
-  __syncthreads();
+  issue_tile(0, 0);
+  wait_tiles_and_sync();
   for (int t = 0; t < ntiles; ++t) {
     const int q0 = t * kTile;
     const char* lds_q = lds[t & 1][0];
     const char* lds_do = lds[t & 1][1];
     const float* lds_lse = lds_stat[t & 1][0];
     const float* lds_dsum = lds_stat[t & 1][1];
-    if (t + 1 < ntiles) {     // the other buffer was last read in iteration t-1, before the barrier
-      qr.store(lds[(t + 1) & 1][0], tid);
-      dor.store(lds[(t + 1) & 1][1], tid);
-      store_stats((t + 1) & 1);
-      if (t + 2 < ntiles) {
-        qr.load(qbase, a.stride_s, q0 + 2 * kTile, a.seq, tid);
-        dor.load(dobase, a.ostride_s, q0 + 2 * kTile, a.seq, tid);
-        load_stats(q0 + 2 * kTile);
+    if (t + 1 < ntiles) issue_tile((t + 1) & 1, q0 + kTile);   // that buffer was last read in iteration t-1, before the barrier
+    // The tile is 64 matrix instructions in a fixed program order, one per step:
+    //   steps  0..15  S, dP of queries  0..31        steps 16..31  S, dP of queries 32..63
+    //   steps 32..47  dV, dK from queries 0..31      steps 48..63  dV, dK from queries 32..63
+    // Each step also issues the LDS read of the operand needed kAhead steps later and one element of
+    // the exponent / dS arithmetic of the previous query half, so that the wave (alone on its SIMD)
+    // keeps the matrix pipe fed; the scheduling fences keep the compiler from regrouping the steps.
+    constexpr int KS = D / 16, NA = 2 * KS, DT = D / 32, NC = 4 * DT, kAhead = 4;
+    constexpr int kSteps = 2 * NA + 2 * NC;
+    auto frag = [&](int n) -> bf16x8_t {
+      if (n < 2 * NA) {
+        const int sub = n / NA, j = n % NA;
+        return frag_rows<D>((j & 1) ? lds_do : lds_q, sub * 32, j >> 1, lane);
       }
-    }
-    const bool ragged = q0 + kTile > a.seq;
+      const int m = n - 2 * NA, sub = m / NC, j = m % NC;
+      return frag_cols<D>((j & 1) ? lds_q : lds_do, sub * 32 + (j / (2 * DT)) * 16, ((j % (2 * DT)) >> 1) * 32, lane);
+    };
+    bf16x8_t fr[kSteps];
+    f32x16_t s[2], dp[2];
+    f32x4_t l4[2][4], d4[2][4];
+    bf16x8_t pf[2][2], dsf[2][2];
+    s[0] = zero16(); s[1] = zero16(); dp[0] = zero16(); dp[1] = zero16();
 #pragma unroll
-    for (int sub = 0; sub < 2; ++sub) {
-      f32x16_t s = zero16(), dp = zero16();
-#pragma unroll
-      for (int ks = 0; ks < D / 16; ++ks) {
-        s = mfma(frag_rows<D>(lds_q, sub * 32, ks, lane), kf[ks], s);
-        dp = mfma(frag_rows<D>(lds_do, sub * 32, ks, lane), vf[ks], dp);
+    for (int n = 0; n < kAhead; ++n) fr[n] = frag(n);
+    static_for<kSteps>([&](auto step) {
+      constexpr int n = decltype(step)::value;
+      if constexpr (n + kAhead < kSteps) fr[n + kAhead] = frag(n + kAhead);
+      if constexpr (n < 2 * NA) {
+        constexpr int sub = n / NA, j = n % NA;
+        if constexpr ((j & 1) != 0) dp[sub] = mfma(fr[n], vf[j >> 1], dp[sub]);
+        else s[sub] = mfma(fr[n], kf[j >> 1], s[sub]);
+        if constexpr (j >= NA - 8) {   // this half's row statistics, one 16-byte read per step
+          constexpr int r = j - (NA - 8), g = r >> 1;
+          const int ql = sub * 32 + g * 8 + (lane >> 5) * 4;
+          if constexpr ((r & 1) != 0) d4[sub][g] = *reinterpret_cast<const f32x4_t*>(lds_dsum + ql);
+          else l4[sub][g] = *reinterpret_cast<const f32x4_t*>(lds_lse + ql);
+        }
+      } else {
+        constexpr int m = n - 2 * NA, sub = m / NC, j = m % NC, ss = j / (2 * DT), dt = (j % (2 * DT)) >> 1;
+        if constexpr ((j & 1) != 0) dk[dt] = mfma(fr[n], dsf[sub][ss], dk[dt]);
+        else dv[dt] = mfma(fr[n], pf[sub][ss], dv[dt]);
       }
+      // exponent / dS work of the half whose S, dP finished one phase ago: 16 elements over NA steps
+      constexpr int w = n - NA;
+      if constexpr (w >= 0 && w < 2 * NA) {
+        constexpr int sub = w / NA, idx = w % NA, per = 16 / NA > 0 ? 16 / NA : 1;
+        if constexpr (idx * per < 16) {
 #pragma unroll
-      for (int g = 0; g < 4; ++g) {
-        const int ql = sub * 32 + g * 8 + (lane >> 5) * 4;
-        const f32x4_t l4 = *reinterpret_cast<const f32x4_t*>(lds_lse + ql);
-        const f32x4_t d4 = *reinterpret_cast<const f32x4_t*>(lds_dsum + ql);
-#pragma unroll
-        for (int x = 0; x < 4; ++x) {
-          const int e = g * 4 + x;
-          const float p = __builtin_amdgcn_exp2f(fmaf(s[e], c, -l4[x]));
-          dp[e] = p * (dp[e] - d4[x]);   // dS
-          s[e] = p;                       // P
+          for (int u = 0; u < per; ++u) {
+            const int e = idx * per + u;
+            const float p = __builtin_amdgcn_exp2f(fmaf(s[sub][e], c, -l4[sub][e >> 2][e & 3]));
+            dp[sub][e] = p * (dp[sub][e] - d4[sub][e >> 2][e & 3]);   // dS
+            s[sub][e] = p;                                             // P
+          }
+          constexpr int last = idx * per + per - 1;
+          if constexpr ((last & 7) == 7) { pf[sub][last >> 3] = pack8(s[sub], last >> 3); dsf[sub][last >> 3] = pack8(dp[sub], last >> 3); }
         }
       }
-      if (ragged) {     // queries past the end (their rows repeat the last query) contribute nothing
-#pragma unroll
-        for (int e = 0; e < 16; ++e)
-          if (q0 + sub * 32 + acc_row(e, lane) >= a.seq) { s[e] = 0.0f; dp[e] = 0.0f; }
-      }
-#pragma unroll
-      for (int ss = 0; ss < 2; ++ss) {
-        const bf16x8_t pf = pack8(s, ss), dsf = pack8(dp, ss);
-#pragma unroll
-        for (int dt = 0; dt < D / 32; ++dt) {
-          dv[dt] = mfma(frag_cols<D>(lds_do, sub * 32 + ss * 16, dt * 32, lane), pf, dv[dt]);
-          dk[dt] = mfma(frag_cols<D>(lds_q, sub * 32 + ss * 16, dt * 32, lane), dsf, dk[dt]);
-        }
-      }
-    }
-    __syncthreads();
+      __builtin_amdgcn_sched_barrier(0);
+    });
+    wait_tiles_and_sync();
   }
   store_rows<D>(a.dv + head_off, a.stride_s, key, a.seq, dv, 1.0f, lane);
   store_rows<D>(a.dk + head_off, a.stride_s, key, a.seq, dk, a.scale, lane);
@@ -459,6 +503,9 @@ int resolve(const hap_attn_desc* d, int j, int* b0, int* nb, int* h0, int* nh) {
     if (d->o_stride_s < d->head_dim || d->o_stride_h < d->head_dim) return hap_fail(HAP_ESHAPE, "O strides overlap head_dim");
     if (d->o_stride_s % 8 || d->o_stride_h % 8 || d->o_stride_b % 8) return hap_fail(HAP_EUNSUPPORTED, "strides must be multiples of 8 elements");
   }
+  // tiles are fetched through 32-bit buffer offsets within one (batch entry, head) matrix
+  const int64_t widest = d->o_stride_s > d->stride_s ? d->o_stride_s : d->stride_s;
+  if ((d->seq + kTile) * widest * 2 >= ((int64_t)1 << 31)) return hap_fail(HAP_EUNSUPPORTED, "seq * stride_s beyond 2^30 elements");
   int64_t lo, hi;
   const int rc = hap_shard_range(d->m, d->offsets, d->shard_over_heads ? d->heads : d->batch, j, &lo, &hi);
   if (rc) return rc;
@@ -509,7 +556,7 @@ int hap_sharded_attn_fwd(const hap_attn_desc* d, int shard_index, const void* Q,
 
 size_t hap_attn_bwd_workspace(const hap_attn_desc* d, int) {
   if (!d || d->batch < 1 || d->heads < 1 || d->seq < 1) return 0;
-  return (size_t)(d->batch * d->heads * d->seq) * sizeof(float);
+  return (size_t)(d->batch * d->heads * d->seq) * 2 * sizeof(float);   // D and lse * log2(e)
 }
 
 int hap_sharded_attn_bwd(const hap_attn_desc* d, int shard_index, const void* Q, const void* K, const void* V,
@@ -528,7 +575,7 @@ int hap_sharded_attn_bwd(const hap_attn_desc* d, int shard_index, const void* Q,
   AttnArgs a = {};
   a.q = (const __bf16*)Q; a.k = (const __bf16*)K; a.v = (const __bf16*)V; a.o = (const __bf16*)O; a.dout = (const __bf16*)dO;
   a.dq = (__bf16*)dQ; a.dk = (__bf16*)dK; a.dv = (__bf16*)dV;
-  a.lse = const_cast<float*>(lse); a.dsum = (float*)ws;
+  a.lse = const_cast<float*>(lse); a.dsum = (float*)ws; a.lse2 = a.dsum + d->batch * d->heads * d->seq;
   a.stride_b = d->stride_b; a.stride_s = d->stride_s; a.stride_h = d->stride_h;
   const bool own_o = d->o_stride_s || d->o_stride_h || d->o_stride_b;
   a.ostride_b = own_o ? d->o_stride_b : d->stride_b; a.ostride_s = own_o ? d->o_stride_s : d->stride_s; a.ostride_h = own_o ? d->o_stride_h : d->stride_h;
@@ -536,7 +583,8 @@ int hap_sharded_attn_bwd(const hap_attn_desc* d, int shard_index, const void* Q,
   a.scale = 1.0f / sqrtf((float)d->head_dim);
   hipStream_t s = (hipStream_t)stream;
   const dim3 grid((unsigned)((d->seq + 32 * kWaves - 1) / (32 * kWaves)), (unsigned)nh, (unsigned)nb);
-  const dim3 grid_d((unsigned)((d->seq + 255) / 256), (unsigned)nh, (unsigned)nb);
+  const int rows_per_block = 256 / (int)(d->head_dim / 8);
+  const dim3 grid_d((unsigned)((d->seq + rows_per_block - 1) / rows_per_block), (unsigned)nh, (unsigned)nb);
   if (d->head_dim == 128) {
     hipLaunchKernelGGL(attn_dsum_kernel<128>, grid_d, dim3(256), 0, s, a);
     if ((rc = launched("attn_dsum"))) return rc;

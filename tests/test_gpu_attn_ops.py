@@ -8,7 +8,7 @@ from oracle import attention as oatt, pointwise as opw
 
 pytestmark = pytest.mark.gpu
 
-from gpu_util import gen, empty, host, check, torch_mod  # noqa: E402
+from gpu_util import gen, empty, host, check, torch_mod, TOL  # noqa: E402
 
 
 @pytest.fixture(scope="module")
@@ -40,6 +40,17 @@ def test_attention_slices_fwd_bwd(hap, B, H, S, D, over_heads, offsets):
     Oo, lseo = oatt.attn_fwd(tr(Qh), tr(Kh), tr(Vh))
     # backward oracle from exact O; the device uses its own bf16 O for D = rowsum(dO * O)
     dQo, dKo, dVo = oatt.attn_bwd(tr(Qh), tr(Kh), tr(Vh), tr(dOh))
+    # dS = P * (dP - D) subtracts two sums that the device forms from bf16 data in different orders (D from its
+    # own bf16 O); where they cancel (one key: dP == D exactly) the exact dQ, dK are ~0 and only this absolute
+    # error is left:  |err dS| <= 2^-8 P (|dP| + |D|),  carried through dQ = scale dS K,  dK = scale dS^T Q.
+    sc = 1.0 / np.sqrt(D)
+    P = np.exp(np.einsum("bhqd,bhkd->bhqk", tr(Qh), tr(Kh)) * sc - lseo[..., None])
+    dPa = np.abs(np.einsum("bhqd,bhkd->bhqk", tr(dOh), tr(Vh)))
+    Da = np.abs((tr(dOh) * Oo).sum(-1))[..., None]
+    eS = 2.0 ** -8 * P * (dPa + Da)
+    floors = {"O": np.zeros_like(Oo), "dV": np.zeros_like(Oo),
+              "dQ": sc * np.einsum("bhqk,bhkd->bhqd", eS, np.abs(tr(Kh))),
+              "dK": sc * np.einsum("bhqk,bhqd->bhkd", eS, np.abs(tr(Qh)))}
     for j in range(len(offsets) - 1):
         lo, hi = offsets[j], offsets[j + 1]
         O.zero_(); lse.zero_(); dQ.zero_(); dK.zero_(); dV.zero_()
@@ -51,7 +62,9 @@ def test_attention_slices_fwd_bwd(hap, B, H, S, D, over_heads, offsets):
         mask = np.zeros((B, H), bool); mask[sl] = True
         for n, ref in (("O", Oo), ("dQ", dQo), ("dK", dKo), ("dV", dVo)):
             if hi > lo:
-                check(f"attn shard{j} {n}", got[n][sl], ref[sl], "bf16")
+                err = np.abs(got[n][sl] - ref[sl]).max()
+                assert np.isfinite(got[n][sl]).all()
+                assert err <= TOL["bf16"] * np.abs(ref[sl]).max() + floors[n][sl].max(), f"attn shard{j} {n}: {err:.3e}"
             assert not got[n][~mask].any(), f"{n}: (batch, head) pairs outside the slice were written"
         if hi > lo:
             assert np.abs(got_lse[sl] - lseo[sl]).max() <= 2e-2
