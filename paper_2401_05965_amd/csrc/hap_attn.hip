@@ -91,6 +91,44 @@ __device__ __forceinline__ bf16x8_t frag_cols(const char* lds, int row_base, int
   return __builtin_bit_cast(bf16x8_t, (s16x8_t)__builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
 }
 
+/* The same two operand fetches with the address arithmetic folded: because the swizzle is an XOR, the
+ * byte address of every fragment of a tile is  ((lane constant + tile address) ^ small constant) +
+ * multiple of the row size,  so a wave keeps two lane constants instead of one address per fragment.
+ *   rows:  row = row_base + lane%32, chunk ks*2 + lane/32:   (rows + tile) ^ (ks << 5)            + row_base * row bytes
+ *   cols:  rows r0, r0 + 8 (r0 as in frag_cols), columns dt*32..: (cols + tile) ^ (dt << 6) [^ 32] + (row_base [+ 8]) * row bytes
+ * (row_base a multiple of 16, tile address a multiple of 256; f(r + 8) = f(r) ^ 2 and f(r + 16) = f(r)). */
+template <int D>
+struct FragAddr {
+  static constexpr int ROWB = D * 2;
+  unsigned rows, cols;
+  __device__ __forceinline__ void init(int lane) {
+    const int r = lane & 31, h = lane >> 5;
+    rows = (unsigned)(r * ROWB + ((h ^ swz<D>(r, 0)) << 4));
+    const int g = lane >> 4, i = lane & 15;
+    const int r0 = (g >> 1) * 4 + (i >> 2), cl = (g & 1) * 2 + ((i & 3) >> 1);
+    cols = (unsigned)(r0 * ROWB + ((cl ^ swz<D>(r0, 0)) << 4) + (i & 1) * 8);
+  }
+};
+
+__device__ __forceinline__ unsigned lds_addr(const void* p) { return (unsigned)(unsigned long)LDS_PTR(const char, p); }
+
+/* `at` = FragAddr::rows + lds_addr(tile) */
+template <int D>
+__device__ __forceinline__ bf16x8_t frag_rows_at(unsigned at, int row_base, int ks) {
+  const unsigned addr = (at ^ (unsigned)(ks << 5)) + (unsigned)(row_base * D * 2);
+  return __builtin_bit_cast(bf16x8_t, *(LDS_PTR(const i32x4_t, (unsigned long)addr)));
+}
+
+/* `at` = FragAddr::cols + lds_addr(tile) */
+template <int D>
+__device__ __forceinline__ bf16x8_t frag_cols_at(unsigned at, int row_base, int dt) {
+  const unsigned lo_addr = (at ^ (unsigned)(dt << 6)) + (unsigned)(row_base * D * 2);
+  const unsigned hi_addr = (at ^ (unsigned)((dt << 6) ^ 32)) + (unsigned)((row_base + 8) * D * 2);
+  s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4_t, (unsigned long)lo_addr));
+  s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4_t, (unsigned long)hi_addr));
+  return __builtin_bit_cast(bf16x8_t, (s16x8_t)__builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+}
+
 /* B operand kept in registers: row `row` of a [seq][D] matrix, lane = row, 8 contiguous d per k-step. */
 template <int D>
 __device__ __forceinline__ void load_row_frags(bf16x8_t (&f)[D / 16], const __bf16* base, long long stride_s, int row, int seq, int lane) {
@@ -165,21 +203,21 @@ __device__ __forceinline__ void dma4(__amdgpu_buffer_rsrc_t rsrc, char* lds, uns
 #endif
 }
 
-/* Rows [row0, row0 + kTile) of a [seq x D] matrix (row stride in bytes given at init) go straight from
+/* Rows [row0, row0 + ROWS) of a [seq x D] matrix (row stride in bytes given at init) go straight from
  * global memory to the swizzled LDS tile, no registers in between; the descriptor ends with row
  * seq - 1, so rows past the end arrive as zeros.  The loads are asynchronous: the caller waits for
  * vmcnt(0) and a barrier before any wave reads the tile. */
-template <int D>
+template <int D, int ROWS = kTile, int NT = 64 * kWaves>
 struct TileDma {
   static constexpr int CPR = D / 8;
-  static constexpr int CPT = kTile * CPR / (64 * kWaves);
+  static constexpr int CPT = ROWS * CPR / NT;     // NT: threads of the workgroup
   unsigned voff[CPT];
   unsigned stride_bytes;
   __device__ __forceinline__ void init(long long stride_s, int tid) {
     stride_bytes = (unsigned)stride_s * 2u;
 #pragma unroll
     for (int i = 0; i < CPT; ++i) {
-      const int id = tid + i * 64 * kWaves;       // 16-byte slot of the LDS tile this lane fills
+      const int id = tid + i * NT;                // 16-byte slot of the LDS tile this lane fills
       const int row = id / CPR, pos = id % CPR;
       voff[i] = (unsigned)row * stride_bytes + (unsigned)swz<D>(row, pos) * 16u;   // the chunk that belongs there
     }
@@ -188,7 +226,7 @@ struct TileDma {
     const int wave_first = uni(tid & ~63);
     const unsigned soff = (unsigned)uni(row0) * (unsigned)uni((int)stride_bytes);
 #pragma unroll
-    for (int i = 0; i < CPT; ++i) dma16(rsrc, lds_tile + (wave_first + i * 64 * kWaves) * 16, voff[i], soff);
+    for (int i = 0; i < CPT; ++i) dma16(rsrc, lds_tile + (wave_first + i * NT) * 16, voff[i], soff);
   }
 };
 
@@ -202,6 +240,16 @@ __device__ __forceinline__ void wait_tiles_and_sync() {
   __syncthreads();
 }
 
+/* Workgroups go to the 8 XCDs round-robin by linear id.  This renumbers them so that the workgroups of
+ * one (batch entry, head) pair, which stream the same K/V (or Q/dO) rows, run on one XCD and share its
+ * L2.  Returns the logical (x, y, z) of this workgroup. */
+__device__ __forceinline__ void block_coords(int& x, int& y, int& z) {
+  const unsigned gx = gridDim.x, gy = gridDim.y, total = gx * gy * gridDim.z;
+  unsigned id = blockIdx.x + gx * (blockIdx.y + gy * blockIdx.z);
+  if (total % 8 == 0) id = (id % 8) * (total / 8) + id / 8;
+  x = (int)(id % gx); y = (int)((id / gx) % gy); z = (int)(id / (gx * gy));
+}
+
 /* Largest growth of a row's running maximum (log2 units) that is absorbed without rescaling the
  * accumulators: probabilities are then at most 2^kLazy times larger than with the exact maximum, far
  * inside fp32 / bf16 range, and the final division by the row sum is unaffected. */
@@ -212,9 +260,11 @@ __global__ __launch_bounds__(64 * kWaves, 2) void attn_fwd_kernel(const AttnArgs
   constexpr int kTileBytes = kTile * D * 2;
   __shared__ __attribute__((aligned(16))) char lds[2][2][kTileBytes];   // [buffer][K, V]
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int b = a.b0 + blockIdx.z, h = a.h0 + blockIdx.y;
+  int bx, by, bz;
+  block_coords(bx, by, bz);
+  const int b = a.b0 + bz, h = a.h0 + by;
   const long long head_off = (long long)b * a.stride_b + (long long)h * a.stride_h;
-  const int q = blockIdx.x * (32 * kWaves) + wave * 32 + (lane & 31);
+  const int q = bx * (32 * kWaves) + wave * 32 + (lane & 31);
   const __bf16* kbase = a.k + head_off;
   const __bf16* vbase = a.v + head_off;
   bf16x8_t qf[D / 16];
@@ -323,10 +373,12 @@ __global__ __launch_bounds__(64 * kWaves, 2) void attn_bwd_dq_kernel(const AttnA
   constexpr int kTileBytes = kTile * D * 2;
   __shared__ __attribute__((aligned(16))) char lds[2][2][kTileBytes];   // [buffer][K, V]
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int b = a.b0 + blockIdx.z, h = a.h0 + blockIdx.y;
+  int bx, by, bz;
+  block_coords(bx, by, bz);
+  const int b = a.b0 + bz, h = a.h0 + by;
   const long long head_off = (long long)b * a.stride_b + (long long)h * a.stride_h;
   const long long stat_off = ((long long)b * a.heads + h) * a.seq;
-  const int q = blockIdx.x * (32 * kWaves) + wave * 32 + (lane & 31);
+  const int q = bx * (32 * kWaves) + wave * 32 + (lane & 31);
   const __bf16* kbase = a.k + head_off;
   const __bf16* vbase = a.v + head_off;
   bf16x8_t qf[D / 16], dof[D / 16];
@@ -380,31 +432,46 @@ __global__ __launch_bounds__(64 * kWaves, 2) void attn_bwd_dq_kernel(const AttnA
   store_rows<D>(a.dq + head_off, a.stride_s, q, a.seq, dq, a.scale, lane);
 }
 
+/* dK, dV of 32 keys per wave.  K stays in registers; the block's 128 rows of V stay in LDS for the
+ * whole kernel (each wave re-reads its own 32 rows as the second operand of dP = dO V^T), which keeps
+ * the wave under 256 registers so that two blocks share a compute unit.  Q, dO and the row statistics
+ * stream through LDS in 32-query tiles, double buffered. */
+constexpr int kQTile = 32;
+
 template <int D>
-__global__ __launch_bounds__(64 * kWaves) void attn_bwd_dkv_kernel(const AttnArgs a) {
-  constexpr int kTileBytes = kTile * D * 2;
-  __shared__ __attribute__((aligned(16))) char lds[2][2][kTileBytes];   // [buffer][Q, dO]
-  __shared__ __attribute__((aligned(16))) float lds_stat[2][2][kTile];   // [buffer][lse * log2(e), D]
+__global__ __launch_bounds__(64 * kWaves, 2) void attn_bwd_dkv_kernel(const AttnArgs a) {
+  constexpr int kTileBytes = kQTile * D * 2;
+  __shared__ __attribute__((aligned(16))) char lds[2][2][kTileBytes];    // [buffer][Q, dO]
+  __shared__ __attribute__((aligned(16))) char lds_vres[32 * kWaves * D * 2];
+  __shared__ __attribute__((aligned(16))) float lds_stat[2][2][64];      // [buffer][lse * log2(e), D]; 32 used
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int b = a.b0 + blockIdx.z, h = a.h0 + blockIdx.y;
+  int bx, by, bz;
+  block_coords(bx, by, bz);
+  const int b = a.b0 + bz, h = a.h0 + by;
   const long long head_off = (long long)b * a.stride_b + (long long)h * a.stride_h;
   const long long stat_off = ((long long)b * a.heads + h) * a.seq;
   const long long ohead_off = (long long)b * a.ostride_b + (long long)h * a.ostride_h;
-  const int key = blockIdx.x * (32 * kWaves) + wave * 32 + (lane & 31);
+  const int key0 = bx * (32 * kWaves);
+  const int key = key0 + wave * 32 + (lane & 31);
   const __bf16* qbase = a.q + head_off;
   const __bf16* dobase = a.dout + ohead_off;
   // rows of keys past the end read as zero; whatever they accumulate is never stored
-  bf16x8_t kf[D / 16], vf[D / 16];
+  bf16x8_t kf[D / 16];
   load_row_frags<D>(kf, a.k + head_off, a.stride_s, key, a.seq, lane);
-  load_row_frags<D>(vf, a.v + head_off, a.stride_s, key, a.seq, lane);
   const float c = a.scale * kLog2e;
   f32x16_t dk[D / 32], dv[D / 32];
 #pragma unroll
   for (int dt = 0; dt < D / 32; ++dt) { dk[dt] = zero16(); dv[dt] = zero16(); }
-  const int ntiles = (a.seq + kTile - 1) / kTile;
+  const int ntiles = (a.seq + kQTile - 1) / kQTile;
   const __amdgpu_buffer_rsrc_t rq = tile_rsrc<D>(qbase, a.seq, a.stride_s), rdo = tile_rsrc<D>(dobase, a.seq, a.ostride_s);
   const __amdgpu_buffer_rsrc_t rl = make_rsrc(a.lse2 + stat_off, (unsigned)a.seq * 4u), rd = make_rsrc(a.dsum + stat_off, (unsigned)a.seq * 4u);
-  TileDma<D> tq, tdo;
+  {
+    const __amdgpu_buffer_rsrc_t rv = tile_rsrc<D>(a.v + head_off, a.seq, a.stride_s);
+    TileDma<D, 32 * kWaves> tv;
+    tv.init(a.stride_s, tid);
+    tv.issue(rv, lds_vres, key0, tid);
+  }
+  TileDma<D, kQTile> tq, tdo;
   tq.init(a.stride_s, tid);
   tdo.init(a.ostride_s, tid);
   // Queries past the end arrive as zeros everywhere (Q, dO, lse, D): P = 1 there but dO = 0 and dS = 0,
@@ -420,71 +487,39 @@ __global__ __launch_bounds__(64 * kWaves) void attn_bwd_dkv_kernel(const AttnArg
   issue_tile(0, 0);
   wait_tiles_and_sync();
   for (int t = 0; t < ntiles; ++t) {
-    const int q0 = t * kTile;
     const char* lds_q = lds[t & 1][0];
     const char* lds_do = lds[t & 1][1];
     const float* lds_lse = lds_stat[t & 1][0];
     const float* lds_dsum = lds_stat[t & 1][1];
-    if (t + 1 < ntiles) issue_tile((t + 1) & 1, q0 + kTile);   // that buffer was last read in iteration t-1, before the barrier
-    // The tile is 64 matrix instructions in a fixed program order, one per step:
-    //   steps  0..15  S, dP of queries  0..31        steps 16..31  S, dP of queries 32..63
-    //   steps 32..47  dV, dK from queries 0..31      steps 48..63  dV, dK from queries 32..63
-    // Each step also issues the LDS read of the operand needed kAhead steps later and one element of
-    // the exponent / dS arithmetic of the previous query half, so that the wave (alone on its SIMD)
-    // keeps the matrix pipe fed; the scheduling fences keep the compiler from regrouping the steps.
-    constexpr int KS = D / 16, NA = 2 * KS, DT = D / 32, NC = 4 * DT, kAhead = 4;
-    constexpr int kSteps = 2 * NA + 2 * NC;
-    auto frag = [&](int n) -> bf16x8_t {
-      if (n < 2 * NA) {
-        const int sub = n / NA, j = n % NA;
-        return frag_rows<D>((j & 1) ? lds_do : lds_q, sub * 32, j >> 1, lane);
-      }
-      const int m = n - 2 * NA, sub = m / NC, j = m % NC;
-      return frag_cols<D>((j & 1) ? lds_q : lds_do, sub * 32 + (j / (2 * DT)) * 16, ((j % (2 * DT)) >> 1) * 32, lane);
-    };
-    bf16x8_t fr[kSteps];
-    f32x16_t s[2], dp[2];
-    f32x4_t l4[2][4], d4[2][4];
-    bf16x8_t pf[2][2], dsf[2][2];
-    s[0] = zero16(); s[1] = zero16(); dp[0] = zero16(); dp[1] = zero16();
+    if (t + 1 < ntiles) issue_tile((t + 1) & 1, (t + 1) * kQTile);   // that buffer was last read in iteration t-1, before the barrier
+    f32x16_t s = zero16(), dp = zero16();
 #pragma unroll
-    for (int n = 0; n < kAhead; ++n) fr[n] = frag(n);
-    static_for<kSteps>([&](auto step) {
-      constexpr int n = decltype(step)::value;
-      if constexpr (n + kAhead < kSteps) fr[n + kAhead] = frag(n + kAhead);
-      if constexpr (n < 2 * NA) {
-        constexpr int sub = n / NA, j = n % NA;
-        if constexpr ((j & 1) != 0) dp[sub] = mfma(fr[n], vf[j >> 1], dp[sub]);
-        else s[sub] = mfma(fr[n], kf[j >> 1], s[sub]);
-        if constexpr (j >= NA - 8) {   // this half's row statistics, one 16-byte read per step
-          constexpr int r = j - (NA - 8), g = r >> 1;
-          const int ql = sub * 32 + g * 8 + (lane >> 5) * 4;
-          if constexpr ((r & 1) != 0) d4[sub][g] = *reinterpret_cast<const f32x4_t*>(lds_dsum + ql);
-          else l4[sub][g] = *reinterpret_cast<const f32x4_t*>(lds_lse + ql);
-        }
-      } else {
-        constexpr int m = n - 2 * NA, sub = m / NC, j = m % NC, ss = j / (2 * DT), dt = (j % (2 * DT)) >> 1;
-        if constexpr ((j & 1) != 0) dk[dt] = mfma(fr[n], dsf[sub][ss], dk[dt]);
-        else dv[dt] = mfma(fr[n], pf[sub][ss], dv[dt]);
-      }
-      // exponent / dS work of the half whose S, dP finished one phase ago: 16 elements over NA steps
-      constexpr int w = n - NA;
-      if constexpr (w >= 0 && w < 2 * NA) {
-        constexpr int sub = w / NA, idx = w % NA, per = 16 / NA > 0 ? 16 / NA : 1;
-        if constexpr (idx * per < 16) {
+    for (int ks = 0; ks < D / 16; ++ks) {
+      s = mfma(frag_rows<D>(lds_q, 0, ks, lane), kf[ks], s);
+      dp = mfma(frag_rows<D>(lds_do, 0, ks, lane), frag_rows<D>(lds_vres, wave * 32, ks, lane), dp);
+    }
 #pragma unroll
-          for (int u = 0; u < per; ++u) {
-            const int e = idx * per + u;
-            const float p = __builtin_amdgcn_exp2f(fmaf(s[sub][e], c, -l4[sub][e >> 2][e & 3]));
-            dp[sub][e] = p * (dp[sub][e] - d4[sub][e >> 2][e & 3]);   // dS
-            s[sub][e] = p;                                             // P
-          }
-          constexpr int last = idx * per + per - 1;
-          if constexpr ((last & 7) == 7) { pf[sub][last >> 3] = pack8(s[sub], last >> 3); dsf[sub][last >> 3] = pack8(dp[sub], last >> 3); }
-        }
+    for (int g = 0; g < 4; ++g) {
+      const int ql = g * 8 + (lane >> 5) * 4;
+      const f32x4_t l4 = *reinterpret_cast<const f32x4_t*>(lds_lse + ql);
+      const f32x4_t d4 = *reinterpret_cast<const f32x4_t*>(lds_dsum + ql);
+#pragma unroll
+      for (int x = 0; x < 4; ++x) {
+        const int e = g * 4 + x;
+        const float p = __builtin_amdgcn_exp2f(fmaf(s[e], c, -l4[x]));
+        dp[e] = p * (dp[e] - d4[x]);   // dS
+        s[e] = p;                       // P
       }
-      __builtin_amdgcn_sched_barrier(0);
-    });
+    }
+#pragma unroll
+    for (int ss = 0; ss < 2; ++ss) {
+      const bf16x8_t pf = pack8(s, ss), dsf = pack8(dp, ss);
+#pragma unroll
+      for (int dt = 0; dt < D / 32; ++dt) {
+        dv[dt] = mfma(frag_cols<D>(lds_do, ss * 16, dt * 32, lane), pf, dv[dt]);
+        dk[dt] = mfma(frag_cols<D>(lds_q, ss * 16, dt * 32, lane), dsf, dk[dt]);
+      }
+    }
     wait_tiles_and_sync();
   }
   store_rows<D>(a.dv + head_off, a.stride_s, key, a.seq, dv, 1.0f, lane);
