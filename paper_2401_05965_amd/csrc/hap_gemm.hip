@@ -23,6 +23,8 @@
 #include <stdlib.h>
 #include <string.h>
 
+#include <type_traits>
+
 #include "hap_gemm.h"
 
 namespace hap_gemm_detail {
@@ -222,6 +224,47 @@ struct Frag<__bf16, KC, ROWS, BK> {
     }
   }
 };
+
+/* The same bf16 fragment fetch with the address arithmetic folded.  The swizzles are XORs, so the byte
+ * address of the fragment of 32-row block i (rows wave_mn + 32 i ..) at k-step kk of a tile is
+ *   K-contiguous:    ((lane constant + tile address) ^ (kk << 5)) + i * 32 rows
+ *   M/N-contiguous:  (lane constant ^ (block index << 6)) + tile address + kk * 16 rows (+ 4 rows, second half)
+ * and a wave keeps one register (K-contiguous) or one per block (M/N-contiguous) instead of an address
+ * per fragment.  Tile addresses are multiples of 512 bytes. */
+template <bool KC, int ROWS, int BK, int NBLK>
+struct FragReader {
+  static constexpr int CPR = (KC ? BK : ROWS) / 8;
+  static constexpr int ROWB = CPR * 16;
+  unsigned at[KC ? 1 : NBLK];
+  __device__ __forceinline__ void init(int lane, int wave_mn) {
+    if constexpr (KC) {
+      const int r = lane & 31, h = lane >> 5;
+      at[0] = (unsigned)((wave_mn + r) * ROWB + ((h ^ swz<true, CPR>(r, 0)) << 4));
+    } else {
+      static_assert(CPR >= 16, "M/N-contiguous fragment addressing assumes rows of 256 bytes or more");
+      const int g = lane >> 4, i = lane & 15;
+      const int x = i >> 2, cl = (g & 1) * 2 + ((i & 3) >> 1);
+      const unsigned lc = (unsigned)(((g >> 1) * 8 + x) * ROWB + (x << 6) + (cl << 4) + (i & 1) * 8);
+#pragma unroll
+      for (int b = 0; b < NBLK; ++b) at[b] = lc ^ (unsigned)(((wave_mn >> 5) + b) << 6);
+    }
+  }
+  __device__ __forceinline__ bf16x8_t read(unsigned tile, int blk, int kk) const {
+    if constexpr (KC) {
+      const unsigned addr = ((at[0] + tile) ^ (unsigned)(kk << 5)) + (unsigned)(blk * 32 * ROWB);
+      return __builtin_bit_cast(bf16x8_t, *(LDS_PTR(const i32x4_t, (unsigned long)addr)));
+    } else {
+      const unsigned addr = at[blk] + tile + (unsigned)(kk * 16 * ROWB);
+      s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4_t, (unsigned long)addr));
+      s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4_t, (unsigned long)(addr + 4 * ROWB)));
+      typedef short s16x8_t __attribute__((ext_vector_type(8)));
+      s16x8_t v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+      return __builtin_bit_cast(bf16x8_t, v);
+    }
+  }
+};
+
+__device__ __forceinline__ unsigned lds_addr(const void* p) { return (unsigned)(unsigned long)LDS_PTR(const char, p); }
 
 template <bool KC, int ROWS, int BK>
 struct Frag<float, KC, ROWS, BK> {
@@ -586,7 +629,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_dma_kernel(const GemmArgs
   typedef DmaLoader<BKC, BN, BK, NT> LB;
   constexpr int LOADS_PER_TILE = LA::CPT + LB::CPT;
 
-  extern __shared__ __attribute__((aligned(16))) char smem[];
+  extern __shared__ __attribute__((aligned(1024))) char smem[];   // FragReader needs tile addresses that are multiples of 512
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm0 = (wave / WGN) * WTM, wn0 = (wave % WGN) * WTN;
@@ -600,6 +643,10 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_dma_kernel(const GemmArgs
   LA la; LB lb;
   la.init(tid, m0, m_lim, args.lda);
   lb.init(tid, n0, n_lim, args.ldb);
+  FragReader<AKC, BM, BK, TM> fra;
+  FragReader<BKC, BN, BK, TN> frb;
+  fra.init(lane, wm0);
+  frb.init(lane, wn0);
 
   f32x16_t acc[TM][TN];
 #pragma unroll
@@ -678,20 +725,26 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_dma_kernel(const GemmArgs
     }
     const bool spread = produce && !edge;
 
-    // fragments of k-step kk+1 are fetched while the MFMAs of k-step kk run
-    bf16x8_t fa[2][TM], fb[2][TN];
+    // fragments run kFragAhead k-steps ahead of the MFMAs that use them: a wave that has its SIMD to itself
+    // (its partner waits at the barrier) must not stall on LDS latency between k-steps
+    constexpr int kFragAhead = KK > 3 ? 3 : (KK > 2 ? 2 : 1), NB = kFragAhead + 1;
+    bf16x8_t fa[NB][TM], fb[NB][TN];
+    const unsigned ta = lds_addr(sa), tb = lds_addr(sb);
 #pragma unroll
-    for (int i = 0; i < TM; ++i) fa[0][i] = Frag<T, AKC, BM, BK>::read(sa, wm0 + i * 32, 0, lane);
+    for (int k0 = 0; k0 < kFragAhead; ++k0) {
 #pragma unroll
-    for (int j = 0; j < TN; ++j) fb[0][j] = Frag<T, BKC, BN, BK>::read(sb, wn0 + j * 32, 0, lane);
+      for (int i = 0; i < TM; ++i) fa[k0][i] = fra.read(ta, i, k0);
+#pragma unroll
+      for (int j = 0; j < TN; ++j) fb[k0][j] = frb.read(tb, j, k0);
+    }
 #pragma unroll
     for (int kk = 0; kk < KK; ++kk) {
-      const int cur = kk & 1, nxt = cur ^ 1;
-      if (kk + 1 < KK) {
+      const int cur = kk % NB, nxt = (kk + kFragAhead) % NB;
+      if (kk + kFragAhead < KK) {
 #pragma unroll
-        for (int i = 0; i < TM; ++i) fa[nxt][i] = Frag<T, AKC, BM, BK>::read(sa, wm0 + i * 32, kk + 1, lane);
+        for (int i = 0; i < TM; ++i) fa[nxt][i] = fra.read(ta, i, kk + kFragAhead);
 #pragma unroll
-        for (int j = 0; j < TN; ++j) fb[nxt][j] = Frag<T, BKC, BN, BK>::read(sb, wn0 + j * 32, kk + 1, lane);
+        for (int j = 0; j < TN; ++j) fb[nxt][j] = frb.read(tb, j, kk + kFragAhead);
       }
 #pragma unroll
       for (int x = 0; x < MF / 2; ++x) acc[x / TN][x % TN] = mfma(fb[cur][x % TN], fa[cur][x / TN], acc[x / TN][x % TN]);
@@ -844,7 +897,7 @@ Plan make_plan(const hap_gemm_problem* p) {
     pl.bm = pl.bn = big ? 256 : 128;
     pl.dma = dma_variant();
     static const char* names[2][2] = {{"bf16_128x128x64_staged", "bf16_128x128x64_dma2"}, {"bf16_256x256x64_staged", "bf16_256x256x64_dma2"}};
-    pl.name = names[big][pl.dma];
+    pl.name = names[big][pl.dma ? 1 : 0];
   }
   return pl;
 }
@@ -861,15 +914,16 @@ int launch_tiled(const GemmArgs& a, hipStream_t st) {
 template <typename TC, bool AKC, bool BKC, int BM, int BN, int BK, int STAGES, int WGM, int WGN>
 int launch_dma(const GemmArgs& a, hipStream_t st) {
   constexpr size_t smem = (size_t)STAGES * (BM + BN) * BK * 2;
+  void (*kernel)(const GemmArgs) = &gemm_dma_kernel<TC, AKC, BKC, BM, BN, BK, WGM, WGN, STAGES>;
   static bool configured = false;     // benign race: the attribute call is idempotent
   if (!configured) {
-    const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_dma_kernel<TC, AKC, BKC, BM, BN, BK, WGM, WGN, STAGES>),
+    const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
                                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
     if (e != hipSuccess) return hap_fail(HAP_EDEVICE, "cannot reserve %zu bytes of LDS: %s", smem, hipGetErrorString(e));
     configured = true;
   }
   const int out_tiles = a.tiles_m * a.tiles_n;
-  hipLaunchKernelGGL((gemm_dma_kernel<TC, AKC, BKC, BM, BN, BK, WGM, WGN, STAGES>), dim3(out_tiles * a.ksplit), dim3(64 * WGM * WGN), smem, st, a);
+  hipLaunchKernelGGL(kernel, dim3(out_tiles * a.ksplit), dim3(64 * WGM * WGN), smem, st, a);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return hap_fail(HAP_EDEVICE, "gemm launch: %s", hipGetErrorString(e));
   if (a.ksplit > 1) {
@@ -902,8 +956,8 @@ int dispatch_tile(const hap_gemm_problem* p, const Plan& pl, const GemmArgs& a, 
   if constexpr (sizeof(T) == 4) {
     return dispatch_layout<T, TC, 64, 64, 16, 2, 2>(p, a, st);
   } else {
-    if (pl.bm == 256 && pl.dma == 1) return dispatch_dma<TC, 256, 256, 64, 2, 2, 4>(p, a, st);
-    if (pl.bm == 128 && pl.dma == 1) return dispatch_dma<TC, 128, 128, 64, 2, 2, 2>(p, a, st);
+    if (pl.bm == 256 && pl.dma >= 1) return dispatch_dma<TC, 256, 256, 64, 2, 2, 4>(p, a, st);
+    if (pl.bm == 128 && pl.dma >= 1) return dispatch_dma<TC, 128, 128, 64, 2, 2, 2>(p, a, st);
     if (pl.bm == 256) return dispatch_layout<T, TC, 256, 256, 64, 2, 4>(p, a, st);
     return dispatch_layout<T, TC, 128, 128, 64, 2, 2>(p, a, st);
   }
