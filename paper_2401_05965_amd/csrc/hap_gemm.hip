@@ -90,7 +90,20 @@ __device__ __forceinline__ void dma16(__amdgpu_buffer_rsrc_t rsrc, char* lds, un
 #endif
 }
 
-__device__ __forceinline__ float gelu_erf(float x) { return 0.5f * x * (1.0f + erff(x * 0.70710678118654752f)); }
+/* erf by the rational-times-Gaussian form of Abramowitz & Stegun 7.1.26 (absolute error <= 1.5e-7, far
+ * inside the fp32 and bf16 output tolerances): one reciprocal, one exponential and five multiply-adds
+ * instead of the branchy library routine, because the epilogue evaluates it for every output element. */
+__device__ __forceinline__ float erf_fast(float x) {
+  const float ax = fabsf(x);
+  const float t = __builtin_amdgcn_rcpf(fmaf(0.3275911f, ax, 1.0f));
+  float p = fmaf(1.061405429f, t, -1.453152027f);
+  p = fmaf(p, t, 1.421413741f);
+  p = fmaf(p, t, -0.284496736f);
+  p = fmaf(p, t, 0.254829592f);
+  const float e = __builtin_amdgcn_exp2f(ax * ax * -1.4426950408889634f);
+  return copysignf(1.0f - p * t * e, x);
+}
+__device__ __forceinline__ float gelu_erf(float x) { return 0.5f * x * (1.0f + erf_fast(x * 0.70710678118654752f)); }
 
 template <typename T> struct Elem;
 template <> struct Elem<__bf16> {
@@ -450,6 +463,17 @@ __device__ __forceinline__ void epilogue_transposed(const GemmArgs& args, f32x16
   const T* bias = static_cast<const T*>(args.bias);
   const int h = lane >> 5, ml = lane & 31;
   const bool vec_ok = args.vec_store != 0;
+  // this lane's bias values: the same 4 consecutive columns of every 8-column group, for all row blocks and passes
+  float bv[TN][4][4];
+#pragma unroll
+  for (int j = 0; j < TN; ++j)
+#pragma unroll
+    for (int g = 0; g < 4; ++g)
+#pragma unroll
+      for (int x = 0; x < 4; ++x) {
+        const int n = col0 + j * 32 + g * 8 + h * 4 + x - args.skewN;
+        bv[j][g][x] = (bias && n >= 0 && n < args.N) ? load_s<T>(bias + n) : 0.0f;
+      }
 #pragma unroll
   for (int i = 0; i < TM; ++i) {
 #pragma unroll
@@ -466,11 +490,7 @@ __device__ __forceinline__ void epilogue_transposed(const GemmArgs& args, f32x16
           TC v[4];
 #pragma unroll
           for (int x = 0; x < 4; ++x) {
-            float f = acc[i][j][g * 4 + x];
-            if (bias) {
-              const int n = col0 + cl + x - args.skewN;
-              f += (n >= 0 && n < args.N) ? load_s<T>(bias + n) : 0.0f;
-            }
+            float f = acc[i][j][g * 4 + x] + bv[j][g][x];
             if (pass == 1 && args.act == HAP_ACT_GELU_ERF) f = gelu_erf(f);
             v[x] = (TC)f;
           }
