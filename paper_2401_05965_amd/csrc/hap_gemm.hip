@@ -974,7 +974,7 @@ int dispatch_layout(const hap_gemm_problem* p, const GemmArgs& a, hipStream_t st
 template <typename T, typename TC>
 int dispatch_tile(const hap_gemm_problem* p, const Plan& pl, const GemmArgs& a, hipStream_t st) {
   if constexpr (sizeof(T) == 4) {
-    return dispatch_layout<T, TC, 64, 64, 16, 2, 2>(p, a, st);
+    return dispatch_layout<T, TC, 64, 64, 64, 2, 2>(p, a, st);
   } else {
     if (pl.bm == 256 && pl.dma >= 1) return dispatch_dma<TC, 256, 256, 64, 2, 2, 4>(p, a, st);
     if (pl.bm == 128 && pl.dma >= 1) return dispatch_dma<TC, 128, 128, 64, 2, 2, 2>(p, a, st);
