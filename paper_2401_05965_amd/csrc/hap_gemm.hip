@@ -57,7 +57,7 @@ struct GemmArgs {
   int vec_store;       // C (and preact) rows are 16-byte addressable: whole-chunk stores allowed
   int ksplit;          // >1: each output tile is computed by ksplit workgroups over disjoint K-tile ranges, fp32 partials go to `partial`
   float* partial;      // [tiles][ksplit][BM][BN] fp32 workspace when ksplit > 1
-  int ntiles;          // K tiles over all segments at the direct-to-LDS kernel's BK (0 for the staged kernel)
+  int ntiles;          // K tiles (of 64) over all segments
   long long lda, ldb, ldc, ldp;
   void* c;
   void* preact;
@@ -363,8 +363,10 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(const GemmArgs arg
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm0 = (wave / WGN) * WTM, wn0 = (wave % WGN) * WTN;
+  // With split-K, ksplit consecutive workgroups share an output tile and take consecutive K-tile ranges.
+  const int ksplit = args.ksplit, out_tile = blockIdx.x / ksplit, split = blockIdx.x - out_tile * ksplit;
   int tm, tn;
-  tile_of_block(blockIdx.x, gridDim.x, args.tiles_m, args.tiles_n, &tm, &tn);
+  tile_of_block(out_tile, gridDim.x / ksplit, args.tiles_m, args.tiles_n, &tm, &tn);
   const int m0 = tm * BM, n0 = tn * BN;                 // physical tile origin
   const int m_lim = args.skewM + args.M, n_lim = args.skewN + args.N;
 
@@ -379,11 +381,21 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(const GemmArgs arg
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
 
+  // this workgroup's range [first, first + ntiles) of the K tiles of all segments laid end to end
+  const int first = (int)((long long)args.ntiles * split / ksplit);
+  int ntiles = (int)((long long)args.ntiles * (split + 1) / ksplit) - first;
+  int seg = 0, skip = first;
+  while (seg + 1 < args.nseg) {
+    const int in_seg = (args.skewK + args.seg[seg].k + BK - 1) / BK;
+    if (skip < in_seg) break;
+    skip -= in_seg;
+    seg = uni(seg + 1);
+  }
   // loader state runs one tile ahead of the compute
-  int seg = 0, k0 = 0;
-  int kend = args.skewK + args.seg[0].k;
-  __amdgpu_buffer_rsrc_t ra = make_rsrc(args.seg[0].a, args.seg[0].a_bytes);
-  __amdgpu_buffer_rsrc_t rb = make_rsrc(args.seg[0].b, args.seg[0].b_bytes);
+  int k0 = skip * BK;
+  int kend = uni(args.skewK + args.seg[seg].k);
+  __amdgpu_buffer_rsrc_t ra = make_rsrc(args.seg[seg].a, args.seg[seg].a_bytes);
+  __amdgpu_buffer_rsrc_t rb = make_rsrc(args.seg[seg].b, args.seg[seg].b_bytes);
 
   auto fetch = [&]() {
     la.load(ra, tid, m0, m_lim, args.lda, k0, args.skewK, kend);
@@ -403,8 +415,8 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(const GemmArgs arg
     const int ck0 = k0, ckend = kend;
     // advance the loader to the next tile
     k0 += BK;
-    bool more = true;
-    if (k0 >= kend) {
+    bool more = --ntiles > 0;
+    if (more && k0 >= kend) {
       ++seg;
       if (seg < args.nseg) {
         k0 = 0;
@@ -436,6 +448,15 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(const GemmArgs arg
     __syncthreads();
   }
 
+  if (ksplit > 1) {
+    // raw fp32 partial tile [BM][BN]; bias, activation and the real store happen in the reduction kernel
+    GemmArgs pa = args;
+    pa.c = args.partial + ((long long)out_tile * ksplit + split) * (BM * BN);
+    pa.ldc = BN; pa.M = BM; pa.N = BN; pa.skewM = 0; pa.skewN = 0;
+    pa.preact = nullptr; pa.bias = nullptr; pa.act = HAP_ACT_NONE; pa.accumulate = 0; pa.vec_store = 1;
+    epilogue<T, float, TM, TN>(pa, acc, wm0, wn0, lane);
+    return;
+  }
   epilogue<T, TC, TM, TN>(args, acc, m0 + wm0, n0 + wn0, lane);
 }
 
@@ -924,10 +945,16 @@ Plan make_plan(const hap_gemm_problem* p) {
 
 template <typename T, typename TC, bool AKC, bool BKC, int BM, int BN, int BK, int WGM, int WGN>
 int launch_tiled(const GemmArgs& a, hipStream_t st) {
-  const int grid = a.tiles_m * a.tiles_n;
-  hipLaunchKernelGGL((gemm_kernel<T, TC, AKC, BKC, BM, BN, BK, WGM, WGN>), dim3(grid), dim3(64 * WGM * WGN), 0, st, a);
-  const hipError_t e = hipGetLastError();
+  const int out_tiles = a.tiles_m * a.tiles_n;
+  hipLaunchKernelGGL((gemm_kernel<T, TC, AKC, BKC, BM, BN, BK, WGM, WGN>), dim3(out_tiles * a.ksplit), dim3(64 * WGM * WGN), 0, st, a);
+  hipError_t e = hipGetLastError();
   if (e != hipSuccess) return hap_fail(HAP_EDEVICE, "gemm launch: %s", hipGetErrorString(e));
+  if (a.ksplit > 1) {
+    const long long threads = (long long)out_tiles * (BM * BN / 4);
+    hipLaunchKernelGGL((splitk_reduce_kernel<T, TC, BM, BN>), dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, st, a, out_tiles);
+    e = hipGetLastError();
+    if (e != hipSuccess) return hap_fail(HAP_EDEVICE, "split-K reduce launch: %s", hipGetErrorString(e));
+  }
   return HAP_OK;
 }
 
@@ -1159,16 +1186,20 @@ int hap_gemm_run(const hap_gemm_problem* p, void* stream) {
   a.ntiles = 0;
   a.ksplit = 1;
   a.partial = nullptr;
-  if (pl.dma) {
-    const int bk = 64;
+  {
+    const int bk = 64;                   // every tiled kernel steps K by 64
     for (int s = 0; s < a.nseg; ++s) a.ntiles += (pl.skewK + a.seg[s].k + bk - 1) / bk;
     if (a.ntiles == 0) a.ntiles = 1;     // empty contraction still runs one (all-zero) tile
+  }
+  if (pl.dma || p->in_dtype == HAP_F32) {
     // Split-K when the output tiles cannot occupy the chip: spread each tile's K range over the idle CUs,
-    // keeping at least 4 K tiles per workgroup, as far as the caller's workspace allows.
+    // keeping at least 4 K tiles per workgroup (2 for the small fp32 tiles, whose loop is bound by one load
+    // latency per tile), as far as the caller's workspace allows.
     const long long out_tiles = (long long)a.tiles_m * a.tiles_n;
-    const long long slots = pl.bm == 256 ? kCUs : 2 * kCUs;
+    const long long slots = pl.bm == 256 ? kCUs : (pl.bm == 128 ? 2 * kCUs : 4 * kCUs);
+    const int min_tiles = pl.bm == 64 ? 2 : 4;
     long long g = slots / out_tiles;
-    if (g > a.ntiles / 4) g = a.ntiles / 4;
+    if (g > a.ntiles / min_tiles) g = a.ntiles / min_tiles;
     if (g > 16) g = 16;
     const size_t per_split = (size_t)out_tiles * pl.bm * pl.bn * sizeof(float);
     if (g >= 2 && p->ws && per_split * 2 <= p->ws_bytes) {

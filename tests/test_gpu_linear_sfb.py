@@ -263,3 +263,25 @@ def test_linear_split_k_with_bias_gelu_and_ragged_view(hap):
     for j in range(3):
         hap.hap_sharded_linear_fwd(desc, j, Xd, Wd, bd, Y, P, ws)
     check("split-k Y", host(Y), Yo, "bf16"); check("split-k preact", host(P), preo, "bf16")
+
+
+def test_cfg1_fp32_split_k_with_workspace(hap):
+    """Config 1 again with workspace: 16 output tiles cannot occupy the chip, so the fp32 kernel splits its 16 K tiles
+    over more workgroups (fp32 partial tiles + reduction); same 1e-5 bar, forward with bias + GeLU and both gradients."""
+    offs = [0, 38, 64]
+    Xh, Xd = gen(0, T.X, (64, 1024), 1.0, "f32"); Wh, Wd = gen(0, T.W, (1024, 1024), 0.02, "f32"); dYh, dYd = gen(0, T.DY, (64, 1024), 1.0, "f32")
+    bh, bd = gen(0, T.BIAS, (1024,), 0.5, "f32")
+    desc = hap.LinearDesc(64, 1024, 1024, hap.SHARD_BATCH, offs, hap.F32, act=hap.ACT_GELU_ERF, has_bias=True)
+    Y = empty((64, 1024), "f32", 0); P = empty((64, 1024), "f32", 0); dX = empty((64, 1024), "f32", 0); db = empty((1024,), "f32", 0)
+    wsf = empty((hap.lib.hap_linear_fwd_workspace(None, 0),), "u8")
+    Yo, Po = olin.linear_fwd(Xh, Wh, bh, True)
+    dW_sum = np.zeros((1024, 1024)); db_sum = np.zeros(1024)
+    for j in range(2):
+        hap.hap_sharded_linear_fwd(desc, j, Xd, Wd, bd, Y, P, wsf)
+        wsb = empty((hap.hap_linear_bwd_workspace(desc, j),), "u8")
+        dW = empty((1024, 1024), "f32", float("nan"))
+        hap.hap_sharded_linear_bwd(desc, j, Xd, Wd, P, dYd, dX, dW, hap.F32, db, wsb)
+        dW_sum += host(dW); db_sum += host(db)
+    dXo, dWo, dbo = olin.linear_bwd(Xh, Wh, Po, dYh, act=True)
+    check("cfg1 split-k Y", host(Y), Yo, "f32"); check("cfg1 split-k preact", host(P), Po, "f32")
+    check("cfg1 split-k dX", host(dX), dXo, "f32"); check("cfg1 split-k dW", dW_sum, dWo, "f32"); check("cfg1 split-k db", db_sum, dbo, "f32")
