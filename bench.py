@@ -126,8 +126,9 @@ def main():
         return res
 
     def other_rows():
-        """Throughput of the path's remaining kernels (attention slice, row / element ops) at config 4's shard-0 shapes
-        (16 x 5 heads x 1024 x 128; 16384 x 2048 rows), measured in this run; not part of `value`."""
+        """Throughput of the path's remaining kernels, measured in this run; not part of `value`: attention slice and
+        row / element ops at config 4's shard-0 shapes (16 x 5 heads x 1024 x 128; 16384 x 2048 rows), config 5's
+        attention slice and deep-K SFB rebuild, and config 3 done the naive way (local dW_i + sum) next to the rebuild."""
         B, S, nh, dh, hid = 16, 1024, 5, 128, 2048
         N = B * S
         res = {}
@@ -164,6 +165,39 @@ def main():
         t = timeit(lambda: hap.hap_gelu_bwd(N, hid, hap.BF16, x, hid, dy, hid, y, hid)); res["gelu_bwd_gbs"] = round(3 * nb / t / 1e9)
         t = timeit(lambda: hap.hap_add(N, hid, hap.BF16, x, hid, dy, hid, g, y, hid)); res["add_bias_gbs"] = round(3 * nb / t / 1e9)
         t = timeit(lambda: hap.hap_colsum(N, hid, hap.BF16, dy, hid, dg, lws)); res["colsum_gbs"] = round(nb / t / 1e9)
+        del qkv, dqkv, o, do, x, y, dy
+        # config 5, shard 0: attention over a batch slice (79 x 16 heads x 197 x 64), SFB rebuilds with K = 50432 (split-K)
+        B5, S5, H5, D5 = 79, 197, 16, 64
+        q5 = dev_bf16(2, T.Q, (B5 * S5, 3 * H5 * D5), 1.0); dq5 = torch.zeros_like(q5)
+        o5 = torch.zeros((B5 * S5, H5 * D5), dtype=torch.bfloat16, device=dev); do5 = dev_bf16(2, T.DO, (B5 * S5, H5 * D5), 1.0)
+        lse5 = torch.zeros((B5, H5, S5), dtype=torch.float32, device=dev)
+        ad5 = hap.AttnDesc(B5, H5, S5, D5, False, [0, B5], stride_b=S5 * 3 * H5 * D5, stride_s=3 * H5 * D5, stride_h=D5, o_strides=(S5 * H5 * D5, H5 * D5, D5))
+        aws5 = torch.empty((hap.hap_attn_bwd_workspace(ad5, 0),), dtype=torch.uint8, device=dev)
+        p5 = q5.data_ptr(); g5 = dq5.data_ptr(); w5 = H5 * D5 * 2
+        fl5 = 4.0 * B5 * H5 * S5 * S5 * D5
+        t = timeit(lambda: hap.hap_sharded_attn_fwd(ad5, 0, p5, p5 + w5, p5 + 2 * w5, o5, lse5)); res["cfg5_attn_fwd_tflops"] = round(fl5 / t / 1e12, 1)
+        t = timeit(lambda: hap.hap_sharded_attn_bwd(ad5, 0, p5, p5 + w5, p5 + 2 * w5, o5, lse5, do5, g5, g5 + w5, g5 + 2 * w5, aws5))
+        res["cfg5_attn_bwd_tflops_2.5x_fwd_flops"] = round(2.5 * fl5 / t / 1e12, 1)
+        del q5, dq5, o5, do5
+        rows5 = [197 * b for b in (79, 63, 63, 31, 20)]
+        X5 = [dev_bf16(3, T.SFB_X + i, (r, 1024), 1.0) for i, r in enumerate(rows5)]
+        dY5 = [dev_bf16(3, T.SFB_DY + i, (r, 4096), 1.0) for i, r in enumerate(rows5)]
+        dW5 = torch.zeros((1024, 4096), dtype=torch.float32, device=dev)
+        ws5 = torch.empty((max(16, hap.hap_sfb_workspace(len(rows5), rows5, 1024, 4096)),), dtype=torch.uint8, device=dev)
+        t = timeit(lambda: hap.hap_sfb_grad(X5, dY5, rows5, 1024, 4096, 1024, 4096, hap.BF16, dW5, 4096, ws=ws5))
+        res["cfg5_sfb_dW1_tflops"] = round(2.0 * 1024 * 4096 * sum(rows5) / t / 1e12, 1)
+        del X5, dY5, dW5, ws5
+        # config 3 the naive way (Fig. "sfb"(b)): every device's own fp32 dW_i, then their sum (what the All-Reduce delivers)
+        inf, outf = w3.dims["in_features"], w3.dims["out_features"]
+        parts = [torch.zeros((inf, outf), dtype=torch.float32, device=dev) for _ in rows]
+
+        def naive():
+            for i, r in enumerate(rows):
+                hap.hap_sfb_grad([sX[i]], [sdY[i]], [r], inf, outf, inf, outf, hap.BF16, parts[i], outf)
+            for i in range(1, len(rows)):
+                hap.hap_add(inf, outf, hap.F32, parts[0], outf, parts[i], outf, None, parts[0], outf)
+        t = timeit(naive, n=3); res["cfg3_naive_local_dW_plus_sum_ms"] = round(t * 1e3, 3)
+        t = timeit(lambda: sfb.run(None), n=5); res["cfg3_sfb_rebuild_ms"] = round(t * 1e3, 3)
         return res
 
     for _ in range(args.warmup):
@@ -206,7 +240,7 @@ def main():
         "calls_tflops": {k: round(call_flops[k] / (per[k] * 1e-3) / 1e12, 1) for k in call_flops},
         "setup_s": round(t_setup, 1),
         "achievable": ceilings(),
-        "other_rows_cfg4_shapes": other_rows(),
+        "other_rows": other_rows(),
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(np, hapgen, T, w2, offsets)
