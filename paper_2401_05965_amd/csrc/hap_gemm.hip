@@ -738,33 +738,37 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_dma_kernel(const GemmArgs
       advance_producer();
     }
 
-  for (int t = 0; t < ntiles; ++t) {
+  // One K tile.  FAST: the tile consumed and the tile requested are both interior tiles of their segments (all k
+  // valid) and a request is due: no per-chunk validity, no fix-up, no data-dependent branch between the MFMAs, so
+  // the whole tile is one scheduling region.  Otherwise the general form.
+  auto tile = [&](int t, auto fast_tag) __attribute__((always_inline)) {
+    constexpr bool FAST = decltype(fast_tag)::value;
     char* sa = smem + cslot * STAGE_BYTES;
     char* sb = sa + A_BYTES;
     // tile t must have landed; up to STAGES-2 newer tiles may stay in flight
     if (STAGES > 2 && t + STAGES - 2 < ntiles) asm volatile("s_waitcnt vmcnt(%0)" ::"n"((STAGES - 2) * LOADS_PER_TILE) : "memory");
     else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    if (ck0 < args.skewK || ck0 + BK > ckend) {
+    if (!FAST && (ck0 < args.skewK || ck0 + BK > ckend)) {
       la.fixup(sa, tid, ck0, args.skewK, ckend);
       lb.fixup(sb, tid, ck0, args.skewK, ckend);
     }
     ck0 += BK;
-    if (ck0 >= ckend && cseg + 1 < args.nseg) { cseg = uni(cseg + 1); ck0 = 0; ckend = uni(args.skewK + args.seg[cseg].k); }
+    if (!FAST && ck0 >= ckend && cseg + 1 < args.nseg) { cseg = uni(cseg + 1); ck0 = 0; ckend = uni(args.skewK + args.seg[cseg].k); }
     __syncthreads();          // tile visible to all waves; every wave is done with the slot refilled below
 
     // the next request goes out in pieces between the MFMA groups of this tile (interior tiles), or
     // at once (first / last tile of a segment, where validity is decided per chunk)
-    const bool produce = t + STAGES - 1 < ntiles;
-    const bool edge = pk0 < args.skewK || pk0 + BK > pkend;
+    const bool produce = FAST || t + STAGES - 1 < ntiles;
+    const bool edge = !FAST && (pk0 < args.skewK || pk0 + BK > pkend);
     char* pa = smem + pslot * STAGE_BYTES;
     char* pb = pa + A_BYTES;
     const unsigned soa = LA::tile_offset(pk0, args.skewK, args.lda);
     const unsigned sob = LB::tile_offset(pk0, args.skewK, args.ldb);
-    if (produce && edge) {
+    if (!FAST && produce && edge) {
       la.issue_edge(ra, pa, tid, soa, pk0, args.skewK, pkend);
       lb.issue_edge(rb, pb, tid, sob, pk0, args.skewK, pkend);
     }
-    const bool spread = produce && !edge;
+    const bool spread = FAST || (produce && !edge);
 
     // fragments run kFragAhead k-steps ahead of the MFMAs that use them: a wave that has its SIMD to itself
     // (its partner waits at the barrier) must not stall on LDS latency between k-steps
@@ -778,6 +782,9 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_dma_kernel(const GemmArgs
 #pragma unroll
       for (int j = 0; j < TN; ++j) fb[k0][j] = frb.read(tb, j, k0);
     }
+    // The scheduling fences keep this order: without them the compiler moves each fragment read down to just before
+    // the MFMA that uses it (fewer live registers), and the wave then waits on LDS in front of every MFMA.
+    if (FAST) __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int kk = 0; kk < KK; ++kk) {
       const int cur = kk % NB, nxt = (kk + kFragAhead) % NB;
@@ -786,16 +793,33 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_dma_kernel(const GemmArgs
         for (int i = 0; i < TM; ++i) fa[nxt][i] = fra.read(ta, i, kk + kFragAhead);
 #pragma unroll
         for (int j = 0; j < TN; ++j) fb[nxt][j] = frb.read(tb, j, kk + kFragAhead);
+        if (FAST) __builtin_amdgcn_sched_barrier(0);
       }
 #pragma unroll
       for (int x = 0; x < MF / 2; ++x) acc[x / TN][x % TN] = mfma(fb[cur][x % TN], fa[cur][x / TN], acc[x / TN][x % TN]);
-      if (spread) la.issue_part(ra, pa, tid, soa, kk, KK);
+      if (FAST || spread) la.issue_part(ra, pa, tid, soa, kk, KK);
+      if (FAST) __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
       for (int x = MF / 2; x < MF; ++x) acc[x / TN][x % TN] = mfma(fb[cur][x % TN], fa[cur][x / TN], acc[x / TN][x % TN]);
-      if (spread) lb.issue_part(rb, pb, tid, sob, kk, KK);
+      if (FAST || spread) lb.issue_part(rb, pb, tid, sob, kk, KK);
+      if (FAST) __builtin_amdgcn_sched_barrier(0);
     }
-    if (produce) advance_producer();
+    if (FAST) {      // the producer stays inside its segment
+      pslot = pslot + 1 == STAGES ? 0 : pslot + 1;
+      pk0 += BK;
+    } else if (produce) {
+      advance_producer();
+    }
     cslot = cslot + 1 == STAGES ? 0 : cslot + 1;
+  };
+  // interior for the consumer: all of [ck0, ck0+BK) valid and not the segment's last tile; for the producer likewise,
+  // and its next position stays inside the segment
+  auto fast = [&](int t) {
+    return t + STAGES - 1 < ntiles && ck0 >= args.skewK && ck0 + 2 * BK <= ckend && pk0 >= args.skewK && pk0 + 2 * BK <= pkend;
+  };
+  for (int t = 0; t < ntiles;) {
+    for (; t < ntiles && !fast(t); ++t) tile(t, std::false_type());
+    for (; t < ntiles && fast(t); ++t) tile(t, std::true_type());
   }
 
   __syncthreads();   // every wave is done reading the ring: reuse it as per-wave store patches
