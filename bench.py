@@ -222,7 +222,7 @@ def main():
     achieved = call_flops[dom] / (per[dom] * 1e-3) / 1e12
     # HBM-side bytes of that launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (KiB), scaled by the factors a
     # plain 256 MiB copy gives (2.000 and 1.000); see profiles/gemm_dma_256x256x64_cfg2_cfg3.md
-    traffic_bytes = int((404684 * 2.000 + 65536 * 1.000) * 1024)
+    traffic_bytes = int((404690 * 2.000 + 65536 * 1.000) * 1024)
     out = {
         "metric": "TFLOP/s of sharded fwd+bwd + SFB dW at uneven ratios; % of MFMA peak",
         "value": round(value, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
