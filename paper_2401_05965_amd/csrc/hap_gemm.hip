@@ -768,7 +768,8 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_dma_kernel(const GemmArgs
       la.issue_edge(ra, pa, tid, soa, pk0, args.skewK, pkend);
       lb.issue_edge(rb, pb, tid, sob, pk0, args.skewK, pkend);
     }
-    const bool spread = FAST || (produce && !edge);
+    const bool spread = !FAST && produce && !edge;
+    constexpr bool kAtOnce = AKC && BKC;   // measured: with two 128-bit-read operands the whole request right after the barrier is faster, otherwise spread
 
     // fragments run kFragAhead k-steps ahead of the MFMAs that use them: a wave that has its SIMD to itself
     // (its partner waits at the barrier) must not stall on LDS latency between k-steps
@@ -785,6 +786,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_dma_kernel(const GemmArgs
     // The scheduling fences keep this order: without them the compiler moves each fragment read down to just before
     // the MFMA that uses it (fewer live registers), and the wave then waits on LDS in front of every MFMA.
     if (FAST) __builtin_amdgcn_sched_barrier(0);
+    if (FAST && kAtOnce) { la.issue(ra, pa, tid, soa); lb.issue(rb, pb, tid, sob); __builtin_amdgcn_sched_barrier(0); }
 #pragma unroll
     for (int kk = 0; kk < KK; ++kk) {
       const int cur = kk % NB, nxt = (kk + kFragAhead) % NB;
@@ -797,11 +799,11 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_dma_kernel(const GemmArgs
       }
 #pragma unroll
       for (int x = 0; x < MF / 2; ++x) acc[x / TN][x % TN] = mfma(fb[cur][x % TN], fa[cur][x / TN], acc[x / TN][x % TN]);
-      if (FAST || spread) la.issue_part(ra, pa, tid, soa, kk, KK);
+      if ((FAST && !kAtOnce) || spread) la.issue_part(ra, pa, tid, soa, kk, KK);
       if (FAST) __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
       for (int x = MF / 2; x < MF; ++x) acc[x / TN][x % TN] = mfma(fb[cur][x % TN], fa[cur][x / TN], acc[x / TN][x % TN]);
-      if (FAST || spread) lb.issue_part(rb, pb, tid, sob, kk, KK);
+      if ((FAST && !kAtOnce) || spread) lb.issue_part(rb, pb, tid, sob, kk, KK);
       if (FAST) __builtin_amdgcn_sched_barrier(0);
     }
     if (FAST) {      // the producer stays inside its segment
