@@ -175,7 +175,12 @@ typedef struct {
 } hap_attn_desc;
 
 /* lse: device fp32 [batch x heads x seq] (whole-tensor indexing), log-sum-exp of each query row,
- * written for the slice; needed by the backward.                                                  */
+ * written for the slice; needed by the backward.  The forward uses no workspace (ws may be NULL).
+ * The backward's workspace (hap_attn_bwd_workspace: two fp32 per (batch, head, query) of the whole
+ * tensor) holds D = rowsum(dO * O) and lse * log2(e).  All tensor pointers 16-byte aligned, strides
+ * multiples of 8 elements, (seq + 64) * stride_s below 2^30 elements (HAP_EUNSUPPORTED otherwise);
+ * rows past the sequence end are never read (tile loads are bounded by a buffer descriptor that ends
+ * with the last valid row of the (batch entry, head) being processed).                              */
 int hap_sharded_attn_fwd(const hap_attn_desc* d, int shard_index, const void* Q, const void* K, const void* V,
                          void* O, float* lse, void* ws, size_t ws_bytes, void* stream);
 int hap_sharded_attn_bwd(const hap_attn_desc* d, int shard_index, const void* Q, const void* K, const void* V,
