@@ -169,6 +169,15 @@ def test_linear_modes_ragged(hap, dtype, mode, full):
     run_linear_case(hap, dtype, tokens, in_f, out_f, mode, offsets, act=act, bias=True, full=full)
 
 
+@pytest.mark.parametrize("full", [True, False])
+def test_linear_deep_ragged_contractions(hap, full):
+    """Contracted ranges that start off the 16-byte grid and span many K tiles: first / last tiles of a range take the
+    general tile body (per-chunk validity, zeroing of out-of-range k), the ones between the branch-free one."""
+    run_linear_case(hap, "bf16", 260, 1000, 272, 2, [0, 333, 1000], act=False, bias=False, full=full)      # K ranges 333 | 667 of X columns
+    run_linear_case(hap, "bf16", 1100, 200, 264, 0, [0, 451, 1100], act=True, bias=True, full=full)        # bwd-weight contracts 451 | 649 rows
+    run_linear_case(hap, "bf16", 150, 264, 1210, 1, [0, 603, 1210], act=True, bias=True, full=full)        # bwd-data contracts 603 | 607 columns
+
+
 def test_linear_unaligned_leading_dimensions_take_the_scalar_kernel(hap):
     # compact slices whose leading dimension is not a multiple of 16 bytes
     run_linear_case(hap, "bf16", 70, 50, 90, 1, [0, 37, 90], act=True, bias=True, full=False, pad=3)
