@@ -123,6 +123,21 @@ def main():
             dst.copy_(src)
         b.record(stream); b.synchronize()
         res["copy_read_plus_write_gbs"] = round(2 * src.numel() * 4 * 20 / (a.elapsed_time(b) * 1e-3) / 1e9, 1)
+        del src, dst
+        # context only: the vendor library's GEMM (torch.matmul -> hipBLASLt) on the roofline launch's shape and on its
+        # bwd-weight counterpart, same box, same run; the product path never calls it
+        big = shards[0]
+        A = torch.randn((big.T, big.f), device=dev).to(torch.bfloat16); Bm = (torch.randn((big.f, big.h), device=dev) * 0.02).to(torch.bfloat16)
+        G = torch.randn((big.T, big.h), device=dev).to(torch.bfloat16)
+        for name, fn in (("vendor_gemm_roofline_shape_tflops", lambda: torch.matmul(A, Bm)), ("vendor_gemm_bwd_weight_shape_tflops", lambda: torch.matmul(A.t(), G))):
+            for _ in range(3):
+                fn()
+            a = torch.cuda.Event(enable_timing=True); b = torch.cuda.Event(enable_timing=True)
+            a.record(stream)
+            for _ in range(10):
+                fn()
+            b.record(stream); b.synchronize()
+            res[name] = round(2.0 * big.T * big.f * big.h * 10 / (a.elapsed_time(b) * 1e-3) / 1e12, 1)
         return res
 
     def other_rows():
