@@ -155,3 +155,32 @@ def test_colsum_unaligned_base(hap, dtype):
         ws = empty((max(hap.hap_colsum_workspace(rows, cols), 16),), "u8")
         hap.hap_colsum(rows, cols, io, ad.data_ptr() + off * esz, ld, s, ws)
         check("colsum skew", host(s), ah[:rows, off:off + cols].sum(0), dtype)
+
+
+def test_row_ops_degenerate_sizes(hap):
+    """Empty and one-element extents: every helper returns HAP_OK and leaves what it does not own untouched."""
+    for dtype in ("bf16", "f32"):
+        io = {"bf16": 1, "f32": 0}[dtype]
+        # LayerNorm over a single column: y = beta, dx = 0, dgamma = 0, dbeta = colsum(dy)
+        xh, xd = gen(6, T.X, (5, 1), 1.0, dtype); gh, gd = gen(6, T.GAMMA, (1,), 1.0, dtype); bh, bd = gen(6, T.BETA, (1,), 1.0, dtype)
+        dyh, dyd = gen(6, T.DY, (5, 1), 1.0, dtype)
+        y = empty((5, 1), dtype, 7); mean = empty((5,), "f32", 0); rstd = empty((5,), "f32", 0)
+        hap.hap_layernorm_fwd(5, 1, io, xd, gd, bd, y, mean, rstd)
+        yo, _, _ = opw.layernorm_fwd(xh, gh, bh)
+        check("ln n=1", host(y), yo, dtype)
+        dx = empty((5, 1), dtype, 7); dg = empty((1,), "f32", 7); db = empty((1,), "f32", 7)
+        ws = empty((max(hap.hap_layernorm_bwd_workspace(5, 1), 16),), "u8")
+        hap.hap_layernorm_bwd(5, 1, io, xd, gd, mean, rstd, dyd, dx, dg, db, ws)
+        dxo, dgo, dbo = opw.layernorm_bwd(xh, gh, dyh)
+        assert np.abs(host(dx) - dxo).max() <= 1e-3 and abs(host(dg)[0] - dgo[0]) <= 1e-2 * max(1.0, np.abs(dyh).sum())
+        check("ln n=1 dbeta", host(db), dbo, dtype)
+        # zero rows: nothing written except the column sums, which are zero
+        s = empty((9,), "f32", float("nan")); keep = empty((4, 9), dtype, 3)
+        ws = empty((16,), "u8")
+        hap.hap_colsum(0, 9, io, keep, 9, s, ws)
+        assert not host(s).any()
+        hap.hap_layernorm_fwd(0, 9, io, keep, keep, keep, keep, mean, rstd)
+        hap.hap_gelu_bwd(0, 9, io, keep, 9, keep, 9, keep, 9)
+        hap.hap_add(0, 9, io, keep, 9, keep, 9, None, keep, 9)
+        hap.hap_add(4, 0, io, keep, 9, keep, 9, None, keep, 9)
+        assert (host(keep) == 3).all()
