@@ -19,9 +19,6 @@
 
 #include <stdint.h>
 
-#include <type_traits>
-#include <utility>
-
 #include "hap_internal.h"
 
 namespace {
@@ -33,12 +30,6 @@ typedef short s16x8_t __attribute__((ext_vector_type(8)));
 typedef float f32x16_t __attribute__((ext_vector_type(16)));
 typedef float f32x4_t __attribute__((ext_vector_type(4)));
 typedef int i32x4_t __attribute__((ext_vector_type(4)));
-
-template <typename F, int... I>
-__device__ __forceinline__ void static_for_impl(F&& f, std::integer_sequence<int, I...>) { (f(std::integral_constant<int, I>{}), ...); }
-/* f(std::integral_constant<int, 0>), ..., f(<N-1>) in order: a loop whose index is a constant in every pass. */
-template <int N, typename F>
-__device__ __forceinline__ void static_for(F&& f) { static_for_impl(f, std::make_integer_sequence<int, N>{}); }
 
 #define LDS_PTR(T, p) ((__attribute__((address_space(3))) T*)(p))
 
@@ -70,32 +61,16 @@ __device__ __forceinline__ int swz(int row, int c) {
   else return c ^ ((((row >> 1) & 1) << 2) | ((row >> 2) & 3));
 }
 
-/* A operand, K-contiguous: rows of the tile are the MFMA M index, head_dim the contraction. */
-template <int D>
-__device__ __forceinline__ bf16x8_t frag_rows(const char* lds, int row_base, int ks, int lane) {
-  const int row = row_base + (lane & 31);
-  const int c = ks * 2 + (lane >> 5);
-  return __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const i32x4_t*>(lds + row * (D * 2) + swz<D>(row, c) * 16));
-}
-
-/* A operand, transposed: MFMA M index = head_dim column (32 starting at col_base), contraction =
- * tile rows in the accumulator's order: k-slot j of lane half h is row row_base + (j/4)*8 + h*4 + j%4. */
-template <int D>
-__device__ __forceinline__ bf16x8_t frag_cols(const char* lds, int row_base, int col_base, int lane) {
-  const int g = lane >> 4, i = lane & 15;
-  const int col = col_base + (g & 1) * 16 + (i & 3) * 4;
-  const int r0 = row_base + (g >> 1) * 4 + (i >> 2);
-  const int c = col >> 3, sub = (col & 7) * 2;
-  s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4_t, lds + r0 * (D * 2) + swz<D>(r0, c) * 16 + sub));
-  s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4_t, lds + (r0 + 8) * (D * 2) + swz<D>(r0 + 8, c) * 16 + sub));
-  return __builtin_bit_cast(bf16x8_t, (s16x8_t)__builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
-}
-
-/* The same two operand fetches with the address arithmetic folded: because the swizzle is an XOR, the
- * byte address of every fragment of a tile is  ((lane constant + tile address) ^ small constant) +
- * multiple of the row size,  so a wave keeps two lane constants instead of one address per fragment.
+/* MFMA operand fetches from an LDS tile.
+ *   rows (A operand, K-contiguous): rows of the tile are the MFMA M index, head_dim the contraction; one 128-bit read.
+ *   cols (A operand, transposed): M index = head_dim column (32 starting at dt*32), contraction = tile rows in the
+ *     accumulator's order (k-slot j of lane half h is row row_base + (j/4)*8 + h*4 + j%4); two transposing 64-bit reads.
+ * The address arithmetic is folded: because the swizzle is an XOR, the byte address of every fragment of a tile is
+ * ((lane constant + tile address) ^ small constant) + multiple of the row size, so a wave keeps two lane constants
+ * instead of one address per fragment.
  *   rows:  row = row_base + lane%32, chunk ks*2 + lane/32:   (rows + tile) ^ (ks << 5)            + row_base * row bytes
- *   cols:  rows r0, r0 + 8 (r0 as in frag_cols), columns dt*32..: (cols + tile) ^ (dt << 6) [^ 32] + (row_base [+ 8]) * row bytes
+ *   cols:  rows r0, r0 + 8 with r0 = row_base + (lane/32)*4 + (lane%16)/4, columns dt*32 + ((lane/16)%2)*16 + (lane%4)*4 ..:
+ *          (cols + tile) ^ (dt << 6) [^ 32] + (row_base [+ 8]) * row bytes
  * (row_base a multiple of 16, tile address a multiple of 256; f(r + 8) = f(r) ^ 2 and f(r + 16) = f(r)). */
 template <int D>
 struct FragAddr {
@@ -258,8 +233,10 @@ constexpr float kLazy = 8.0f;
 template <int D>
 __global__ __launch_bounds__(64 * kWaves, 2) void attn_fwd_kernel(const AttnArgs a) {
   constexpr int kTileBytes = kTile * D * 2;
-  __shared__ __attribute__((aligned(16))) char lds[2][2][kTileBytes];   // [buffer][K, V]
+  __shared__ __attribute__((aligned(256))) char lds[2][2][kTileBytes];   // [buffer][K, V]
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  FragAddr<D> fa;
+  fa.init(lane);
   int bx, by, bz;
   block_coords(bx, by, bz);
   const int b = a.b0 + bz, h = a.h0 + by;
@@ -294,7 +271,7 @@ __global__ __launch_bounds__(64 * kWaves, 2) void attn_fwd_kernel(const AttnArgs
     for (int sub = 0; sub < 2; ++sub) {
       s[sub] = zero16();
 #pragma unroll
-      for (int ks = 0; ks < D / 16; ++ks) s[sub] = mfma(frag_rows<D>(lds_k, sub * 32, ks, lane), qf[ks], s[sub]);
+      for (int ks = 0; ks < D / 16; ++ks) s[sub] = mfma(frag_rows_at<D>(fa.rows + lds_addr(lds_k), sub * 32, ks), qf[ks], s[sub]);
     }
     if (kv0 + kTile > a.seq) {   // ragged last tile: keys past the end drop out
 #pragma unroll
@@ -334,7 +311,7 @@ __global__ __launch_bounds__(64 * kWaves, 2) void attn_fwd_kernel(const AttnArgs
       for (int ss = 0; ss < 2; ++ss) {
         const bf16x8_t p = pack8(s[sub], ss);
 #pragma unroll
-        for (int dt = 0; dt < D / 32; ++dt) o[dt] = mfma(frag_cols<D>(lds_v, sub * 32 + ss * 16, dt * 32, lane), p, o[dt]);
+        for (int dt = 0; dt < D / 32; ++dt) o[dt] = mfma(frag_cols_at<D>(fa.cols + lds_addr(lds_v), sub * 32 + ss * 16, dt), p, o[dt]);
       }
     wait_tiles_and_sync();
   }
@@ -371,8 +348,10 @@ __global__ __launch_bounds__(256) void attn_dsum_kernel(const AttnArgs a) {
 template <int D>
 __global__ __launch_bounds__(64 * kWaves, 2) void attn_bwd_dq_kernel(const AttnArgs a) {
   constexpr int kTileBytes = kTile * D * 2;
-  __shared__ __attribute__((aligned(16))) char lds[2][2][kTileBytes];   // [buffer][K, V]
+  __shared__ __attribute__((aligned(256))) char lds[2][2][kTileBytes];   // [buffer][K, V]
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  FragAddr<D> fa;
+  fa.init(lane);
   int bx, by, bz;
   block_coords(bx, by, bz);
   const int b = a.b0 + bz, h = a.h0 + by;
@@ -411,8 +390,8 @@ __global__ __launch_bounds__(64 * kWaves, 2) void attn_bwd_dq_kernel(const AttnA
       f32x16_t s = zero16(), dp = zero16();
 #pragma unroll
       for (int ks = 0; ks < D / 16; ++ks) {
-        s = mfma(frag_rows<D>(lds_k, sub * 32, ks, lane), qf[ks], s);
-        dp = mfma(frag_rows<D>(lds_v, sub * 32, ks, lane), dof[ks], dp);
+        s = mfma(frag_rows_at<D>(fa.rows + lds_addr(lds_k), sub * 32, ks), qf[ks], s);
+        dp = mfma(frag_rows_at<D>(fa.rows + lds_addr(lds_v), sub * 32, ks), dof[ks], dp);
       }
 #pragma unroll
       for (int e = 0; e < 16; ++e) {
@@ -424,7 +403,7 @@ __global__ __launch_bounds__(64 * kWaves, 2) void attn_bwd_dq_kernel(const AttnA
       for (int ss = 0; ss < 2; ++ss) {
         const bf16x8_t ds = pack8(s, ss);
 #pragma unroll
-        for (int dt = 0; dt < D / 32; ++dt) dq[dt] = mfma(frag_cols<D>(lds_k, sub * 32 + ss * 16, dt * 32, lane), ds, dq[dt]);
+        for (int dt = 0; dt < D / 32; ++dt) dq[dt] = mfma(frag_cols_at<D>(fa.cols + lds_addr(lds_k), sub * 32 + ss * 16, dt), ds, dq[dt]);
       }
     }
     wait_tiles_and_sync();
@@ -441,10 +420,12 @@ constexpr int kQTile = 32;
 template <int D>
 __global__ __launch_bounds__(64 * kWaves, 2) void attn_bwd_dkv_kernel(const AttnArgs a) {
   constexpr int kTileBytes = kQTile * D * 2;
-  __shared__ __attribute__((aligned(16))) char lds[2][2][kTileBytes];    // [buffer][Q, dO]
-  __shared__ __attribute__((aligned(16))) char lds_vres[32 * kWaves * D * 2];
+  __shared__ __attribute__((aligned(256))) char lds[2][2][kTileBytes];    // [buffer][Q, dO]
+  __shared__ __attribute__((aligned(256))) char lds_vres[32 * kWaves * D * 2];
   __shared__ __attribute__((aligned(16))) float lds_stat[2][2][64];      // [buffer][lse * log2(e), D]; 32 used
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  FragAddr<D> fa;
+  fa.init(lane);
   int bx, by, bz;
   block_coords(bx, by, bz);
   const int b = a.b0 + bz, h = a.h0 + by;
@@ -495,8 +476,8 @@ __global__ __launch_bounds__(64 * kWaves, 2) void attn_bwd_dkv_kernel(const Attn
     f32x16_t s = zero16(), dp = zero16();
 #pragma unroll
     for (int ks = 0; ks < D / 16; ++ks) {
-      s = mfma(frag_rows<D>(lds_q, 0, ks, lane), kf[ks], s);
-      dp = mfma(frag_rows<D>(lds_do, 0, ks, lane), frag_rows<D>(lds_vres, wave * 32, ks, lane), dp);
+      s = mfma(frag_rows_at<D>(fa.rows + lds_addr(lds_q), 0, ks), kf[ks], s);
+      dp = mfma(frag_rows_at<D>(fa.rows + lds_addr(lds_do), 0, ks), frag_rows_at<D>(fa.rows + lds_addr(lds_vres), wave * 32, ks), dp);
     }
 #pragma unroll
     for (int g = 0; g < 4; ++g) {
@@ -516,8 +497,8 @@ __global__ __launch_bounds__(64 * kWaves, 2) void attn_bwd_dkv_kernel(const Attn
       const bf16x8_t pf = pack8(s, ss), dsf = pack8(dp, ss);
 #pragma unroll
       for (int dt = 0; dt < D / 32; ++dt) {
-        dv[dt] = mfma(frag_cols<D>(lds_do, ss * 16, dt * 32, lane), pf, dv[dt]);
-        dk[dt] = mfma(frag_cols<D>(lds_q, ss * 16, dt * 32, lane), dsf, dk[dt]);
+        dv[dt] = mfma(frag_cols_at<D>(fa.cols + lds_addr(lds_do), ss * 16, dt), pf, dv[dt]);
+        dk[dt] = mfma(frag_cols_at<D>(fa.cols + lds_addr(lds_q), ss * 16, dt), dsf, dk[dt]);
       }
     }
     wait_tiles_and_sync();
