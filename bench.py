@@ -43,7 +43,7 @@ def main():
     import hapgen
     from hapgen import TensorId as T
     import paper_2401_05965_amd as hap
-    from paper_2401_05965_amd.programs import MlpShard, SfbRebuild
+    from paper_2401_05965_amd.programs import EncoderShard, MlpShard, SfbRebuild
 
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
@@ -202,6 +202,27 @@ def main():
         t = timeit(lambda: hap.hap_sfb_grad(X5, dY5, rows5, 1024, 4096, 1024, 4096, hap.BF16, dW5, 4096, ws=ws5))
         res["cfg5_sfb_dW1_tflops"] = round(2.0 * 1024 * 4096 * sum(rows5) / t / 1e12, 1)
         del X5, dY5, dW5, ws5
+        # whole encoder layer, forward + backward, as one device runs it (every GEMM, attention and row kernel in order):
+        # config 4 sharded over heads / ffn (devices 0 and 2), config 5's batch shard of device 0
+        def layer(style, j, B, S, hid, heads, d, ffn, hoffs, foffs, boffs):
+            gen4 = torch.Generator(device=dev); gen4.manual_seed(4)       # same distributions as hapgen's, drawn on the device to keep set-up short
+            sw = lambda tid, shp, sg: (torch.randn(shp, generator=gen4, device=dev) * sg).to(torch.bfloat16)
+            prm = {"Wq": sw(T.WQ, (hid, hid), 0.02), "Wk": sw(T.WK, (hid, hid), 0.02), "Wv": sw(T.WV, (hid, hid), 0.02), "Wo": sw(T.WO, (hid, hid), 0.02),
+                   "W1": sw(T.W, (hid, ffn), 0.02), "W2": sw(T.W2, (ffn, hid), 0.02), "b1": sw(T.BIAS, (ffn,), 0.02)}
+            for i, n in enumerate(("bq", "bk", "bv", "bo", "b2", "be1", "be2")):
+                prm[n] = sw(T.MISC + i, (hid,), 0.02)
+            prm["g1"] = torch.ones((hid,), dtype=torch.bfloat16, device=dev); prm["g2"] = prm["g1"].clone()
+            sh = EncoderShard(style, j, B, S, hid, heads, d, ffn, hoffs, foffs, boffs, prm)
+            xs = sw(T.X, (sh.N, hid), 1.0); dys = sw(T.DY, (sh.N, hid), 1.0)
+            buf = {n: torch.zeros_like(xs) for n in ("x1", "y", "dx1", "dx")}
+            buf["dbo"] = torch.zeros((hid,), dtype=torch.float32, device=dev); buf["db2"] = torch.zeros_like(buf["dbo"])
+            t = timeit(lambda: sh.device_step(xs, dys, buf, prm["bo"], prm["b2"]), n=5)
+            f, b = sh.flops()
+            return {"ms": round(t * 1e3, 3), "gflop": round((f + b) / 1e9, 1), "tflops": round((f + b) / t / 1e12, 1)}
+        c4 = (16, 1024, 2048, 16, 128, 8192, [0, 5, 10, 13, 16], [0, 2731, 5462, 6827, 8192], [0, 16])
+        res["cfg4_layer_fwd_bwd_device0_5heads_ffn2731"] = layer("tensor", 0, *c4)
+        res["cfg4_layer_fwd_bwd_device2_3heads_ffn1365"] = layer("tensor", 2, *c4)
+        res["cfg5_layer_fwd_bwd_device0_79samples"] = layer("data", 0, 256, 197, 1024, 16, 64, 4096, [0, 16], [0, 4096], [0, 79, 142, 205, 236, 256])
         # config 3 the naive way (Fig. "sfb"(b)): every device's own fp32 dW_i, then their sum (what the All-Reduce delivers)
         inf, outf = w3.dims["in_features"], w3.dims["out_features"]
         parts = [torch.zeros((inf, outf), dtype=torch.float32, device=dev) for _ in rows]

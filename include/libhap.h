@@ -195,9 +195,12 @@ size_t hap_attn_bwd_workspace(const hap_attn_desc* d, int shard_index);
  * 16-byte aligned pointers with n a multiple of 16 / sizeof(element) take the vector path.          */
 int hap_layernorm_fwd(int64_t rows, int64_t n, int io_dtype, const void* x, const void* gamma, const void* beta,
                       void* y, float* mean, float* rstd, void* stream);
-/* dx in io_dtype; dgamma, dbeta fp32 [n], overwritten.  ws from hap_layernorm_bwd_workspace.        */
+/* dx in io_dtype; dgamma, dbeta fp32 [n], overwritten.  ws from hap_layernorm_bwd_workspace.
+ * dresidual: NULL, or [rows x n] in io_dtype that is added to dx before the one rounding to io_dtype (a
+ * pre-LayerNorm layer's gradient on the residual path, which bypasses the normalisation); it may be dx
+ * itself, no other aliasing.                                                                        */
 int hap_layernorm_bwd(int64_t rows, int64_t n, int io_dtype, const void* x, const void* gamma, const float* mean,
-                      const float* rstd, const void* dy, void* dx, float* dgamma, float* dbeta,
+                      const float* rstd, const void* dy, const void* dresidual, void* dx, float* dgamma, float* dbeta,
                       void* ws, size_t ws_bytes, void* stream);
 size_t hap_layernorm_bwd_workspace(int64_t rows, int64_t n);
 

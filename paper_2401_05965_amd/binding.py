@@ -220,10 +220,10 @@ def hap_layernorm_bwd_workspace(rows, n) -> int:
     return int(lib.hap_layernorm_bwd_workspace(C.c_int64(rows), C.c_int64(n)))
 
 
-def hap_layernorm_bwd(rows, n, io_dtype, x, gamma, mean, rstd, dy, dx, dgamma, dbeta, ws, stream=None):
+def hap_layernorm_bwd(rows, n, io_dtype, x, gamma, mean, rstd, dy, dx, dgamma, dbeta, ws, stream=None, dresidual=None):
     wp, wb = _ws(ws)
     _check(lib.hap_layernorm_bwd(C.c_int64(rows), C.c_int64(n), C.c_int(io_dtype), _ptr(x), _ptr(gamma), _ptr(mean), _ptr(rstd),
-                                 _ptr(dy), _ptr(dx), _ptr(dgamma), _ptr(dbeta), wp, wb, _stream(stream)), "hap_layernorm_bwd")
+                                 _ptr(dy), _ptr(dresidual), _ptr(dx), _ptr(dgamma), _ptr(dbeta), wp, wb, _stream(stream)), "hap_layernorm_bwd")
 
 
 def hap_gelu_bwd(rows, cols, io_dtype, preact, ldp, dy, lddy, out, ldo, stream=None):

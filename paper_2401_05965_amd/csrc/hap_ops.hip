@@ -183,11 +183,11 @@ __global__ __launch_bounds__(256) void layernorm_fwd_kernel(int64_t rows, int n,
 }
 
 /* LayerNorm backward.  Block = 4 waves, each wave walks rows (stride 4*gridDim.x); per row it forms dx
- * and adds the row's contribution to its lanes' dgamma / dbeta accumulators; the four waves' sums meet
+ * (plus the row of dres when given: the gradient that bypasses the normalisation on the residual path) and adds the row's contribution to its lanes' dgamma / dbeta accumulators; the four waves' sums meet
  * in LDS and go to part[block][2][n]; layernorm_bwd_final_kernel folds the blocks. */
 template <typename T, int V, int NCH>
 __global__ __launch_bounds__(256) void layernorm_bwd_kernel(int64_t rows, int n, const T* x, const T* gamma, const float* mean,
-                                                            const float* rstd, const T* dy, T* dx, float* part) {
+                                                            const float* rstd, const T* dy, const T* dres, T* dx, float* part) {
   __shared__ float red[4][64 * V * NCH];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   float dg[NCH][V], db[NCH][V];
@@ -225,9 +225,10 @@ __global__ __launch_bounds__(256) void layernorm_bwd_kernel(int64_t rows, int n,
     for (int i = 0; i < NCH; ++i) {
       const int c = (i * 64 + lane) * V;
       if (c < n) {
-        Pack<T, V> o;
+        Pack<T, V> o, r;
+        if (dres) r = *reinterpret_cast<const Pack<T, V>*>(dres + row * n + c);
 #pragma unroll
-        for (int e = 0; e < V; ++e) o.v[e] = (T)(rs * (g[i][e] - s1 - xh[i][e] * s2));
+        for (int e = 0; e < V; ++e) o.v[e] = (T)(rs * (g[i][e] - s1 - xh[i][e] * s2) + (dres ? (float)r.v[e] : 0.0f));
         *reinterpret_cast<Pack<T, V>*>(dx + row * n + c) = o;
       }
     }
@@ -358,12 +359,12 @@ int layernorm_fwd_t(int64_t rows, int n, const void* x, const void* g, const voi
 
 template <typename T>
 int layernorm_bwd_t(int64_t rows, int n, const void* x, const void* g, const float* mean, const float* rstd, const void* dy,
-                    void* dx, float* dgamma, float* dbeta, float* part, hipStream_t s) {
+                    const void* dres, void* dx, float* dgamma, float* dbeta, float* part, hipStream_t s) {
   const int nblocks = (int)((rows + 3) / 4 < kLnBlocks ? (rows + 3) / 4 : kLnBlocks);
-  const bool vec_ok = aligned16(x) && aligned16(dy) && aligned16(dx) && aligned16(g);
+  const bool vec_ok = aligned16(x) && aligned16(dy) && aligned16(dx) && aligned16(g) && aligned16(dres);
   const bool ok = ln_dispatch<T>(n, vec_ok, [&](auto v, auto nch) {
     hipLaunchKernelGGL((layernorm_bwd_kernel<T, decltype(v)::value, decltype(nch)::value>), dim3(nblocks), dim3(256), 0, s, rows, n, (const T*)x,
-                       (const T*)g, mean, rstd, (const T*)dy, (T*)dx, part);
+                       (const T*)g, mean, rstd, (const T*)dy, (const T*)dres, (T*)dx, part);
   });
   if (!ok) return hap_fail(HAP_EUNSUPPORTED, "layernorm row of %d elements is too long for this layout", n);
   int rc = check_launch("layernorm_bwd");
@@ -473,7 +474,7 @@ size_t hap_layernorm_bwd_workspace(int64_t rows, int64_t n) {
 }
 
 int hap_layernorm_bwd(int64_t rows, int64_t n, int io_dtype, const void* x, const void* gamma, const float* mean,
-                      const float* rstd, const void* dy, void* dx, float* dgamma, float* dbeta,
+                      const float* rstd, const void* dy, const void* dresidual, void* dx, float* dgamma, float* dbeta,
                       void* ws, size_t ws_bytes, void* stream) {
   hap_clear_error();
   if (rows < 0 || n < 1) return hap_fail(HAP_EINVAL, "bad size");
@@ -482,8 +483,8 @@ int hap_layernorm_bwd(int64_t rows, int64_t n, int io_dtype, const void* x, cons
   const size_t need = hap_layernorm_bwd_workspace(rows, n);
   if (!ws || ws_bytes < need) return hap_fail(HAP_EWORKSPACE, "layernorm_bwd needs %zu workspace bytes", need);
   hipStream_t s = (hipStream_t)stream;
-  if (io_dtype == HAP_BF16) return layernorm_bwd_t<__bf16>(rows, (int)n, x, gamma, mean, rstd, dy, dx, dgamma, dbeta, (float*)ws, s);
-  if (io_dtype == HAP_F32) return layernorm_bwd_t<float>(rows, (int)n, x, gamma, mean, rstd, dy, dx, dgamma, dbeta, (float*)ws, s);
+  if (io_dtype == HAP_BF16) return layernorm_bwd_t<__bf16>(rows, (int)n, x, gamma, mean, rstd, dy, dresidual, dx, dgamma, dbeta, (float*)ws, s);
+  if (io_dtype == HAP_F32) return layernorm_bwd_t<float>(rows, (int)n, x, gamma, mean, rstd, dy, dresidual, dx, dgamma, dbeta, (float*)ws, s);
   return hap_fail(HAP_EINVAL, "bad dtype %d", io_dtype);
 }
 

@@ -154,7 +154,6 @@ class EncoderShard:
         # gradients
         self.dH, self.dln2_part, self.dln1_part = z(N, ldf), z(N, hidden), z(N, hidden)
         self.do, self.dqkv = z(N, max(hd, 8)), z(N, max(3 * hd, 8))
-        self.dx1_ln, self.dx_ln = z(N, hidden), z(N, hidden)
         self.dWqkv, self.dWo = z(hidden, max(3 * hd, 8)), z(max(hd, 1), hidden)
         self.dW1, self.dW2 = z(hidden, ldf), z(max(self.f, 1), hidden)
         self.dbqkv, self.db1 = zf(max(3 * hd, 1)), zf(max(self.f, 1))
@@ -212,9 +211,10 @@ class EncoderShard:
         _call(timer, "fc2_bwd", lambda: hap.hap_sharded_linear_bwd(self.d_fc2, 0, self.H, self.W2, None, dy, self.dH, self.dW2, self.io, None, self.ws))
         _call(timer, "fc1_bwd", lambda: hap.hap_sharded_linear_bwd(self.d_fc1, 0, self.ln2, self.W1, self.pre, self.dH, self.dln2_part, self.dW1, self.io, self.db1, self.ws))
 
-    def ln2_backward(self, x1, dln2, timer=None):
-        _call(timer, "ln2_bwd", lambda: hap.hap_layernorm_bwd(self.N, self.hidden, self.io, x1, self.g2, self.mean2, self.rstd2, dln2, self.dx1_ln,
-                                                              self.dg2, self.dbe2, self.ws))
+    def ln2_backward(self, x1, dln2, dres, dx1, timer=None):
+        """dx1 = dres + LayerNorm2-backward(dln2): the residual path's gradient joins in the same kernel."""
+        _call(timer, "ln2_bwd", lambda: hap.hap_layernorm_bwd(self.N, self.hidden, self.io, x1, self.g2, self.mean2, self.rstd2, dln2, dx1,
+                                                              self.dg2, self.dbe2, self.ws, dresidual=dres))
 
     def attn_backward(self, dx1, timer=None):
         """dx1: gradient at the residual stream after attention.  Leaves the QKV bwd-data product in dln1_part."""
@@ -229,9 +229,23 @@ class EncoderShard:
         _call(timer, "qkv_bwd", lambda: hap.hap_sharded_linear_bwd(self.d_qkv, 0, self.ln1, self.Wqkv, None, self.dqkv, self.dln1_part, self.dWqkv,
                                                                    self.io, self.dbqkv, self.ws))
 
-    def ln1_backward(self, x, dln1, timer=None):
-        _call(timer, "ln1_bwd", lambda: hap.hap_layernorm_bwd(self.N, self.hidden, self.io, x, self.g1, self.mean1, self.rstd1, dln1, self.dx_ln,
-                                                              self.dg1, self.dbe1, self.ws))
+    def ln1_backward(self, x, dln1, dres, dx, timer=None):
+        _call(timer, "ln1_bwd", lambda: hap.hap_layernorm_bwd(self.N, self.hidden, self.io, x, self.g1, self.mean1, self.rstd1, dln1, dx,
+                                                              self.dg1, self.dbe1, self.ws, dresidual=dres))
+
+    def device_step(self, x, dy, buf, bo, b2):
+        """Every instruction device j runs for one forward + backward of the layer, in order, with its own
+        partial products standing in for what the All-Reduce would deliver (timing aid: the values equal the
+        layer's only when j is the single device).  buf: dict of [N x hidden] tensors x1, y, dx1, dx and fp32
+        [hidden] vectors dbo, db2."""
+        N, h = self.N, self.hidden
+        add = lambda a, b, bias, out: hap.hap_add(N, h, self.io, a, h, b, h, bias, out, h)
+        self.attn_forward(x); add(x, self.attn_part, bo, buf["x1"])
+        self.mlp_forward(buf["x1"]); add(buf["x1"], self.mlp_part, b2, buf["y"])
+        self.mlp_backward(dy); self.ln2_backward(buf["x1"], self.dln2_part, dy, buf["dx1"])
+        self.attn_backward(buf["dx1"]); self.ln1_backward(x, self.dln1_part, buf["dx1"], buf["dx"])
+        hap.hap_colsum(N, h, self.io, dy, h, buf["db2"], self.ws)
+        hap.hap_colsum(N, h, self.io, buf["dx1"], h, buf["dbo"], self.ws)
 
 
 class EncoderLayerProgram:
@@ -295,23 +309,19 @@ class EncoderLayerProgram:
             for s in self.shards:
                 s.mlp_backward(self.dy)
             self._reduce([s.dln2_part for s in self.shards], self.red)
-            s0.ln2_backward(self.x1, self.red)                       # replicated: every device computes the same
-            self._add(N, self.dy, s0.dx1_ln, None, self.dx1)
+            s0.ln2_backward(self.x1, self.red, self.dy, self.dx1)    # replicated: every device computes the same
             for s in self.shards:
                 s.attn_backward(self.dx1)
             self._reduce([s.dln1_part for s in self.shards], self.red)
-            s0.ln1_backward(self.x, self.red)
-            self._add(N, self.dx1, s0.dx_ln, None, self.dx)
+            s0.ln1_backward(self.x, self.red, self.dx1, self.dx)
         else:
             for s in self.shards:
                 if s.N == 0:
                     continue
                 xr, x1r, dyr, dx1r, dxr = (s.rows(t) for t in (self.x, self.x1, self.dy, self.dx1, self.dx))
                 s.mlp_backward(dyr)
-                s.ln2_backward(x1r, s.dln2_part)
-                self._add(s.N, dyr, s.dx1_ln, None, dx1r)
+                s.ln2_backward(x1r, s.dln2_part, dyr, dx1r)
                 s.attn_backward(dx1r)
-                s.ln1_backward(xr, s.dln1_part)
-                self._add(s.N, dx1r, s.dx_ln, None, dxr)
+                s.ln1_backward(xr, s.dln1_part, dx1r, dxr)
         hap.hap_colsum(N, self.hidden, hap.BF16, self.dy, self.hidden, self.db2, self.ws)
         hap.hap_colsum(N, self.hidden, hap.BF16, self.dx1, self.hidden, self.dbo, self.ws)

@@ -120,6 +120,14 @@ def test_layernorm_fwd_bwd(hap, dtype, rows, n):
     hap.hap_layernorm_bwd(rows, n, {"bf16": 1, "f32": 0}[dtype], xd, gd, mean, rstd, dyd, dx, dg, db, ws)
     dxo, dgo, dbo = opw.layernorm_bwd(xh, gh, dyh)
     check("ln dx", host(dx), dxo, dtype); check("ln dgamma", host(dg), dgo, dtype); check("ln dbeta", host(db), dbo, dtype)
+    # with the residual path's gradient added in the same kernel, out of place and in place (dx = dresidual)
+    rh, rd = gen(2, T.DO, (rows, n), 1.0, dtype)
+    dx2 = empty((rows, n), dtype, 0)
+    hap.hap_layernorm_bwd(rows, n, {"bf16": 1, "f32": 0}[dtype], xd, gd, mean, rstd, dyd, dx2, dg, db, ws, dresidual=rd)
+    check("ln dx + dres", host(dx2), dxo + rh, dtype); check("ln dgamma", host(dg), dgo, dtype)
+    inpl = rd.clone()
+    hap.hap_layernorm_bwd(rows, n, {"bf16": 1, "f32": 0}[dtype], xd, gd, mean, rstd, dyd, inpl, dg, db, ws, dresidual=inpl)
+    assert (host(inpl) == host(dx2)).all()
 
 
 @pytest.mark.parametrize("dtype", ["bf16", "f32"])
