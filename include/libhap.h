@@ -155,6 +155,44 @@ int hap_sfb_grad(int m, const void* const* X, const void* const* dY, const int64
                  float* dW, int64_t lddw, int accumulate, void* ws, size_t ws_bytes, void* stream);
 size_t hap_sfb_workspace(int m, const int64_t* rows, int64_t in_features, int64_t out_features);
 
+/* ------------------------------------------------------------------ device: MoE experts --- */
+
+/* One fully-connected layer per expert of a Mixture-of-Experts layer whose EXPERT axis is sharded
+ * unevenly (Sec. 7.6, "Uneven Placement of Experts"): device j owns the experts
+ * [offsets[j], offsets[j+1]) - offsets from hap_round_shards over `experts`, any integer split,
+ * a device may own none - and runs exactly those, all in one grouped launch; no expert is padded in.
+ *   X     [experts x capacity x in_features]   tokens dispatched to each expert (row stride ldx)
+ *   W     [experts x in_features x out_features] (row stride ldw),  bias [experts x out_features]
+ *   Y     [experts x capacity x out_features]  (row stride ldy); preact and dY likewise, dX like X,
+ *         dW like W (dtype dW_dtype), dbias [experts x out_features] fp32
+ * Consecutive experts lie capacity*ldx, in_features*ldw, capacity*ldy, out_features elements apart.
+ * operands_are_full = 1: pointers address expert 0 of the whole layer and the library steps to the
+ * device's first expert; 0: they address the device's first expert (compact per-device buffers).
+ * rows: DEVICE array of int32, one count per expert (indexed like the tensors), of the buffer rows
+ * that hold a token, clamped to [0, capacity]; NULL = every row.  Rows at or beyond the count may
+ * hold anything (NaN included): they influence no result, and the matching rows of Y, preact and dX
+ * are left untouched; an expert with no token gets dW = 0 and dbias = 0.  The counts stay on the
+ * device: no host synchronisation.                                                                */
+typedef struct {
+  int64_t experts, capacity, in_features, out_features;   /* UNSHARDED expert count                  */
+  int m;
+  const int64_t* offsets;   /* host, [m+1] over experts                                              */
+  int io_dtype;             /* hap_dtype of X, W, bias, Y, preact, dY, dX; accumulation is fp32     */
+  int act;                  /* hap_act, applied after the bias                                       */
+  int has_bias;
+  int64_t ldx, ldw, ldy;
+  int operands_are_full;
+} hap_moe_desc;
+
+int hap_moe_linear_fwd(const hap_moe_desc* d, int shard_index, const void* X, const void* W, const void* bias,
+                       const int32_t* rows, void* Y, void* preact, void* stream);
+/* Any of dX, dW, dbias may be NULL to skip it.  ws: hap_moe_linear_bwd_workspace bytes (0 when act is
+ * NONE and dbias is NULL), holds dP = dY * act'(preact) and column-sum partials.                   */
+int hap_moe_linear_bwd(const hap_moe_desc* d, int shard_index, const void* X, const void* W, const void* preact,
+                       const void* dY, const int32_t* rows, void* dX, void* dW, int dW_dtype, float* dbias,
+                       void* ws, size_t ws_bytes, void* stream);
+size_t hap_moe_linear_bwd_workspace(const hap_moe_desc* d, int shard_index);
+
 /* ------------------------------------------------------------------ device: attention slice --- */
 
 /* Softmax attention per (batch, head): S = Q K^T / sqrt(head_dim), P = softmax_keys(S), O = P V;

@@ -57,6 +57,14 @@ class _AttnDesc(C.Structure):
                 ("o_stride_b", C.c_int64), ("o_stride_s", C.c_int64), ("o_stride_h", C.c_int64)]
 
 
+class _MoeDesc(C.Structure):
+    _fields_ = [("experts", C.c_int64), ("capacity", C.c_int64), ("in_features", C.c_int64), ("out_features", C.c_int64),
+                ("m", C.c_int), ("offsets", C.POINTER(C.c_int64)),
+                ("io_dtype", C.c_int), ("act", C.c_int), ("has_bias", C.c_int),
+                ("ldx", C.c_int64), ("ldw", C.c_int64), ("ldy", C.c_int64),
+                ("operands_are_full", C.c_int)]
+
+
 class LinearDesc:
     """Python mirror of hap_linear_desc; keeps the offsets array alive."""
 
@@ -72,6 +80,22 @@ class LinearDesc:
                              ldw if ldw is not None else out_features,
                              ldy if ldy is not None else out_features,
                              int(bool(operands_are_full)))
+
+
+class MoeDesc:
+    """Python mirror of hap_moe_desc; keeps the offsets array (expert ranges of the devices) alive."""
+
+    def __init__(self, experts, capacity, in_features, out_features, offsets: Sequence[int], io_dtype,
+                 act=ACT_NONE, has_bias=False, ldx=None, ldw=None, ldy=None, operands_are_full=True):
+        offsets = list(offsets)
+        self._offs = (C.c_int64 * len(offsets))(*offsets)
+        self.m = len(offsets) - 1
+        self.c = _MoeDesc(experts, capacity, in_features, out_features, self.m, C.cast(self._offs, C.POINTER(C.c_int64)),
+                          io_dtype, act, int(bool(has_bias)),
+                          ldx if ldx is not None else in_features,
+                          ldw if ldw is not None else out_features,
+                          ldy if ldy is not None else out_features,
+                          int(bool(operands_are_full)))
 
 
 class AttnDesc:
@@ -93,7 +117,7 @@ lib.hap_strerror.argtypes = [C.c_int]
 lib.hap_last_error.restype = C.c_char_p
 lib.hap_version.restype = C.c_char_p
 for _n in ("hap_linear_fwd_workspace", "hap_linear_bwd_workspace", "hap_sfb_workspace", "hap_attn_bwd_workspace",
-           "hap_layernorm_bwd_workspace", "hap_colsum_workspace"):
+           "hap_layernorm_bwd_workspace", "hap_colsum_workspace", "hap_moe_linear_bwd_workspace"):
     if hasattr(lib, _n):
         getattr(lib, _n).restype = C.c_size_t
 
@@ -193,6 +217,21 @@ def hap_sfb_grad(Xs, dYs, rows, in_features, out_features, ldx, ldy, in_dtype, d
 
 def hap_sfb_workspace(m, rows, in_features, out_features) -> int:
     return int(lib.hap_sfb_workspace(C.c_int(m), (C.c_int64 * m)(*map(int, rows)), C.c_int64(in_features), C.c_int64(out_features)))
+
+
+def hap_moe_linear_bwd_workspace(desc: MoeDesc, shard_index: int) -> int:
+    return int(lib.hap_moe_linear_bwd_workspace(C.byref(desc.c), C.c_int(shard_index)))
+
+
+def hap_moe_linear_fwd(desc: MoeDesc, shard_index, X, W, bias, rows, Y, preact=None, stream=None):
+    _check(lib.hap_moe_linear_fwd(C.byref(desc.c), C.c_int(shard_index), _ptr(X), _ptr(W), _ptr(bias), _ptr(rows), _ptr(Y),
+                                  _ptr(preact), _stream(stream)), "hap_moe_linear_fwd")
+
+
+def hap_moe_linear_bwd(desc: MoeDesc, shard_index, X, W, preact, dY, rows, dX, dW, dW_dtype, dbias, ws=None, stream=None):
+    wp, wb = _ws(ws)
+    _check(lib.hap_moe_linear_bwd(C.byref(desc.c), C.c_int(shard_index), _ptr(X), _ptr(W), _ptr(preact), _ptr(dY), _ptr(rows),
+                                  _ptr(dX), _ptr(dW), C.c_int(dW_dtype), _ptr(dbias), wp, wb, _stream(stream)), "hap_moe_linear_bwd")
 
 
 def hap_attn_bwd_workspace(desc: AttnDesc, shard_index: int) -> int:

@@ -36,6 +36,16 @@ struct hap_gemm_problem {
   int force_generic;                   /* testing aid: take the scalar fallback kernel            */
   void* ws; size_t ws_bytes;           /* optional device scratch for split-K partial tiles (NULL: never split K)   */
   int tile;                            /* 0: engine chooses (and may split the problem); 128 / 256: fixed output tile */
+  /* Grouped launch: `groups` independent products of the same shape in one launch, group g's operands
+   * g strides further on (the experts of an MoE layer, Sec. 7.6).  Needs nseg == 1; neither strip
+   * splitting nor split-K apply.  group_len (a DEVICE array, one int per group, or NULL) holds the valid
+   * length of the ragged axis per group, clamped to [0, the problem's extent]: group_ragged = 1 bounds M
+   * (rows of A and C beyond it are neither read nor written), 2 bounds the contraction k[0]. */
+  int groups;                          /* 0 or 1: a single product                               */
+  int64_t ga, gb, gbias;               /* strides between groups, in in_dtype elements           */
+  int64_t gc, gp;                      /* ... of C and preact, in c_dtype elements               */
+  const int32_t* group_len;
+  int group_ragged;
 };
 
 /* Validates nothing beyond what the kernels need (callers validate user input); returns hap_status. */

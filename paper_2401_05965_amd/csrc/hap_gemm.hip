@@ -63,8 +63,45 @@ struct GemmArgs {
   void* preact;
   const void* bias;
   int act, accumulate;
+  // Grouped launch: blockIdx.y picks one of `groups` independent products that differ only in their base
+  // addresses (byte strides below) and, when group_len is given, in the valid length of one axis.
+  int ragged;              // 0: every group is M x N x k;  1: group_len bounds M;  2: group_len bounds the contraction (nseg == 1)
+  const int* group_len;    // device array [groups], or nullptr
+  long long ga, gb, gc, gp, gbias;
   SegArg seg[HAP_GEMM_MAX_SEG];
 };
+
+/* What the workgroup's group changes: valid rows, contracted length of the single segment (-1: as in
+ * the segment table), byte offsets of the operands and outputs. */
+struct GroupView {
+  int M, k;
+  long long oa, ob;
+};
+
+__device__ __forceinline__ GroupView group_view(const GemmArgs& args) {
+  GroupView g;
+  const int grp = blockIdx.y;
+  g.M = args.M; g.k = -1;
+  g.oa = grp * args.ga; g.ob = grp * args.gb;
+  if (args.ragged) {
+    int len = __builtin_amdgcn_readfirstlane(args.group_len[grp]);
+    len = len < 0 ? 0 : len;
+    if (args.ragged == 1) g.M = len < args.M ? len : args.M;
+    else g.k = len < args.seg[0].k ? len : args.seg[0].k;
+  }
+  return g;
+}
+
+/* The arguments as the epilogue of this workgroup's group sees them. */
+__device__ __forceinline__ GemmArgs group_outputs(const GemmArgs& args, const GroupView& g) {
+  GemmArgs e = args;
+  const int grp = blockIdx.y;
+  e.M = g.M;
+  e.c = static_cast<char*>(args.c) + grp * args.gc;
+  if (args.preact) e.preact = static_cast<char*>(args.preact) + grp * args.gp;
+  if (args.bias) e.bias = static_cast<const char*>(args.bias) + grp * args.gbias;
+  return e;
+}
 
 /* Values that are the same in every lane but that the compiler cannot prove uniform (they depend on
  * a table entry picked by a loop-carried index) are pinned to scalar registers; otherwise every
@@ -368,7 +405,10 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(const GemmArgs arg
   int tm, tn;
   tile_of_block(out_tile, gridDim.x / ksplit, args.tiles_m, args.tiles_n, &tm, &tn);
   const int m0 = tm * BM, n0 = tn * BN;                 // physical tile origin
-  const int m_lim = args.skewM + args.M, n_lim = args.skewN + args.N;
+  const GroupView gv = group_view(args);
+  const int m_lim = args.skewM + gv.M, n_lim = args.skewN + args.N;
+  if (args.ragged == 1 && (gv.M == 0 || m0 >= m_lim)) return;   // the group's rows end before this tile
+  const int all_tiles = gv.k >= 0 ? (args.skewK + gv.k + BK - 1 >= BK ? (args.skewK + gv.k + BK - 1) / BK : 1) : args.ntiles;
 
   TileLoader<T, AKC, BM, BK, NT> la;
   TileLoader<T, BKC, BN, BK, NT> lb;
@@ -382,8 +422,8 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(const GemmArgs arg
       for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
 
   // this workgroup's range [first, first + ntiles) of the K tiles of all segments laid end to end
-  const int first = (int)((long long)args.ntiles * split / ksplit);
-  int ntiles = (int)((long long)args.ntiles * (split + 1) / ksplit) - first;
+  const int first = (int)((long long)all_tiles * split / ksplit);
+  int ntiles = (int)((long long)all_tiles * (split + 1) / ksplit) - first;
   int seg = 0, skip = first;
   while (seg + 1 < args.nseg) {
     const int in_seg = (args.skewK + args.seg[seg].k + BK - 1) / BK;
@@ -393,9 +433,9 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(const GemmArgs arg
   }
   // loader state runs one tile ahead of the compute
   int k0 = skip * BK;
-  int kend = uni(args.skewK + args.seg[seg].k);
-  __amdgpu_buffer_rsrc_t ra = make_rsrc(args.seg[seg].a, args.seg[seg].a_bytes);
-  __amdgpu_buffer_rsrc_t rb = make_rsrc(args.seg[seg].b, args.seg[seg].b_bytes);
+  int kend = uni(args.skewK + (gv.k >= 0 ? gv.k : args.seg[seg].k));
+  __amdgpu_buffer_rsrc_t ra = make_rsrc(static_cast<const char*>(args.seg[seg].a) + gv.oa, args.seg[seg].a_bytes);
+  __amdgpu_buffer_rsrc_t rb = make_rsrc(static_cast<const char*>(args.seg[seg].b) + gv.ob, args.seg[seg].b_bytes);
 
   auto fetch = [&]() {
     la.load(ra, tid, m0, m_lim, args.lda, k0, args.skewK, kend);
@@ -422,8 +462,8 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(const GemmArgs arg
         k0 = 0;
         seg = uni(seg);
         kend = uni(args.skewK + args.seg[seg].k);
-        ra = make_rsrc(args.seg[seg].a, args.seg[seg].a_bytes);
-        rb = make_rsrc(args.seg[seg].b, args.seg[seg].b_bytes);
+        ra = make_rsrc(static_cast<const char*>(args.seg[seg].a) + gv.oa, args.seg[seg].a_bytes);
+        rb = make_rsrc(static_cast<const char*>(args.seg[seg].b) + gv.ob, args.seg[seg].b_bytes);
       } else {
         more = false;
       }
@@ -457,7 +497,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(const GemmArgs arg
     epilogue<T, float, TM, TN>(pa, acc, wm0, wn0, lane);
     return;
   }
-  epilogue<T, TC, TM, TN>(args, acc, m0 + wm0, n0 + wn0, lane);
+  epilogue<T, TC, TM, TN>(group_outputs(args, gv), acc, m0 + wm0, n0 + wn0, lane);
 }
 
 /* Epilogue of the direct-to-LDS kernels.  Their accumulators are TRANSPOSED tiles (the MFMA is fed
@@ -679,7 +719,10 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_dma_kernel(const GemmArgs
   int tm, tn;
   tile_of_block(out_tile, gridDim.x / ksplit, args.tiles_m, args.tiles_n, &tm, &tn);
   const int m0 = tm * BM, n0 = tn * BN;
-  const int m_lim = args.skewM + args.M, n_lim = args.skewN + args.N;
+  const GroupView gv = group_view(args);
+  const int m_lim = args.skewM + gv.M, n_lim = args.skewN + args.N;
+  if (args.ragged == 1 && (gv.M == 0 || m0 >= m_lim)) return;   // the group's rows end before this tile
+  const int all_tiles = gv.k >= 0 ? (args.skewK + gv.k + BK - 1 >= BK ? (args.skewK + gv.k + BK - 1) / BK : 1) : args.ntiles;
 
   LA la; LB lb;
   la.init(tid, m0, m_lim, args.lda);
@@ -698,8 +741,8 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_dma_kernel(const GemmArgs
       for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
 
   // this workgroup's range [first, first + ntiles) of the K tiles of all segments laid end to end
-  const int first = (int)((long long)args.ntiles * split / ksplit);
-  const int ntiles = (int)((long long)args.ntiles * (split + 1) / ksplit) - first;
+  const int first = (int)((long long)all_tiles * split / ksplit);
+  const int ntiles = (int)((long long)all_tiles * (split + 1) / ksplit) - first;
   int seg0 = 0, skip = first;
   while (seg0 + 1 < args.nseg) {
     const int in_seg = (args.skewK + args.seg[seg0].k + BK - 1) / BK;
@@ -708,9 +751,9 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_dma_kernel(const GemmArgs
     seg0 = uni(seg0 + 1);
   }
   // producer state (runs STAGES-1 tiles ahead of the consumer)
-  int pseg = seg0, pk0 = skip * BK, pkend = uni(args.skewK + args.seg[seg0].k), pslot = 0;
-  __amdgpu_buffer_rsrc_t ra = make_rsrc(args.seg[seg0].a, args.seg[seg0].a_bytes);
-  __amdgpu_buffer_rsrc_t rb = make_rsrc(args.seg[seg0].b, args.seg[seg0].b_bytes);
+  int pseg = seg0, pk0 = skip * BK, pkend = uni(args.skewK + (gv.k >= 0 ? gv.k : args.seg[seg0].k)), pslot = 0;
+  __amdgpu_buffer_rsrc_t ra = make_rsrc(static_cast<const char*>(args.seg[seg0].a) + gv.oa, args.seg[seg0].a_bytes);
+  __amdgpu_buffer_rsrc_t rb = make_rsrc(static_cast<const char*>(args.seg[seg0].b) + gv.ob, args.seg[seg0].b_bytes);
   // consumer state: k range of the tile being consumed (for the edge fix-up)
   int cseg = seg0, ck0 = pk0, ckend = pkend, cslot = 0;
   constexpr int KK = BK / 16;
@@ -723,8 +766,8 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_dma_kernel(const GemmArgs
       pseg = uni(pseg + 1);
       pk0 = 0;
       pkend = uni(args.skewK + args.seg[pseg].k);
-      ra = make_rsrc(args.seg[pseg].a, args.seg[pseg].a_bytes);
-      rb = make_rsrc(args.seg[pseg].b, args.seg[pseg].b_bytes);
+      ra = make_rsrc(static_cast<const char*>(args.seg[pseg].a) + gv.oa, args.seg[pseg].a_bytes);
+      rb = make_rsrc(static_cast<const char*>(args.seg[pseg].b) + gv.ob, args.seg[pseg].b_bytes);
     }
   };
 
@@ -834,7 +877,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_dma_kernel(const GemmArgs
     epilogue_transposed<T, float, TM, TN>(pa, acc, wm0, wn0, lane, smem + wave * (32 * (TN * 32 * 4 + 16)));
     return;
   }
-  epilogue_transposed<T, TC, TM, TN>(args, acc, m0 + wm0, n0 + wn0, lane, smem + wave * (32 * (TN * 32 * (int)sizeof(TC) + 16)));
+  epilogue_transposed<T, TC, TM, TN>(group_outputs(args, gv), acc, m0 + wm0, n0 + wn0, lane, smem + wave * (32 * (TN * 32 * (int)sizeof(TC) + 16)));
 }
 
 /* Split-K reduction: sums the ksplit fp32 partial tiles of every output tile and applies what the
@@ -880,6 +923,9 @@ struct GenericArgs {
   int a_kcontig, b_kcontig;
   void* c; void* preact; const void* bias;
   int act, accumulate;
+  int ragged;                        // as in GemmArgs; blockIdx.z is the group
+  const int* group_len;
+  long long ga, gb, gc, gp, gbias;   // byte strides between groups
   const void* a[HAP_GEMM_MAX_SEG];
   const void* b[HAP_GEMM_MAX_SEG];
   int k[HAP_GEMM_MAX_SEG];
@@ -889,21 +935,26 @@ template <typename T, typename TC>
 __global__ __launch_bounds__(256) void gemm_generic_kernel(const GenericArgs g) {
   const int n = blockIdx.x * 16 + (threadIdx.x & 15);
   const int m = blockIdx.y * 16 + (threadIdx.x >> 4);
-  if (m >= g.M || n >= g.N) return;
+  const int grp = blockIdx.z;
+  int len = g.ragged ? g.group_len[grp] : 0;
+  len = len < 0 ? 0 : len;
+  const int M = g.ragged == 1 && len < g.M ? len : g.M;
+  if (m >= M || n >= g.N) return;
   float acc = 0.0f;
   for (int s = 0; s < g.nseg; ++s) {
-    const T* A = static_cast<const T*>(g.a[s]);
-    const T* B = static_cast<const T*>(g.b[s]);
-    for (int k = 0; k < g.k[s]; ++k) {
+    const T* A = reinterpret_cast<const T*>(static_cast<const char*>(g.a[s]) + grp * g.ga);
+    const T* B = reinterpret_cast<const T*>(static_cast<const char*>(g.b[s]) + grp * g.gb);
+    const int ks = g.ragged == 2 && len < g.k[s] ? len : g.k[s];
+    for (int k = 0; k < ks; ++k) {
       const float av = load_s<T>(g.a_kcontig ? A + (long long)m * g.lda + k : A + (long long)k * g.lda + m);
       const float bv = load_s<T>(g.b_kcontig ? B + (long long)n * g.ldb + k : B + (long long)k * g.ldb + n);
       acc = fmaf(av, bv, acc);
     }
   }
-  if (g.bias) acc += load_s<T>(static_cast<const T*>(g.bias) + n);
-  if (g.preact) store_c<TC>(static_cast<TC*>(g.preact) + (long long)m * g.ldp + n, acc);
+  if (g.bias) acc += load_s<T>(reinterpret_cast<const T*>(static_cast<const char*>(g.bias) + grp * g.gbias) + n);
+  if (g.preact) store_c<TC>(reinterpret_cast<TC*>(static_cast<char*>(g.preact) + grp * g.gp) + (long long)m * g.ldp + n, acc);
   if (g.act == HAP_ACT_GELU_ERF) acc = gelu_erf(acc);
-  TC* dst = static_cast<TC*>(g.c) + (long long)m * g.ldc + n;
+  TC* dst = reinterpret_cast<TC*>(static_cast<char*>(g.c) + grp * g.gc) + (long long)m * g.ldc + n;
   if (g.accumulate) acc += load_s<TC>(dst);
   store_c<TC>(dst, acc);
 }
@@ -938,6 +989,7 @@ Plan make_plan(const hap_gemm_problem* p) {
   if (p->force_generic) return pl;
   const int es = esize(p->in_dtype);
   if ((p->lda * es) % 16 || (p->ldb * es) % 16) return pl;
+  if (p->groups > 1 && ((p->ga * es) % 16 || (p->gb * es) % 16)) return pl;   // every group needs the first one's 16-byte phase
   int sa = -1, sb = -1;
   for (int s = 0; s < p->nseg; ++s) {
     if (p->k[s] == 0) continue;
@@ -960,7 +1012,12 @@ Plan make_plan(const hap_gemm_problem* p) {
   pl.tiled = true;
   if (p->in_dtype == HAP_F32) { pl.bm = pl.bn = 64; pl.name = "f32_64x64x16"; }
   else {
-    const bool big = p->tile ? p->tile == 256 : (p->M + pl.skewM > 128 && p->N + pl.skewN > 128);
+    bool big = p->tile ? p->tile == 256 : (p->M + pl.skewM > 128 && p->N + pl.skewN > 128);
+    if (big && !p->tile && (p->groups > 1 || p->group_len)) {
+      // a grouped launch is neither cut into strips nor split along K: take the small tile when big ones would leave CUs idle
+      const long long g = p->groups > 1 ? p->groups : 1;
+      big = g * ((p->M + pl.skewM + 255) / 256) * ((p->N + pl.skewN + 255) / 256) >= kCUs;
+    }
     pl.bm = pl.bn = big ? 256 : 128;
     pl.dma = dma_variant();
     static const char* names[2][2] = {{"bf16_128x128x64_staged", "bf16_128x128x64_dma2"}, {"bf16_256x256x64_staged", "bf16_256x256x64_dma2"}};
@@ -970,9 +1027,9 @@ Plan make_plan(const hap_gemm_problem* p) {
 }
 
 template <typename T, typename TC, bool AKC, bool BKC, int BM, int BN, int BK, int WGM, int WGN>
-int launch_tiled(const GemmArgs& a, hipStream_t st) {
+int launch_tiled(const GemmArgs& a, int groups, hipStream_t st) {
   const int out_tiles = a.tiles_m * a.tiles_n;
-  hipLaunchKernelGGL((gemm_kernel<T, TC, AKC, BKC, BM, BN, BK, WGM, WGN>), dim3(out_tiles * a.ksplit), dim3(64 * WGM * WGN), 0, st, a);
+  hipLaunchKernelGGL((gemm_kernel<T, TC, AKC, BKC, BM, BN, BK, WGM, WGN>), dim3(out_tiles * a.ksplit, groups), dim3(64 * WGM * WGN), 0, st, a);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return hap_fail(HAP_EDEVICE, "gemm launch: %s", hipGetErrorString(e));
   if (a.ksplit > 1) {
@@ -985,7 +1042,7 @@ int launch_tiled(const GemmArgs& a, hipStream_t st) {
 }
 
 template <typename TC, bool AKC, bool BKC, int BM, int BN, int BK, int STAGES, int WGM, int WGN>
-int launch_dma(const GemmArgs& a, hipStream_t st) {
+int launch_dma(const GemmArgs& a, int groups, hipStream_t st) {
   constexpr size_t smem = (size_t)STAGES * (BM + BN) * BK * 2;
   void (*kernel)(const GemmArgs) = &gemm_dma_kernel<TC, AKC, BKC, BM, BN, BK, WGM, WGN, STAGES>;
   static bool configured = false;     // benign race: the attribute call is idempotent
@@ -996,7 +1053,7 @@ int launch_dma(const GemmArgs& a, hipStream_t st) {
     configured = true;
   }
   const int out_tiles = a.tiles_m * a.tiles_n;
-  hipLaunchKernelGGL(kernel, dim3(out_tiles * a.ksplit), dim3(64 * WGM * WGN), smem, st, a);
+  hipLaunchKernelGGL(kernel, dim3(out_tiles * a.ksplit, groups), dim3(64 * WGM * WGN), smem, st, a);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return hap_fail(HAP_EDEVICE, "gemm launch: %s", hipGetErrorString(e));
   if (a.ksplit > 1) {
@@ -1009,30 +1066,30 @@ int launch_dma(const GemmArgs& a, hipStream_t st) {
 }
 
 template <typename TC, int BM, int BN, int BK, int STAGES, int WGM, int WGN>
-int dispatch_dma(const hap_gemm_problem* p, const GemmArgs& a, hipStream_t st) {
-  if (p->a_kcontig && p->b_kcontig) return launch_dma<TC, true, true, BM, BN, BK, STAGES, WGM, WGN>(a, st);
-  if (p->a_kcontig && !p->b_kcontig) return launch_dma<TC, true, false, BM, BN, BK, STAGES, WGM, WGN>(a, st);
-  if (!p->a_kcontig && !p->b_kcontig) return launch_dma<TC, false, false, BM, BN, BK, STAGES, WGM, WGN>(a, st);
-  return launch_dma<TC, false, true, BM, BN, BK, STAGES, WGM, WGN>(a, st);
+int dispatch_dma(const hap_gemm_problem* p, const GemmArgs& a, int groups, hipStream_t st) {
+  if (p->a_kcontig && p->b_kcontig) return launch_dma<TC, true, true, BM, BN, BK, STAGES, WGM, WGN>(a, groups, st);
+  if (p->a_kcontig && !p->b_kcontig) return launch_dma<TC, true, false, BM, BN, BK, STAGES, WGM, WGN>(a, groups, st);
+  if (!p->a_kcontig && !p->b_kcontig) return launch_dma<TC, false, false, BM, BN, BK, STAGES, WGM, WGN>(a, groups, st);
+  return launch_dma<TC, false, true, BM, BN, BK, STAGES, WGM, WGN>(a, groups, st);
 }
 
 template <typename T, typename TC, int BM, int BN, int BK, int WGM, int WGN>
-int dispatch_layout(const hap_gemm_problem* p, const GemmArgs& a, hipStream_t st) {
-  if (p->a_kcontig && p->b_kcontig) return launch_tiled<T, TC, true, true, BM, BN, BK, WGM, WGN>(a, st);
-  if (p->a_kcontig && !p->b_kcontig) return launch_tiled<T, TC, true, false, BM, BN, BK, WGM, WGN>(a, st);
-  if (!p->a_kcontig && !p->b_kcontig) return launch_tiled<T, TC, false, false, BM, BN, BK, WGM, WGN>(a, st);
-  return launch_tiled<T, TC, false, true, BM, BN, BK, WGM, WGN>(a, st);
+int dispatch_layout(const hap_gemm_problem* p, const GemmArgs& a, int groups, hipStream_t st) {
+  if (p->a_kcontig && p->b_kcontig) return launch_tiled<T, TC, true, true, BM, BN, BK, WGM, WGN>(a, groups, st);
+  if (p->a_kcontig && !p->b_kcontig) return launch_tiled<T, TC, true, false, BM, BN, BK, WGM, WGN>(a, groups, st);
+  if (!p->a_kcontig && !p->b_kcontig) return launch_tiled<T, TC, false, false, BM, BN, BK, WGM, WGN>(a, groups, st);
+  return launch_tiled<T, TC, false, true, BM, BN, BK, WGM, WGN>(a, groups, st);
 }
 
 template <typename T, typename TC>
-int dispatch_tile(const hap_gemm_problem* p, const Plan& pl, const GemmArgs& a, hipStream_t st) {
+int dispatch_tile(const hap_gemm_problem* p, const Plan& pl, const GemmArgs& a, int groups, hipStream_t st) {
   if constexpr (sizeof(T) == 4) {
-    return dispatch_layout<T, TC, 64, 64, 64, 2, 2>(p, a, st);
+    return dispatch_layout<T, TC, 64, 64, 64, 2, 2>(p, a, groups, st);
   } else {
-    if (pl.bm == 256 && pl.dma >= 1) return dispatch_dma<TC, 256, 256, 64, 2, 2, 4>(p, a, st);
-    if (pl.bm == 128 && pl.dma >= 1) return dispatch_dma<TC, 128, 128, 64, 2, 2, 2>(p, a, st);
-    if (pl.bm == 256) return dispatch_layout<T, TC, 256, 256, 64, 2, 4>(p, a, st);
-    return dispatch_layout<T, TC, 128, 128, 64, 2, 2>(p, a, st);
+    if (pl.bm == 256 && pl.dma >= 1) return dispatch_dma<TC, 256, 256, 64, 2, 2, 4>(p, a, groups, st);
+    if (pl.bm == 128 && pl.dma >= 1) return dispatch_dma<TC, 128, 128, 64, 2, 2, 2>(p, a, groups, st);
+    if (pl.bm == 256) return dispatch_layout<T, TC, 256, 256, 64, 2, 4>(p, a, groups, st);
+    return dispatch_layout<T, TC, 128, 128, 64, 2, 2>(p, a, groups, st);
   }
 }
 
@@ -1148,12 +1205,21 @@ int hap_gemm_run(const hap_gemm_problem* p, void* stream) {
   if (p->M > 0x7fffffff || p->N > 0x7fffffff) return hap_fail(HAP_EUNSUPPORTED, "GEMM extent exceeds 2^31");
   if (p->accumulate && p->c_dtype != HAP_F32) return hap_fail(HAP_EINVAL, "accumulate needs an fp32 output");
   if (p->in_dtype == HAP_F32 && p->c_dtype != HAP_F32) return hap_fail(HAP_EUNSUPPORTED, "fp32 inputs need fp32 output");
-  const int es = esize(p->in_dtype);
+  const int es = esize(p->in_dtype), ces_out = esize(p->c_dtype);
+  const int groups = p->groups > 1 ? p->groups : 1;
+  const bool grouped = groups > 1 || p->group_len;
+  if (grouped) {
+    if (p->nseg != 1) return hap_fail(HAP_EINVAL, "a grouped product has one contracted segment");
+    if (groups > 65535) return hap_fail(HAP_EUNSUPPORTED, "more than 65535 groups");
+    if (p->group_len && p->group_ragged != 1 && p->group_ragged != 2) return hap_fail(HAP_EINVAL, "group_len needs group_ragged 1 or 2");
+    if (p->k[0] > 0x7fffffff) return hap_fail(HAP_EUNSUPPORTED, "segment longer than 2^31");
+  }
+  const int ragged = p->group_len ? p->group_ragged : 0;
   const Plan pl = make_plan(p);
   static const bool split_ok = !(getenv("HAP_GEMM_SPLIT") && !strcmp(getenv("HAP_GEMM_SPLIT"), "0"));   // tuning aid
   static const int forced_tile = getenv("HAP_GEMM_TILE") ? atoi(getenv("HAP_GEMM_TILE")) : 0;             // tuning aid
-  if (forced_tile && p->tile == 0 && pl.tiled && pl.dma) { hap_gemm_problem q = *p; q.tile = forced_tile; return hap_gemm_run(&q, stream); }
-  if (pl.tiled && pl.dma && p->tile == 0 && pl.bm == 256 && split_ok) return run_auto_tiled(p, pl, stream);
+  if (forced_tile && p->tile == 0 && pl.tiled && pl.dma && !grouped) { hap_gemm_problem q = *p; q.tile = forced_tile; return hap_gemm_run(&q, stream); }
+  if (pl.tiled && pl.dma && p->tile == 0 && pl.bm == 256 && split_ok && !grouped) return run_auto_tiled(p, pl, stream);
 
   if (!pl.tiled) {
     GenericArgs g;
@@ -1161,12 +1227,14 @@ int hap_gemm_run(const hap_gemm_problem* p, void* stream) {
     g.lda = p->lda; g.ldb = p->ldb; g.ldc = p->ldc; g.ldp = p->ldp;
     g.a_kcontig = p->a_kcontig; g.b_kcontig = p->b_kcontig;
     g.c = p->c; g.preact = p->preact; g.bias = p->bias; g.act = p->act; g.accumulate = p->accumulate;
+    g.ragged = ragged; g.group_len = p->group_len;
+    g.ga = p->ga * es; g.gb = p->gb * es; g.gc = p->gc * ces_out; g.gp = p->gp * ces_out; g.gbias = p->gbias * es;
     for (int s = 0; s < p->nseg; ++s) {
       if (p->k[s] <= 0) continue;
       if (p->k[s] > 0x7fffffff) return hap_fail(HAP_EUNSUPPORTED, "segment longer than 2^31");
       g.a[g.nseg] = p->a[s]; g.b[g.nseg] = p->b[s]; g.k[g.nseg] = (int)p->k[s]; ++g.nseg;
     }
-    dim3 grid((unsigned)((p->N + 15) / 16), (unsigned)((p->M + 15) / 16));
+    dim3 grid((unsigned)((p->N + 15) / 16), (unsigned)((p->M + 15) / 16), (unsigned)groups);
     if (grid.y > 65535u) return hap_fail(HAP_EUNSUPPORTED, "generic GEMM fallback: too many rows");
     if (p->in_dtype == HAP_BF16 && p->c_dtype == HAP_BF16) hipLaunchKernelGGL((gemm_generic_kernel<__bf16, __bf16>), grid, dim3(256), 0, st, g);
     else if (p->in_dtype == HAP_BF16) hipLaunchKernelGGL((gemm_generic_kernel<__bf16, float>), grid, dim3(256), 0, st, g);
@@ -1181,6 +1249,8 @@ int hap_gemm_run(const hap_gemm_problem* p, void* stream) {
   a.skewM = pl.skewM; a.skewN = pl.skewN; a.skewK = pl.skewK;
   a.lda = p->lda; a.ldb = p->ldb; a.ldc = p->ldc; a.ldp = p->ldp;
   a.c = p->c; a.preact = p->preact; a.bias = p->bias; a.act = p->act; a.accumulate = p->accumulate;
+  a.ragged = ragged; a.group_len = p->group_len;
+  a.ga = p->ga * es; a.gb = p->gb * es; a.gc = p->gc * ces_out; a.gp = p->gp * ces_out; a.gbias = p->gbias * es;
   a.tiles_m = (int)((p->M + pl.skewM + pl.bm - 1) / pl.bm);
   a.tiles_n = (int)((p->N + pl.skewN + pl.bn - 1) / pl.bn);
   a.nseg = 0;
@@ -1207,7 +1277,8 @@ int hap_gemm_run(const hap_gemm_problem* p, void* stream) {
   {
     const int ces = esize(p->c_dtype), cepc = 16 / ces;
     a.vec_store = pl.skewN == 0 && ((uintptr_t)p->c % 16) == 0 && p->ldc % cepc == 0 &&
-                  (!p->preact || (((uintptr_t)p->preact % 16) == 0 && p->ldp % cepc == 0));
+                  (!p->preact || (((uintptr_t)p->preact % 16) == 0 && p->ldp % cepc == 0)) &&
+                  (groups == 1 || (p->gc % cepc == 0 && (!p->preact || p->gp % cepc == 0)));
   }
   a.ntiles = 0;
   a.ksplit = 1;
@@ -1217,7 +1288,7 @@ int hap_gemm_run(const hap_gemm_problem* p, void* stream) {
     for (int s = 0; s < a.nseg; ++s) a.ntiles += (pl.skewK + a.seg[s].k + bk - 1) / bk;
     if (a.ntiles == 0) a.ntiles = 1;     // empty contraction still runs one (all-zero) tile
   }
-  if (pl.dma || p->in_dtype == HAP_F32) {
+  if ((pl.dma || p->in_dtype == HAP_F32) && !grouped) {
     // Split-K when the output tiles cannot occupy the chip: spread each tile's K range over the idle CUs,
     // keeping at least 4 K tiles per workgroup (2 for the small fp32 tiles, whose loop is bound by one load
     // latency per tile), as far as the caller's workspace allows.
@@ -1234,7 +1305,7 @@ int hap_gemm_run(const hap_gemm_problem* p, void* stream) {
       a.partial = static_cast<float*>(p->ws);
     }
   }
-  if (p->in_dtype == HAP_BF16 && p->c_dtype == HAP_BF16) return dispatch_tile<__bf16, __bf16>(p, pl, a, st);
-  if (p->in_dtype == HAP_BF16) return dispatch_tile<__bf16, float>(p, pl, a, st);
-  return dispatch_tile<float, float>(p, pl, a, st);
+  if (p->in_dtype == HAP_BF16 && p->c_dtype == HAP_BF16) return dispatch_tile<__bf16, __bf16>(p, pl, a, groups, st);
+  if (p->in_dtype == HAP_BF16) return dispatch_tile<__bf16, float>(p, pl, a, groups, st);
+  return dispatch_tile<float, float>(p, pl, a, groups, st);
 }

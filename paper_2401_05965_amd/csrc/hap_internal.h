@@ -16,6 +16,13 @@ void hap_clear_error(void);
  * half-open range of device j in lo and hi.  Returns HAP_OK or an error already recorded. */
 int hap_shard_range(int m, const int64_t* offsets, int64_t dim_len, int j, int64_t* lo, int64_t* hi);
 
+/* Column sums of `groups` matrices [rows x cols] (ld = lda) that lie group_stride elements apart; group g sums only
+ * its first group_len[g] rows (group_len: DEVICE array clamped to [0, rows], or NULL = all rows) into out[g*ldo + c].
+ * Does not clear the error state (hap_colsum is the public entry). */
+size_t hap_colsum_grouped_workspace(int groups, int64_t rows, int64_t cols);
+int hap_colsum_grouped(int groups, int64_t rows, int64_t cols, int io_dtype, const void* a, int64_t lda, int64_t group_stride,
+                       const int32_t* group_len, float* out, int64_t ldo, void* ws, size_t ws_bytes, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

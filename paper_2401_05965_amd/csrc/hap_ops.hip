@@ -82,9 +82,16 @@ __global__ __launch_bounds__(256) void add_kernel(int64_t rows, int64_t cols, co
  * their partials meet in LDS.  partial[by][col] is fp32. */
 template <typename T, int V>
 __global__ __launch_bounds__(256) void colsum_partial_kernel(int64_t rows, int64_t cols, const T* a, int64_t lda, int skew,
-                                                             int64_t rpb, float* partial) {
+                                                             int64_t rpb, float* partial, int64_t group_stride, const int* group_len) {
   __shared__ float red[4][64 * V];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  // blockIdx.z: one of several matrices group_stride elements apart, each with its own count of valid rows
+  a += blockIdx.z * group_stride;
+  partial += (int64_t)blockIdx.z * gridDim.y * cols;
+  if (group_len) {
+    const int64_t len = group_len[blockIdx.z];
+    rows = len < 0 ? 0 : (len < rows ? len : rows);
+  }
   const int64_t c0 = ((int64_t)blockIdx.x * 64 + lane) * V - skew;
   const int64_t r0 = (int64_t)blockIdx.y * rpb;
   const int64_t r1 = r0 + rpb < rows ? r0 + rpb : rows;
@@ -120,9 +127,11 @@ __global__ __launch_bounds__(256) void colsum_partial_kernel(int64_t rows, int64
 
 /* Stage 2: out[c] = sum over nparts of partial[p][c].  A block owns 16 columns; its 16 thread groups
  * walk the partial rows 16 apart and meet in LDS. */
-__global__ __launch_bounds__(256) void colsum_final_kernel(int64_t cols, int nparts, const float* partial, float* out) {
+__global__ __launch_bounds__(256) void colsum_final_kernel(int64_t cols, int nparts, const float* partial, float* out, int64_t ldo) {
   __shared__ float red[16][17];
   const int tx = threadIdx.x & 15, ty = threadIdx.x >> 4;
+  partial += (int64_t)blockIdx.y * nparts * cols;     // blockIdx.y: group
+  out += blockIdx.y * ldo;
   const int64_t c = (int64_t)blockIdx.x * 16 + tx;
   float a = 0.0f;
   if (c < cols)
@@ -420,38 +429,51 @@ size_t hap_colsum_workspace(int64_t rows, int64_t cols) {
 int hap_colsum(int64_t rows, int64_t cols, int io_dtype, const void* a, int64_t lda, float* out,
                void* ws, size_t ws_bytes, void* stream) {
   hap_clear_error();
-  if (rows < 0 || cols < 0) return hap_fail(HAP_EINVAL, "negative size");
-  if (cols == 0) return HAP_OK;
+  return hap_colsum_grouped(1, rows, cols, io_dtype, a, lda, 0, NULL, out, cols, ws, ws_bytes, stream);
+}
+
+size_t hap_colsum_grouped_workspace(int groups, int64_t rows, int64_t cols) {
+  return (size_t)(groups > 1 ? groups : 1) * hap_colsum_workspace(rows, cols);
+}
+
+int hap_colsum_grouped(int groups, int64_t rows, int64_t cols, int io_dtype, const void* a, int64_t lda, int64_t group_stride,
+                       const int32_t* group_len, float* out, int64_t ldo, void* ws, size_t ws_bytes, void* stream) {
+  if (rows < 0 || cols < 0 || groups < 0) return hap_fail(HAP_EINVAL, "negative size");
+  if (cols == 0 || groups == 0) return HAP_OK;
+  if (groups > 65535) return hap_fail(HAP_EUNSUPPORTED, "more than 65535 groups");
   if (!out) return hap_fail(HAP_EINVAL, "NULL output");
+  if (ldo < cols) return hap_fail(HAP_ESHAPE, "output stride below cols");
   hipStream_t s = (hipStream_t)stream;
-  if (rows == 0) {   // empty sum
-    hipLaunchKernelGGL(colsum_final_kernel, dim3((unsigned)((cols + 15) / 16)), dim3(256), 0, s, cols, 0, (const float*)out, out);
+  const dim3 fgrid((unsigned)((cols + 15) / 16), (unsigned)groups);
+  if (rows == 0) {   // empty sums
+    hipLaunchKernelGGL(colsum_final_kernel, fgrid, dim3(256), 0, s, cols, 0, (const float*)out, out, ldo);
     return check_launch("colsum");
   }
   if (!a) return hap_fail(HAP_EINVAL, "NULL input");
   if (lda < cols) return hap_fail(HAP_ESHAPE, "leading dimension below cols");
   if (io_dtype != HAP_BF16 && io_dtype != HAP_F32) return hap_fail(HAP_EINVAL, "bad dtype %d", io_dtype);
-  const size_t need = hap_colsum_workspace(rows, cols);
+  const size_t need = hap_colsum_grouped_workspace(groups, rows, cols);
   if (!ws || ws_bytes < need) return hap_fail(HAP_EWORKSPACE, "colsum needs %zu workspace bytes", need);
   const int64_t parts = (rows + kColsumRowsPerBlock - 1) / kColsumRowsPerBlock;
   if (parts > 65535) return hap_fail(HAP_EUNSUPPORTED, "colsum over more than 65535 * 64 rows");
   const int esz = io_dtype == HAP_BF16 ? 2 : 4, V = 16 / esz;
-  const bool vec = (uintptr_t)a % esz == 0 && lda % V == 0;
+  const bool vec = (uintptr_t)a % esz == 0 && lda % V == 0 && (groups == 1 || group_stride % V == 0);
   const int skew = vec ? (int)(((uintptr_t)a % 16) / esz) : 0;
   const char* base = static_cast<const char*>(a) - (size_t)skew * esz;
   const int64_t per_block = vec ? 64 * V : 64;
-  const dim3 grid((unsigned)((cols + skew + per_block - 1) / per_block), (unsigned)parts);
+  const dim3 grid((unsigned)((cols + skew + per_block - 1) / per_block), (unsigned)parts, (unsigned)groups);
   const int64_t rpb = kColsumRowsPerBlock;
+  const int* gl = group_len;
   if (io_dtype == HAP_BF16) {
-    if (vec) hipLaunchKernelGGL((colsum_partial_kernel<__bf16, 8>), grid, dim3(256), 0, s, rows, cols, (const __bf16*)base, lda, skew, rpb, (float*)ws);
-    else hipLaunchKernelGGL((colsum_partial_kernel<__bf16, 1>), grid, dim3(256), 0, s, rows, cols, (const __bf16*)a, lda, 0, rpb, (float*)ws);
+    if (vec) hipLaunchKernelGGL((colsum_partial_kernel<__bf16, 8>), grid, dim3(256), 0, s, rows, cols, (const __bf16*)base, lda, skew, rpb, (float*)ws, group_stride, gl);
+    else hipLaunchKernelGGL((colsum_partial_kernel<__bf16, 1>), grid, dim3(256), 0, s, rows, cols, (const __bf16*)a, lda, 0, rpb, (float*)ws, group_stride, gl);
   } else {
-    if (vec) hipLaunchKernelGGL((colsum_partial_kernel<float, 4>), grid, dim3(256), 0, s, rows, cols, (const float*)base, lda, skew, rpb, (float*)ws);
-    else hipLaunchKernelGGL((colsum_partial_kernel<float, 1>), grid, dim3(256), 0, s, rows, cols, (const float*)a, lda, 0, rpb, (float*)ws);
+    if (vec) hipLaunchKernelGGL((colsum_partial_kernel<float, 4>), grid, dim3(256), 0, s, rows, cols, (const float*)base, lda, skew, rpb, (float*)ws, group_stride, gl);
+    else hipLaunchKernelGGL((colsum_partial_kernel<float, 1>), grid, dim3(256), 0, s, rows, cols, (const float*)a, lda, 0, rpb, (float*)ws, group_stride, gl);
   }
   int rc = check_launch("colsum_partial");
   if (rc) return rc;
-  hipLaunchKernelGGL(colsum_final_kernel, dim3((unsigned)((cols + 15) / 16)), dim3(256), 0, s, cols, (int)parts, (const float*)ws, out);
+  hipLaunchKernelGGL(colsum_final_kernel, fgrid, dim3(256), 0, s, cols, (int)parts, (const float*)ws, out, ldo);
   return check_launch("colsum_final");
 }
 

@@ -118,3 +118,27 @@ def test_host_side_argument_errors(hap):
     assert hap.lib.hap_sfb_grad(1, ptrs, ptrs, rows, C.c_int64(8), C.c_int64(8), C.c_int64(8), C.c_int64(8), 1, one, C.c_int64(8), 0, z, C.c_size_t(0), z) == 1
     assert hap.lib.hap_sfb_grad(65, ptrs, ptrs, rows, C.c_int64(8), C.c_int64(8), C.c_int64(8), C.c_int64(8), 1, one, C.c_int64(8), 0, z, C.c_size_t(0), z) == 1
     assert hap.lib.hap_strerror(5) == b"workspace missing or too small"
+
+
+def test_moe_host_side_argument_errors(hap):
+    """Expert-sharded layer (Sec. 7.6): descriptor and pointer checks happen before any launch."""
+    z = C.c_void_p(0)
+    fwd = lambda d, j: hap.lib.hap_moe_linear_fwd(C.byref(d.c), j, z, z, z, z, z, z, z)
+    d = hap.MoeDesc(7, 16, 8, 8, [0, 3, 5, 6, 8], hap.BF16)
+    assert fwd(d, 0) == 2                                                   # expert ranges do not end at the expert count
+    d = hap.MoeDesc(7, 16, 8, 8, [0, 3, 5, 6, 7], hap.BF16)
+    assert fwd(d, 4) == 1                                                   # device index out of range
+    assert fwd(d, 1) == 1 and b"NULL" in hap.lib.hap_last_error()           # NULL tensors
+    d = hap.MoeDesc(7, 16, 8, 8, [0, 3, 5, 7, 7], hap.BF16)
+    assert fwd(d, 3) == 0                                                   # a device without experts: OK, no launch
+    assert hap.hap_moe_linear_bwd_workspace(d, 3) == 0
+    d = hap.MoeDesc(7, 16, 8, 8, [0, 3, 5, 6, 7], hap.BF16, ldy=4)
+    assert fwd(d, 0) == 2                                                   # ld below width
+    d = hap.MoeDesc(7, 16, 8, 8, [0, 3, 5, 6, 7], hap.BF16, act=hap.ACT_GELU_ERF, has_bias=True)
+    one = C.c_void_p(256)
+    assert hap.lib.hap_moe_linear_fwd(C.byref(d.c), 0, one, one, z, z, one, z, z) == 1            # has_bias without a bias pointer
+    need = hap.hap_moe_linear_bwd_workspace(d, 0)
+    assert need >= 3 * 16 * 8 * 2
+    assert hap.lib.hap_moe_linear_bwd(C.byref(d.c), 0, one, one, one, one, z, one, one, 1, z, z, C.c_size_t(0), z) == 5   # workspace missing
+    assert hap.lib.hap_moe_linear_bwd(C.byref(d.c), 0, one, one, z, one, z, one, one, 1, z, one, C.c_size_t(need), z) == 1  # no saved pre-activation
+    assert hap.lib.hap_moe_linear_bwd(C.byref(d.c), 0, one, one, one, one, z, one, one, 7, z, one, C.c_size_t(need), z) == 1  # bad dW dtype
