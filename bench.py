@@ -43,7 +43,7 @@ def main():
     import hapgen
     from hapgen import TensorId as T
     import paper_2401_05965_amd as hap
-    from paper_2401_05965_amd.programs import EncoderShard, MlpShard, SfbRebuild
+    from paper_2401_05965_amd.programs import EncoderShard, MlpShard, MoeExpertShard, SfbRebuild
 
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
@@ -223,6 +223,30 @@ def main():
         res["cfg4_layer_fwd_bwd_device0_5heads_ffn2731"] = layer("tensor", 0, *c4)
         res["cfg4_layer_fwd_bwd_device2_3heads_ffn1365"] = layer("tensor", 2, *c4)
         res["cfg5_layer_fwd_bwd_device0_79samples"] = layer("data", 0, 256, 197, 1024, 16, 64, 4096, [0, 16], [0, 4096], [0, 79, 142, 205, 236, 256])
+        # MoE feed-forward layer with 30 experts on 4 devices of speeds (1, 1, .5, .5): the LP + rounding places (10, 10, 5, 5);
+        # an even split has to pad to 32 experts, 8 per device.  One device's forward + backward, all expert buffers full.
+        wm = hapgen.WORKLOADS["moe_experts_bf16"]
+        Em, Cm, Hm, Fm = (wm.dims[k] for k in ("experts", "capacity", "hidden", "ffn"))
+        rm, _ = hap.hap_shard_ratios(list(wm.speeds), [(1.0, 0.0, 0.0, 0.0)])
+        msizes, moffs = hap.hap_round_shards(rm, Em, 1)
+        genm = torch.Generator(device=dev); genm.manual_seed(5)
+        rnd = lambda shp, sg: (torch.randn(shp, generator=genm, device=dev) * sg).to(torch.bfloat16)
+        nmax = max(max(msizes), (Em + len(msizes) - 1) // len(msizes))
+        mX, mdO = rnd((nmax, Cm, Hm), 1.0), rnd((nmax, Cm, Hm), 1.0)
+        mW1, mb1, mW2, mb2 = rnd((nmax, Hm, Fm), 0.02), rnd((nmax, Fm), 0.02), rnd((nmax, Fm, Hm), 0.02), rnd((nmax, Hm), 0.02)
+
+        def moe_row(n, rows):
+            sh = MoeExpertShard(n, Cm, Hm, Fm, [0, n], 0, mX, mW1, mb1, mW2, mb2, rows, mdO)
+            t = timeit(lambda: (sh.forward(), sh.backward()), n=10)
+            f, b = sh.flops(None if rows is None else rows[:n].tolist())
+            return {"experts": n, "ms": round(t * 1e3, 3), "gflop": round((f + b) / 1e9, 1), "tflops": round((f + b) / t / 1e12, 1)}
+        res["moe_expert_placement"] = msizes
+        res["moe_ffn_fwd_bwd_device0"] = moe_row(msizes[0], None)
+        res["moe_ffn_fwd_bwd_device2"] = moe_row(msizes[2], None)
+        res["moe_ffn_fwd_bwd_even_split_padded_to_32"] = moe_row((Em + len(msizes) - 1) // len(msizes), None)
+        ragged = torch.randint(Cm // 2, Cm + 1, (nmax,), generator=genm, device=dev, dtype=torch.int32)
+        res["moe_ffn_fwd_bwd_device0_ragged_tokens"] = moe_row(msizes[0], ragged)
+        del mX, mdO, mW1, mW2
         # config 3 the naive way (Fig. "sfb"(b)): every device's own fp32 dW_i, then their sum (what the All-Reduce delivers)
         inf, outf = w3.dims["in_features"], w3.dims["out_features"]
         parts = [torch.zeros((inf, outf), dtype=torch.float32, device=dev) for _ in rows]

@@ -47,4 +47,9 @@ WORKLOADS = {
         "cfg5_vit_bf16", "bf16", (1.0, 0.8, 0.8, 0.4, 0.25),
         dict(batch=256, seq=197, hidden=1024, heads=16, head_dim=64, ffn=4096),
         note="ViT-L-style layer, batch sharded for attention block, ffn sharded for MLP"),
+    "moe_experts_bf16": Workload(
+        "moe_experts_bf16", "bf16", (1.0, 1.0, 0.5, 0.5),
+        dict(experts=30, capacity=2048, hidden=768, ffn=3072),
+        note="BERT-Base-sized MoE feed-forward layer, 30 experts (not a multiple of the 4 devices) placed by the LP + rounding; "
+             "every expert buffer holds `capacity` tokens (tokens proportional to experts)"),
 }

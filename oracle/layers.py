@@ -36,6 +36,18 @@ def mlp_block(X, W1, b1, W2, b2, dOut):
     return dict(pre=pre, H=H, out=out, dH=dH, dP=dP, dX=dX, dW1=dW1, db1=db1, dW2=dW2, db2=db2)
 
 
+
+def moe_ffn_block(X, W1, b1, W2, b2, dOut, rows=None):
+    """Expert feed-forward layer of an MoE block (Sec. 7.6): per expert e, on its rows[e] tokens,
+    H_e = gelu(X_e W1_e + b1_e), Out_e = H_e W2_e + b2_e, and the gradients of L = sum(Out * dOut).
+    X, dOut [E x C x hidden]; W1 [E x hidden x ffn]; W2 [E x ffn x hidden]; biases [E x ffn], [E x hidden]."""
+    from . import moe
+    H, pre = moe.moe_linear_fwd(X, W1, b1, rows, act=True)
+    out, _ = moe.moe_linear_fwd(H, W2, b2, rows, act=False)
+    dH, dW2, db2 = moe.moe_linear_bwd(H, W2, None, dOut, rows, act=False)
+    dX, dW1, db1 = moe.moe_linear_bwd(X, W1, pre, dH, rows, act=True)
+    return dict(pre=pre, H=H, out=out, dH=dH, dX=dX, dW1=dW1, db1=db1, dW2=dW2, db2=db2)
+
 def _split_heads(t, batch, seq, heads, d):
     return t.reshape(batch, seq, heads, d).transpose(0, 2, 1, 3)
 

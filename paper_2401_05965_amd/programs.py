@@ -80,6 +80,57 @@ class MlpShard:
                                                                    self.io, self.db1, self.ws))
 
 
+
+class MoeExpertShard:
+    """Device j's experts of an MoE feed-forward layer (Sec. 7.6): for each expert e the device owns,
+
+        H_e = gelu(X_e W1_e + b1_e);   Out_e = H_e W2_e + b2_e        on the rows[e] tokens dispatched to e
+
+    Expert parallelism shards the expert axis, so nothing is summed across devices: the device's
+    outputs and gradients are exact slices.  Buffers are the device's compact [experts_j x ...] slices;
+    `rows` (int32, on the device) holds the token count of every expert buffer.
+    """
+
+    def __init__(self, experts, capacity, hidden, ffn, offsets, j, X, W1, b1, W2, b2, rows, dOut, dtype=torch.bfloat16):
+        self.j, self.C, self.h, self.f = j, capacity, hidden, ffn
+        lo, hi = offsets[j], offsets[j + 1]
+        self.n = n = hi - lo
+        dev = X.device
+        io = self.io = hap.BF16 if dtype == torch.bfloat16 else hap.F32
+        sl = slice(lo, hi)
+        self.X, self.dOut = X[sl].contiguous(), dOut[sl].contiguous()
+        self.W1, self.b1, self.W2, self.b2 = W1[sl].contiguous(), b1[sl].contiguous(), W2[sl].contiguous(), b2[sl].contiguous()
+        self.rows = rows[sl].contiguous() if rows is not None else None
+        z = lambda *shape: torch.zeros(shape, dtype=dtype, device=dev)
+        m = max(n, 1)
+        self.H, self.pre, self.dH = z(m, capacity, ffn), z(m, capacity, ffn), z(m, capacity, ffn)
+        self.Out, self.dX = z(m, capacity, hidden), z(m, capacity, hidden)
+        self.dW1, self.dW2 = z(m, hidden, ffn), z(m, ffn, hidden)
+        self.db1 = torch.zeros((m, ffn), dtype=torch.float32, device=dev)
+        self.db2 = torch.zeros((m, hidden), dtype=torch.float32, device=dev)
+        self.fc1 = hap.MoeDesc(experts, capacity, hidden, ffn, offsets, io, act=hap.ACT_GELU_ERF, has_bias=True, operands_are_full=False)
+        self.fc2 = hap.MoeDesc(experts, capacity, ffn, hidden, offsets, io, has_bias=True, operands_are_full=False)
+        nws = max(hap.hap_moe_linear_bwd_workspace(self.fc1, j), hap.hap_moe_linear_bwd_workspace(self.fc2, j), 256)
+        self.ws = torch.empty((nws,), dtype=torch.uint8, device=dev)
+
+    def flops(self, rows_host=None):
+        """Algorithmic flops of (fwd, bwd) over the tokens actually held: 2 GEMMs forward, 4 backward, 2*M*N*K each."""
+        tokens = float(sum(rows_host)) if rows_host is not None else float(self.n * self.C)
+        g = 2.0 * tokens * self.h * self.f
+        return 2 * g, 4 * g
+
+    def forward(self, timer=None):
+        j = self.j
+        _call(timer, "moe_fc1_fwd", lambda: hap.hap_moe_linear_fwd(self.fc1, j, self.X, self.W1, self.b1, self.rows, self.H, self.pre))
+        _call(timer, "moe_fc2_fwd", lambda: hap.hap_moe_linear_fwd(self.fc2, j, self.H, self.W2, self.b2, self.rows, self.Out, None))
+
+    def backward(self, timer=None):
+        j = self.j
+        _call(timer, "moe_fc2_bwd", lambda: hap.hap_moe_linear_bwd(self.fc2, j, self.H, self.W2, None, self.dOut, self.rows, self.dH, self.dW2,
+                                                                   self.io, self.db2, self.ws))
+        _call(timer, "moe_fc1_bwd", lambda: hap.hap_moe_linear_bwd(self.fc1, j, self.X, self.W1, self.pre, self.dH, self.rows, self.dX, self.dW1,
+                                                                   self.io, self.db1, self.ws))
+
 class SfbRebuild:
     """dW = sum_i X_i^T dY_i over m devices' gathered factors held in padded-capacity buffers."""
 

@@ -153,3 +153,30 @@ def test_moe_single_expert_device_equals_linear_layer(hap):
     hap.hap_sharded_linear_fwd(ld, 0, Xd, Wd, bd, Y2, P2)
     torch.cuda.synchronize()
     assert torch.equal(Y[0], Y2) and torch.equal(P[0], P2)
+
+
+def test_moe_expert_ffn_block_uneven_devices(hap):
+    """Whole expert feed-forward block (fc1 + GeLU + fc2, forward and backward) for 11 experts placed (4, 4, 2, 1) on devices of
+    speeds (1, 1, 0.5, 0.3): every device's slice against the unsharded oracle block."""
+    from oracle import layers as olay
+    from paper_2401_05965_amd.programs import MoeExpertShard
+    torch = torch_mod()
+    E, C, Hd, F = 11, 200, 192, 456
+    sizes, offs = expert_offsets(hap, (1.0, 1.0, 0.5, 0.3), E)
+    assert sizes == [4, 4, 2, 1]
+    Xh, Xd = gen(6, T.X, (E, C, Hd), 1.0, "bf16"); dOh, dOd = gen(6, T.DY, (E, C, Hd), 1.0, "bf16")
+    W1h, W1d = gen(6, T.W, (E, Hd, F), 0.05, "bf16"); b1h, b1d = gen(6, T.BIAS, (E, F), 0.1, "bf16")
+    W2h, W2d = gen(6, T.W2, (E, F, Hd), 0.05, "bf16"); b2h, b2d = gen(6, T.BETA, (E, Hd), 0.1, "bf16")
+    rows = np.array([200, 150, 0, 200, 37, 128, 129, 64, 199, 1, 200])
+    rows_d = torch.from_numpy(rows.astype(np.int32)).cuda()
+    ref = olay.moe_ffn_block(Xh, W1h, b1h, W2h, b2h, dOh, rows)
+    live = np.arange(C)[None, :] < rows[:, None]
+    for j in range(4):
+        s = slice(offs[j], offs[j + 1])
+        sh = MoeExpertShard(E, C, Hd, F, offs, j, Xd, W1d, b1d, W2d, b2d, rows_d, dOd)
+        sh.forward(); sh.backward()
+        lv = live[s]
+        for name, t in (("H", sh.H), ("out", sh.Out), ("dH", sh.dH), ("dX", sh.dX)):
+            check(f"{name} dev{j}", host(t)[lv], ref[name][s][lv], "bf16")
+        for name, t in (("dW1", sh.dW1), ("db1", sh.db1), ("dW2", sh.dW2), ("db2", sh.db2)):
+            check(f"{name} dev{j}", host(t), ref[name][s], "bf16")

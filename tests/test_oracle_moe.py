@@ -131,3 +131,28 @@ def test_padded_expert_changes_nothing_and_full_capacity_default():
     assert np.array_equal(dXp[:3], dX) and np.array_equal(dWp[:3], dW) and not dWp[3].any() and not dbp[3].any()
     with pytest.raises(ValueError):
         moe.moe_linear_fwd(X, W, b, [8, 0, 0])
+
+
+def test_expert_ffn_block_is_one_mlp_block_per_expert():
+    """The two-layer expert block composes the per-expert layers: each expert equals the (separately pinned) dense MLP
+    block on its own tokens, and the block's dX matches finite differences through both layers."""
+    from oracle import layers
+    E, C, Hd, F = 4, 6, 5, 7
+    X = hapgen.normal(2, T.X, (E, C, Hd)); dOut = hapgen.normal(2, T.DY, (E, C, Hd))
+    W1 = hapgen.normal(2, T.W, (E, Hd, F), 0.4); b1 = hapgen.normal(2, T.BIAS, (E, F), 0.3)
+    W2 = hapgen.normal(2, T.W2, (E, F, Hd), 0.4); b2 = hapgen.normal(2, T.BETA, (E, Hd), 0.3)
+    rows = [6, 0, 3, 5]
+    r = layers.moe_ffn_block(X, W1, b1, W2, b2, dOut, rows)
+    for e in range(E):
+        n = rows[e]
+        ref = layers.mlp_block(X[e, :n], W1[e], b1[e], W2[e], b2[e], dOut[e, :n])
+        for k in ("pre", "H", "out", "dH", "dX"):
+            np.testing.assert_allclose(r[k][e, :n], ref[k], rtol=1e-12, atol=1e-12)
+            assert not r[k][e, n:].any()
+        for k in ("dW1", "db1", "dW2", "db2"):
+            np.testing.assert_allclose(r[k][e], ref[k], rtol=1e-12, atol=1e-12)
+    L = lambda X_: float((layers.moe_ffn_block(X_, W1, b1, W2, b2, dOut, rows)["out"] * dOut).sum())
+    h = 1e-6
+    for idx in [(0, 0, 0), (2, 2, 4), (3, 4, 1), (2, 4, 0)]:
+        Xp, Xm = X.copy(), X.copy(); Xp[idx] += h; Xm[idx] -= h
+        assert (L(Xp) - L(Xm)) / (2 * h) == pytest.approx(r["dX"][idx], rel=1e-6, abs=1e-7)
