@@ -185,12 +185,15 @@ typedef struct {
 } hap_moe_desc;
 
 int hap_moe_linear_fwd(const hap_moe_desc* d, int shard_index, const void* X, const void* W, const void* bias,
-                       const int32_t* rows, void* Y, void* preact, void* stream);
-/* Any of dX, dW, dbias may be NULL to skip it.  ws: hap_moe_linear_bwd_workspace bytes (0 when act is
- * NONE and dbias is NULL), holds dP = dY * act'(preact) and column-sum partials.                   */
+                       const int32_t* rows, void* Y, void* preact, void* ws, size_t ws_bytes, void* stream);
+/* Any of dX, dW, dbias may be NULL to skip it.  ws holds dP = dY * act'(preact) and column-sum partials
+ * (required when act != NONE or dbias is given).  As for the linear layers, the forward's workspace and
+ * the last 64 MiB of the backward's are OPTIONAL scratch that lets a device with few experts split the
+ * contracted axis over idle compute units; results are the same without it.                         */
 int hap_moe_linear_bwd(const hap_moe_desc* d, int shard_index, const void* X, const void* W, const void* preact,
                        const void* dY, const int32_t* rows, void* dX, void* dW, int dW_dtype, float* dbias,
                        void* ws, size_t ws_bytes, void* stream);
+size_t hap_moe_linear_fwd_workspace(const hap_moe_desc* d, int shard_index);
 size_t hap_moe_linear_bwd_workspace(const hap_moe_desc* d, int shard_index);
 
 /* ------------------------------------------------------------------ device: attention slice --- */

@@ -117,7 +117,7 @@ lib.hap_strerror.argtypes = [C.c_int]
 lib.hap_last_error.restype = C.c_char_p
 lib.hap_version.restype = C.c_char_p
 for _n in ("hap_linear_fwd_workspace", "hap_linear_bwd_workspace", "hap_sfb_workspace", "hap_attn_bwd_workspace",
-           "hap_layernorm_bwd_workspace", "hap_colsum_workspace", "hap_moe_linear_bwd_workspace"):
+           "hap_layernorm_bwd_workspace", "hap_colsum_workspace", "hap_moe_linear_fwd_workspace", "hap_moe_linear_bwd_workspace"):
     if hasattr(lib, _n):
         getattr(lib, _n).restype = C.c_size_t
 
@@ -219,13 +219,18 @@ def hap_sfb_workspace(m, rows, in_features, out_features) -> int:
     return int(lib.hap_sfb_workspace(C.c_int(m), (C.c_int64 * m)(*map(int, rows)), C.c_int64(in_features), C.c_int64(out_features)))
 
 
+def hap_moe_linear_fwd_workspace(desc: MoeDesc, shard_index: int) -> int:
+    return int(lib.hap_moe_linear_fwd_workspace(C.byref(desc.c), C.c_int(shard_index)))
+
+
 def hap_moe_linear_bwd_workspace(desc: MoeDesc, shard_index: int) -> int:
     return int(lib.hap_moe_linear_bwd_workspace(C.byref(desc.c), C.c_int(shard_index)))
 
 
-def hap_moe_linear_fwd(desc: MoeDesc, shard_index, X, W, bias, rows, Y, preact=None, stream=None):
+def hap_moe_linear_fwd(desc: MoeDesc, shard_index, X, W, bias, rows, Y, preact=None, ws=None, stream=None):
+    wp, wb = _ws(ws)
     _check(lib.hap_moe_linear_fwd(C.byref(desc.c), C.c_int(shard_index), _ptr(X), _ptr(W), _ptr(bias), _ptr(rows), _ptr(Y),
-                                  _ptr(preact), _stream(stream)), "hap_moe_linear_fwd")
+                                  _ptr(preact), wp, wb, _stream(stream)), "hap_moe_linear_fwd")
 
 
 def hap_moe_linear_bwd(desc: MoeDesc, shard_index, X, W, preact, dY, rows, dX, dW, dW_dtype, dbias, ws=None, stream=None):

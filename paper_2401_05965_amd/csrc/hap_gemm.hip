@@ -56,7 +56,7 @@ struct GemmArgs {
   int tiles_m, tiles_n;
   int vec_store;       // C (and preact) rows are 16-byte addressable: whole-chunk stores allowed
   int ksplit;          // >1: each output tile is computed by ksplit workgroups over disjoint K-tile ranges, fp32 partials go to `partial`
-  float* partial;      // [tiles][ksplit][BM][BN] fp32 workspace when ksplit > 1
+  float* partial;      // [group][tile][ksplit][BM][BN] fp32 workspace when ksplit > 1
   int ntiles;          // K tiles (of 64) over all segments
   long long lda, ldb, ldc, ldp;
   void* c;
@@ -450,8 +450,8 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(const GemmArgs arg
     lb.store(lds_b, tid);
   };
 
-  fetch();
-  while (true) {
+  if (ntiles > 0) fetch();
+  while (ntiles > 0) {     // (a split's share of a contraction shortened on the device side can be empty)
     const int ck0 = k0, ckend = kend;
     // advance the loader to the next tile
     k0 += BK;
@@ -491,7 +491,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(const GemmArgs arg
   if (ksplit > 1) {
     // raw fp32 partial tile [BM][BN]; bias, activation and the real store happen in the reduction kernel
     GemmArgs pa = args;
-    pa.c = args.partial + ((long long)out_tile * ksplit + split) * (BM * BN);
+    pa.c = args.partial + (((long long)blockIdx.y * (gridDim.x / ksplit) + out_tile) * ksplit + split) * (BM * BN);
     pa.ldc = BN; pa.M = BM; pa.N = BN; pa.skewM = 0; pa.skewN = 0;
     pa.preact = nullptr; pa.bias = nullptr; pa.act = HAP_ACT_NONE; pa.accumulate = 0; pa.vec_store = 1;
     epilogue<T, float, TM, TN>(pa, acc, wm0, wn0, lane);
@@ -871,7 +871,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_dma_kernel(const GemmArgs
   if (ksplit > 1) {
     // raw fp32 partial tile [BM][BN]; bias, activation and the real store happen in the reduction kernel
     GemmArgs pa = args;
-    pa.c = args.partial + ((long long)out_tile * ksplit + split) * (BM * BN);
+    pa.c = args.partial + (((long long)blockIdx.y * (gridDim.x / ksplit) + out_tile) * ksplit + split) * (BM * BN);
     pa.ldc = BN; pa.M = BM; pa.N = BN; pa.skewM = 0; pa.skewN = 0;
     pa.preact = nullptr; pa.bias = nullptr; pa.act = HAP_ACT_NONE; pa.accumulate = 0; pa.vec_store = 1;
     epilogue_transposed<T, float, TM, TN>(pa, acc, wm0, wn0, lane, smem + wave * (32 * (TN * 32 * 4 + 16)));
@@ -884,7 +884,8 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_dma_kernel(const GemmArgs
  * one-pass epilogue would have (bias, pre-activation copy, activation, accumulation, conversion),
  * storing only the logical rows / columns.  One thread per 4 consecutive columns. */
 template <typename T, typename TC, int BM, int BN>
-__global__ __launch_bounds__(256) void splitk_reduce_kernel(const GemmArgs args, int out_tiles) {
+__global__ __launch_bounds__(256) void splitk_reduce_kernel(const GemmArgs args_in, int out_tiles) {
+  const GemmArgs args = group_outputs(args_in, group_view(args_in));   // blockIdx.y: group
   constexpr int QPT = BM * BN / 4;                 // column quads per tile
   const long long gid = (long long)blockIdx.x * 256 + threadIdx.x;
   const int tile = (int)(gid / QPT), q = (int)(gid % QPT);
@@ -896,7 +897,7 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(const GemmArgs args,
   if (m < 0 || m >= args.M || n >= args.N || n + 4 <= 0) return;
   typedef float f32x4_t __attribute__((ext_vector_type(4)));
   f32x4_t sum = {0.0f, 0.0f, 0.0f, 0.0f};
-  const float* p = args.partial + (long long)tile * args.ksplit * (BM * BN) + r * BN + c4;
+  const float* p = args.partial + ((long long)blockIdx.y * out_tiles + tile) * args.ksplit * (BM * BN) + r * BN + c4;
   for (int s = 0; s < args.ksplit; ++s) sum += *reinterpret_cast<const f32x4_t*>(p + (long long)s * (BM * BN));
   TC* C = static_cast<TC*>(args.c);
   TC* P = static_cast<TC*>(args.preact);
@@ -1014,9 +1015,15 @@ Plan make_plan(const hap_gemm_problem* p) {
   else {
     bool big = p->tile ? p->tile == 256 : (p->M + pl.skewM > 128 && p->N + pl.skewN > 128);
     if (big && !p->tile && (p->groups > 1 || p->group_len)) {
-      // a grouped launch is neither cut into strips nor split along K: take the small tile when big ones would leave CUs idle
+      // A grouped launch is not cut into strips: compare whole rounds of big tiles (one per CU, time 1 each) with rounds
+      // of small ones (two per CU, a quarter of the work each at lower efficiency: 0.6 per round, 0.3 when half empty).
       const long long g = p->groups > 1 ? p->groups : 1;
-      big = g * ((p->M + pl.skewM + 255) / 256) * ((p->N + pl.skewN + 255) / 256) >= kCUs;
+      const long long nb = g * ((p->M + pl.skewM + 255) / 256) * ((p->N + pl.skewN + 255) / 256);
+      const long long ns = g * ((p->M + pl.skewM + 127) / 128) * ((p->N + pl.skewN + 127) / 128);
+      // few big tiles: split-K can spread them over the chip at about a third of a round for the partial-tile traffic
+      const double tb = nb * 2 <= kCUs ? 0.35 + 1.0 / (double)(kCUs / nb) : (double)((nb + kCUs - 1) / kCUs);
+      const double ts = ns <= kCUs ? 0.3 : 0.6 * (double)((ns + 2 * kCUs - 1) / (2 * kCUs));
+      big = tb <= ts;
     }
     pl.bm = pl.bn = big ? 256 : 128;
     pl.dma = dma_variant();
@@ -1034,7 +1041,7 @@ int launch_tiled(const GemmArgs& a, int groups, hipStream_t st) {
   if (e != hipSuccess) return hap_fail(HAP_EDEVICE, "gemm launch: %s", hipGetErrorString(e));
   if (a.ksplit > 1) {
     const long long threads = (long long)out_tiles * (BM * BN / 4);
-    hipLaunchKernelGGL((splitk_reduce_kernel<T, TC, BM, BN>), dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, st, a, out_tiles);
+    hipLaunchKernelGGL((splitk_reduce_kernel<T, TC, BM, BN>), dim3((unsigned)((threads + 255) / 256), groups), dim3(256), 0, st, a, out_tiles);
     e = hipGetLastError();
     if (e != hipSuccess) return hap_fail(HAP_EDEVICE, "split-K reduce launch: %s", hipGetErrorString(e));
   }
@@ -1058,7 +1065,7 @@ int launch_dma(const GemmArgs& a, int groups, hipStream_t st) {
   if (e != hipSuccess) return hap_fail(HAP_EDEVICE, "gemm launch: %s", hipGetErrorString(e));
   if (a.ksplit > 1) {
     const long long threads = (long long)out_tiles * (BM * BN / 4);
-    hipLaunchKernelGGL((splitk_reduce_kernel<__bf16, TC, BM, BN>), dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, st, a, out_tiles);
+    hipLaunchKernelGGL((splitk_reduce_kernel<__bf16, TC, BM, BN>), dim3((unsigned)((threads + 255) / 256), groups), dim3(256), 0, st, a, out_tiles);
     e = hipGetLastError();
     if (e != hipSuccess) return hap_fail(HAP_EDEVICE, "split-K reduce launch: %s", hipGetErrorString(e));
   }
@@ -1288,11 +1295,11 @@ int hap_gemm_run(const hap_gemm_problem* p, void* stream) {
     for (int s = 0; s < a.nseg; ++s) a.ntiles += (pl.skewK + a.seg[s].k + bk - 1) / bk;
     if (a.ntiles == 0) a.ntiles = 1;     // empty contraction still runs one (all-zero) tile
   }
-  if ((pl.dma || p->in_dtype == HAP_F32) && !grouped) {
+  if (pl.dma || p->in_dtype == HAP_F32) {
     // Split-K when the output tiles cannot occupy the chip: spread each tile's K range over the idle CUs,
     // keeping at least 4 K tiles per workgroup (2 for the small fp32 tiles, whose loop is bound by one load
     // latency per tile), as far as the caller's workspace allows.
-    const long long out_tiles = (long long)a.tiles_m * a.tiles_n;
+    const long long out_tiles = (long long)a.tiles_m * a.tiles_n * groups;
     const long long slots = pl.bm == 256 ? kCUs : (pl.bm == 128 ? 2 * kCUs : 4 * kCUs);
     const int min_tiles = pl.bm == 64 ? 2 : 4;
     long long g = slots / out_tiles;

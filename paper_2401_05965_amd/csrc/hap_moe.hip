@@ -59,14 +59,24 @@ hap_gemm_problem grouped(const hap_moe_desc* d, int64_t n, const int32_t* rows, 
 
 extern "C" {
 
+static size_t required_bwd_bytes(const hap_moe_desc* d, int64_t n, bool with_dbias) {
+  return dp_bytes(d, n) + (with_dbias ? (size_t)round_up((int64_t)hap_colsum_grouped_workspace((int)n, d->capacity, d->out_features), 256) : 0);
+}
+
+size_t hap_moe_linear_fwd_workspace(const hap_moe_desc* d, int shard_index) {
+  int64_t lo, n;
+  if (resolve(d, shard_index, &lo, &n) != HAP_OK || n == 0 || d->capacity == 0) return 0;
+  return HAP_GEMM_WS_BYTES;                                   // optional: split-K partial tiles
+}
+
 size_t hap_moe_linear_bwd_workspace(const hap_moe_desc* d, int shard_index) {
   int64_t lo, n;
   if (resolve(d, shard_index, &lo, &n) != HAP_OK || n == 0 || d->capacity == 0) return 0;
-  return dp_bytes(d, n) + hap_colsum_grouped_workspace((int)n, d->capacity, d->out_features);
+  return required_bwd_bytes(d, n, true) + HAP_GEMM_WS_BYTES;  // the last part is optional split-K scratch
 }
 
 int hap_moe_linear_fwd(const hap_moe_desc* d, int shard_index, const void* X, const void* W, const void* bias,
-                       const int32_t* rows, void* Y, void* preact, void* stream) {
+                       const int32_t* rows, void* Y, void* preact, void* ws, size_t ws_bytes, void* stream) {
   hap_clear_error();
   int64_t lo, n;
   const int rc = resolve(d, shard_index, &lo, &n);
@@ -85,6 +95,7 @@ int hap_moe_linear_fwd(const hap_moe_desc* d, int shard_index, const void* X, co
   if (bias) { p.bias = at(bias, first * d->out_features, es); p.gbias = d->out_features; }
   if (preact) { p.preact = at(preact, first * gy, es); p.ldp = d->ldy; p.gp = gy; }
   p.act = d->act;
+  p.ws = ws; p.ws_bytes = ws ? ws_bytes : 0;
   return hap_gemm_run(&p, stream);
 }
 
@@ -103,8 +114,11 @@ int hap_moe_linear_bwd(const hap_moe_desc* d, int shard_index, const void* X, co
   if (live && dX && !W) return hap_fail(HAP_EINVAL, "dX requested but W is NULL");
   if (live && dW && !X) return hap_fail(HAP_EINVAL, "dW requested but X is NULL");
   if (live && d->act != HAP_ACT_NONE && !preact) return hap_fail(HAP_EINVAL, "activation backward needs the saved pre-activation");
-  const size_t need = (d->act != HAP_ACT_NONE ? dp_bytes(d, n) : 0) + (dbias ? hap_colsum_grouped_workspace((int)n, d->capacity, d->out_features) : 0);
+  const size_t need = required_bwd_bytes(d, n, dbias != NULL);
   if (live && need && (!ws || ws_bytes < need)) return hap_fail(HAP_EWORKSPACE, "moe_linear_bwd needs %zu workspace bytes", need);
+  // [dP][column-sum scratch][optional split-K scratch for the GEMM engine]
+  char* gemm_ws = ws ? static_cast<char*>(ws) + need : NULL;
+  const size_t gemm_ws_bytes = (ws && ws_bytes > need) ? ws_bytes - need : 0;
   const int es = esize(d->io_dtype);
   const int64_t first = d->operands_are_full ? lo : 0;
   const int64_t gx = d->capacity * d->ldx, gw = d->in_features * d->ldw, gy = d->capacity * d->ldy;
@@ -131,6 +145,7 @@ int hap_moe_linear_bwd(const hap_moe_desc* d, int shard_index, const void* X, co
     p.a[0] = dP; p.lda = lddp; p.a_kcontig = 1; p.ga = gdp;
     p.b[0] = at(W, first * gw, es); p.ldb = d->ldw; p.b_kcontig = 1; p.gb = gw;     // B(k = out, n = in) = W_e[n*ldw + k]
     p.c = at(dX, first * gx, es); p.ldc = d->ldx; p.c_dtype = d->io_dtype; p.gc = gx;
+    p.ws = gemm_ws_bytes ? gemm_ws : NULL; p.ws_bytes = gemm_ws_bytes;
     if ((rc = hap_gemm_run(&p, stream))) return rc;
   }
   if (dW) {
@@ -140,11 +155,12 @@ int hap_moe_linear_bwd(const hap_moe_desc* d, int shard_index, const void* X, co
     p.a[0] = live ? at(X, first * gx, es) : NULL; p.lda = d->ldx; p.a_kcontig = 0; p.ga = gx;   // A(m = in, k = token) = X_e[k*ldx + m]
     p.b[0] = dP; p.ldb = lddp; p.b_kcontig = 0; p.gb = gdp;
     p.c = at(dW, first * gw, wes); p.ldc = d->ldw; p.c_dtype = dW_dtype; p.gc = gw;
+    p.ws = gemm_ws_bytes ? gemm_ws : NULL; p.ws_bytes = gemm_ws_bytes;
     if ((rc = hap_gemm_run(&p, stream))) return rc;
   }
   if (dbias) {
     rc = hap_colsum_grouped((int)n, d->capacity, d->out_features, d->io_dtype, dP, lddp, gdp, rows_j, dbias + first * d->out_features,
-                            d->out_features, wsp, ws ? ws_bytes - (size_t)(wsp - static_cast<char*>(ws)) : 0, stream);
+                            d->out_features, wsp, hap_colsum_grouped_workspace((int)n, d->capacity, d->out_features), stream);
     if (rc) return rc;
   }
   return HAP_OK;

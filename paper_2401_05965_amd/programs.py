@@ -121,8 +121,8 @@ class MoeExpertShard:
 
     def forward(self, timer=None):
         j = self.j
-        _call(timer, "moe_fc1_fwd", lambda: hap.hap_moe_linear_fwd(self.fc1, j, self.X, self.W1, self.b1, self.rows, self.H, self.pre))
-        _call(timer, "moe_fc2_fwd", lambda: hap.hap_moe_linear_fwd(self.fc2, j, self.H, self.W2, self.b2, self.rows, self.Out, None))
+        _call(timer, "moe_fc1_fwd", lambda: hap.hap_moe_linear_fwd(self.fc1, j, self.X, self.W1, self.b1, self.rows, self.H, self.pre, self.ws))
+        _call(timer, "moe_fc2_fwd", lambda: hap.hap_moe_linear_fwd(self.fc2, j, self.H, self.W2, self.b2, self.rows, self.Out, None, self.ws))
 
     def backward(self, timer=None):
         j = self.j

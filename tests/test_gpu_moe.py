@@ -31,7 +31,7 @@ def expert_offsets(hap, speeds, experts):
     return sizes, offs
 
 
-def run_moe_case(hap, dtype, E, C, in_f, out_f, offs, rows, act, bias, full, dw_dtype=None, pad=0, seed=9):
+def run_moe_case(hap, dtype, E, C, in_f, out_f, offs, rows, act, bias, full, dw_dtype=None, pad=0, seed=9, fwd_ws=False):
     torch = torch_mod()
     dw_dtype = dw_dtype or dtype
     ldx, ldw, ldy = in_f + pad, out_f + pad, out_f + pad
@@ -76,8 +76,8 @@ def run_moe_case(hap, dtype, E, C, in_f, out_f, offs, rows, act, bias, full, dw_
                 Xj = Wj = dYj = bj = rj = None
         Y = empty((ne, C, ldy), dtype, SENTINEL); P = empty((ne, C, ldy), dtype, SENTINEL) if act else None
         dX = empty((ne, C, ldx), dtype, SENTINEL); dW = empty((ne, in_f, ldw), dw_dtype, SENTINEL); db = empty((ne, out_f), "f32", SENTINEL)
-        hap.hap_moe_linear_fwd(desc, j, Xj, Wj, bj if bias else None, rj, Y, P)
-        ws = empty((max(hap.hap_moe_linear_bwd_workspace(desc, j), 16),), "u8")
+        ws = empty((max(hap.hap_moe_linear_bwd_workspace(desc, j), hap.hap_moe_linear_fwd_workspace(desc, j), 16),), "u8")
+        hap.hap_moe_linear_fwd(desc, j, Xj, Wj, bj if bias else None, rj, Y, P, ws if fwd_ws else None)
         hap.hap_moe_linear_bwd(desc, j, Xj, Wj, P, dYj, rj, dX, dW, DT[dw_dtype], db, ws)
         got = {k: host(v) for k, v in (("Y", Y), ("dX", dX), ("dW", dW), ("db", db))}
         if act:
@@ -180,3 +180,11 @@ def test_moe_expert_ffn_block_uneven_devices(hap):
             check(f"{name} dev{j}", host(t)[lv], ref[name][s][lv], "bf16")
         for name, t in (("dW1", sh.dW1), ("db1", sh.db1), ("dW2", sh.dW2), ("db2", sh.db2)):
             check(f"{name} dev{j}", host(t), ref[name][s], "bf16")
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_moe_few_experts_split_k(hap, dtype):
+    """Devices with one expert each and workspace given: outputs have too few tiles to fill the chip, so the contracted axis is
+    split over workgroups - also where the token count (known only on the device) leaves some workgroups without any K tile."""
+    run_moe_case(hap, dtype, 2, 1024, 256, 384, [0, 1, 2], [700, 130], act=True, bias=True, full=True, fwd_ws=True)
+    run_moe_case(hap, dtype, 3, 1024, 512, 128, [0, 1, 3], [0, 1024, 65], act=False, bias=True, full=False, fwd_ws=True, dw_dtype="f32")

@@ -123,7 +123,7 @@ def test_host_side_argument_errors(hap):
 def test_moe_host_side_argument_errors(hap):
     """Expert-sharded layer (Sec. 7.6): descriptor and pointer checks happen before any launch."""
     z = C.c_void_p(0)
-    fwd = lambda d, j: hap.lib.hap_moe_linear_fwd(C.byref(d.c), j, z, z, z, z, z, z, z)
+    fwd = lambda d, j: hap.lib.hap_moe_linear_fwd(C.byref(d.c), j, z, z, z, z, z, z, z, C.c_size_t(0), z)
     d = hap.MoeDesc(7, 16, 8, 8, [0, 3, 5, 6, 8], hap.BF16)
     assert fwd(d, 0) == 2                                                   # expert ranges do not end at the expert count
     d = hap.MoeDesc(7, 16, 8, 8, [0, 3, 5, 6, 7], hap.BF16)
@@ -136,7 +136,7 @@ def test_moe_host_side_argument_errors(hap):
     assert fwd(d, 0) == 2                                                   # ld below width
     d = hap.MoeDesc(7, 16, 8, 8, [0, 3, 5, 6, 7], hap.BF16, act=hap.ACT_GELU_ERF, has_bias=True)
     one = C.c_void_p(256)
-    assert hap.lib.hap_moe_linear_fwd(C.byref(d.c), 0, one, one, z, z, one, z, z) == 1            # has_bias without a bias pointer
+    assert hap.lib.hap_moe_linear_fwd(C.byref(d.c), 0, one, one, z, z, one, z, z, C.c_size_t(0), z) == 1            # has_bias without a bias pointer
     need = hap.hap_moe_linear_bwd_workspace(d, 0)
     assert need >= 3 * 16 * 8 * 2
     assert hap.lib.hap_moe_linear_bwd(C.byref(d.c), 0, one, one, one, one, z, one, one, 1, z, z, C.c_size_t(0), z) == 5   # workspace missing
