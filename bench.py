@@ -30,6 +30,7 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--moe-only", action="store_true", help="only run the MoE expert rows (profiling aid)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run a plain 256 MiB device copy 10 times (reference for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
@@ -140,6 +141,33 @@ def main():
             res[name] = round(2.0 * big.T * big.f * big.h * 10 / (a.elapsed_time(b) * 1e-3) / 1e12, 1)
         return res
 
+    def moe_rows(res, timeit):
+        """Rows for the unevenly placed MoE experts (Sec. 7.6); also run alone by --moe-only (profiling aid)."""
+        # MoE feed-forward layer with 30 experts on 4 devices of speeds (1, 1, .5, .5): the LP + rounding places (10, 10, 5, 5);
+        # an even split has to pad to 32 experts, 8 per device.  One device's forward + backward, all expert buffers full.
+        wm = hapgen.WORKLOADS["moe_experts_bf16"]
+        Em, Cm, Hm, Fm = (wm.dims[k] for k in ("experts", "capacity", "hidden", "ffn"))
+        rm, _ = hap.hap_shard_ratios(list(wm.speeds), [(1.0, 0.0, 0.0, 0.0)])
+        msizes, moffs = hap.hap_round_shards(rm, Em, 1)
+        genm = torch.Generator(device=dev); genm.manual_seed(5)
+        rnd = lambda shp, sg: (torch.randn(shp, generator=genm, device=dev) * sg).to(torch.bfloat16)
+        nmax = max(max(msizes), (Em + len(msizes) - 1) // len(msizes))
+        mX, mdO = rnd((nmax, Cm, Hm), 1.0), rnd((nmax, Cm, Hm), 1.0)
+        mW1, mb1, mW2, mb2 = rnd((nmax, Hm, Fm), 0.02), rnd((nmax, Fm), 0.02), rnd((nmax, Fm, Hm), 0.02), rnd((nmax, Hm), 0.02)
+
+        def moe_row(n, rows):
+            sh = MoeExpertShard(n, Cm, Hm, Fm, [0, n], 0, mX, mW1, mb1, mW2, mb2, rows, mdO)
+            t = timeit(lambda: (sh.forward(), sh.backward()), n=10)
+            f, b = sh.flops(None if rows is None else rows[:n].tolist())
+            return {"experts": n, "ms": round(t * 1e3, 3), "gflop": round((f + b) / 1e9, 1), "tflops": round((f + b) / t / 1e12, 1)}
+        res["moe_expert_placement"] = msizes
+        res["moe_ffn_fwd_bwd_device0"] = moe_row(msizes[0], None)
+        res["moe_ffn_fwd_bwd_device2"] = moe_row(msizes[2], None)
+        res["moe_ffn_fwd_bwd_even_split_padded_to_32"] = moe_row((Em + len(msizes) - 1) // len(msizes), None)
+        ragged = torch.randint(Cm // 2, Cm + 1, (nmax,), generator=genm, device=dev, dtype=torch.int32)
+        res["moe_ffn_fwd_bwd_device0_ragged_tokens"] = moe_row(msizes[0], ragged)
+        del mX, mdO, mW1, mW2
+
     def other_rows():
         """Throughput of the path's remaining kernels, measured in this run; not part of `value`: attention slice and
         row / element ops at config 4's shard-0 shapes (16 x 5 heads x 1024 x 128; 16384 x 2048 rows), config 5's
@@ -223,30 +251,7 @@ def main():
         res["cfg4_layer_fwd_bwd_device0_5heads_ffn2731"] = layer("tensor", 0, *c4)
         res["cfg4_layer_fwd_bwd_device2_3heads_ffn1365"] = layer("tensor", 2, *c4)
         res["cfg5_layer_fwd_bwd_device0_79samples"] = layer("data", 0, 256, 197, 1024, 16, 64, 4096, [0, 16], [0, 4096], [0, 79, 142, 205, 236, 256])
-        # MoE feed-forward layer with 30 experts on 4 devices of speeds (1, 1, .5, .5): the LP + rounding places (10, 10, 5, 5);
-        # an even split has to pad to 32 experts, 8 per device.  One device's forward + backward, all expert buffers full.
-        wm = hapgen.WORKLOADS["moe_experts_bf16"]
-        Em, Cm, Hm, Fm = (wm.dims[k] for k in ("experts", "capacity", "hidden", "ffn"))
-        rm, _ = hap.hap_shard_ratios(list(wm.speeds), [(1.0, 0.0, 0.0, 0.0)])
-        msizes, moffs = hap.hap_round_shards(rm, Em, 1)
-        genm = torch.Generator(device=dev); genm.manual_seed(5)
-        rnd = lambda shp, sg: (torch.randn(shp, generator=genm, device=dev) * sg).to(torch.bfloat16)
-        nmax = max(max(msizes), (Em + len(msizes) - 1) // len(msizes))
-        mX, mdO = rnd((nmax, Cm, Hm), 1.0), rnd((nmax, Cm, Hm), 1.0)
-        mW1, mb1, mW2, mb2 = rnd((nmax, Hm, Fm), 0.02), rnd((nmax, Fm), 0.02), rnd((nmax, Fm, Hm), 0.02), rnd((nmax, Hm), 0.02)
-
-        def moe_row(n, rows):
-            sh = MoeExpertShard(n, Cm, Hm, Fm, [0, n], 0, mX, mW1, mb1, mW2, mb2, rows, mdO)
-            t = timeit(lambda: (sh.forward(), sh.backward()), n=10)
-            f, b = sh.flops(None if rows is None else rows[:n].tolist())
-            return {"experts": n, "ms": round(t * 1e3, 3), "gflop": round((f + b) / 1e9, 1), "tflops": round((f + b) / t / 1e12, 1)}
-        res["moe_expert_placement"] = msizes
-        res["moe_ffn_fwd_bwd_device0"] = moe_row(msizes[0], None)
-        res["moe_ffn_fwd_bwd_device2"] = moe_row(msizes[2], None)
-        res["moe_ffn_fwd_bwd_even_split_padded_to_32"] = moe_row((Em + len(msizes) - 1) // len(msizes), None)
-        ragged = torch.randint(Cm // 2, Cm + 1, (nmax,), generator=genm, device=dev, dtype=torch.int32)
-        res["moe_ffn_fwd_bwd_device0_ragged_tokens"] = moe_row(msizes[0], ragged)
-        del mX, mdO, mW1, mW2
+        moe_rows(res, timeit)
         # config 3 the naive way (Fig. "sfb"(b)): every device's own fp32 dW_i, then their sum (what the All-Reduce delivers)
         inf, outf = w3.dims["in_features"], w3.dims["out_features"]
         parts = [torch.zeros((inf, outf), dtype=torch.float32, device=dev) for _ in rows]
@@ -259,6 +264,21 @@ def main():
         t = timeit(naive, n=3); res["cfg3_naive_local_dW_plus_sum_ms"] = round(t * 1e3, 3)
         t = timeit(lambda: sfb.run(None), n=5); res["cfg3_sfb_rebuild_ms"] = round(t * 1e3, 3)
         return res
+
+    if args.moe_only:
+        def timeit(fn, n=10):
+            for _ in range(2):
+                fn()
+            a = torch.cuda.Event(enable_timing=True); b = torch.cuda.Event(enable_timing=True)
+            a.record(stream)
+            for _ in range(n):
+                fn()
+            b.record(stream); b.synchronize()
+            return a.elapsed_time(b) / n * 1e-3
+        res = {}
+        moe_rows(res, timeit)
+        print(json.dumps(res))
+        return
 
     for _ in range(args.warmup):
         step()

@@ -63,7 +63,7 @@ struct GemmArgs {
   void* preact;
   const void* bias;
   int act, accumulate;
-  // Grouped launch: blockIdx.y picks one of `groups` independent products that differ only in their base
+  // Grouped launch (gridDim.y groups): a workgroup works on one of `groups` independent products that differ only in their base
   // addresses (byte strides below) and, when group_len is given, in the valid length of one axis.
   int ragged;              // 0: every group is M x N x k;  1: group_len bounds M;  2: group_len bounds the contraction (nseg == 1)
   const int* group_len;    // device array [groups], or nullptr
@@ -78,9 +78,8 @@ struct GroupView {
   long long oa, ob;
 };
 
-__device__ __forceinline__ GroupView group_view(const GemmArgs& args) {
+__device__ __forceinline__ GroupView group_view(const GemmArgs& args, int grp) {
   GroupView g;
-  const int grp = blockIdx.y;
   g.M = args.M; g.k = -1;
   g.oa = grp * args.ga; g.ob = grp * args.gb;
   if (args.ragged) {
@@ -93,9 +92,8 @@ __device__ __forceinline__ GroupView group_view(const GemmArgs& args) {
 }
 
 /* The arguments as the epilogue of this workgroup's group sees them. */
-__device__ __forceinline__ GemmArgs group_outputs(const GemmArgs& args, const GroupView& g) {
+__device__ __forceinline__ GemmArgs group_outputs(const GemmArgs& args, const GroupView& g, int grp) {
   GemmArgs e = args;
-  const int grp = blockIdx.y;
   e.M = g.M;
   e.c = static_cast<char*>(args.c) + grp * args.gc;
   if (args.preact) e.preact = static_cast<char*>(args.preact) + grp * args.gp;
@@ -342,17 +340,48 @@ __device__ __forceinline__ f32x16_t mfma(float a, float b, f32x16_t c) {
 
 /* Workgroup id -> tile, keeping the workgroups that share an XCD (ids congruent mod 8 are
  * dispatched to the same die and L2) on a compact block of the tile grid. */
-__device__ __forceinline__ void tile_of_block(int bid, int nblocks, int tiles_m, int tiles_n, int* tm, int* tn) {
-  constexpr int XCDS = 8, GM = 4;
+__device__ __forceinline__ int xcd_logical(int bid, int nblocks) {
+  constexpr int XCDS = 8;
   const int xcd = bid % XCDS, local = bid / XCDS;
   const int q = nblocks / XCDS, r = nblocks % XCDS;
-  const int logical = xcd * q + (xcd < r ? xcd : r) + local;
+  return xcd * q + (xcd < r ? xcd : r) + local;
+}
+
+__device__ __forceinline__ void tile_of_logical(int logical, int tiles_m, int tiles_n, int* tm, int* tn) {
+  constexpr int GM = 4;
   const int per_group = GM * tiles_n;
   const int group = logical / per_group, in_group = logical % per_group;
   const int first_m = group * GM;
   const int gsize = tiles_m - first_m < GM ? tiles_m - first_m : GM;
   *tm = first_m + in_group % gsize;
   *tn = in_group / gsize;
+}
+
+__device__ __forceinline__ void tile_of_block(int bid, int nblocks, int tiles_m, int tiles_n, int* tm, int* tn) {
+  tile_of_logical(xcd_logical(bid, nblocks), tiles_m, tiles_n, tm, tn);
+}
+
+/* Which group, output tile and K split a workgroup of the tiled kernels works on.  A single product keeps
+ * the map above.  In a grouped launch (gridDim.y groups of gridDim.x workgroups, dispatched x-fastest)
+ * the XCD-contiguous renumbering runs over ALL workgroups, so an XCD works through whole groups one
+ * after the other (a group's tiles share its operands in that XCD's L2) and every XCD gets the same
+ * number of workgroups whatever the group count. */
+struct BlockPos { int grp, out_tile, split, tm, tn; };
+__device__ __forceinline__ BlockPos block_pos(const GemmArgs& args) {
+  BlockPos b;
+  const int ksplit = args.ksplit;
+  if (gridDim.y == 1) {
+    b.grp = 0;
+    b.out_tile = blockIdx.x / ksplit; b.split = blockIdx.x - b.out_tile * ksplit;
+    tile_of_block(b.out_tile, gridDim.x / ksplit, args.tiles_m, args.tiles_n, &b.tm, &b.tn);
+  } else {
+    const int logical = xcd_logical(blockIdx.y * gridDim.x + blockIdx.x, gridDim.x * gridDim.y);
+    b.grp = logical / (int)gridDim.x;
+    const int in_group = logical - b.grp * (int)gridDim.x;
+    b.out_tile = in_group / ksplit; b.split = in_group - b.out_tile * ksplit;
+    tile_of_logical(b.out_tile, args.tiles_m, args.tiles_n, &b.tm, &b.tn);
+  }
+  return b;
 }
 
 /* Writes a wave's TM x TN accumulator tiles.  Accumulator element e of lane l is row
@@ -401,11 +430,10 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(const GemmArgs arg
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm0 = (wave / WGN) * WTM, wn0 = (wave % WGN) * WTN;
   // With split-K, ksplit consecutive workgroups share an output tile and take consecutive K-tile ranges.
-  const int ksplit = args.ksplit, out_tile = blockIdx.x / ksplit, split = blockIdx.x - out_tile * ksplit;
-  int tm, tn;
-  tile_of_block(out_tile, gridDim.x / ksplit, args.tiles_m, args.tiles_n, &tm, &tn);
+  const BlockPos bp = block_pos(args);
+  const int ksplit = args.ksplit, out_tile = bp.out_tile, split = bp.split, tm = bp.tm, tn = bp.tn;
   const int m0 = tm * BM, n0 = tn * BN;                 // physical tile origin
-  const GroupView gv = group_view(args);
+  const GroupView gv = group_view(args, bp.grp);
   const int m_lim = args.skewM + gv.M, n_lim = args.skewN + args.N;
   if (args.ragged == 1 && (gv.M == 0 || m0 >= m_lim)) return;   // the group's rows end before this tile
   const int all_tiles = gv.k >= 0 ? (args.skewK + gv.k + BK - 1 >= BK ? (args.skewK + gv.k + BK - 1) / BK : 1) : args.ntiles;
@@ -491,13 +519,13 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(const GemmArgs arg
   if (ksplit > 1) {
     // raw fp32 partial tile [BM][BN]; bias, activation and the real store happen in the reduction kernel
     GemmArgs pa = args;
-    pa.c = args.partial + (((long long)blockIdx.y * (gridDim.x / ksplit) + out_tile) * ksplit + split) * (BM * BN);
+    pa.c = args.partial + (((long long)bp.grp * (gridDim.x / ksplit) + out_tile) * ksplit + split) * (BM * BN);
     pa.ldc = BN; pa.M = BM; pa.N = BN; pa.skewM = 0; pa.skewN = 0;
     pa.preact = nullptr; pa.bias = nullptr; pa.act = HAP_ACT_NONE; pa.accumulate = 0; pa.vec_store = 1;
     epilogue<T, float, TM, TN>(pa, acc, wm0, wn0, lane);
     return;
   }
-  epilogue<T, TC, TM, TN>(group_outputs(args, gv), acc, m0 + wm0, n0 + wn0, lane);
+  epilogue<T, TC, TM, TN>(group_outputs(args, gv, bp.grp), acc, m0 + wm0, n0 + wn0, lane);
 }
 
 /* Epilogue of the direct-to-LDS kernels.  Their accumulators are TRANSPOSED tiles (the MFMA is fed
@@ -715,11 +743,10 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_dma_kernel(const GemmArgs
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm0 = (wave / WGN) * WTM, wn0 = (wave % WGN) * WTN;
   // With split-K, ksplit consecutive workgroups share an output tile and take consecutive K-tile ranges.
-  const int ksplit = args.ksplit, out_tile = blockIdx.x / ksplit, split = blockIdx.x - out_tile * ksplit;
-  int tm, tn;
-  tile_of_block(out_tile, gridDim.x / ksplit, args.tiles_m, args.tiles_n, &tm, &tn);
+  const BlockPos bp = block_pos(args);
+  const int ksplit = args.ksplit, out_tile = bp.out_tile, split = bp.split, tm = bp.tm, tn = bp.tn;
   const int m0 = tm * BM, n0 = tn * BN;
-  const GroupView gv = group_view(args);
+  const GroupView gv = group_view(args, bp.grp);
   const int m_lim = args.skewM + gv.M, n_lim = args.skewN + args.N;
   if (args.ragged == 1 && (gv.M == 0 || m0 >= m_lim)) return;   // the group's rows end before this tile
   const int all_tiles = gv.k >= 0 ? (args.skewK + gv.k + BK - 1 >= BK ? (args.skewK + gv.k + BK - 1) / BK : 1) : args.ntiles;
@@ -871,13 +898,13 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_dma_kernel(const GemmArgs
   if (ksplit > 1) {
     // raw fp32 partial tile [BM][BN]; bias, activation and the real store happen in the reduction kernel
     GemmArgs pa = args;
-    pa.c = args.partial + (((long long)blockIdx.y * (gridDim.x / ksplit) + out_tile) * ksplit + split) * (BM * BN);
+    pa.c = args.partial + (((long long)bp.grp * (gridDim.x / ksplit) + out_tile) * ksplit + split) * (BM * BN);
     pa.ldc = BN; pa.M = BM; pa.N = BN; pa.skewM = 0; pa.skewN = 0;
     pa.preact = nullptr; pa.bias = nullptr; pa.act = HAP_ACT_NONE; pa.accumulate = 0; pa.vec_store = 1;
     epilogue_transposed<T, float, TM, TN>(pa, acc, wm0, wn0, lane, smem + wave * (32 * (TN * 32 * 4 + 16)));
     return;
   }
-  epilogue_transposed<T, TC, TM, TN>(group_outputs(args, gv), acc, m0 + wm0, n0 + wn0, lane, smem + wave * (32 * (TN * 32 * (int)sizeof(TC) + 16)));
+  epilogue_transposed<T, TC, TM, TN>(group_outputs(args, gv, bp.grp), acc, m0 + wm0, n0 + wn0, lane, smem + wave * (32 * (TN * 32 * (int)sizeof(TC) + 16)));
 }
 
 /* Split-K reduction: sums the ksplit fp32 partial tiles of every output tile and applies what the
@@ -885,13 +912,14 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_dma_kernel(const GemmArgs
  * storing only the logical rows / columns.  One thread per 4 consecutive columns. */
 template <typename T, typename TC, int BM, int BN>
 __global__ __launch_bounds__(256) void splitk_reduce_kernel(const GemmArgs args_in, int out_tiles) {
-  const GemmArgs args = group_outputs(args_in, group_view(args_in));   // blockIdx.y: group
+  const GemmArgs args = group_outputs(args_in, group_view(args_in, blockIdx.y), blockIdx.y);   // blockIdx.y: group
   constexpr int QPT = BM * BN / 4;                 // column quads per tile
   const long long gid = (long long)blockIdx.x * 256 + threadIdx.x;
   const int tile = (int)(gid / QPT), q = (int)(gid % QPT);
   if (tile >= out_tiles) return;
   int tm, tn;
-  tile_of_block(tile, out_tiles, args.tiles_m, args.tiles_n, &tm, &tn);
+  if (gridDim.y == 1) tile_of_block(tile, out_tiles, args.tiles_m, args.tiles_n, &tm, &tn);   // the maps of block_pos()
+  else tile_of_logical(tile, args.tiles_m, args.tiles_n, &tm, &tn);
   const int r = q / (BN / 4), c4 = (q % (BN / 4)) * 4;
   const int m = tm * BM + r - args.skewM, n = tn * BN + c4 - args.skewN;
   if (m < 0 || m >= args.M || n >= args.N || n + 4 <= 0) return;
