@@ -1,0 +1,51 @@
+"""Pins for oracle.gather (Sec. 2.2: All-Gather concatenates the slices along d; Sec. 2.3.1: padded vs grouped)."""
+import numpy as np
+import pytest
+
+from oracle import gather, lp, rounding
+
+
+def _full(rows, cols, dtype=np.uint16):
+    return (np.arange(rows * cols, dtype=np.int64).reshape(rows, cols) * 2654435761 % 65521).astype(dtype)
+
+
+@pytest.mark.parametrize("dim", [0, 1])
+def test_gather_of_the_shards_is_the_tensor_both_layouts(dim):
+    """Slicing a tensor by the LP + rounding ranges and gathering the slices back - through padded slots or at their own
+    sizes - is the identity (the definition of All-Gather), for a placement with an empty shard."""
+    full = _full(23, 31)
+    n = full.shape[dim]
+    ratios, _ = lp.shard_ratios((1.0, 0.6, 0.35, 0.001), [(1.0, 0, 0, 0)])
+    sizes, offs = rounding.round_shards(ratios, n, 1)
+    assert sum(sizes) == n and sizes[-1] == 0
+    shards = [gather.shard(full, offs, j, dim) for j in range(4)]
+    assert [s.shape[dim] for s in shards] == sizes
+    cap = max(sizes)
+    slots = [gather.pad(s.astype(np.float64), cap, dim) for s in shards]           # NaN padding: a read of it would show
+    assert all(s.shape[dim] == cap for s in slots)
+    assert np.array_equal(gather.assemble(slots, offs, dim), full.astype(np.float64))
+    assert np.array_equal(gather.assemble(shards, offs, dim), full)
+    assert np.array_equal(gather.assemble(shards, offs, dim), np.concatenate(shards, axis=dim))
+
+
+def test_elementwise_placement_brute_force():
+    full = _full(7, 5)
+    offs = [0, 3, 3, 7]
+    out = gather.assemble([gather.pad(gather.shard(full, offs, j, 0), 4, 0, fill=9) for j in range(3)], offs, 0)
+    for r in range(7):
+        j = 0 if r < 3 else 2
+        for c in range(5):
+            assert out[r, c] == full[r, c] == gather.shard(full, offs, j, 0)[r - offs[j], c]
+    offs = [0, 1, 5]
+    out = gather.assemble([gather.pad(gather.shard(full, offs, j, 1), 4, 1, fill=9) for j in range(2)], offs, 1)
+    for r in range(7):
+        for c in range(5):
+            j = 0 if c < 1 else 1
+            assert out[r, c] == gather.shard(full, offs, j, 1)[r, c - offs[j]]
+
+
+def test_bad_offsets_rejected():
+    with pytest.raises(ValueError):
+        gather.assemble([_full(2, 2)], [1, 3], 0)
+    with pytest.raises(ValueError):
+        gather.assemble([_full(2, 2)], [0, 2, 4], 0)
