@@ -251,6 +251,20 @@ def main():
         res["cfg4_layer_fwd_bwd_device0_5heads_ffn2731"] = layer("tensor", 0, *c4)
         res["cfg4_layer_fwd_bwd_device2_3heads_ffn1365"] = layer("tensor", 2, *c4)
         res["cfg5_layer_fwd_bwd_device0_79samples"] = layer("data", 0, 256, 197, 1024, 16, 64, 4096, [0, 16], [0, 4096], [0, 79, 142, 205, 236, 256])
+        # uneven All-Gather data movement (Sec. 2.3.1): the padded slots of config 2's hidden activations (8402 | 5041 | 2941 of 16384
+        # columns: byte offsets 16804 and 26886, nothing 16-byte aligned) and of config 5's token rows (batch 79 | 63 | 63 | 31 | 20 x 197)
+        def gather_row(rows_, cols_, dim_, offs_):
+            gd = hap.GatherDesc(rows_, cols_, dim_, offs_, 2)
+            cap = hap.hap_allgather_capacity(gd)
+            m_ = len(offs_) - 1
+            shp = (cap, cols_) if dim_ == 0 else (rows_, cap)
+            slots = torch.empty((m_,) + shp, dtype=torch.bfloat16, device=dev).normal_()
+            outg = torch.empty((rows_, cols_), dtype=torch.bfloat16, device=dev)
+            ptrs = [slots[j_].data_ptr() for j_ in range(m_)]
+            t_ = timeit(lambda: hap.hap_allgather_assemble(gd, ptrs, [shp[1]] * m_, outg, cols_))
+            return round(2.0 * rows_ * cols_ * 2 / t_ / 1e9)
+        res["allgather_trim_cfg2_hidden_dim1_gbs"] = gather_row(Tn, F, 1, offsets)
+        res["allgather_trim_cfg5_tokens_dim0_gbs"] = gather_row(256 * 197, 1024, 0, [197 * b for b in (0, 79, 142, 205, 236, 256)])
         moe_rows(res, timeit)
         # config 3 the naive way (Fig. "sfb"(b)): every device's own fp32 dW_i, then their sum (what the All-Reduce delivers)
         inf, outf = w3.dims["in_features"], w3.dims["out_features"]

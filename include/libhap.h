@@ -256,6 +256,39 @@ int hap_colsum(int64_t rows, int64_t cols, int io_dtype, const void* a, int64_t 
                void* ws, size_t ws_bytes, void* stream);
 size_t hap_colsum_workspace(int64_t rows, int64_t cols);
 
+/* ------------------------------------------------------------------ device: uneven All-Gather data movement --- */
+
+/* The copies one device performs around an All-Gather of a tensor [rows x cols] that is sharded
+ * unevenly along `dim` (Sec. 2.2; Sec. 2.3.1, Fig. "comm_opt").  Collective libraries gather
+ * equal-size pieces, so either every shard is padded to capacity = max_j size_j along `dim` before the
+ * exchange and trimmed after it (padded All-Gather), or every shard travels at its own size (grouped
+ * Broadcast).  Either way piece j ends up at [offsets[j], offsets[j+1]) of the sharded axis of `out`.
+ * The exchange itself is not part of this library.  Element type is opaque: elem_bytes in {1,2,4,8};
+ * leading dimensions are in elements; no alignment is required (16-byte accesses when everything
+ * allows, smaller powers of two otherwise).  Bit-exact by construction.                             */
+typedef struct {
+  int64_t rows, cols;       /* the FULL tensor                                                       */
+  int dim;                  /* 0: sharded over rows, 1: over columns                                 */
+  int m;                    /* devices, <= HAP_SFB_MAX_DEVICES                                       */
+  const int64_t* offsets;   /* host, [m+1] over the sharded axis                                     */
+  int elem_bytes;
+} hap_gather_desc;
+
+/* max_j size_j: the extent of a padded slot along `dim` (-1 on a bad descriptor).                   */
+int64_t hap_allgather_capacity(const hap_gather_desc* d);
+/* "Pad": copies device shard_index's shard ([size_j x cols] or [rows x size_j], ld_shard) to the front
+ * of its send slot (ld_slot).  The rest of the slot is left as it is: what the padding holds is never
+ * looked at.                                                                                        */
+int hap_allgather_pad(const hap_gather_desc* d, int shard_index, const void* shard, int64_t ld_shard,
+                      void* slot, int64_t ld_slot, void* stream);
+/* "Trim" / place: out[range of j along dim] = first size_j rows (dim 0) or columns (dim 1) of pieces[j],
+ * for all j in one launch.  pieces, ld_pieces: HOST arrays [m] (device pointers, leading dimensions);
+ * padded layout: pieces[j] = slots + j * slot_extent, ld = cols (dim 0) or capacity (dim 1); grouped
+ * layout: each shard's own buffer and width.  Empty shards may have NULL pieces.  out must not overlap
+ * any piece.                                                                                        */
+int hap_allgather_assemble(const hap_gather_desc* d, const void* const* pieces, const int64_t* ld_pieces,
+                           void* out, int64_t ld_out, void* stream);
+
 /* ------------------------------------------------------------------ diagnostics --- */
 
 /* Issue-rate probe for the roofline report: 256 blocks x 8 waves run `iters` rounds of 8 independent

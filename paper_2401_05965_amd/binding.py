@@ -65,6 +65,21 @@ class _MoeDesc(C.Structure):
                 ("operands_are_full", C.c_int)]
 
 
+class _GatherDesc(C.Structure):
+    _fields_ = [("rows", C.c_int64), ("cols", C.c_int64), ("dim", C.c_int), ("m", C.c_int),
+                ("offsets", C.POINTER(C.c_int64)), ("elem_bytes", C.c_int)]
+
+
+class GatherDesc:
+    """Python mirror of hap_gather_desc; keeps the offsets array alive."""
+
+    def __init__(self, rows, cols, dim, offsets: Sequence[int], elem_bytes):
+        offsets = list(offsets)
+        self._offs = (C.c_int64 * len(offsets))(*offsets)
+        self.m = len(offsets) - 1
+        self.c = _GatherDesc(rows, cols, dim, self.m, C.cast(self._offs, C.POINTER(C.c_int64)), elem_bytes)
+
+
 class LinearDesc:
     """Python mirror of hap_linear_desc; keeps the offsets array alive."""
 
@@ -116,6 +131,7 @@ lib.hap_strerror.restype = C.c_char_p
 lib.hap_strerror.argtypes = [C.c_int]
 lib.hap_last_error.restype = C.c_char_p
 lib.hap_version.restype = C.c_char_p
+lib.hap_allgather_capacity.restype = C.c_int64
 for _n in ("hap_linear_fwd_workspace", "hap_linear_bwd_workspace", "hap_sfb_workspace", "hap_attn_bwd_workspace",
            "hap_layernorm_bwd_workspace", "hap_colsum_workspace", "hap_moe_linear_fwd_workspace", "hap_moe_linear_bwd_workspace"):
     if hasattr(lib, _n):
@@ -237,6 +253,22 @@ def hap_moe_linear_bwd(desc: MoeDesc, shard_index, X, W, preact, dY, rows, dX, d
     wp, wb = _ws(ws)
     _check(lib.hap_moe_linear_bwd(C.byref(desc.c), C.c_int(shard_index), _ptr(X), _ptr(W), _ptr(preact), _ptr(dY), _ptr(rows),
                                   _ptr(dX), _ptr(dW), C.c_int(dW_dtype), _ptr(dbias), wp, wb, _stream(stream)), "hap_moe_linear_bwd")
+
+
+def hap_allgather_capacity(desc: GatherDesc) -> int:
+    return int(lib.hap_allgather_capacity(C.byref(desc.c)))
+
+
+def hap_allgather_pad(desc: GatherDesc, shard_index, shard, ld_shard, slot, ld_slot, stream=None):
+    _check(lib.hap_allgather_pad(C.byref(desc.c), C.c_int(shard_index), _ptr(shard), C.c_int64(ld_shard), _ptr(slot), C.c_int64(ld_slot),
+                                 _stream(stream)), "hap_allgather_pad")
+
+
+def hap_allgather_assemble(desc: GatherDesc, pieces, ld_pieces, out, ld_out, stream=None):
+    m = desc.m
+    pp = (C.c_void_p * m)(*[_ptr(t) for t in pieces])
+    _check(lib.hap_allgather_assemble(C.byref(desc.c), pp, (C.c_int64 * m)(*map(int, ld_pieces)), _ptr(out), C.c_int64(ld_out),
+                                      _stream(stream)), "hap_allgather_assemble")
 
 
 def hap_attn_bwd_workspace(desc: AttnDesc, shard_index: int) -> int:

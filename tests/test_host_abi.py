@@ -142,3 +142,25 @@ def test_moe_host_side_argument_errors(hap):
     assert hap.lib.hap_moe_linear_bwd(C.byref(d.c), 0, one, one, one, one, z, one, one, 1, z, z, C.c_size_t(0), z) == 5   # workspace missing
     assert hap.lib.hap_moe_linear_bwd(C.byref(d.c), 0, one, one, z, one, z, one, one, 1, z, one, C.c_size_t(need), z) == 1  # no saved pre-activation
     assert hap.lib.hap_moe_linear_bwd(C.byref(d.c), 0, one, one, one, one, z, one, one, 7, z, one, C.c_size_t(need), z) == 1  # bad dW dtype
+
+
+def test_allgather_host_side_argument_errors(hap):
+    """Uneven All-Gather data movement (Sec. 2.3.1): descriptor checks and the padded-slot capacity need no GPU."""
+    z = C.c_void_p(0)
+    d = hap.GatherDesc(100, 64, 0, [0, 50, 81, 100], 2)
+    assert hap.hap_allgather_capacity(d) == 50
+    d1 = hap.GatherDesc(64, 100, 1, [0, 10, 10, 100], 4)
+    assert hap.hap_allgather_capacity(d1) == 90
+    assert hap.hap_allgather_capacity(hap.GatherDesc(100, 64, 0, [0, 50, 99], 2)) == -1          # ranges do not end at the axis length
+    assert hap.hap_allgather_capacity(hap.GatherDesc(100, 64, 2, [0, 50, 100], 2)) == -1         # bad dim
+    assert hap.hap_allgather_capacity(hap.GatherDesc(100, 64, 0, [0, 50, 100], 3)) == -1         # bad element size
+    assert hap.lib.hap_allgather_pad(C.byref(d.c), 3, z, C.c_int64(64), z, C.c_int64(64), z) == 1   # device index out of range
+    assert hap.lib.hap_allgather_pad(C.byref(d.c), 0, z, C.c_int64(64), z, C.c_int64(64), z) == 1   # NULL pointers
+    one = C.c_void_p(256)
+    assert hap.lib.hap_allgather_pad(C.byref(d.c), 0, one, C.c_int64(63), one, C.c_int64(64), z) == 2   # ld below width
+    assert hap.lib.hap_allgather_pad(C.byref(d1.c), 1, z, C.c_int64(0), z, C.c_int64(0), z) == 0        # empty shard: OK, no launch
+    ptrs = (C.c_void_p * 3)(256, 0, 256)
+    lds = (C.c_int64 * 3)(10, 0, 89)
+    assert hap.lib.hap_allgather_assemble(C.byref(d1.c), ptrs, lds, one, C.c_int64(100), z) == 2    # piece 2: ld 89 < its 90 columns
+    assert hap.lib.hap_allgather_assemble(C.byref(d1.c), ptrs, lds, one, C.c_int64(99), z) == 2     # ld_out below cols
+    assert hap.lib.hap_allgather_assemble(C.byref(d1.c), z, lds, one, C.c_int64(100), z) == 1
