@@ -168,6 +168,48 @@ def main():
         res["moe_ffn_fwd_bwd_device0_ragged_tokens"] = moe_row(msizes[0], ragged)
         del mX, mdO, mW1, mW2
 
+    def cost_model_rows():
+        """Cost model of Sec. 3.2 fed with MEASURED kernel times (Sec. 7.7 checks the model's accuracy): the MLP block's
+        forward + backward time is fitted as alpha * B + beta through shards 0 and 2 and compared with the measured middle
+        shard; the fitted stage then goes through the LP for a range of All-Gather bandwidths next to the proportional (CP)
+        and even (EV) splits of Sec. 2.3 (predictions of the model, not measurements: one GPU, no exchange)."""
+        def t_block(sh, n=10):
+            for _ in range(2):
+                sh.forward(); sh.backward()
+            a = torch.cuda.Event(enable_timing=True); b = torch.cuda.Event(enable_timing=True)
+            a.record(stream)
+            for _ in range(n):
+                sh.forward(); sh.backward()
+            b.record(stream); b.synchronize()
+            return a.elapsed_time(b) / n * 1e-3
+        gen7 = torch.Generator(device=dev); gen7.manual_seed(7)
+        W1r = (torch.randn((h, F), generator=gen7, device=dev) * 0.02).to(torch.bfloat16)
+        W2r = (torch.randn((F, h), generator=gen7, device=dev) * 0.02).to(torch.bfloat16)
+        b1r = torch.zeros((F,), dtype=torch.bfloat16, device=dev)
+        mid = MlpShard(Tn, h, F, offsets, 1, X, W1r, b1r, W2r, dOut)
+        del W1r, W2r
+        t0, t2, t1 = t_block(shards[0]), t_block(shards[1]), t_block(mid)
+        B0, B1, B2 = (sizes[j] / F for j in range(3))
+        alpha = (t0 - t2) / (B0 - B2); beta = t0 - alpha * B0
+        pred1 = alpha * B1 + beta
+        out = {"block_fwd_bwd_ms_by_shard": {str(sizes[0]): round(t0 * 1e3, 3), str(sizes[1]): round(t1 * 1e3, 3), str(sizes[2]): round(t2 * 1e3, 3)},
+               "fit_seconds": {"per_unit_ratio": round(alpha, 6), "fixed": round(beta, 6)},
+               "middle_shard_predicted_ms": round(pred1 * 1e3, 3), "middle_shard_error_pct": round(100 * (pred1 - t1) / t1, 2)}
+        # one stage: compute = (alpha * B_j + beta) / relative speed_j; communication = one All-Gather forward and one
+        # Reduce-Scatter backward of the block's [tokens x hidden] bf16 activations, time = bytes / bandwidth * max_j B_j
+        act_bytes = 2.0 * Tn * h * 2
+        speeds = list(w2.speeds)
+        cp = [v / sum(speeds) for v in speeds]; ev = [1.0 / len(speeds)] * len(speeds)
+        table = []
+        for bw in (1.25e9, 2.5e9, 5e9, 12.5e9, 50e9, 200e9, 900e9):      # 10 GbE ... xGMI-class
+            st = [(alpha, beta, 0.0, act_bytes / bw)]
+            Blp, tlp = hap.hap_shard_ratios(speeds, st)
+            table.append({"allgather_GBps": bw / 1e9, "t_cp_ms": round(hap.hap_iteration_time(speeds, st, cp) * 1e3, 3),
+                          "t_ev_ms": round(hap.hap_iteration_time(speeds, st, ev) * 1e3, 3), "t_lp_ms": round(tlp * 1e3, 3),
+                          "B_lp": [round(v, 4) for v in Blp]})
+        out["cp_ev_lp_predictions"] = table
+        return out
+
     def other_rows():
         """Throughput of the path's remaining kernels, measured in this run; not part of `value`: attention slice and
         row / element ops at config 4's shard-0 shapes (16 x 5 heads x 1024 x 128; 16384 x 2048 rows), config 5's
@@ -335,6 +377,7 @@ def main():
         "setup_s": round(t_setup, 1),
         "achievable": ceilings(),
         "other_rows": other_rows(),
+        "cost_model": cost_model_rows(),
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(np, hapgen, T, w2, offsets)

@@ -74,6 +74,18 @@ int hap_shard_ratios(int m, const double* speed, int n_stages, const hap_stage* 
 int hap_iteration_time(int m, const double* speed, int n_stages, const hap_stage* st,
                        const double* ratios, double* seconds);
 
+/* Different ratios across the model (Sec. 5.2): the stages are cut into g consecutive segments
+ * [seg_offsets[k], seg_offsets[k+1]) (host array [g+1], 0 .. n_stages, no empty segment) and B becomes a
+ * g x m matrix, row k for the tensors of segment k.  An All-To-All re-shards at every segment boundary
+ * (its cost is the communication of the next segment's first stage), devices synchronise there, every
+ * stage lies inside one segment, so each segment is Eq. (opt_B) by itself.  ratios: [g*m] out, row-major;
+ * objective: sum of the segments' times (may be NULL).  hap_iteration_time_segments evaluates t for a
+ * given g x m matrix.                                                                             */
+int hap_shard_ratios_segments(int m, const double* speed, int n_stages, const hap_stage* st, int g, const int* seg_offsets,
+                              double* ratios, double* objective);
+int hap_iteration_time_segments(int m, const double* speed, int n_stages, const hap_stage* st, int g, const int* seg_offsets,
+                                const double* ratios, double* seconds);
+
 /* Sec. 5.1 rounding: sizes nearest to ratios[j]*dim_len, then +-1 on the shard whose size after the
  * move is closest to its target until they sum to dim_len (ties: .5 up, lowest device first, never
  * below 0).  Sizes are multiples of `granule` (>= 1, must divide dim_len).  offsets[j] = sum of the

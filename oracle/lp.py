@@ -58,3 +58,22 @@ def shard_ratios(speed, stages):
     B = np.clip(res.x[:m], 0.0, None)
     B = B / B.sum()
     return B, iteration_time(B, s, stages)
+
+
+def shard_ratios_segments(speed, stages, seg_offsets):
+    """Different ratios across the model (Sec. 5.2): stages [seg_offsets[k], seg_offsets[k+1]) form segment k, devices
+    synchronise at every boundary (where an All-To-All re-shards), so each segment is Eq. (opt_B) on its own stages.
+    Returns (g x m array, total seconds)."""
+    o = [int(v) for v in seg_offsets]
+    if o[0] != 0 or o[-1] != len(stages) or any(b <= a for a, b in zip(o, o[1:])):
+        raise ValueError("segments must be non-empty and cover all stages")
+    rows, total = [], 0.0
+    for a, b in zip(o, o[1:]):
+        B, t = shard_ratios(speed, stages[a:b])
+        rows.append(B); total += t
+    return np.array(rows), total
+
+
+def iteration_time_segments(B, speed, stages, seg_offsets) -> float:
+    o = [int(v) for v in seg_offsets]
+    return sum(iteration_time(B[k], speed, stages[a:b]) for k, (a, b) in enumerate(zip(o, o[1:])))

@@ -193,6 +193,26 @@ def hap_iteration_time(speed, stages, ratios) -> float:
     return sec.value
 
 
+def hap_shard_ratios_segments(speed: Sequence[float], stages, seg_offsets: Sequence[int]):
+    """Per-segment ratios (Sec. 5.2).  Returns (g x m list of lists, seconds)."""
+    m, g = len(speed), len(seg_offsets) - 1
+    out = (C.c_double * (g * m))()
+    obj = C.c_double()
+    _check(lib.hap_shard_ratios_segments(C.c_int(m), (C.c_double * m)(*map(float, speed)), C.c_int(len(stages)), _stages(stages), C.c_int(g),
+                                         (C.c_int * (g + 1))(*map(int, seg_offsets)), out, C.byref(obj)), "hap_shard_ratios_segments")
+    return [list(out[k * m:(k + 1) * m]) for k in range(g)], obj.value
+
+
+def hap_iteration_time_segments(speed, stages, seg_offsets, ratios) -> float:
+    m, g = len(speed), len(seg_offsets) - 1
+    flat = [float(v) for row in ratios for v in row]
+    sec = C.c_double()
+    _check(lib.hap_iteration_time_segments(C.c_int(m), (C.c_double * m)(*map(float, speed)), C.c_int(len(stages)), _stages(stages), C.c_int(g),
+                                           (C.c_int * (g + 1))(*map(int, seg_offsets)), (C.c_double * (g * m))(*flat), C.byref(sec)),
+           "hap_iteration_time_segments")
+    return sec.value
+
+
 def hap_round_shards(ratios: Sequence[float], dim_len: int, granule: int = 1):
     m = len(ratios)
     sizes = (C.c_int64 * m)()

@@ -252,6 +252,53 @@ int hap_shard_ratios(int m, const double* speed, int n_stages, const hap_stage* 
   return status;
 }
 
+/* ---------------------------------------------------------------- per-segment ratios (Sec. 5.2) --- */
+
+static int check_segments(int n_stages, int g, const int* seg_offsets) {
+  if (g < 1) return hap_fail(HAP_EINVAL, "g = %d < 1", g);
+  if (!seg_offsets) return hap_fail(HAP_EINVAL, "seg_offsets is NULL");
+  if (seg_offsets[0] != 0 || seg_offsets[g] != n_stages) return hap_fail(HAP_ESHAPE, "segments must cover stages [0, %d)", n_stages);
+  for (int k = 0; k < g; ++k)
+    if (seg_offsets[k + 1] <= seg_offsets[k]) return hap_fail(HAP_ESHAPE, "segment %d holds no stage", k);
+  return HAP_OK;
+}
+
+int hap_shard_ratios_segments(int m, const double* speed, int n_stages, const hap_stage* st, int g, const int* seg_offsets,
+                              double* ratios, double* objective) {
+  hap_clear_error();
+  int rc = check_lp_inputs(m, speed, n_stages, st);
+  if (rc) return rc;
+  if ((rc = check_segments(n_stages, g, seg_offsets))) return rc;
+  if (!ratios) return hap_fail(HAP_EINVAL, "ratios is NULL");
+  double total = 0.0;
+  for (int k = 0; k < g; ++k) {   /* a synchronisation point at every boundary: the segments are independent problems */
+    double sec = 0.0;
+    rc = hap_shard_ratios(m, speed, seg_offsets[k + 1] - seg_offsets[k], st + seg_offsets[k], ratios + (size_t)k * m, &sec);
+    if (rc) return rc;
+    total += sec;
+  }
+  if (objective) *objective = total;
+  return HAP_OK;
+}
+
+int hap_iteration_time_segments(int m, const double* speed, int n_stages, const hap_stage* st, int g, const int* seg_offsets,
+                                const double* ratios, double* seconds) {
+  hap_clear_error();
+  int rc = check_lp_inputs(m, speed, n_stages, st);
+  if (rc) return rc;
+  if ((rc = check_segments(n_stages, g, seg_offsets))) return rc;
+  if (!ratios || !seconds) return hap_fail(HAP_EINVAL, "ratios or seconds is NULL");
+  double total = 0.0;
+  for (int k = 0; k < g; ++k) {
+    double sec = 0.0;
+    rc = hap_iteration_time(m, speed, seg_offsets[k + 1] - seg_offsets[k], st + seg_offsets[k], ratios + (size_t)k * m, &sec);
+    if (rc) return rc;
+    total += sec;
+  }
+  *seconds = total;
+  return HAP_OK;
+}
+
 /* ---------------------------------------------------------------- rounding (Sec. 5.1) --- */
 
 int hap_round_shards(int m, const double* ratios, int64_t dim_len, int64_t granule,

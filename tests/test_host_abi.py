@@ -164,3 +164,27 @@ def test_allgather_host_side_argument_errors(hap):
     assert hap.lib.hap_allgather_assemble(C.byref(d1.c), ptrs, lds, one, C.c_int64(100), z) == 2    # piece 2: ld 89 < its 90 columns
     assert hap.lib.hap_allgather_assemble(C.byref(d1.c), ptrs, lds, one, C.c_int64(99), z) == 2     # ld_out below cols
     assert hap.lib.hap_allgather_assemble(C.byref(d1.c), z, lds, one, C.c_int64(100), z) == 1
+
+
+def test_segment_ratios_match_oracle(hap):
+    """Per-segment ratios (Sec. 5.2): objective parity with the oracle on random staged models, ratios where unique."""
+    from oracle import lp as olp
+    rng = np.random.default_rng(5)
+    for trial in range(20):
+        m = int(rng.integers(2, 6)); n = int(rng.integers(2, 9))
+        speed = rng.uniform(0.2, 2.0, m)
+        stages = [(float(rng.uniform(0, 5)), float(rng.uniform(0, 1)), float(rng.uniform(0, 0.2)), float(rng.uniform(0, 4))) for _ in range(n)]
+        cuts = sorted(set([0, n] + [int(c) for c in rng.integers(1, n, size=int(rng.integers(0, 3)))]))
+        Bo, to = olp.shard_ratios_segments(speed, stages, cuts)
+        B, t = hap.hap_shard_ratios_segments(speed, stages, cuts)
+        assert t == pytest.approx(to, rel=1e-9, abs=1e-12)
+        assert hap.hap_iteration_time_segments(speed, stages, cuts, B) == pytest.approx(t, rel=1e-12)
+        assert all(abs(sum(row) - 1) < 1e-12 and min(row) >= 0 for row in B)
+    B, t = hap.hap_shard_ratios_segments((3.0, 1.0), [(6.0, 0, 0, 0), (0, 0, 0.1, 4.0)], [0, 1, 2])
+    assert B[0] == pytest.approx([0.75, 0.25], abs=1e-12) and B[1] == pytest.approx([0.5, 0.5], abs=1e-12)
+    with pytest.raises(hap.HapError) as e:
+        hap.hap_shard_ratios_segments((1.0, 1.0), [(1, 0, 0, 0), (1, 0, 0, 0)], [0, 0, 2])
+    assert e.value.status == 2
+    with pytest.raises(hap.HapError) as e:
+        hap.hap_shard_ratios_segments((1.0, 1.0), [(1, 0, 0, 0), (1, 0, 0, 0)], [0, 1])
+    assert e.value.status == 2

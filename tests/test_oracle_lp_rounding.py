@@ -144,3 +144,27 @@ def test_rounding_granule():
     assert all(s % 128 == 0 for s in sizes) and sum(sizes) == 2048
     with pytest.raises(ValueError):
         rounding.round_shards([0.5, 0.5], 10, 3)
+
+
+def test_segment_ratios_sec_5_2():
+    """Different ratios across the model (Sec. 5.2): a compute-only segment gets ratios proportional to speed, a
+    communication-only one an even split; per-segment ratios are never slower than the best single B for the whole model
+    (any shared B is feasible for every segment); one segment is the base case; brute force on a two-device grid."""
+    speed = (3.0, 1.0)
+    stages = [(6.0, 0, 0, 0), (2.0, 0, 0, 0), (0, 0, 0.1, 4.0), (1.0, 0, 0.2, 3.0)]
+    B, t = lp.shard_ratios_segments(speed, stages, [0, 2, 3, 4])
+    np.testing.assert_allclose(B[0], [0.75, 0.25], atol=1e-9)          # compute only: proportional to speed (CP)
+    np.testing.assert_allclose(B[1], [0.5, 0.5], atol=1e-9)            # communication only: even (EV)
+    assert 0.5 - 1e-9 <= B[2][0] <= 0.75 + 1e-9                        # mixed: between EV and CP
+    assert t == pytest.approx(lp.iteration_time_segments(B, speed, stages, [0, 2, 3, 4]), rel=1e-12)
+    Bs, ts = lp.shard_ratios(speed, stages)
+    assert t <= ts + 1e-12 and t < ts - 1e-3                           # strictly better here: the segments want different ratios
+    B1, t1 = lp.shard_ratios_segments(speed, stages, [0, 4])
+    assert t1 == pytest.approx(ts, rel=1e-9)
+    # brute force: every segment's optimum over a fine grid of B_0 (m = 2)
+    grid = np.linspace(0, 1, 20001)
+    for k, (a, b) in enumerate([(0, 2), (2, 3), (3, 4)]):
+        best = min(lp.iteration_time([x, 1 - x], speed, stages[a:b]) for x in grid)
+        assert lp.iteration_time(B[k], speed, stages[a:b]) <= best + 1e-9
+    with pytest.raises(ValueError):
+        lp.shard_ratios_segments(speed, stages, [0, 2, 2, 4])
