@@ -99,3 +99,44 @@ def test_cfg3_sfb_full_size_sampled(hap):
     for i in range(len(rows)):
         hap.hap_sfb_grad([Xd[i]], [Yd[i]], [rows[i]], inf, outf, inf, outf, hap.BF16, naive, outf, accumulate=True)
     assert np.abs(host(naive) - got).max() <= 1e-3 * np.abs(got).max()
+
+
+def test_moe_expert_block_full_size_sampled(hap):
+    """The MoE row at the size bench.py times (device 0 of `moe_experts_bf16`: 10 experts x 2048 rows, hidden 768, ffn 3072), with
+    ragged token counts; sampled token rows (forward, bwd-data) and sampled ffn columns (weight / bias gradients) of three experts."""
+    from oracle import pointwise as opw
+    from paper_2401_05965_amd.programs import MoeExpertShard
+    torch = torch_mod()
+    w = hapgen.WORKLOADS["moe_experts_bf16"]
+    E, C, Hd, F = w.dims["experts"], w.dims["capacity"], w.dims["hidden"], w.dims["ffn"]
+    ratios, _ = hap.hap_shard_ratios(w.speeds, [(1.0, 0, 0, 0)])
+    sizes, offs = hap.hap_round_shards(ratios, E)
+    assert (sizes, offs) == ornd.round_shards(olp.shard_ratios(w.speeds, [(1.0, 0, 0, 0)])[0], E) and sizes == [10, 10, 5, 5]
+    n = sizes[0]
+    Xh, X = gen(8, T.X, (n, C, Hd), 1.0, "bf16"); dOh, dO = gen(8, T.DY, (n, C, Hd), 1.0, "bf16")
+    W1h, W1 = gen(8, T.W, (n, Hd, F), 0.02, "bf16"); b1h, b1 = gen(8, T.BIAS, (n, F), 0.02, "bf16")
+    W2h, W2 = gen(8, T.W2, (n, F, Hd), 0.02, "bf16"); b2h, b2 = gen(8, T.BETA, (n, Hd), 0.02, "bf16")
+    rng = np.random.default_rng(8)
+    rows = rng.integers(C // 2, C + 1, n); rows[0] = C; rows[3] = 1000; rows[n - 1] = 1
+    sh = MoeExpertShard(n, C, Hd, F, [0, n], 0, X, W1, b1, W2, b2, torch.from_numpy(rows.astype(np.int32)).cuda(), dO)
+    sh.forward(); sh.backward()
+    for e in (0, 3, n - 1):
+        ne = int(rows[e])
+        r = np.unique(np.concatenate([[0, ne - 1, min(255, ne - 1), min(256, ne - 1)], rng.integers(0, ne, 12)]))
+        pre = Xh[e][r] @ W1h[e] + b1h[e]
+        H = opw.gelu(pre)
+        check(f"H e{e}", host(sh.H[e][r]), H, "bf16")
+        check(f"out e{e}", host(sh.Out[e][r]), H @ W2h[e] + b2h[e], "bf16")
+        dH = dOh[e][r] @ W2h[e].T
+        check(f"dH e{e}", host(sh.dH[e][r]), dH, "bf16")
+        check(f"dX e{e}", host(sh.dX[e][r]), (dH * opw.gelu_grad(pre)) @ W1h[e].T, "bf16")
+        cols = np.unique(np.concatenate([[0, 255, 256, F - 1], rng.integers(0, F, 8)]))
+        Xe, dOe = Xh[e][:ne], dOh[e][:ne]
+        pre_c = Xe @ W1h[e][:, cols] + b1h[e][cols]
+        dP_c = (dOe @ W2h[e][cols].T) * opw.gelu_grad(pre_c)
+        check(f"dW1 e{e}", host(sh.dW1[e])[:, cols], Xe.T @ dP_c, "bf16")
+        check(f"db1 e{e}", host(sh.db1[e])[cols], dP_c.sum(0), "bf16")
+        check(f"dW2 e{e}", host(sh.dW2[e])[cols], opw.gelu(pre_c).T @ dOe, "bf16")
+        check(f"db2 e{e}", host(sh.db2[e]), dOe.sum(0), "bf16")
+        if ne < C:      # rows without a token stay as allocated (zero)
+            assert not host(sh.H[e][ne:]).any() and not host(sh.dX[e][ne:]).any()

@@ -98,3 +98,8 @@ def test_gather_cfg2_feature_shards_bf16(hap):
 
 def test_gather_many_devices(hap):
     run_case(hap, 4099, 40, 0, tuple(1.0 + 0.03 * i for i in range(64)), 2)
+
+
+def test_gather_cfg2_full_size(hap):
+    """The size bench.py times: config 2's [8192 x 16384] bf16 activations from three padded column slots, every byte compared."""
+    run_case(hap, 8192, 16384, 1, (1.0, 0.6, 0.35), 2)
