@@ -94,6 +94,44 @@ int hap_iteration_time_segments(int m, const double* speed, int n_stages, const 
 int hap_round_shards(int m, const double* ratios, int64_t dim_len, int64_t granule,
                      int64_t* sizes, int64_t* offsets);
 
+/* ------------------------------------------------------------------ host: program synthesis on small graphs --- */
+
+/* Sec. 4: a distributed program is synthesized for a single-device graph so that it provably produces
+ * the same loss.  Tensors are 2-D; node e's output is reference tensor e; inputs must be earlier nodes;
+ * the last node is the loss (a Sum).  A property (e, form) states which collective turns the
+ * distributed tensor into e on every device (Sec. 4.2); the theory holds the Hoare triples of
+ * Fig. "semantics" for MatMul and the collectives, the Grouped-Broadcast and replicated-MatMul rules
+ * of Sec. 4.4, and element-wise / transpose / sum rules of the same kind.  The search is the A* of
+ * Fig. "a*" with its dominance pruning; the score adds to the time so far (Sec. 3.2) what every device
+ * still has to compute with all remaining operations sharded and infinite bandwidth.  Restrictions: a
+ * tensor is communicated at most once, loaded tensors never (Sec. 4.5); every tensor is computed once,
+ * in graph order.  At most 16 nodes and 16 devices.                                                  */
+typedef enum { HAP_OP_PLACEHOLDER = 0, HAP_OP_PARAMETER = 1, HAP_OP_MATMUL = 2, HAP_OP_UNARY = 3, HAP_OP_ADD = 4,
+               HAP_OP_TRANSPOSE = 5, HAP_OP_SUM = 6 } hap_op;
+typedef struct { int op; int a, b; int64_t rows, cols; } hap_graph_node;   /* a, b: input nodes (-1: none); rows x cols: output */
+typedef enum { HAP_FORM_ID = 0, HAP_FORM_AG0 = 1, HAP_FORM_AG1 = 2, HAP_FORM_AR = 3 } hap_form;  /* replicated, sharded on 0 / 1, partial sums */
+typedef enum { HAP_I_PLACEHOLDER = 0, HAP_I_PLACEHOLDER_SHARD = 1, HAP_I_PARAMETER = 2, HAP_I_PARAMETER_SHARD = 3,
+               HAP_I_MATMUL = 4, HAP_I_UNARY = 5, HAP_I_ADD = 6, HAP_I_TRANSPOSE = 7, HAP_I_SUM = 8,
+               HAP_I_ALL_REDUCE = 9, HAP_I_REDUCE_SCATTER = 10, HAP_I_ALL_GATHER = 11, HAP_I_GROUPED_BROADCAST = 12,
+               HAP_I_ALL_TO_ALL = 13 } hap_instr_kind;
+/* tensor: the reference tensor the instruction produces (computations, loads) or moves (collectives).
+ * arg0, arg1: the sharded dimension of a *_SHARD load / Reduce-Scatter / All-Gather / Grouped-Broadcast,
+ * (from, to) dimensions of an All-To-All, the forms (hap_form) of the inputs of a computation.        */
+typedef struct { int kind; int tensor; int arg0, arg1; } hap_instr;
+typedef struct { double latency, bandwidth; int elem_bytes; } hap_net;   /* seconds, bytes/s: the fitted linear model of Sec. 3.2 */
+typedef struct { int placeholder_dims_mask, parameter_dims_mask;          /* bit d: the loads may shard dimension d       */
+                 int grouped_broadcast, replicated_matmul, placeholder_replicated; } hap_synth_rules;   /* NULL = everything on */
+
+/* The cheapest complete program for the given ratios (host pointers throughout).  program: room for
+ * `capacity` instructions (HAP_EWORKSPACE if too few); seconds = t(Q, B); expanded (may be NULL) =
+ * partial programs taken from the queue.  HAP_EINFEASIBLE if the rules admit no complete program.     */
+int hap_synthesize(int n_nodes, const hap_graph_node* graph, int m, const double* ratios, const double* speed,
+                   const hap_net* net, const hap_synth_rules* rules, hap_instr* program, int capacity, int* n_instr,
+                   double* seconds, int64_t* expanded);
+/* t(Q, B) of a given program (Sec. 3.2): a collective ends a stage; a stage costs its slowest device.  */
+int hap_program_time(int n_nodes, const hap_graph_node* graph, int n_instr, const hap_instr* program, int m,
+                     const double* ratios, const double* speed, const hap_net* net, double* seconds);
+
 /* ------------------------------------------------------------------ device: sharded linear --- */
 
 typedef enum { HAP_F32 = 0, HAP_BF16 = 1 } hap_dtype;

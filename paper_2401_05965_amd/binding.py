@@ -213,6 +213,89 @@ def hap_iteration_time_segments(speed, stages, seg_offsets, ratios) -> float:
     return sec.value
 
 
+class _GraphNode(C.Structure):
+    _fields_ = [("op", C.c_int), ("a", C.c_int), ("b", C.c_int), ("rows", C.c_int64), ("cols", C.c_int64)]
+
+
+class _Instr(C.Structure):
+    _fields_ = [("kind", C.c_int), ("tensor", C.c_int), ("arg0", C.c_int), ("arg1", C.c_int)]
+
+
+class _Net(C.Structure):
+    _fields_ = [("latency", C.c_double), ("bandwidth", C.c_double), ("elem_bytes", C.c_int)]
+
+
+class _SynthRules(C.Structure):
+    _fields_ = [("placeholder_dims_mask", C.c_int), ("parameter_dims_mask", C.c_int), ("grouped_broadcast", C.c_int),
+                ("replicated_matmul", C.c_int), ("placeholder_replicated", C.c_int)]
+
+
+OPS = {"placeholder": 0, "parameter": 1, "matmul": 2, "unary": 3, "add": 4, "transpose": 5, "sum": 6}
+INSTR_NAMES = ("placeholder", "placeholder-shard", "parameter", "parameter-shard", "matmul", "unary", "add", "transpose", "sum",
+               "all-reduce", "reduce-scatter", "all-gather", "grouped-broadcast", "all-to-all")
+FORM_NAMES = ("id", "ag0", "ag1", "ar")
+
+
+def _graph(nodes):
+    arr = (_GraphNode * len(nodes))()
+    for i, n in enumerate(nodes):
+        arr[i] = _GraphNode(OPS[n["op"]] if isinstance(n["op"], str) else n["op"], n.get("a", -1), n.get("b", -1), n["rows"], n["cols"])
+    return arr
+
+
+def _instr_tuple(i: _Instr):
+    """(name, tensor, args...) in the notation of the paper's figures: dimensions for loads and collectives, input forms for computations."""
+    name = INSTR_NAMES[i.kind]
+    if name in ("placeholder", "parameter", "all-reduce"):
+        return (name, i.tensor)
+    if name in ("placeholder-shard", "parameter-shard", "reduce-scatter", "all-gather", "grouped-broadcast"):
+        return (name, i.tensor, i.arg0)
+    if name == "all-to-all":
+        return (name, i.tensor, i.arg0, i.arg1)
+    if name == "matmul":
+        return (name, i.tensor, FORM_NAMES[i.arg0], FORM_NAMES[i.arg1])
+    return (name, i.tensor, FORM_NAMES[i.arg0])
+
+
+def _instr_struct(t):
+    name = t[0]
+    k = INSTR_NAMES.index(name)
+    if name == "matmul":
+        return _Instr(k, t[1], FORM_NAMES.index(t[2]), FORM_NAMES.index(t[3]))
+    if name in ("unary", "add", "transpose", "sum"):
+        return _Instr(k, t[1], FORM_NAMES.index(t[2]), 0)
+    args = list(t[2:]) + [0, 0]
+    return _Instr(k, t[1], args[0], args[1])
+
+
+def hap_synthesize(nodes, ratios, speed, net, rules=None, capacity=64):
+    """nodes: list of dicts (op, a, b, rows, cols); net: dict(latency, bandwidth, elem_bytes); rules: dict of the
+    hap_synth_rules fields or None.  Returns (program as list of tuples, seconds, partial programs expanded)."""
+    m = len(ratios)
+    prog = (_Instr * capacity)()
+    n = C.c_int(); sec = C.c_double(); exp = C.c_int64()
+    r = None
+    if rules is not None:
+        dm = lambda dims: sum(1 << d for d in dims)
+        r = C.byref(_SynthRules(dm(rules.get("placeholder_dims", (0, 1))), dm(rules.get("parameter_dims", (0, 1))),
+                                int(rules.get("grouped_broadcast", True)), int(rules.get("replicated_matmul", True)),
+                                int(rules.get("placeholder_replicated", True))))
+    _check(lib.hap_synthesize(C.c_int(len(nodes)), _graph(nodes), C.c_int(m), (C.c_double * m)(*map(float, ratios)),
+                              (C.c_double * m)(*map(float, speed)), C.byref(_Net(net["latency"], net["bandwidth"], net["elem_bytes"])), r,
+                              prog, C.c_int(capacity), C.byref(n), C.byref(sec), C.byref(exp)), "hap_synthesize")
+    return [_instr_tuple(prog[i]) for i in range(n.value)], sec.value, exp.value
+
+
+def hap_program_time(nodes, program, ratios, speed, net) -> float:
+    m = len(ratios)
+    arr = (_Instr * max(len(program), 1))(*[_instr_struct(t) for t in program])
+    sec = C.c_double()
+    _check(lib.hap_program_time(C.c_int(len(nodes)), _graph(nodes), C.c_int(len(program)), arr, C.c_int(m), (C.c_double * m)(*map(float, ratios)),
+                                (C.c_double * m)(*map(float, speed)), C.byref(_Net(net["latency"], net["bandwidth"], net["elem_bytes"])),
+                                C.byref(sec)), "hap_program_time")
+    return sec.value
+
+
 def hap_round_shards(ratios: Sequence[float], dim_len: int, granule: int = 1):
     m = len(ratios)
     sizes = (C.c_int64 * m)()

@@ -10,7 +10,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libhap.so")
 HIP_SOURCES = ["hap_gemm.hip", "hap_ops.hip", "hap_linear.hip", "hap_moe.hip", "hap_gather.hip", "hap_attn.hip"]
-C_SOURCES = ["hap_host.c"]
+C_SOURCES = ["hap_host.c", "hap_synth.c"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 HIP_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
              "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

@@ -1,0 +1,104 @@
+"""The library's A* synthesizer (Sec. 4.3, Fig. "a*") against the exhaustive-enumeration oracle: same optimal time on every case,
+a program that is one of the oracle's optimal programs, and the same cost model t(Q, B) on arbitrary programs.  Host only."""
+import numpy as np
+import pytest
+
+from oracle import synth as S
+
+
+@pytest.fixture(scope="module")
+def hap():
+    import paper_2401_05965_amd as h
+    return h
+
+
+def mlp(b, h, f, tail_unary=False):
+    g = [S.node("placeholder", rows=b, cols=h), S.node("parameter", rows=h, cols=f), S.node("matmul", 0, 1, b, f), S.node("unary", 2, rows=b, cols=f),
+         S.node("parameter", rows=f, cols=h), S.node("matmul", 3, 4, b, h)]
+    if tail_unary:
+        g.append(S.node("unary", 5, rows=b, cols=h))
+    g.append(S.node("sum", len(g) - 1))
+    return g
+
+
+def two_inputs(b, h, f, k):
+    """loss = sum(y (unary(x w))): the second product consumes a computed tensor as its right operand."""
+    return [S.node("placeholder", rows=b, cols=h), S.node("parameter", rows=h, cols=f), S.node("matmul", 0, 1, b, f), S.node("unary", 2, rows=b, cols=f),
+            S.node("placeholder", rows=k, cols=b), S.node("matmul", 4, 3, k, f), S.node("sum", 5)]
+
+
+def check(hap, g, B, speed, net, rules=None):
+    t, ties, _ = S.best_program(g, B, speed, net, **(rules or {}))
+    prog, sec, expanded = hap.hap_synthesize(g, B, speed, net, rules)
+    assert sec == pytest.approx(t, rel=1e-12)
+    assert prog in ties, (prog, ties[:3])
+    assert hap.hap_program_time(g, prog, B, speed, net) == pytest.approx(sec, rel=1e-12)
+    return prog, expanded
+
+
+def test_worked_example_program_7(hap):
+    """Fig. "a*_example": the search arrives at Placeholder-Shard(0), Parameter, MatMul, Sum in five loops."""
+    g = [S.node("placeholder", rows=64, cols=128), S.node("parameter", rows=128, cols=256), S.node("matmul", 0, 1, 64, 256), S.node("sum", 2)]
+    rules = dict(placeholder_dims=(0,), parameter_dims=(1,), grouped_broadcast=False, replicated_matmul=False, placeholder_replicated=False)
+    prog, expanded = check(hap, g, [0.5, 0.5], [1e12, 1e12], dict(latency=1e-5, bandwidth=1e10, elem_bytes=4), rules)
+    assert prog == [("placeholder-shard", 0, 0), ("parameter", 1), ("matmul", 2, "ag0", "id"), ("sum", 3, "ag0")]
+    assert expanded == 5
+
+
+def test_random_cases_match_exhaustive_search(hap):
+    rng = np.random.default_rng(11)
+    seen = set()
+    for trial in range(40):
+        m = int(rng.integers(2, 5))
+        B = rng.dirichlet(np.ones(m) * 2); speed = rng.uniform(0.3, 2.0, m) * 1e12
+        net = dict(latency=float(10 ** rng.uniform(-7, -4)), bandwidth=float(10 ** rng.uniform(8, 11.5)), elem_bytes=int(rng.choice([2, 4])))
+        kind = trial % 4
+        if kind == 0:
+            g = mlp(int(rng.integers(4, 512)), int(rng.integers(8, 256)), int(rng.integers(8, 512)))
+        elif kind == 1:
+            g = mlp(int(rng.integers(4, 512)), int(rng.integers(8, 256)), int(rng.integers(8, 512)), tail_unary=True)
+        else:
+            g = two_inputs(int(rng.integers(4, 2048)), int(rng.integers(8, 128)), int(rng.integers(8, 128)), int(rng.integers(4, 64)))
+        rules = None
+        if kind == 1:      # the input cannot be sharded: the feature / reduction pair leaves partial sums in front of a non-linear op
+            rules = dict(placeholder_dims=())
+        if kind == 3:      # loads restricted so that a computed tensor has to be gathered or recomputed replicated
+            rules = dict(placeholder_dims=(0,), parameter_dims=(), grouped_broadcast=True, replicated_matmul=bool(trial % 8 == 3), placeholder_replicated=False)
+        prog, _ = check(hap, g, list(B), list(speed), net, rules)
+        seen |= {ins[0] for ins in prog}
+    assert {"reduce-scatter", "placeholder-shard", "parameter-shard"} <= seen
+    assert seen & {"all-gather", "grouped-broadcast"}
+
+
+def test_padded_all_gather_versus_grouped_broadcast(hap):
+    """Sec. 2.3.1 / Sec. 4.4: with an even split the padded All-Gather (one launch) wins, with a skewed split the grouped
+    Broadcast (no padding) does; the search keeps whichever is cheaper under the given ratios."""
+    g = two_inputs(4096, 64, 64, 32)
+    rules = dict(placeholder_dims=(0,), parameter_dims=(), grouped_broadcast=True, replicated_matmul=False, placeholder_replicated=False)
+    net = dict(latency=2e-5, bandwidth=2e9, elem_bytes=4)
+    speed = [1e12] * 4
+    even, _ = check(hap, g, [0.25] * 4, speed, net, rules)
+    skew, _ = check(hap, g, [0.7, 0.1, 0.1, 0.1], speed, net, rules)
+    assert any(i[0] == "all-gather" for i in even) and not any(i[0] == "grouped-broadcast" for i in even)
+    assert any(i[0] == "grouped-broadcast" for i in skew) and not any(i[0] == "all-gather" for i in skew)
+
+
+def test_cost_model_on_arbitrary_programs_and_errors(hap):
+    g = mlp(12, 8, 10, tail_unary=True)
+    B, speed, net = [0.5, 0.3, 0.2], [2e9, 1e9, 0.5e9], dict(latency=1e-3, bandwidth=1e6, elem_bytes=2)
+    for i, prog in enumerate(S.all_programs(g)):
+        if i % 97 == 0:
+            assert hap.hap_program_time(g, prog, B, speed, net) == pytest.approx(S.program_time(g, prog, B, speed, net), rel=1e-12)
+    with pytest.raises(hap.HapError) as e:       # no way to get a partial-sum loss if nothing may be sharded
+        hap.hap_synthesize(g, B, speed, net, dict(placeholder_dims=(), parameter_dims=()))
+    assert e.value.status == 3
+    with pytest.raises(hap.HapError) as e:
+        hap.hap_synthesize(g, B, speed, net, capacity=3)
+    assert e.value.status == 5
+    bad = [dict(n) for n in g]; bad[2]["a"] = 5
+    with pytest.raises(hap.HapError) as e:
+        hap.hap_synthesize(bad, B, speed, net)
+    assert e.value.status == 2
+    with pytest.raises(hap.HapError) as e:
+        hap.hap_synthesize(g[:-1], B, speed, net)
+    assert e.value.status == 1
