@@ -132,6 +132,18 @@ int hap_synthesize(int n_nodes, const hap_graph_node* graph, int m, const double
 int hap_program_time(int n_nodes, const hap_graph_node* graph, int n_instr, const hap_instr* program, int m,
                      const double* ratios, const double* speed, const hap_net* net, double* seconds);
 
+/* The stages of a program as Eq. (opt_B) takes them: stages[0] is the computation before the first
+ * collective, every collective opens a new stage.  hap_iteration_time on the result equals
+ * hap_program_time on the program.  stages: room for `capacity` (HAP_EWORKSPACE if too few).          */
+int hap_program_stages(int n_nodes, const hap_graph_node* graph, int n_instr, const hap_instr* program, int m,
+                       const hap_net* net, hap_stage* stages, int capacity, int* n_stages);
+/* The iterative optimisation of Sec. 3.1: Q(s) = argmin_Q t(Q, B(s-1)), B(s) = argmin_B t(Q(s), B), from
+ * ratios proportional to speed, until a step brings no gain or max_steps is reached; returns the best
+ * (program, ratios[m], seconds) seen and the number of steps taken.                                   */
+int hap_optimize(int n_nodes, const hap_graph_node* graph, int m, const double* speed, const hap_net* net,
+                 const hap_synth_rules* rules, int max_steps, hap_instr* program, int capacity, int* n_instr,
+                 double* ratios, double* seconds, int* steps);
+
 /* ------------------------------------------------------------------ device: sharded linear --- */
 
 typedef enum { HAP_F32 = 0, HAP_BF16 = 1 } hap_dtype;

@@ -165,3 +165,40 @@ def best_program(graph, B, speed, net, **rules):
         elif t <= best * (1 + 1e-12):
             ties.append(prog)
     return best, ties, count
+
+
+def program_stages(graph, program, m, net):
+    """The program's stages as (F, G, a, c) tuples for the load balancer (Sec. 5.1): F flops that scale with the ratio,
+    G flops that do not, a + c * max_j B_j the time of the collective that opens the stage."""
+    stages = [[0.0, 0.0, 0.0, 0.0]]
+    for ins in program:
+        if ins[0] in COMM:
+            a = comm_time(graph, ins, [0.0] * m, net)
+            c = comm_time(graph, ins, [1.0] + [0.0] * (m - 1), net) - a
+            stages.append([0.0, 0.0, a, c])
+        else:
+            f1, f0 = flops(graph, ins, 1.0), flops(graph, ins, 0.0)
+            stages[-1][0] += f1 - f0
+            stages[-1][1] += f0
+    return [tuple(s) for s in stages]
+
+
+def optimize(graph, speed, net, max_steps=10, **rules):
+    """The alternating optimisation of Sec. 3.1 with exhaustive synthesis and the LP oracle: returns the sequence of
+    (t(Q(s), B(s-1)), t(Q(s), B(s))) per step and the best time seen."""
+    from . import lp
+    m = len(speed)
+    B = [s / sum(speed) for s in speed]
+    history, best, prev = [], float("inf"), float("inf")
+    for _ in range(max_steps):
+        tq, ties, _ = best_program(graph, B, speed, net, **rules)
+        # among equally cheap programs the load balancer may do better with one than another: take the best of them
+        cand = [lp.shard_ratios(speed, program_stages(graph, p, m, net)) for p in ties]
+        Bn, tb = min(cand, key=lambda x: x[1])
+        history.append((tq, tb))
+        best = min(best, tq, tb)
+        B = list(Bn)
+        if not tb < prev * (1 - 1e-12):
+            break
+        prev = tb
+    return history, best

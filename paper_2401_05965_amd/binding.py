@@ -286,6 +286,38 @@ def hap_synthesize(nodes, ratios, speed, net, rules=None, capacity=64):
     return [_instr_tuple(prog[i]) for i in range(n.value)], sec.value, exp.value
 
 
+def _rules(rules):
+    if rules is None:
+        return None
+    dm = lambda dims: sum(1 << d for d in dims)
+    return C.byref(_SynthRules(dm(rules.get("placeholder_dims", (0, 1))), dm(rules.get("parameter_dims", (0, 1))),
+                               int(rules.get("grouped_broadcast", True)), int(rules.get("replicated_matmul", True)),
+                               int(rules.get("placeholder_replicated", True))))
+
+
+def hap_program_stages(nodes, program, m, net, capacity=64):
+    """Stage tuples (flops_sharded, flops_fixed, comm_latency, comm_per_ratio) of a program, as hap_shard_ratios takes them."""
+    arr = (_Instr * max(len(program), 1))(*[_instr_struct(t) for t in program])
+    st = (Stage * capacity)()
+    n = C.c_int()
+    _check(lib.hap_program_stages(C.c_int(len(nodes)), _graph(nodes), C.c_int(len(program)), arr, C.c_int(m),
+                                  C.byref(_Net(net["latency"], net["bandwidth"], net["elem_bytes"])), st, C.c_int(capacity), C.byref(n)),
+           "hap_program_stages")
+    return [(st[i].flops_sharded, st[i].flops_fixed, st[i].comm_latency, st[i].comm_per_ratio) for i in range(n.value)]
+
+
+def hap_optimize(nodes, speed, net, rules=None, max_steps=10, capacity=64):
+    """Alternating optimisation of Sec. 3.1.  Returns (program, ratios, seconds, steps)."""
+    m = len(speed)
+    prog = (_Instr * capacity)()
+    n = C.c_int(); sec = C.c_double(); steps = C.c_int()
+    B = (C.c_double * m)()
+    _check(lib.hap_optimize(C.c_int(len(nodes)), _graph(nodes), C.c_int(m), (C.c_double * m)(*map(float, speed)),
+                            C.byref(_Net(net["latency"], net["bandwidth"], net["elem_bytes"])), _rules(rules), C.c_int(max_steps),
+                            prog, C.c_int(capacity), C.byref(n), B, C.byref(sec), C.byref(steps)), "hap_optimize")
+    return [_instr_tuple(prog[i]) for i in range(n.value)], list(B), sec.value, steps.value
+
+
 def hap_program_time(nodes, program, ratios, speed, net) -> float:
     m = len(ratios)
     arr = (_Instr * max(len(program), 1))(*[_instr_struct(t) for t in program])

@@ -174,6 +174,71 @@ int hap_program_time(int n_nodes, const hap_graph_node* graph, int n_instr, cons
   return HAP_OK;
 }
 
+/* The stages of a program in the form Eq. (opt_B) takes (Sec. 3.2): a collective opens a stage; its time is
+ * latency + per_ratio * max_j B_j; the stage's computation is (sharded * B_j + fixed) / speed_j. */
+int hap_program_stages(int n_nodes, const hap_graph_node* graph, int n_instr, const hap_instr* program, int m,
+                       const hap_net* net, hap_stage* stages, int capacity, int* n_stages) {
+  hap_clear_error();
+  int rc = check_graph(n_nodes, graph);
+  if (rc) return rc;
+  if (m < 1 || m > MAX_DEV || !net) return hap_fail(HAP_EINVAL, "bad m or NULL network model");
+  if (n_instr < 0 || (n_instr > 0 && !program) || !stages || !n_stages || capacity < 1) return hap_fail(HAP_EINVAL, "bad program or no room for stages");
+  int ns = 0;
+  memset(&stages[0], 0, sizeof(hap_stage));
+  for (int i = 0; i < n_instr; ++i) {
+    if (program[i].tensor < 0 || program[i].tensor >= n_nodes) return hap_fail(HAP_EINVAL, "instruction %d names no tensor of the graph", i);
+    if (is_comm(program[i].kind)) {
+      if (++ns >= capacity) return hap_fail(HAP_EWORKSPACE, "more than %d stages", capacity);
+      memset(&stages[ns], 0, sizeof(hap_stage));
+      /* comm_seconds() is affine in the largest ratio: read off its two coefficients */
+      stages[ns].comm_latency = comm_seconds(graph, &program[i], m, 0.0, net);
+      stages[ns].comm_per_ratio = comm_seconds(graph, &program[i], m, 1.0, net) - stages[ns].comm_latency;
+    } else {
+      const double f1 = instr_flops(graph, &program[i], 1.0), f0 = instr_flops(graph, &program[i], 0.0);
+      stages[ns].flops_sharded += f1 - f0;
+      stages[ns].flops_fixed += f0;
+    }
+  }
+  *n_stages = ns + 1;
+  return HAP_OK;
+}
+
+/* Sec. 3.1: alternate Q(s) = argmin_Q t(Q, B(s-1)) and B(s) = argmin_B t(Q(s), B), starting from ratios proportional to the
+ * speeds, until the pair repeats or max_steps is reached; the best pair seen is returned. */
+int hap_optimize(int n_nodes, const hap_graph_node* graph, int m, const double* speed, const hap_net* net,
+                 const hap_synth_rules* rules, int max_steps, hap_instr* program, int capacity, int* n_instr,
+                 double* ratios, double* seconds, int* steps) {
+  hap_clear_error();
+  if (!speed || !ratios || !program || !n_instr) return hap_fail(HAP_EINVAL, "NULL argument");
+  if (m < 1 || m > MAX_DEV) return hap_fail(HAP_EUNSUPPORTED, "m = %d outside [1, %d]", m, MAX_DEV);
+  if (max_steps < 1) max_steps = 1;
+  double B[MAX_DEV], total = 0.0, best_t = INFINITY, prev_t = INFINITY;
+  for (int j = 0; j < m; ++j) { if (!(speed[j] > 0.0)) return hap_fail(HAP_EINVAL, "speed[%d] must be positive", j); total += speed[j]; }
+  for (int j = 0; j < m; ++j) B[j] = speed[j] / total;
+  hap_instr* cur = (hap_instr*)malloc(sizeof(hap_instr) * (size_t)capacity);
+  hap_stage* st = (hap_stage*)malloc(sizeof(hap_stage) * (size_t)(capacity + 1));
+  if (!cur || !st) { free(cur); free(st); return hap_fail(HAP_EINVAL, "out of host memory"); }
+  int rc = HAP_OK, s = 0;
+  for (s = 1; s <= max_steps; ++s) {
+    int len = 0, ns = 0;
+    double tq = 0.0, tb = 0.0;
+    if ((rc = hap_synthesize(n_nodes, graph, m, B, speed, net, rules, cur, capacity, &len, &tq, NULL))) break;
+    if (tq < best_t) { best_t = tq; memcpy(program, cur, sizeof(hap_instr) * (size_t)len); *n_instr = len; memcpy(ratios, B, sizeof(double) * (size_t)m); }
+    if ((rc = hap_program_stages(n_nodes, graph, len, cur, m, net, st, capacity + 1, &ns))) break;
+    double Bn[MAX_DEV];
+    if ((rc = hap_shard_ratios(m, speed, ns, st, Bn, &tb))) break;
+    if (tb < best_t) { best_t = tb; memcpy(program, cur, sizeof(hap_instr) * (size_t)len); *n_instr = len; memcpy(ratios, Bn, sizeof(double) * (size_t)m); }
+    memcpy(B, Bn, sizeof(double) * (size_t)m);
+    if (!(tb < prev_t * (1.0 - 1e-12))) break;      /* no further gain: converged (or about to oscillate) */
+    prev_t = tb;
+  }
+  free(cur); free(st);
+  if (rc) return rc;
+  if (seconds) *seconds = best_t;
+  if (steps) *steps = s > max_steps ? max_steps : s;
+  return HAP_OK;
+}
+
 /* A partial program: its last instruction and its parent (the program is the chain back to the root). */
 typedef struct {
   int parent;

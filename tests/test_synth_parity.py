@@ -102,3 +102,51 @@ def test_cost_model_on_arbitrary_programs_and_errors(hap):
     with pytest.raises(hap.HapError) as e:
         hap.hap_synthesize(g[:-1], B, speed, net)
     assert e.value.status == 1
+
+
+def test_program_stages_feed_the_load_balancer(hap):
+    """A program's stages in Eq. (opt_B)'s form reproduce t(Q, B) for any B, on both sides."""
+    from oracle import lp as olp
+    g = mlp(48, 32, 64, tail_unary=True)
+    net = dict(latency=3e-5, bandwidth=4e9, elem_bytes=2)
+    speed = [2e12, 1e12, 0.5e12]
+    rng = np.random.default_rng(3)
+    for i, prog in enumerate(S.all_programs(g)):
+        if i % 211:
+            continue
+        st = hap.hap_program_stages(g, prog, 3, net)
+        so = S.program_stages(g, prog, 3, net)
+        assert len(st) == len(so) and all(a == pytest.approx(b, rel=1e-12, abs=1e-30) for x, y in zip(st, so) for a, b in zip(x, y))
+        B = list(rng.dirichlet(np.ones(3)))
+        assert hap.hap_iteration_time(speed, st, B) == pytest.approx(hap.hap_program_time(g, prog, B, speed, net), rel=1e-12)
+        assert olp.iteration_time(B, speed, so) == pytest.approx(S.program_time(g, prog, B, speed, net), rel=1e-12)
+
+
+def test_alternating_optimisation_sec_3_1(hap):
+    """Q and B optimised in turn from ratios proportional to speed: the returned time is t(Q, B) of the returned pair; it is
+    never worse than the best program at the initial ratios; the returned ratios are optimal for the returned program (LP
+    oracle on the oracle's stages); and it is at least as good as the first full step of the oracle's own alternation."""
+    from oracle import lp as olp
+    rng = np.random.default_rng(21)
+    for trial in range(12):
+        m = int(rng.integers(2, 5))
+        speed = list(rng.uniform(0.3, 2.0, m) * 1e12)
+        net = dict(latency=float(10 ** rng.uniform(-6, -4)), bandwidth=float(10 ** rng.uniform(8.5, 11)), elem_bytes=2)
+        if trial % 3 == 0:
+            g, rules = mlp(int(rng.integers(64, 512)), 64, 128, tail_unary=True), dict(placeholder_dims=())
+        elif trial % 3 == 1:
+            g, rules = two_inputs(int(rng.integers(256, 4096)), 64, 64, 32), dict(placeholder_dims=(0,), parameter_dims=(), placeholder_replicated=False)
+        else:
+            g, rules = mlp(int(rng.integers(64, 512)), 64, 128), None
+        prog, B, t, steps = hap.hap_optimize(g, speed, net, rules)
+        assert 1 <= steps <= 10 and abs(sum(B) - 1) < 1e-9 and min(B) >= 0
+        assert hap.hap_program_time(g, prog, B, speed, net) == pytest.approx(t, rel=1e-9)
+        B0 = [s / sum(speed) for s in speed]
+        t0, _, _ = S.best_program(g, B0, speed, net, **(rules or {}))
+        assert t <= t0 * (1 + 1e-12)
+        # B is optimal for the returned program (the load balancer's job), by the LP oracle on the oracle's stages
+        _, tb = olp.shard_ratios(speed, S.program_stages(g, prog, m, net))
+        assert t <= tb * (1 + 1e-9)
+        hist, best = S.optimize(g, speed, net, **(rules or {}))
+        assert hist[0][0] == pytest.approx(t0, rel=1e-12)
+        assert t <= hist[0][1] * (1 + 1e-9)          # at least the first full step's result
