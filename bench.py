@@ -31,6 +31,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--moe-only", action="store_true", help="only run the MoE expert rows (profiling aid)")
+    ap.add_argument("--main-only", action="store_true",
+                    help="timed step and roofline only: no ceilings, other_rows, cost_model or cpu_baseline (profiling aid)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run a plain 256 MiB device copy 10 times (reference for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
@@ -358,7 +360,7 @@ def main():
     achieved = call_flops[dom] / (per[dom] * 1e-3) / 1e12
     # HBM-side bytes of that launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (KiB), scaled by the factors a
     # plain 256 MiB copy gives (2.000 and 1.000); see profiles/gemm_dma_256x256x64_cfg2_cfg3.md
-    traffic_bytes = int((404690 * 2.000 + 65536 * 1.000) * 1024)
+    traffic_bytes = int((404685 * 2.000 + 65536 * 1.000) * 1024)
     out = {
         "metric": "TFLOP/s of sharded fwd+bwd + SFB dW at uneven ratios; % of MFMA peak",
         "value": round(value, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -375,11 +377,12 @@ def main():
         "calls_ms": {k: round(v, 4) for k, v in sorted(per.items())},
         "calls_tflops": {k: round(call_flops[k] / (per[k] * 1e-3) / 1e12, 1) for k in call_flops},
         "setup_s": round(t_setup, 1),
-        "achievable": ceilings(),
-        "other_rows": other_rows(),
-        "cost_model": cost_model_rows(),
     }
-    if not args.no_cpu_baseline:
+    if not args.main_only:
+        out["achievable"] = ceilings()
+        out["other_rows"] = other_rows()
+        out["cost_model"] = cost_model_rows()
+    if not args.no_cpu_baseline and not args.main_only:
         out["cpu_baseline"] = cpu_baseline(np, hapgen, T, w2, offsets)
     print(json.dumps(out))
 
