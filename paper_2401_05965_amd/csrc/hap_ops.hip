@@ -55,7 +55,8 @@ __global__ __launch_bounds__(256) void gelu_bwd_kernel(int64_t rows, int64_t col
   }
 }
 
-template <typename T, int V>
+/* out = a + b (+ bias per column).  BV: the bias can be fetched as one V-element chunk (its base is aligned like the rows). */
+template <typename T, int V, bool BV>
 __global__ __launch_bounds__(256) void add_kernel(int64_t rows, int64_t cols, const T* a, int64_t lda, const T* b,
                                                   int64_t ldb, const T* bias, T* out, int64_t ldo) {
   const int64_t cv = (cols + V - 1) / V;
@@ -64,11 +65,12 @@ __global__ __launch_bounds__(256) void add_kernel(int64_t rows, int64_t cols, co
     const int64_t r = i / cv, c = (i % cv) * V;
     Pack<T, V> x = *reinterpret_cast<const Pack<T, V>*>(a + r * lda + c);
     Pack<T, V> y = *reinterpret_cast<const Pack<T, V>*>(b + r * ldb + c);
-    Pack<T, V> o;
+    Pack<T, V> o, bb;
+    if (BV && bias) bb = *reinterpret_cast<const Pack<T, V>*>(bias + c);
 #pragma unroll
     for (int e = 0; e < V; ++e) {
       float v = (float)x.v[e] + (float)y.v[e];
-      if (bias) v += (float)bias[c + e];
+      if (bias) v += BV ? (float)bb.v[e] : (float)bias[c + e];
       o.v[e] = (T)v;
     }
     *reinterpret_cast<Pack<T, V>*>(out + r * ldo + c) = o;
@@ -78,7 +80,7 @@ __global__ __launch_bounds__(256) void add_kernel(int64_t rows, int64_t cols, co
 /* Column sums, stage 1: block (bx, by) sums rows [by*rpb, (by+1)*rpb) of the 64*V columns starting at
  * bx*64*V - skew.  `a` is the caller's pointer moved down by `skew` elements to a multiple of V
  * elements, so each lane reads one aligned V-element chunk per row (a chunk is read only when it
- * holds at least one wanted column).  The 4 waves stride over the rows, four rows in flight each, and
+ * holds at least one wanted column).  The 4 waves stride over the rows, eight rows in flight each, and
  * their partials meet in LDS.  partial[by][col] is fp32. */
 template <typename T, int V>
 __global__ __launch_bounds__(256) void colsum_partial_kernel(int64_t rows, int64_t cols, const T* a, int64_t lda, int skew,
@@ -101,12 +103,12 @@ __global__ __launch_bounds__(256) void colsum_partial_kernel(int64_t rows, int64
   if (c0 + V > 0 && c0 < cols) {
     const T* p = a + c0 + skew;
     int64_t r = r0 + wave;
-    for (; r + 12 < r1; r += 16) {
-      Pack<T, V> q[4];
+    for (; r + 28 < r1; r += 32) {
+      Pack<T, V> q[8];
 #pragma unroll
-      for (int u = 0; u < 4; ++u) q[u] = *reinterpret_cast<const Pack<T, V>*>(p + (r + 4 * u) * lda);
+      for (int u = 0; u < 8; ++u) q[u] = *reinterpret_cast<const Pack<T, V>*>(p + (r + 4 * u) * lda);
 #pragma unroll
-      for (int u = 0; u < 4; ++u)
+      for (int u = 0; u < 8; ++u)
 #pragma unroll
         for (int e = 0; e < V; ++e) s[e] += (float)q[u].v[e];
     }
@@ -316,7 +318,7 @@ inline int grid_for(int64_t work_items) {
 }
 
 constexpr int kLnBlocks = 512;    // layernorm backward: blocks (= partial rows of dgamma/dbeta)
-constexpr int kColsumRowsPerBlock = 64;
+constexpr int kColsumRowsPerBlock = 128;
 
 template <typename T>
 int gelu_bwd_t(int64_t rows, int64_t cols, const void* pre, int64_t ldp, const void* dy, int64_t lddy, void* out, int64_t ldo, hipStream_t s) {
@@ -331,8 +333,9 @@ template <typename T>
 int add_t(int64_t rows, int64_t cols, const void* a, int64_t lda, const void* b, int64_t ldb, const void* bias, void* out, int64_t ldo, hipStream_t s) {
   constexpr int V = 16 / sizeof(T);
   const bool vec = cols % V == 0 && lda % V == 0 && ldb % V == 0 && ldo % V == 0 && aligned16(a) && aligned16(b) && aligned16(out);
-  if (vec) hipLaunchKernelGGL((add_kernel<T, V>), dim3(grid_for(rows * (cols / V))), dim3(256), 0, s, rows, cols, (const T*)a, lda, (const T*)b, ldb, (const T*)bias, (T*)out, ldo);
-  else hipLaunchKernelGGL((add_kernel<T, 1>), dim3(grid_for(rows * cols)), dim3(256), 0, s, rows, cols, (const T*)a, lda, (const T*)b, ldb, (const T*)bias, (T*)out, ldo);
+  if (vec && aligned16(bias)) hipLaunchKernelGGL((add_kernel<T, V, true>), dim3(grid_for(rows * (cols / V))), dim3(256), 0, s, rows, cols, (const T*)a, lda, (const T*)b, ldb, (const T*)bias, (T*)out, ldo);
+  else if (vec) hipLaunchKernelGGL((add_kernel<T, V, false>), dim3(grid_for(rows * (cols / V))), dim3(256), 0, s, rows, cols, (const T*)a, lda, (const T*)b, ldb, (const T*)bias, (T*)out, ldo);
+  else hipLaunchKernelGGL((add_kernel<T, 1, false>), dim3(grid_for(rows * cols)), dim3(256), 0, s, rows, cols, (const T*)a, lda, (const T*)b, ldb, (const T*)bias, (T*)out, ldo);
   return check_launch("add");
 }
 
@@ -455,7 +458,7 @@ int hap_colsum_grouped(int groups, int64_t rows, int64_t cols, int io_dtype, con
   const size_t need = hap_colsum_grouped_workspace(groups, rows, cols);
   if (!ws || ws_bytes < need) return hap_fail(HAP_EWORKSPACE, "colsum needs %zu workspace bytes", need);
   const int64_t parts = (rows + kColsumRowsPerBlock - 1) / kColsumRowsPerBlock;
-  if (parts > 65535) return hap_fail(HAP_EUNSUPPORTED, "colsum over more than 65535 * 64 rows");
+  if (parts > 65535) return hap_fail(HAP_EUNSUPPORTED, "colsum over more than 65535 * 128 rows");
   const int esz = io_dtype == HAP_BF16 ? 2 : 4, V = 16 / esz;
   const bool vec = (uintptr_t)a % esz == 0 && lda % V == 0 && (groups == 1 || group_stride % V == 0);
   const int skew = vec ? (int)(((uintptr_t)a % 16) / esz) : 0;
