@@ -38,7 +38,10 @@ __device__ __forceinline__ float gelu_grad(float x) {
 /* Vector of V elements of T moved as one access when V > 1. */
 template <typename T, int V> struct Pack { T v[V]; } __attribute__((aligned(sizeof(T) * V)));
 
-/* out[r,c] = dy[r,c] * gelu'(pre[r,c]); V elements per thread along the row (V = 1 handles any alignment). */
+/* out[r,c] = dy[r,c] * gelu'(pre[r,c]); V elements per thread along the row (V = 1 handles any alignment).  With V > 1 the
+ * leading dimensions are multiples of V, so the last chunk of a ragged row (cols % V != 0) is still read whole - the
+ * bytes lie inside the row's pitch, and an aligned chunk that starts inside an allocation cannot leave its page - and only
+ * its valid elements are stored. */
 template <typename T, int V>
 __global__ __launch_bounds__(256) void gelu_bwd_kernel(int64_t rows, int64_t cols, const T* pre, int64_t ldp,
                                                        const T* dy, int64_t lddy, T* out, int64_t ldo) {
@@ -51,7 +54,13 @@ __global__ __launch_bounds__(256) void gelu_bwd_kernel(int64_t rows, int64_t col
     Pack<T, V> o;
 #pragma unroll
     for (int e = 0; e < V; ++e) o.v[e] = (T)((float)g.v[e] * gelu_grad((float)p.v[e]));
-    *reinterpret_cast<Pack<T, V>*>(out + r * ldo + c) = o;
+    if (c + V <= cols) {
+      *reinterpret_cast<Pack<T, V>*>(out + r * ldo + c) = o;
+    } else {
+#pragma unroll
+      for (int e = 0; e < V; ++e)
+        if (c + e < cols) out[r * ldo + c + e] = o.v[e];
+    }
   }
 }
 
@@ -323,8 +332,8 @@ constexpr int kColsumRowsPerBlock = 128;
 template <typename T>
 int gelu_bwd_t(int64_t rows, int64_t cols, const void* pre, int64_t ldp, const void* dy, int64_t lddy, void* out, int64_t ldo, hipStream_t s) {
   constexpr int V = 16 / sizeof(T);
-  const bool vec = cols % V == 0 && ldp % V == 0 && lddy % V == 0 && ldo % V == 0 && aligned16(pre) && aligned16(dy) && aligned16(out);
-  if (vec) hipLaunchKernelGGL((gelu_bwd_kernel<T, V>), dim3(grid_for(rows * (cols / V))), dim3(256), 0, s, rows, cols, (const T*)pre, ldp, (const T*)dy, lddy, (T*)out, ldo);
+  const bool vec = ldp % V == 0 && lddy % V == 0 && ldo % V == 0 && aligned16(pre) && aligned16(dy) && aligned16(out);
+  if (vec) hipLaunchKernelGGL((gelu_bwd_kernel<T, V>), dim3(grid_for(rows * ((cols + V - 1) / V))), dim3(256), 0, s, rows, cols, (const T*)pre, ldp, (const T*)dy, lddy, (T*)out, ldo);
   else hipLaunchKernelGGL((gelu_bwd_kernel<T, 1>), dim3(grid_for(rows * cols)), dim3(256), 0, s, rows, cols, (const T*)pre, ldp, (const T*)dy, lddy, (T*)out, ldo);
   return check_launch("gelu_bwd");
 }

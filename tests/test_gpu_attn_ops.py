@@ -134,7 +134,7 @@ def test_layernorm_fwd_bwd(hap, dtype, rows, n):
 def test_gelu_bwd_add_colsum(hap, dtype):
     torch = torch_mod()
     io = {"bf16": 1, "f32": 0}[dtype]
-    for rows, cols, ld in [(300, 520, 520), (77, 137, 141), (1030, 64, 64)]:
+    for rows, cols, ld in [(300, 520, 520), (77, 137, 141), (1030, 64, 64), (77, 137, 144), (513, 2731, 2736), (5, 3, 8)]:   # incl. ragged widths on aligned pitches
         ph, pd = gen(4, T.X, (rows, ld), 1.5, dtype); dyh, dyd = gen(4, T.DY, (rows, ld), 1.0, dtype)
         out = empty((rows, ld), dtype, 0)
         hap.hap_gelu_bwd(rows, cols, io, pd, ld, dyd, ld, out, ld)
