@@ -42,7 +42,7 @@ template <typename T, int V> struct Pack { T v[V]; } __attribute__((aligned(size
  * leading dimensions are multiples of V, so the last chunk of a ragged row (cols % V != 0) is still read whole - the
  * bytes lie inside the row's pitch, and an aligned chunk that starts inside an allocation cannot leave its page - and only
  * its valid elements are stored. */
-template <typename T, int V>
+template <typename T, int V, bool RAGGED>
 __global__ __launch_bounds__(256) void gelu_bwd_kernel(int64_t rows, int64_t cols, const T* pre, int64_t ldp,
                                                        const T* dy, int64_t lddy, T* out, int64_t ldo) {
   const int64_t cv = (cols + V - 1) / V;
@@ -54,7 +54,7 @@ __global__ __launch_bounds__(256) void gelu_bwd_kernel(int64_t rows, int64_t col
     Pack<T, V> o;
 #pragma unroll
     for (int e = 0; e < V; ++e) o.v[e] = (T)((float)g.v[e] * gelu_grad((float)p.v[e]));
-    if (c + V <= cols) {
+    if (!RAGGED || c + V <= cols) {
       *reinterpret_cast<Pack<T, V>*>(out + r * ldo + c) = o;
     } else {
 #pragma unroll
@@ -333,8 +333,9 @@ template <typename T>
 int gelu_bwd_t(int64_t rows, int64_t cols, const void* pre, int64_t ldp, const void* dy, int64_t lddy, void* out, int64_t ldo, hipStream_t s) {
   constexpr int V = 16 / sizeof(T);
   const bool vec = ldp % V == 0 && lddy % V == 0 && ldo % V == 0 && aligned16(pre) && aligned16(dy) && aligned16(out);
-  if (vec) hipLaunchKernelGGL((gelu_bwd_kernel<T, V>), dim3(grid_for(rows * ((cols + V - 1) / V))), dim3(256), 0, s, rows, cols, (const T*)pre, ldp, (const T*)dy, lddy, (T*)out, ldo);
-  else hipLaunchKernelGGL((gelu_bwd_kernel<T, 1>), dim3(grid_for(rows * cols)), dim3(256), 0, s, rows, cols, (const T*)pre, ldp, (const T*)dy, lddy, (T*)out, ldo);
+  if (vec && cols % V == 0) hipLaunchKernelGGL((gelu_bwd_kernel<T, V, false>), dim3(grid_for(rows * (cols / V))), dim3(256), 0, s, rows, cols, (const T*)pre, ldp, (const T*)dy, lddy, (T*)out, ldo);
+  else if (vec) hipLaunchKernelGGL((gelu_bwd_kernel<T, V, true>), dim3(grid_for(rows * ((cols + V - 1) / V))), dim3(256), 0, s, rows, cols, (const T*)pre, ldp, (const T*)dy, lddy, (T*)out, ldo);
+  else hipLaunchKernelGGL((gelu_bwd_kernel<T, 1, false>), dim3(grid_for(rows * cols)), dim3(256), 0, s, rows, cols, (const T*)pre, ldp, (const T*)dy, lddy, (T*)out, ldo);
   return check_launch("gelu_bwd");
 }
 
