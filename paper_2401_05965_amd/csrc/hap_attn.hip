@@ -218,11 +218,13 @@ __device__ __forceinline__ void wait_tiles_and_sync() {
 /* Workgroups go to the 8 XCDs round-robin by linear id.  This renumbers them so that the workgroups of
  * one (batch entry, head) pair, which stream the same K/V (or Q/dO) rows, run on one XCD and share its
  * L2.  Returns the logical (x, y, z) of this workgroup. */
-__device__ __forceinline__ void block_coords(int& x, int& y, int& z) {
-  const unsigned gx = gridDim.x, gy = gridDim.y, total = gx * gy * gridDim.z;
-  unsigned id = blockIdx.x + gx * (blockIdx.y + gy * blockIdx.z);
+__device__ __forceinline__ void block_coords_of(unsigned id, unsigned gx, unsigned gy, unsigned gz, int& x, int& y, int& z) {
+  const unsigned total = gx * gy * gz;
   if (total % 8 == 0) id = (id % 8) * (total / 8) + id / 8;
   x = (int)(id % gx); y = (int)((id / gx) % gy); z = (int)(id / (gx * gy));
+}
+__device__ __forceinline__ void block_coords(int& x, int& y, int& z) {
+  block_coords_of(blockIdx.x + gridDim.x * (blockIdx.y + gridDim.y * blockIdx.z), gridDim.x, gridDim.y, gridDim.z, x, y, z);
 }
 
 /* Largest growth of a row's running maximum (log2 units) that is absorbed without rescaling the
@@ -345,15 +347,16 @@ __global__ __launch_bounds__(256) void attn_dsum_kernel(const AttnArgs a) {
   }
 }
 
+/* dQ of 32 queries per wave (recomputes S and dP against every K/V tile).  smem: kDqSmem<D> bytes, 256-byte aligned. */
+template <int D> constexpr int kDqSmem = 2 * 2 * kTile * D * 2;
+
 template <int D>
-__global__ __launch_bounds__(64 * kWaves, 2) void attn_bwd_dq_kernel(const AttnArgs a) {
+__device__ __forceinline__ void attn_bwd_dq_body(const AttnArgs& a, char* smem, int bx, int by, int bz) {
   constexpr int kTileBytes = kTile * D * 2;
-  __shared__ __attribute__((aligned(256))) char lds[2][2][kTileBytes];   // [buffer][K, V]
+  char (*lds)[2][kTileBytes] = reinterpret_cast<char (*)[2][kTileBytes]>(smem);   // [buffer][K, V]
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   FragAddr<D> fa;
   fa.init(lane);
-  int bx, by, bz;
-  block_coords(bx, by, bz);
   const int b = a.b0 + bz, h = a.h0 + by;
   const long long head_off = (long long)b * a.stride_b + (long long)h * a.stride_h;
   const long long stat_off = ((long long)b * a.heads + h) * a.seq;
@@ -416,18 +419,17 @@ __global__ __launch_bounds__(64 * kWaves, 2) void attn_bwd_dq_kernel(const AttnA
  * the wave under 256 registers so that two blocks share a compute unit.  Q, dO and the row statistics
  * stream through LDS in 32-query tiles, double buffered. */
 constexpr int kQTile = 32;
+template <int D> constexpr int kDkvSmem = 2 * 2 * kQTile * D * 2 + 32 * kWaves * D * 2 + 2 * 2 * 64 * 4;
 
 template <int D>
-__global__ __launch_bounds__(64 * kWaves, 2) void attn_bwd_dkv_kernel(const AttnArgs a) {
+__device__ __forceinline__ void attn_bwd_dkv_body(const AttnArgs& a, char* smem, int bx, int by, int bz) {
   constexpr int kTileBytes = kQTile * D * 2;
-  __shared__ __attribute__((aligned(256))) char lds[2][2][kTileBytes];    // [buffer][Q, dO]
-  __shared__ __attribute__((aligned(256))) char lds_vres[32 * kWaves * D * 2];
-  __shared__ __attribute__((aligned(16))) float lds_stat[2][2][64];      // [buffer][lse * log2(e), D]; 32 used
+  char (*lds)[2][kTileBytes] = reinterpret_cast<char (*)[2][kTileBytes]>(smem);                     // [buffer][Q, dO]
+  char* lds_vres = smem + 4 * kTileBytes;                                                            // the block's 128 rows of V
+  float (*lds_stat)[2][64] = reinterpret_cast<float (*)[2][64]>(smem + 4 * kTileBytes + 32 * kWaves * D * 2);   // [buffer][lse * log2(e), D]; 32 used
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   FragAddr<D> fa;
   fa.init(lane);
-  int bx, by, bz;
-  block_coords(bx, by, bz);
   const int b = a.b0 + bz, h = a.h0 + by;
   const long long head_off = (long long)b * a.stride_b + (long long)h * a.stride_h;
   const long long stat_off = ((long long)b * a.heads + h) * a.seq;
@@ -505,6 +507,22 @@ __global__ __launch_bounds__(64 * kWaves, 2) void attn_bwd_dkv_kernel(const Attn
   }
   store_rows<D>(a.dv + head_off, a.stride_s, key, a.seq, dv, 1.0f, lane);
   store_rows<D>(a.dk + head_off, a.stride_s, key, a.seq, dk, a.scale, lane);
+}
+
+/* Both halves of the backward in ONE launch of 2 x (blocks per half) workgroups: z < gridDim.z / 2 computes dK / dV,
+ * the rest dQ.  The two are independent, so the dQ workgroups start as soon as slots free up behind the (longer) dK / dV
+ * ones instead of waiting for that kernel's last, partly filled round: 640 + 640 workgroups on 512 slots are 2.5 rounds
+ * rather than 2 + 2.  Both bodies carve the same LDS buffer, which keeps two workgroups per compute unit. */
+template <int D>
+__global__ __launch_bounds__(64 * kWaves, 2) void attn_bwd_kernel(const AttnArgs a) {
+  constexpr int kSmem = kDkvSmem<D> > kDqSmem<D> ? kDkvSmem<D> : kDqSmem<D>;
+  __shared__ __attribute__((aligned(256))) char smem[kSmem];
+  const unsigned gz = gridDim.z / 2;
+  const bool dq_role = blockIdx.z >= gz;
+  int bx, by, bz;
+  block_coords_of(blockIdx.x + gridDim.x * (blockIdx.y + gridDim.y * (blockIdx.z - (dq_role ? gz : 0u))), gridDim.x, gridDim.y, gz, bx, by, bz);
+  if (dq_role) attn_bwd_dq_body<D>(a, smem, bx, by, bz);
+  else attn_bwd_dkv_body<D>(a, smem, bx, by, bz);
 }
 
 int resolve(const hap_attn_desc* d, int j, int* b0, int* nb, int* h0, int* nh) {
@@ -601,20 +619,18 @@ int hap_sharded_attn_bwd(const hap_attn_desc* d, int shard_index, const void* Q,
   const dim3 grid((unsigned)((d->seq + 32 * kWaves - 1) / (32 * kWaves)), (unsigned)nh, (unsigned)nb);
   const int rows_per_block = 256 / (int)(d->head_dim / 8);
   const dim3 grid_d((unsigned)((d->seq + rows_per_block - 1) / rows_per_block), (unsigned)nh, (unsigned)nb);
+  if (2 * (int64_t)nb > 65535) return hap_fail(HAP_EUNSUPPORTED, "more than 32767 batch entries in one call");
+  const dim3 grid2(grid.x, grid.y, 2 * grid.z);     // dK / dV workgroups first, dQ workgroups behind them
   if (d->head_dim == 128) {
     hipLaunchKernelGGL(attn_dsum_kernel<128>, grid_d, dim3(256), 0, s, a);
     if ((rc = launched("attn_dsum"))) return rc;
-    hipLaunchKernelGGL(attn_bwd_dkv_kernel<128>, grid, dim3(64 * kWaves), 0, s, a);
-    if ((rc = launched("attn_bwd_dkv"))) return rc;
-    hipLaunchKernelGGL(attn_bwd_dq_kernel<128>, grid, dim3(64 * kWaves), 0, s, a);
+    hipLaunchKernelGGL(attn_bwd_kernel<128>, grid2, dim3(64 * kWaves), 0, s, a);
   } else {
     hipLaunchKernelGGL(attn_dsum_kernel<64>, grid_d, dim3(256), 0, s, a);
     if ((rc = launched("attn_dsum"))) return rc;
-    hipLaunchKernelGGL(attn_bwd_dkv_kernel<64>, grid, dim3(64 * kWaves), 0, s, a);
-    if ((rc = launched("attn_bwd_dkv"))) return rc;
-    hipLaunchKernelGGL(attn_bwd_dq_kernel<64>, grid, dim3(64 * kWaves), 0, s, a);
+    hipLaunchKernelGGL(attn_bwd_kernel<64>, grid2, dim3(64 * kWaves), 0, s, a);
   }
-  return launched("attn_bwd_dq");
+  return launched("attn_bwd");
 }
 
 }  // extern "C"
