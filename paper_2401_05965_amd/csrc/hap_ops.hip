@@ -145,8 +145,18 @@ __global__ __launch_bounds__(256) void colsum_final_kernel(int64_t cols, int npa
   out += blockIdx.y * ldo;
   const int64_t c = (int64_t)blockIdx.x * 16 + tx;
   float a = 0.0f;
-  if (c < cols)
-    for (int p = ty; p < nparts; p += 16) a += partial[(int64_t)p * cols + c];
+  if (c < cols) {    // four independent partial sums keep four loads in flight per thread
+    float a1 = 0.0f, a2 = 0.0f, a3 = 0.0f;
+    int p = ty;
+    for (; p + 48 < nparts; p += 64) {
+      a += partial[(int64_t)p * cols + c];
+      a1 += partial[(int64_t)(p + 16) * cols + c];
+      a2 += partial[(int64_t)(p + 32) * cols + c];
+      a3 += partial[(int64_t)(p + 48) * cols + c];
+    }
+    for (; p < nparts; p += 16) a += partial[(int64_t)p * cols + c];
+    a = (a + a1) + (a2 + a3);
+  }
   red[ty][tx] = a;
   __syncthreads();
   if (ty == 0 && c < cols) {
@@ -273,8 +283,18 @@ __global__ __launch_bounds__(256) void layernorm_bwd_final_kernel(int n, int nbl
   const int tx = threadIdx.x & 15, ty = threadIdx.x >> 4;
   const int c = blockIdx.x * 16 + tx;
   float a = 0.0f;
-  if (c < n)
-    for (int p = ty; p < nblocks; p += 16) a += part[((int64_t)p * 2 + blockIdx.y) * n + c];
+  if (c < n) {       // four independent partial sums keep four loads in flight per thread
+    float a1 = 0.0f, a2 = 0.0f, a3 = 0.0f;
+    int p = ty;
+    for (; p + 48 < nblocks; p += 64) {
+      a += part[((int64_t)p * 2 + blockIdx.y) * n + c];
+      a1 += part[((int64_t)(p + 16) * 2 + blockIdx.y) * n + c];
+      a2 += part[((int64_t)(p + 32) * 2 + blockIdx.y) * n + c];
+      a3 += part[((int64_t)(p + 48) * 2 + blockIdx.y) * n + c];
+    }
+    for (; p < nblocks; p += 16) a += part[((int64_t)p * 2 + blockIdx.y) * n + c];
+    a = (a + a1) + (a2 + a3);
+  }
   red[ty][tx] = a;
   __syncthreads();
   if (ty == 0 && c < n) {
