@@ -274,12 +274,7 @@ def hap_synthesize(nodes, ratios, speed, net, rules=None, capacity=64):
     m = len(ratios)
     prog = (_Instr * capacity)()
     n = C.c_int(); sec = C.c_double(); exp = C.c_int64()
-    r = None
-    if rules is not None:
-        dm = lambda dims: sum(1 << d for d in dims)
-        r = C.byref(_SynthRules(dm(rules.get("placeholder_dims", (0, 1))), dm(rules.get("parameter_dims", (0, 1))),
-                                int(rules.get("grouped_broadcast", True)), int(rules.get("replicated_matmul", True)),
-                                int(rules.get("placeholder_replicated", True))))
+    r = _rules(rules)
     _check(lib.hap_synthesize(C.c_int(len(nodes)), _graph(nodes), C.c_int(m), (C.c_double * m)(*map(float, ratios)),
                               (C.c_double * m)(*map(float, speed)), C.byref(_Net(net["latency"], net["bandwidth"], net["elem_bytes"])), r,
                               prog, C.c_int(capacity), C.byref(n), C.byref(sec), C.byref(exp)), "hap_synthesize")
