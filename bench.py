@@ -295,6 +295,23 @@ def main():
         res["cfg4_layer_fwd_bwd_device0_5heads_ffn2731"] = layer("tensor", 0, *c4)
         res["cfg4_layer_fwd_bwd_device2_3heads_ffn1365"] = layer("tensor", 2, *c4)
         res["cfg5_layer_fwd_bwd_device0_79samples"] = layer("data", 0, 256, 197, 1024, 16, 64, 4096, [0, 16], [0, 4096], [0, 79, 142, 205, 236, 256])
+        # config 1: one fp32 fully-connected layer, 64 x 1024 x 1024, rows split (38, 26): latency-bound, reported in microseconds (warm)
+        w1 = hapgen.WORKLOADS["cfg1_fc_f32"]
+        r1, _ = hap.hap_shard_ratios(list(w1.speeds), [(1.0, 0.0, 0.0, 0.0)])
+        s1, o1 = hap.hap_round_shards(r1, w1.dims["tokens"])
+        gen1 = torch.Generator(device=dev); gen1.manual_seed(1)
+        X1 = torch.randn((64, 1024), generator=gen1, device=dev); W1c = torch.randn((1024, 1024), generator=gen1, device=dev) * 0.02
+        dY1 = torch.randn((64, 1024), generator=gen1, device=dev)
+        Y1 = torch.zeros_like(dY1); dX1 = torch.zeros_like(X1); dW1c = torch.zeros_like(W1c)
+        d1 = hap.LinearDesc(64, 1024, 1024, hap.SHARD_BATCH, o1, hap.F32)
+        ws1 = torch.empty((hap.hap_linear_bwd_workspace(d1, 0),), dtype=torch.uint8, device=dev)
+        c1 = {"rows": s1}
+        for j1 in range(2):
+            c1[f"fwd_dev{j1}_us"] = round(timeit(lambda: hap.hap_sharded_linear_fwd(d1, j1, X1, W1c, None, Y1, None, ws1), n=50) * 1e6, 1)
+            c1[f"bwd_dev{j1}_us"] = round(timeit(lambda: hap.hap_sharded_linear_bwd(d1, j1, X1, W1c, None, dY1, dX1, dW1c, hap.F32, None, ws1), n=50) * 1e6, 1)
+        c1["sfb_rebuild_us"] = round(timeit(lambda: hap.hap_sfb_grad([X1[:s1[0]], X1[s1[0]:]], [dY1[:s1[0]], dY1[s1[0]:]], s1, 1024, 1024, 1024, 1024,
+                                                                   hap.F32, dW1c, 1024, ws=ws1), n=50) * 1e6, 1)
+        res["cfg1_fc_f32_latency"] = c1
         # uneven All-Gather data movement (Sec. 2.3.1): the padded slots of config 2's hidden activations (8402 | 5041 | 2941 of 16384
         # columns: byte offsets 16804 and 26886, nothing 16-byte aligned) and of config 5's token rows (batch 79 | 63 | 63 | 31 | 20 x 197)
         def gather_row(rows_, cols_, dim_, offs_):
