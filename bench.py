@@ -273,7 +273,26 @@ def main():
         ws5 = torch.empty((max(16, hap.hap_sfb_workspace(len(rows5), rows5, 1024, 4096)),), dtype=torch.uint8, device=dev)
         t = timeit(lambda: hap.hap_sfb_grad(X5, dY5, rows5, 1024, 4096, 1024, 4096, hap.BF16, dW5, 4096, ws=ws5))
         res["cfg5_sfb_dW1_tflops"] = round(2.0 * 1024 * 4096 * sum(rows5) / t / 1e12, 1)
-        del X5, dY5, dW5, ws5
+        # dW2 [4096 x 1024]: the factors swap roles (hidden activations [rows x 4096], output gradients [rows x 1024])
+        dW5b = torch.zeros((4096, 1024), dtype=torch.float32, device=dev)
+        t = timeit(lambda: hap.hap_sfb_grad(dY5, X5, rows5, 4096, 1024, 4096, 1024, hap.BF16, dW5b, 1024, ws=ws5))
+        res["cfg5_sfb_dW2_tflops"] = round(2.0 * 1024 * 4096 * sum(rows5) / t / 1e12, 1)
+        del X5, dY5, dW5, dW5b, ws5
+        # config 5's MLP with the ffn axis sharded (1261 | 1008 | 1008 | 504 | 315 of 4096) over all 50432 tokens: devices 0 and 4
+        T5, h5, F5 = 256 * 197, 1024, 4096
+        r5, _ = hap.hap_shard_ratios([1.0, 0.8, 0.8, 0.4, 0.25], [(1.0, 0.0, 0.0, 0.0)])
+        s5, o5f = hap.hap_round_shards(r5, F5)
+        gen5 = torch.Generator(device=dev); gen5.manual_seed(6)
+        rnd5 = lambda shp, sg: (torch.randn(shp, generator=gen5, device=dev) * sg).to(torch.bfloat16)
+        Xm, dOm = rnd5((T5, h5), 1.0), rnd5((T5, h5), 1.0)
+        W1m, b1m, W2m = rnd5((h5, F5), 0.02), rnd5((F5,), 0.02), rnd5((F5, h5), 0.02)
+        for j5 in (0, 4):
+            sh5 = MlpShard(T5, h5, F5, o5f, j5, Xm, W1m, b1m, W2m, dOm)
+            t = timeit(lambda: (sh5.forward(), sh5.backward()), n=5)
+            f5, b5 = sh5.flops()
+            res[f"cfg5_mlp_fwd_bwd_device{j5}_ffn{s5[j5]}"] = {"ms": round(t * 1e3, 3), "gflop": round((f5 + b5) / 1e9, 1), "tflops": round((f5 + b5) / t / 1e12, 1)}
+            del sh5
+        del Xm, dOm, W1m, W2m
         # whole encoder layer, forward + backward, as one device runs it (every GEMM, attention and row kernel in order):
         # config 4 sharded over heads / ffn (devices 0 and 2), config 5's batch shard of device 0
         def layer(style, j, B, S, hid, heads, d, ffn, hoffs, foffs, boffs):
