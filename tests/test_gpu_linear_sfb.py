@@ -294,3 +294,25 @@ def test_cfg1_fp32_split_k_with_workspace(hap):
     dXo, dWo, dbo = olin.linear_bwd(Xh, Wh, Po, dYh, act=True)
     check("cfg1 split-k Y", host(Y), Yo, "f32"); check("cfg1 split-k preact", host(P), Po, "f32")
     check("cfg1 split-k dX", host(dX), dXo, "f32"); check("cfg1 split-k dW", dW_sum, dWo, "f32"); check("cfg1 split-k db", db_sum, dbo, "f32")
+
+
+def test_linear_seeded_random_sweep(hap):
+    """A seeded sweep over shapes, rules, layouts and options nobody hand-picked: tiny to multi-tile extents, ragged everything,
+    random shard boundaries (including empty shards), compact and whole-tensor operands, odd pads."""
+    rng = np.random.default_rng(20240105)
+    for trial in range(28):
+        dtype = "bf16" if trial % 3 else "f32"
+        tokens = int(rng.choice([1, 7, 33, 130, 257, 515, 700]))
+        in_f = int(rng.choice([1, 8, 24, 100, 264, 513]))
+        out_f = int(rng.choice([1, 8, 40, 136, 300, 520]))
+        mode = int(rng.choice([olin.BATCH, olin.FEATURE, olin.REDUCTION, olin.REPLICATED]))
+        axis = {olin.BATCH: tokens, olin.FEATURE: out_f, olin.REDUCTION: in_f, olin.REPLICATED: 1}[mode]
+        m = int(rng.integers(1, 4))
+        cuts = sorted(int(c) for c in rng.integers(0, axis + 1, m - 1))
+        offsets = [0] + cuts + [axis] if mode != olin.REPLICATED else [0, 1]
+        act = bool(rng.integers(0, 2)) and mode != olin.REDUCTION
+        bias = bool(rng.integers(0, 2))
+        full = bool(rng.integers(0, 2))
+        pad = int(rng.choice([0, 0, 1, 8])) if not full else 0
+        dw_dtype = "f32" if (dtype == "f32" or rng.integers(0, 2)) else "bf16"
+        run_linear_case(hap, dtype, tokens, in_f, out_f, mode, offsets, act, bias, full, dw_dtype=dw_dtype, pad=pad, seed=100 + trial)
