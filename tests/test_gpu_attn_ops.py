@@ -26,6 +26,11 @@ def _bshd_to_bhsd(a, B, S, H, D):
     (5, 3, 197, 64, False, [0, 2, 3, 5]),      # ViT-like: batch slices, seq 197, head_dim 64
     (1, 2, 64, 128, True, [0, 2]),             # exactly one tile
     (1, 1, 1, 64, True, [0, 1]),               # degenerate: a single token attends to itself
+    (3, 4, 129, 128, True, [0, 1, 4]),         # one query past a 128-query block, one key past two 64-key tiles
+    (2, 2, 63, 64, False, [0, 0, 2]),          # shorter than one tile; first device empty
+    (1, 3, 513, 64, True, [0, 3]),             # several blocks with a 1-query tail (512 + 1)
+    (4, 2, 31, 128, False, [0, 3, 4]),         # fewer queries than one wave holds
+    (1, 9, 256, 128, True, [0, 4, 9]),         # exact multiples of the block and tile sizes
 ])
 def test_attention_slices_fwd_bwd(hap, B, H, S, D, over_heads, offsets):
     torch = torch_mod()
