@@ -330,6 +330,21 @@ def main():
             c1[f"bwd_dev{j1}_us"] = round(timeit(lambda: hap.hap_sharded_linear_bwd(d1, j1, X1, W1c, None, dY1, dX1, dW1c, hap.F32, None, ws1), n=50) * 1e6, 1)
         c1["sfb_rebuild_us"] = round(timeit(lambda: hap.hap_sfb_grad([X1[:s1[0]], X1[s1[0]:]], [dY1[:s1[0]], dY1[s1[0]:]], s1, 1024, 1024, 1024, 1024,
                                                                    hap.F32, dW1c, 1024, ws=ws1), n=50) * 1e6, 1)
+        # the whole config-1 step (forward + backward of both devices, SFB rebuild: 11 small kernels), eager and replayed from a HIP graph
+        def step1():
+            for j1 in range(2):
+                hap.hap_sharded_linear_fwd(d1, j1, X1, W1c, None, Y1, None, ws1)
+                hap.hap_sharded_linear_bwd(d1, j1, X1, W1c, None, dY1, dX1, dW1c, hap.F32, None, ws1)
+            hap.hap_sfb_grad([X1[:s1[0]], X1[s1[0]:]], [dY1[:s1[0]], dY1[s1[0]:]], s1, 1024, 1024, 1024, 1024, hap.F32, dW1c, 1024, ws=ws1)
+        c1["step_eager_us"] = round(timeit(step1, n=50) * 1e6, 1)
+        side = torch.cuda.Stream()
+        with torch.cuda.stream(side):
+            step1()
+        side.synchronize()
+        graph1 = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph1, stream=side):
+            step1()
+        c1["step_hip_graph_us"] = round(timeit(graph1.replay, n=50) * 1e6, 1)
         res["cfg1_fc_f32_latency"] = c1
         # uneven All-Gather data movement (Sec. 2.3.1): the padded slots of config 2's hidden activations (8402 | 5041 | 2941 of 16384
         # columns: byte offsets 16804 and 26886, nothing 16-byte aligned) and of config 5's token rows (batch 79 | 63 | 63 | 31 | 20 x 197)

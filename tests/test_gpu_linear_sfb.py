@@ -316,3 +316,41 @@ def test_linear_seeded_random_sweep(hap):
         pad = int(rng.choice([0, 0, 1, 8])) if not full else 0
         dw_dtype = "f32" if (dtype == "f32" or rng.integers(0, 2)) else "bf16"
         run_linear_case(hap, dtype, tokens, in_f, out_f, mode, offsets, act, bias, full, dw_dtype=dw_dtype, pad=pad, seed=100 + trial)
+
+
+def test_cfg1_step_replays_from_a_hip_graph(hap):
+    """The library's calls only launch kernels on the given stream (no allocation, no memset, no host synchronisation), so a
+    whole latency-bound step - config 1: forward + backward of both devices and the SFB rebuild - can be captured once and
+    replayed.  Every replay, with eager work and synchronisations in between, must reproduce the eager results bit for bit."""
+    torch = torch_mod()
+    offs = [0, 38, 64]
+    _, Xd = gen(0, T.X, (64, 1024), 1.0, "f32"); _, Wd = gen(0, T.W, (1024, 1024), 0.02, "f32"); _, dYd = gen(0, T.DY, (64, 1024), 1.0, "f32")
+    desc = hap.LinearDesc(64, 1024, 1024, hap.SHARD_BATCH, offs, hap.F32)
+    ws = empty((hap.hap_linear_bwd_workspace(desc, 0),), "u8")
+    out = {k: empty(s, "f32", 0) for k, s in (("Y", (64, 1024)), ("dX", (64, 1024)), ("dW0", (1024, 1024)), ("dW1", (1024, 1024)), ("dWs", (1024, 1024)))}
+
+    def step():
+        for j in range(2):
+            hap.hap_sharded_linear_fwd(desc, j, Xd, Wd, None, out["Y"], None, ws)
+            hap.hap_sharded_linear_bwd(desc, j, Xd, Wd, None, dYd, out["dX"], out[f"dW{j}"], hap.F32, None, ws)
+        hap.hap_sfb_grad([Xd[:38], Xd[38:]], [dYd[:38], dYd[38:]], [38, 26], 1024, 1024, 1024, 1024, hap.F32, out["dWs"], 1024, ws=ws)
+    step()
+    torch.cuda.synchronize()
+    want = {k: v.clone() for k, v in out.items()}
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        step()                      # warm the capture stream's state
+    side.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        step()
+    for rep in range(3):
+        for v in out.values():
+            v.fill_(float(rep + 1))                      # eager work between replays: results must come from the replay
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for k in out:
+            assert torch.equal(out[k], want[k]), (rep, k)
+        step()                                           # and an eager step in between
+        torch.cuda.synchronize()
