@@ -23,6 +23,12 @@ size_t hap_colsum_grouped_workspace(int groups, int64_t rows, int64_t cols);
 int hap_colsum_grouped(int groups, int64_t rows, int64_t cols, int io_dtype, const void* a, int64_t lda, int64_t group_stride,
                        const int32_t* group_len, float* out, int64_t ldo, void* ws, size_t ws_bytes, void* stream);
 
+/* hap_gelu_bwd over `groups` row groups of `rows` rows each, stacked in the same buffers (group g starts at row g * rows);
+ * group_len: DEVICE array clamped to [0, rows] (NULL = all rows): rows at or beyond it are neither read nor written.
+ * Does not clear the error state. */
+int hap_gelu_bwd_grouped(int groups, int64_t rows, int64_t cols, int io_dtype, const void* preact, int64_t ldp, const void* dy,
+                         int64_t lddy, void* out, int64_t ldo, const int32_t* group_len, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -124,7 +124,7 @@ int hap_moe_linear_bwd(const hap_moe_desc* d, int shard_index, const void* X, co
   const int64_t gx = d->capacity * d->ldx, gw = d->in_features * d->ldw, gy = d->capacity * d->ldy;
   const int32_t* rows_j = rows ? rows + first : NULL;
 
-  // dP = dY * act'(preact) over all buffer rows of the device's experts (one [n*capacity x out] matrix), or dY itself
+  // dP = dY * act'(preact) over the token rows of the device's experts, or dY itself
   const void* dP = dY ? at(dY, first * gy, es) : NULL;
   int64_t lddp = d->ldy, gdp = gy;
   char* wsp = static_cast<char*>(ws);
@@ -133,9 +133,9 @@ int hap_moe_linear_bwd(const hap_moe_desc* d, int shard_index, const void* X, co
     lddp = lddp_of(d); gdp = d->capacity * lddp;
     const int64_t phase = W ? (int64_t)(((uintptr_t)at(W, first * gw, es) % 16) / es) : 0;
     char* dst = wsp + phase * es;
-    rc = hap_gelu_bwd(n * d->capacity, d->out_features, d->io_dtype, at(preact, first * gy, es), d->ldy, dP, d->ldy, dst, lddp, stream);
+    rc = hap_gelu_bwd_grouped((int)n, d->capacity, d->out_features, d->io_dtype, at(preact, first * gy, es), d->ldy, dP, d->ldy, dst, lddp,
+                              rows_j, stream);
     if (rc) return rc;
-    hap_clear_error();
     dP = dst;
     wsp += dp_bytes(d, n);
   }

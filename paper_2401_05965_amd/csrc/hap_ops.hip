@@ -42,10 +42,17 @@ template <typename T, int V> struct Pack { T v[V]; } __attribute__((aligned(size
  * leading dimensions are multiples of V, so the last chunk of a ragged row (cols % V != 0) is still read whole - the
  * bytes lie inside the row's pitch, and an aligned chunk that starts inside an allocation cannot leave its page - and only
  * its valid elements are stored. */
+/* blockIdx.y: one of several row groups of `rows` rows each, stacked in the same buffers; with group_len only the first
+ * group_len[g] rows of group g are processed (the experts of an MoE layer and their token counts). */
 template <typename T, int V, bool RAGGED>
 __global__ __launch_bounds__(256) void gelu_bwd_kernel(int64_t rows, int64_t cols, const T* pre, int64_t ldp,
-                                                       const T* dy, int64_t lddy, T* out, int64_t ldo) {
+                                                       const T* dy, int64_t lddy, T* out, int64_t ldo, const int* group_len) {
   const int64_t cv = (cols + V - 1) / V;
+  pre += (int64_t)blockIdx.y * rows * ldp; dy += (int64_t)blockIdx.y * rows * lddy; out += (int64_t)blockIdx.y * rows * ldo;
+  if (group_len) {
+    const int64_t len = group_len[blockIdx.y];
+    rows = len < 0 ? 0 : (len < rows ? len : rows);
+  }
   const int64_t total = rows * cv;
   for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (int64_t)gridDim.x * 256) {
     const int64_t r = i / cv, c = (i % cv) * V;
@@ -350,12 +357,14 @@ constexpr int kLnBlocks = 512;    // layernorm backward: blocks (= partial rows 
 constexpr int kColsumRowsPerBlock = 128;
 
 template <typename T>
-int gelu_bwd_t(int64_t rows, int64_t cols, const void* pre, int64_t ldp, const void* dy, int64_t lddy, void* out, int64_t ldo, hipStream_t s) {
+int gelu_bwd_t(int groups, int64_t rows, int64_t cols, const void* pre, int64_t ldp, const void* dy, int64_t lddy, void* out, int64_t ldo,
+               const int* group_len, hipStream_t s) {
   constexpr int V = 16 / sizeof(T);
   const bool vec = ldp % V == 0 && lddy % V == 0 && ldo % V == 0 && aligned16(pre) && aligned16(dy) && aligned16(out);
-  if (vec && cols % V == 0) hipLaunchKernelGGL((gelu_bwd_kernel<T, V, false>), dim3(grid_for(rows * (cols / V))), dim3(256), 0, s, rows, cols, (const T*)pre, ldp, (const T*)dy, lddy, (T*)out, ldo);
-  else if (vec) hipLaunchKernelGGL((gelu_bwd_kernel<T, V, true>), dim3(grid_for(rows * ((cols + V - 1) / V))), dim3(256), 0, s, rows, cols, (const T*)pre, ldp, (const T*)dy, lddy, (T*)out, ldo);
-  else hipLaunchKernelGGL((gelu_bwd_kernel<T, 1, false>), dim3(grid_for(rows * cols)), dim3(256), 0, s, rows, cols, (const T*)pre, ldp, (const T*)dy, lddy, (T*)out, ldo);
+  const unsigned gy = (unsigned)groups;
+  if (vec && cols % V == 0) hipLaunchKernelGGL((gelu_bwd_kernel<T, V, false>), dim3(grid_for(rows * (cols / V)), gy), dim3(256), 0, s, rows, cols, (const T*)pre, ldp, (const T*)dy, lddy, (T*)out, ldo, group_len);
+  else if (vec) hipLaunchKernelGGL((gelu_bwd_kernel<T, V, true>), dim3(grid_for(rows * ((cols + V - 1) / V)), gy), dim3(256), 0, s, rows, cols, (const T*)pre, ldp, (const T*)dy, lddy, (T*)out, ldo, group_len);
+  else hipLaunchKernelGGL((gelu_bwd_kernel<T, 1, false>), dim3(grid_for(rows * cols), gy), dim3(256), 0, s, rows, cols, (const T*)pre, ldp, (const T*)dy, lddy, (T*)out, ldo, group_len);
   return check_launch("gelu_bwd");
 }
 
@@ -430,13 +439,19 @@ int hap_probe_mfma_bf16(int random_operands, int iters, float* scratch, double* 
 int hap_gelu_bwd(int64_t rows, int64_t cols, int io_dtype, const void* preact, int64_t ldp, const void* dy,
                  int64_t lddy, void* out, int64_t ldo, void* stream) {
   hap_clear_error();
-  if (rows < 0 || cols < 0) return hap_fail(HAP_EINVAL, "negative size");
-  if (rows == 0 || cols == 0) return HAP_OK;
+  return hap_gelu_bwd_grouped(1, rows, cols, io_dtype, preact, ldp, dy, lddy, out, ldo, NULL, stream);
+}
+
+int hap_gelu_bwd_grouped(int groups, int64_t rows, int64_t cols, int io_dtype, const void* preact, int64_t ldp, const void* dy,
+                         int64_t lddy, void* out, int64_t ldo, const int32_t* group_len, void* stream) {
+  if (rows < 0 || cols < 0 || groups < 0) return hap_fail(HAP_EINVAL, "negative size");
+  if (groups > 65535) return hap_fail(HAP_EUNSUPPORTED, "more than 65535 groups");
+  if (rows == 0 || cols == 0 || groups == 0) return HAP_OK;
   if (!preact || !dy || !out) return hap_fail(HAP_EINVAL, "NULL pointer");
   if (ldp < cols || lddy < cols || ldo < cols) return hap_fail(HAP_ESHAPE, "leading dimension below cols");
   hipStream_t s = (hipStream_t)stream;
-  if (io_dtype == HAP_BF16) return gelu_bwd_t<__bf16>(rows, cols, preact, ldp, dy, lddy, out, ldo, s);
-  if (io_dtype == HAP_F32) return gelu_bwd_t<float>(rows, cols, preact, ldp, dy, lddy, out, ldo, s);
+  if (io_dtype == HAP_BF16) return gelu_bwd_t<__bf16>(groups, rows, cols, preact, ldp, dy, lddy, out, ldo, group_len, s);
+  if (io_dtype == HAP_F32) return gelu_bwd_t<float>(groups, rows, cols, preact, ldp, dy, lddy, out, ldo, group_len, s);
   return hap_fail(HAP_EINVAL, "bad dtype %d", io_dtype);
 }
 
