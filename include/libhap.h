@@ -44,7 +44,7 @@ typedef enum {
   HAP_EUNBOUNDED = 4,   /* LP unbounded (negative cost coefficients) */
   HAP_EWORKSPACE = 5,   /* ws NULL or ws_bytes below hap_*_workspace() */
   HAP_EDEVICE = 6,      /* HIP launch failed */
-  HAP_EUNSUPPORTED = 7  /* valid request this build does not implement (e.g. one operand view >= 2 GiB) */
+  HAP_EUNSUPPORTED = 7  /* valid request this build does not implement (e.g. head_dim other than 64 / 128) */
 } hap_status;
 
 const char* hap_strerror(int status);  /* static string */
@@ -359,6 +359,13 @@ int hap_allgather_assemble(const hap_gather_desc* d, const void* const* pieces, 
  * real GEMM can expect.  scratch: device, >= 256*512 floats, overwritten.  *flops (host, may be NULL)
  * receives the floating-point operations of one launch; the caller times the launch.              */
 int hap_probe_mfma_bf16(int random_operands, int iters, float* scratch, double* flops, void* stream);
+
+/* Testing aid.  The tiled GEMM kernels address an operand with 32-bit offsets, so the engine cuts a product whose
+ * operand view reaches 2 GiB into row blocks (K-contiguous operand: separate launches) or contraction segments
+ * (M- / N-contiguous operand: one launch).  This lowers that threshold so that the cutting can be exercised on
+ * small inputs; bytes <= 0 (or above the hardware reach) restores the default.  Returns how many products the
+ * engine has run in pieces so far in this process.  Process-wide, not thread-safe.                             */
+int64_t hap_debug_set_gemm_view_limit(int64_t bytes);
 
 #ifdef __cplusplus
 }

@@ -131,6 +131,7 @@ lib.hap_strerror.restype = C.c_char_p
 lib.hap_strerror.argtypes = [C.c_int]
 lib.hap_last_error.restype = C.c_char_p
 lib.hap_version.restype = C.c_char_p
+lib.hap_debug_set_gemm_view_limit.restype = C.c_int64
 lib.hap_allgather_capacity.restype = C.c_int64
 for _n in ("hap_linear_fwd_workspace", "hap_linear_bwd_workspace", "hap_sfb_workspace", "hap_attn_bwd_workspace",
            "hap_layernorm_bwd_workspace", "hap_colsum_workspace", "hap_moe_linear_fwd_workspace", "hap_moe_linear_bwd_workspace"):
@@ -450,6 +451,12 @@ def hap_colsum(rows, cols, io_dtype, a, lda, out, ws, stream=None):
     wp, wb = _ws(ws)
     _check(lib.hap_colsum(C.c_int64(rows), C.c_int64(cols), C.c_int(io_dtype), _ptr(a), C.c_int64(lda), _ptr(out), wp, wb,
                           _stream(stream)), "hap_colsum")
+
+
+def hap_debug_set_gemm_view_limit(nbytes: int) -> int:
+    """Testing aid: operand-view size from which the GEMM engine cuts a product into pieces (0 restores the default).
+    Returns the number of products run in pieces so far."""
+    return int(lib.hap_debug_set_gemm_view_limit(C.c_int64(int(nbytes))))
 
 
 def hap_probe_mfma_bf16(random_operands: bool, iters: int, scratch, stream=None) -> float:

@@ -38,6 +38,7 @@ typedef int i32x4_t __attribute__((ext_vector_type(4)));
 
 constexpr int kCUs = 256;                     // compute units of MI355X
 constexpr unsigned kOobOffset = 0x80000000u;  // beyond any num_records we pass: reads as zero
+constexpr int64_t kViewLimitBytes = 2147483000;  // reach of the tiled kernels' 32-bit buffer offsets: operand views stay below it
 constexpr int kRsrcFlags = 0x00020000;        // raw buffer, 32-bit data format
 
 struct SegArg {
@@ -1036,7 +1037,7 @@ Plan make_plan(const hap_gemm_problem* p) {
   for (int s = 0; s < p->nseg; ++s) {
     const double ea = p->a_kcontig ? ((double)(p->M - 1) * p->lda + pl.skewK + p->k[s]) : ((double)(p->k[s] - 1) * p->lda + pl.skewM + p->M);
     const double eb = p->b_kcontig ? ((double)(p->N - 1) * p->ldb + pl.skewK + p->k[s]) : ((double)(p->k[s] - 1) * p->ldb + pl.skewN + p->N);
-    if (ea * es >= 2147483000.0 || eb * es >= 2147483000.0) return pl;
+    if (ea * es >= (double)kViewLimitBytes || eb * es >= (double)kViewLimitBytes) return pl;
   }
   pl.tiled = true;
   if (p->in_dtype == HAP_F32) { pl.bm = pl.bn = 64; pl.name = "f32_64x64x16"; }
@@ -1080,12 +1081,15 @@ template <typename TC, bool AKC, bool BKC, int BM, int BN, int BK, int STAGES, i
 int launch_dma(const GemmArgs& a, int groups, hipStream_t st) {
   constexpr size_t smem = (size_t)STAGES * (BM + BN) * BK * 2;
   void (*kernel)(const GemmArgs) = &gemm_dma_kernel<TC, AKC, BKC, BM, BN, BK, WGM, WGN, STAGES>;
-  static bool configured = false;     // benign race: the attribute call is idempotent
-  if (!configured) {
+  // the attribute belongs to the kernel's copy on the current device (benign race: the call is idempotent)
+  static bool configured[64] = {};
+  int device = 0;
+  if (hipGetDevice(&device) != hipSuccess || device < 0 || device >= 64) device = -1;
+  if (device < 0 || !configured[device]) {
     const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
                                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
     if (e != hipSuccess) return hap_fail(HAP_EDEVICE, "cannot reserve %zu bytes of LDS: %s", smem, hipGetErrorString(e));
-    configured = true;
+    if (device >= 0) configured[device] = true;
   }
   const int out_tiles = a.tiles_m * a.tiles_n;
   hipLaunchKernelGGL(kernel, dim3(out_tiles * a.ksplit, groups), dim3(64 * WGM * WGN), smem, st, a);
@@ -1162,6 +1166,78 @@ hap_gemm_problem sub_problem(const hap_gemm_problem* p, int64_t m_lo, int64_t m_
 }
 
 }  // namespace
+
+static int64_t g_view_limit = kViewLimitBytes;
+static int64_t g_cut_products = 0;      // products run in pieces so far (testing aid, not synchronised)
+
+extern "C" int64_t hap_debug_set_gemm_view_limit(int64_t bytes) {
+  g_view_limit = bytes > 0 && bytes < kViewLimitBytes ? bytes : kViewLimitBytes;
+  return g_cut_products;
+}
+
+/* Operand views of 2 GiB and more.  The product is cut on the host so that every piece stays inside that reach:
+ * a K-contiguous operand by rows (row or column blocks of C, one launch each), an M- / N-contiguous operand, whose
+ * rows are k, along the contraction (more segments of the same launch; cuts at multiples of 64 keep every piece's
+ * 16-byte phase).  Returns true if it ran the product (status in *rc), false if nothing needs cutting or a cut is
+ * not possible (more than HAP_GEMM_MAX_SEG pieces, unaligned leading dimensions): the caller goes on as before. */
+static bool run_large(const hap_gemm_problem* p, void* stream, int* rc) {
+  const int es = esize(p->in_dtype);
+  if ((p->lda * es) % 16 || (p->ldb * es) % 16) return false;
+  const double limit = (double)g_view_limit / es;       // elements
+  const int64_t slack = 16;                              // skew and chunk rounding
+  int64_t kmax = 0;
+  for (int s = 0; s < p->nseg; ++s) kmax = p->k[s] > kmax ? p->k[s] : kmax;
+  // rows r of pitch ld and width w with ((r - 1) * ld + w + slack) elements inside the reach
+  auto rows_fit = [&](int64_t ld, int64_t w, int64_t granule) -> int64_t {
+    const double r = (limit - (double)(w + slack)) / (double)ld;
+    return r < (double)granule ? 0 : (int64_t)(r / granule) * granule;
+  };
+  auto too_big = [&](int64_t rows, int64_t ld, int64_t w) { return (double)(rows - 1) * ld + w + slack >= limit; };
+  if (p->a_kcontig && too_big(p->M, p->lda, kmax)) {
+    const int64_t r = rows_fit(p->lda, kmax, 256);
+    if (r == 0) return false;
+    ++g_cut_products;
+    for (int64_t lo = 0; lo < p->M; lo += r) {
+      const hap_gemm_problem q = sub_problem(p, lo, lo + r < p->M ? lo + r : p->M, 0, p->N, p->tile);
+      if ((*rc = hap_gemm_run(&q, stream))) return true;
+    }
+    *rc = HAP_OK;
+    return true;
+  }
+  if (p->b_kcontig && too_big(p->N, p->ldb, kmax)) {
+    const int64_t r = rows_fit(p->ldb, kmax, 256);
+    if (r == 0) return false;
+    ++g_cut_products;
+    for (int64_t lo = 0; lo < p->N; lo += r) {
+      const hap_gemm_problem q = sub_problem(p, 0, p->M, lo, lo + r < p->N ? lo + r : p->N, p->tile);
+      if ((*rc = hap_gemm_run(&q, stream))) return true;
+    }
+    *rc = HAP_OK;
+    return true;
+  }
+  bool cut = false;
+  for (int s = 0; s < p->nseg; ++s)
+    cut = cut || (!p->a_kcontig && too_big(p->k[s], p->lda, p->M)) || (!p->b_kcontig && too_big(p->k[s], p->ldb, p->N));
+  if (!cut) return false;
+  int64_t piece = INT64_MAX;
+  if (!p->a_kcontig) piece = rows_fit(p->lda, p->M, 64);
+  if (!p->b_kcontig) { const int64_t r = rows_fit(p->ldb, p->N, 64); piece = r < piece ? r : piece; }
+  if (piece == 0) return false;
+  hap_gemm_problem q = *p;
+  q.nseg = 0;
+  for (int s = 0; s < p->nseg; ++s)
+    for (int64_t k0 = 0; k0 < p->k[s]; k0 += piece) {
+      if (q.nseg == HAP_GEMM_MAX_SEG) return false;
+      q.a[q.nseg] = static_cast<const char*>(p->a[s]) + (p->a_kcontig ? k0 : k0 * p->lda) * es;
+      q.b[q.nseg] = static_cast<const char*>(p->b[s]) + (p->b_kcontig ? k0 : k0 * p->ldb) * es;
+      q.k[q.nseg] = p->k[s] - k0 < piece ? p->k[s] - k0 : piece;
+      ++q.nseg;
+    }
+  if (q.nseg == 0) return false;
+  ++g_cut_products;
+  *rc = hap_gemm_run(&q, stream);
+  return true;
+}
 
 /* 256x256 tiles on 256 CUs quantise badly: 33 tile columns of 32 rows are 4.1 rounds of work that take
  * 5.  The engine therefore cuts the output into a part whose big tiles fill whole rounds and a
@@ -1250,6 +1326,10 @@ int hap_gemm_run(const hap_gemm_problem* p, void* stream) {
     if (p->k[0] > 0x7fffffff) return hap_fail(HAP_EUNSUPPORTED, "segment longer than 2^31");
   }
   const int ragged = p->group_len ? p->group_ragged : 0;
+  if (!grouped && !p->force_generic) {
+    int rc;
+    if (run_large(p, stream, &rc)) return rc;
+  }
   const Plan pl = make_plan(p);
   static const bool split_ok = !(getenv("HAP_GEMM_SPLIT") && !strcmp(getenv("HAP_GEMM_SPLIT"), "0"));   // tuning aid
   static const int forced_tile = getenv("HAP_GEMM_TILE") ? atoi(getenv("HAP_GEMM_TILE")) : 0;             // tuning aid
