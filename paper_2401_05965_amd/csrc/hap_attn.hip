@@ -17,6 +17,8 @@
  */
 #include <hip/hip_runtime.h>
 
+#include <type_traits>
+
 #include <stdint.h>
 
 #include "hap_internal.h"
@@ -260,7 +262,10 @@ __global__ __launch_bounds__(64 * kWaves, 2) void attn_fwd_kernel(const AttnArgs
   td.issue(rk, lds[0][0], 0, tid);
   td.issue(rv, lds[0][1], 0, tid);
   wait_tiles_and_sync();
-  for (int t = 0; t < ntiles; ++t) {
+  // One tile of 64 keys; HALF: the last tile when its second 32 keys all lie past the end of the sequence (a 197-long
+  // sequence: 3 tiles and 5 keys), which then costs half the matrix and exponential work.
+  auto tile_body = [&](int t, auto half_tag) __attribute__((always_inline)) {
+    constexpr int NSUB = decltype(half_tag)::value ? 1 : 2;
     const int kv0 = t * kTile;
     const char* lds_k = lds[t & 1][0];
     const char* lds_v = lds[t & 1][1];
@@ -268,23 +273,23 @@ __global__ __launch_bounds__(64 * kWaves, 2) void attn_fwd_kernel(const AttnArgs
       td.issue(rk, lds[(t + 1) & 1][0], kv0 + kTile, tid);
       td.issue(rv, lds[(t + 1) & 1][1], kv0 + kTile, tid);
     }
-    f32x16_t s[2];
+    f32x16_t s[NSUB];
 #pragma unroll
-    for (int sub = 0; sub < 2; ++sub) {
+    for (int sub = 0; sub < NSUB; ++sub) {
       s[sub] = zero16();
 #pragma unroll
       for (int ks = 0; ks < D / 16; ++ks) s[sub] = mfma(frag_rows_at<D>(fa.rows + lds_addr(lds_k), sub * 32, ks), qf[ks], s[sub]);
     }
     if (kv0 + kTile > a.seq) {   // ragged last tile: keys past the end drop out
 #pragma unroll
-      for (int sub = 0; sub < 2; ++sub)
+      for (int sub = 0; sub < NSUB; ++sub)
 #pragma unroll
         for (int e = 0; e < 16; ++e)
           if (kv0 + sub * 32 + acc_row(e, lane) >= a.seq) s[sub][e] = -INFINITY;
     }
     float mx = -INFINITY;
 #pragma unroll
-    for (int sub = 0; sub < 2; ++sub)
+    for (int sub = 0; sub < NSUB; ++sub)
 #pragma unroll
       for (int e = 0; e < 16; ++e) mx = fmaxf(mx, s[sub][e]);
     mx = fmaxf(mx, __shfl_xor(mx, 32, 64)) * c;   // finite: every tile holds at least one valid key
@@ -300,7 +305,7 @@ __global__ __launch_bounds__(64 * kWaves, 2) void attn_fwd_kernel(const AttnArgs
     }
     float rs = 0.0f;
 #pragma unroll
-    for (int sub = 0; sub < 2; ++sub)
+    for (int sub = 0; sub < NSUB; ++sub)
 #pragma unroll
       for (int e = 0; e < 16; ++e) {
         s[sub][e] = __builtin_amdgcn_exp2f(fmaf(s[sub][e], c, -m_ref));
@@ -308,7 +313,7 @@ __global__ __launch_bounds__(64 * kWaves, 2) void attn_fwd_kernel(const AttnArgs
       }
     l_i += rs;      // this lane's half of the row; the halves meet after the loop
 #pragma unroll
-    for (int sub = 0; sub < 2; ++sub)
+    for (int sub = 0; sub < NSUB; ++sub)
 #pragma unroll
       for (int ss = 0; ss < 2; ++ss) {
         const bf16x8_t p = pack8(s[sub], ss);
@@ -316,7 +321,11 @@ __global__ __launch_bounds__(64 * kWaves, 2) void attn_fwd_kernel(const AttnArgs
         for (int dt = 0; dt < D / 32; ++dt) o[dt] = mfma(frag_cols_at<D>(fa.cols + lds_addr(lds_v), sub * 32 + ss * 16, dt), p, o[dt]);
       }
     wait_tiles_and_sync();
-  }
+  };
+  const bool last_half = (ntiles - 1) * kTile + 32 >= a.seq;
+  const int nwhole = last_half ? ntiles - 1 : ntiles;
+  for (int t = 0; t < nwhole; ++t) tile_body(t, std::false_type());
+  if (last_half) tile_body(ntiles - 1, std::true_type());
   l_i += __shfl_xor(l_i, 32, 64);
   const long long ohead_off = (long long)b * a.ostride_b + (long long)h * a.ostride_h;
   store_rows<D>(a.out + ohead_off, a.ostride_s, q, a.seq, o, 1.0f / l_i, lane);
@@ -380,7 +389,9 @@ __device__ __forceinline__ void attn_bwd_dq_body(const AttnArgs& a, char* smem, 
   td.issue(rk, lds[0][0], 0, tid);
   td.issue(rv, lds[0][1], 0, tid);
   wait_tiles_and_sync();
-  for (int t = 0; t < ntiles; ++t) {
+  // HALF: the last tile when its second 32 keys all lie past the end (their K rows are zero: nothing to add to dQ)
+  auto tile_body = [&](int t, auto half_tag) __attribute__((always_inline)) {
+    constexpr int NSUB = decltype(half_tag)::value ? 1 : 2;
     const int kv0 = t * kTile;
     const char* lds_k = lds[t & 1][0];
     const char* lds_v = lds[t & 1][1];
@@ -389,7 +400,7 @@ __device__ __forceinline__ void attn_bwd_dq_body(const AttnArgs& a, char* smem, 
       td.issue(rv, lds[(t + 1) & 1][1], kv0 + kTile, tid);
     }
 #pragma unroll
-    for (int sub = 0; sub < 2; ++sub) {
+    for (int sub = 0; sub < NSUB; ++sub) {
       f32x16_t s = zero16(), dp = zero16();
 #pragma unroll
       for (int ks = 0; ks < D / 16; ++ks) {
@@ -410,7 +421,11 @@ __device__ __forceinline__ void attn_bwd_dq_body(const AttnArgs& a, char* smem, 
       }
     }
     wait_tiles_and_sync();
-  }
+  };
+  const bool last_half = (ntiles - 1) * kTile + 32 >= a.seq;
+  const int nwhole = last_half ? ntiles - 1 : ntiles;
+  for (int t = 0; t < nwhole; ++t) tile_body(t, std::false_type());
+  if (last_half) tile_body(ntiles - 1, std::true_type());
   store_rows<D>(a.dq + head_off, a.stride_s, q, a.seq, dq, a.scale, lane);
 }
 

@@ -31,6 +31,9 @@ def _bshd_to_bhsd(a, B, S, H, D):
     (1, 3, 513, 64, True, [0, 3]),             # several blocks with a 1-query tail (512 + 1)
     (4, 2, 31, 128, False, [0, 3, 4]),         # fewer queries than one wave holds
     (1, 9, 256, 128, True, [0, 4, 9]),         # exact multiples of the block and tile sizes
+    (2, 2, 96, 64, True, [0, 2]),              # the last 64-key tile is exactly half full (its second half is skipped)
+    (1, 2, 97, 128, True, [0, 2]),             # ... and one key more: the second half holds a single key
+    (2, 1, 32, 128, False, [0, 1, 2]),         # a single half tile
 ])
 def test_attention_slices_fwd_bwd(hap, B, H, S, D, over_heads, offsets):
     torch = torch_mod()
