@@ -108,6 +108,11 @@ def main():
         """Achievable ceilings measured in this run: MFMA issue rate on register operands, plain copy bandwidth."""
         scratch = torch.empty((256 * 512,), dtype=torch.float32, device=dev)
         res = {}
+        # where the roofline's peak comes from: compute units x clock x 4096 bf16 flop per clock and unit (4 SIMDs, each one
+        # 32x32x16 MFMA = 32768 flop per 32 clocks), with the unit count and clock this device reports
+        units, khz = hap.hap_device_info()
+        res["peak_derivation"] = {"compute_units": units, "clock_ghz": round(khz / 1e6, 3), "bf16_flop_per_clock_per_unit": 4096,
+                                  "tflops": round(units * khz * 1e3 * 4096 / 1e12, 1)}
         for name, rnd in (("mfma_bf16_constant_operands_tflops", False), ("mfma_bf16_random_operands_tflops", True)):
             for _ in range(20):
                 fl = hap.hap_probe_mfma_bf16(rnd, 2000, scratch)

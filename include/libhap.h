@@ -359,6 +359,9 @@ int hap_allgather_assemble(const hap_gather_desc* d, const void* const* pieces, 
  * real GEMM can expect.  scratch: device, >= 256*512 floats, overwritten.  *flops (host, may be NULL)
  * receives the floating-point operations of one launch; the caller times the launch.              */
 int hap_probe_mfma_bf16(int random_operands, int iters, float* scratch, double* flops, void* stream);
+/* Compute units and peak engine clock (kHz) of the current device, for the report's derivation of the roofline
+ * (units x clock x 4096 bf16 flop per clock and unit).  Either pointer may be NULL.                        */
+int hap_device_info(int* compute_units, int* clock_khz);
 
 /* Testing aid.  The tiled GEMM kernels address an operand with 32-bit offsets, so the engine cuts a product whose
  * operand view reaches 2 GiB into row blocks (K-contiguous operand: separate launches) or contraction segments

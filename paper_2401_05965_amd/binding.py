@@ -459,6 +459,13 @@ def hap_debug_set_gemm_view_limit(nbytes: int) -> int:
     return int(lib.hap_debug_set_gemm_view_limit(C.c_int64(int(nbytes))))
 
 
+def hap_device_info():
+    """(compute units, peak engine clock in kHz) of the current device."""
+    cu, khz = C.c_int(0), C.c_int(0)
+    _check(lib.hap_device_info(C.byref(cu), C.byref(khz)), "hap_device_info")
+    return cu.value, khz.value
+
+
 def hap_probe_mfma_bf16(random_operands: bool, iters: int, scratch, stream=None) -> float:
     """Launches the MFMA issue-rate probe; returns the flops of the launch (the caller times it)."""
     fl = C.c_double()

@@ -436,6 +436,16 @@ int hap_probe_mfma_bf16(int random_operands, int iters, float* scratch, double* 
   return check_launch("mfma_probe");
 }
 
+int hap_device_info(int* compute_units, int* clock_khz) {
+  hap_clear_error();
+  int dev = 0;
+  hipDeviceProp_t prop;
+  if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess) return hap_fail(HAP_EDEVICE, "cannot query the device");
+  if (compute_units) *compute_units = prop.multiProcessorCount;
+  if (clock_khz) *clock_khz = prop.clockRate;
+  return HAP_OK;
+}
+
 int hap_gelu_bwd(int64_t rows, int64_t cols, int io_dtype, const void* preact, int64_t ldp, const void* dy,
                  int64_t lddy, void* out, int64_t ldo, void* stream) {
   hap_clear_error();
