@@ -168,3 +168,45 @@ def test_cfg5_vit_layer_full_widths(hap):
     (5 devices -> 8,6,6,3,3 samples)."""
     w = hapgen.WORKLOADS["cfg5_vit_bf16"]; d = w.dims
     _check_layer(hap, "data", B=26, S=d["seq"], hidden=d["hidden"], heads=d["heads"], d=d["head_dim"], ffn=d["ffn"], speeds=w.speeds)
+
+
+def test_encoder_layer_replays_from_a_hip_graph(hap):
+    """A whole bf16 encoder layer of all four devices' shards (projections, attention, LayerNorm, GeLU, residuals, every
+    gradient: about 150 kernels incl. split-K reductions) captured once and replayed: the library only launches kernels on
+    the caller's stream, so every replay - with eager work and synchronisations in between - is bit-identical to eager."""
+    from paper_2401_05965_amd.programs import EncoderLayerProgram
+    torch = torch_mod()
+    B, S, hidden, heads, d, ffn, speeds = 2, 200, 768, 6, 128, 1000, (1.0, 1.0, 0.5, 0.5)
+    _, pd = make_params(1, hidden, ffn, 0.05)
+    _, xd = gen(1, T.X, (B * S, hidden), 1.0, "bf16"); _, dyd = gen(1, T.DY, (B * S, hidden), 1.0, "bf16")
+    _, hoffs = ratios_offsets(hap, speeds, heads)
+    _, foffs = ratios_offsets(hap, speeds, ffn)
+    _, boffs = ratios_offsets(hap, speeds, B)
+    prog = EncoderLayerProgram("tensor", B, S, hidden, heads, d, ffn, hoffs, foffs, boffs, pd, xd, dyd)
+
+    def step():
+        prog.forward(); prog.backward()
+    outs = {"x1": prog.x1, "y": prog.y, "dx1": prog.dx1, "dx": prog.dx, "db2": prog.db2, "dbo": prog.dbo}
+    for j, s in enumerate(prog.shards):
+        # the valid parts of the compact buffers (the library never writes their padding)
+        outs.update({f"dWqkv{j}": s.dWqkv[:, :3 * s.hd], f"dWo{j}": s.dWo[:s.hd], f"dW1{j}": s.dW1[:, :s.f], f"dW2{j}": s.dW2[:s.f], f"db1{j}": s.db1[:s.f]})
+    step()
+    torch.cuda.synchronize()
+    want = {k: v.clone() for k, v in outs.items()}
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        step()
+    side.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        step()
+    for rep in range(3):
+        for v in outs.values():
+            v.fill_(float(rep + 1))
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for k in outs:
+            assert torch.equal(outs[k], want[k]), (rep, k)
+        step()
+        torch.cuda.synchronize()
