@@ -1249,14 +1249,29 @@ static int run_auto_tiled(const hap_gemm_problem* p, const Plan& pl, void* strea
   // A remainder strip of r big tiles can also stay on big tiles with its K range split over the idle CUs
   // (needs workspace); that costs about a third of a round for the partial-tile traffic plus 1/g rounds.
   const bool can_split_k = p->ws && p->ws_bytes >= (size_t)8 << 20;
+  long long nk = 0;                 // K tiles of the contraction
+  for (int s = 0; s < p->nseg; ++s) nk += p->k[s] > 0 ? cdiv(pl.skewK + p->k[s], 64) : 0;
+  // A part whose big tiles cannot fill the chip: 128-tiles (two per CU) or 256-tiles, either with the K range split over
+  // the idle slots as the launcher will do it.  Measured on this chip (microseconds): a workgroup spends 2.0 per K tile
+  // on a 256-tile and 1.05 on a 128-tile that shares its CU, plus 7 / 5 for prologue and epilogue; a split costs 3 for
+  // the reduction launch and 0.025 / 0.00625 per partial tile written and read back.  Returned in rounds of big tiles.
+  auto few_tiles_us = [&](long long tiles, long long slots, double per_ktile, double fixed, double per_partial) {
+    long long g = can_split_k ? slots / tiles : 1;
+    if (g > nk / 4) g = nk / 4;
+    if (g > 16) g = 16;
+    if (g < 1) g = 1;
+    const double rounds = (double)cdiv(tiles * g, slots);
+    return rounds * ((double)nk / (double)g * per_ktile + fixed) + (g > 1 ? 3.0 + (double)(tiles * g) * per_partial : 0.0);
+  };
   auto strip_time = [&](long long big_tiles, long long small_tiles, int* tile) {
-    double t = small_tiles_time(small_tiles);
-    *tile = 128;
-    if (can_split_k && big_tiles * 2 <= kCUs) {
-      const double ts = 0.35 + 1.0 / (double)(kCUs / big_tiles);
-      if (ts < t) { t = ts; *tile = 256; }
+    if (big_tiles < kCUs && nk > 0) {
+      const double round_us = (double)nk * 2.0 + 7.0;
+      const double tb = few_tiles_us(big_tiles, kCUs, 2.0, 7.0, 0.025), ts = few_tiles_us(small_tiles, 2 * kCUs, 1.05, 5.0, 0.00625);
+      *tile = tb <= ts ? 256 : 128;
+      return (tb <= ts ? tb : ts) / round_us;
     }
-    return t;
+    *tile = 128;
+    return small_tiles_time(small_tiles);
   };
   double best = (double)cdiv(tm * tn, kCUs);
   int choice = 0;                 // 0: all big, 1: all small, 2: split columns, 3: split rows
