@@ -335,6 +335,22 @@ def hap_round_shards(ratios: Sequence[float], dim_len: int, granule: int = 1):
 
 # ---------------------------------------------------------------- device
 
+def hap_version() -> str:
+    return lib.hap_version().decode()
+
+
+def hap_strerror(status: int) -> str:
+    return lib.hap_strerror(C.c_int(int(status))).decode()
+
+
+def hap_last_error() -> str:
+    return (lib.hap_last_error() or b"").decode()
+
+
+def hap_linear_fwd_workspace(desc: LinearDesc, shard_index: int) -> int:
+    return int(lib.hap_linear_fwd_workspace(C.byref(desc.c), C.c_int(shard_index)))
+
+
 def hap_linear_bwd_workspace(desc: LinearDesc, shard_index: int) -> int:
     return int(lib.hap_linear_bwd_workspace(C.byref(desc.c), C.c_int(shard_index)))
 

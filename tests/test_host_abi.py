@@ -26,7 +26,9 @@ def test_every_declared_symbol_is_exported(hap):
     assert len(names) >= 20
     for n in sorted(names):
         assert hasattr(hap.lib, n), f"{n} declared in libhap.h but not exported"
-    assert hap.lib.hap_version().startswith(b"libhap")
+        assert callable(getattr(hap, n, None)), f"{n} has no Python binding of the same name"
+    assert hap.lib.hap_version().startswith(b"libhap") and hap.hap_version().startswith("libhap")
+    assert hap.hap_strerror(0) and hap.hap_last_error() is not None
 
 
 def test_lp_matches_oracle_on_random_problems(hap):
