@@ -1144,8 +1144,10 @@ namespace {
  * quarter of the work at lower efficiency, and two of them share a CU. */
 double small_tiles_time(long long n) {
   if (n <= 0) return 0.0;
-  if (n <= kCUs) return 0.3;
-  return 0.6 * (double)((n + 2 * kCUs - 1) / (2 * kCUs));
+  // measured: a round of 512 small tiles takes 0.58 of a round of 256 big ones; a last round that leaves every CU at
+  // most one small tile 0.36 (the tile has the CU to itself)
+  const long long full = n / (2 * kCUs), rest = n % (2 * kCUs);
+  return 0.58 * (double)full + (rest == 0 ? 0.0 : (rest <= kCUs ? 0.36 : 0.58));
 }
 
 inline long long cdiv(long long a, long long b) { return (a + b - 1) / b; }
@@ -1285,17 +1287,19 @@ static int run_auto_tiled(const hap_gemm_problem* p, const Plan& pl, void* strea
     const double all_small = small_tiles_time(sm * sn);
     if (all_small < best - 1e-9) { best = all_small; choice = 1; }
   }
+  // a plan of two launches pays for the second one: the strip starts when the last big tile has finished (~10 us)
+  const double second_launch = nk > 0 ? 10.0 / ((double)nk * 2.0 + 7.0) : 0.0;
   for (long long c = tn - 1; c >= 1; --c)
     if ((tm * c) % kCUs == 0) {
       int tl;
-      const double t = (double)(tm * c / kCUs) + strip_time(tm * (tn - c), sm * cdiv(Np - c * 256, 128), &tl);
+      const double t = (double)(tm * c / kCUs) + strip_time(tm * (tn - c), sm * cdiv(Np - c * 256, 128), &tl) + second_launch;
       if (t < best - 1e-9) { best = t; choice = 2; cut = c; strip_tile = tl; }
       break;
     }
   for (long long r = tm - 1; r >= 1; --r)
     if ((tn * r) % kCUs == 0) {
       int tl;
-      const double t = (double)(tn * r / kCUs) + strip_time(tn * (tm - r), sn * cdiv(Mp - r * 256, 128), &tl);
+      const double t = (double)(tn * r / kCUs) + strip_time(tn * (tm - r), sn * cdiv(Mp - r * 256, 128), &tl) + second_launch;
       if (t < best - 1e-9) { best = t; choice = 3; cut = r; strip_tile = tl; }
       break;
     }
