@@ -27,8 +27,8 @@ PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA peak
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--moe-only", action="store_true", help="only run the MoE expert rows (profiling aid)")
     ap.add_argument("--main-only", action="store_true",
@@ -91,6 +91,23 @@ def main():
 
     stream = torch.cuda.current_stream()
     marks = {}
+
+    def steady_time(fn, n=10):
+        """Seconds per call of fn in steady state.  The GPU drops its clocks while the host prepares inputs and needs tens of
+        milliseconds of work to raise them again (the first 20 ms after an idle phase run ~15 % slow), so fn is repeated for
+        about 50 ms before the timed repetitions, which cover at least 20 ms."""
+        fn(); fn()
+        a = torch.cuda.Event(enable_timing=True); b = torch.cuda.Event(enable_timing=True)
+        a.record(stream); fn(); b.record(stream); b.synchronize()
+        est = max(a.elapsed_time(b), 0.005)                      # ms
+        for _ in range(min(2000, int(50.0 / est) + 1)):
+            fn()
+        n = max(n, min(2000, int(20.0 / est) + 1))
+        a.record(stream)
+        for _ in range(n):
+            fn()
+        b.record(stream); b.synchronize()
+        return a.elapsed_time(b) / n * 1e-3
 
     def timer(label, fn):
         a = torch.cuda.Event(enable_timing=True); b = torch.cuda.Event(enable_timing=True)
@@ -181,14 +198,7 @@ def main():
         shard; the fitted stage then goes through the LP for a range of All-Gather bandwidths next to the proportional (CP)
         and even (EV) splits of Sec. 2.3 (predictions of the model, not measurements: one GPU, no exchange)."""
         def t_block(sh, n=10):
-            for _ in range(2):
-                sh.forward(); sh.backward()
-            a = torch.cuda.Event(enable_timing=True); b = torch.cuda.Event(enable_timing=True)
-            a.record(stream)
-            for _ in range(n):
-                sh.forward(); sh.backward()
-            b.record(stream); b.synchronize()
-            return a.elapsed_time(b) / n * 1e-3
+            return steady_time(lambda: (sh.forward(), sh.backward()), n)
         gen7 = torch.Generator(device=dev); gen7.manual_seed(7)
         W1r = (torch.randn((h, F), generator=gen7, device=dev) * 0.02).to(torch.bfloat16)
         W2r = (torch.randn((F, h), generator=gen7, device=dev) * 0.02).to(torch.bfloat16)
@@ -225,15 +235,7 @@ def main():
         N = B * S
         res = {}
 
-        def timeit(fn, n=10):
-            for _ in range(2):
-                fn()
-            a = torch.cuda.Event(enable_timing=True); b = torch.cuda.Event(enable_timing=True)
-            a.record(stream)
-            for _ in range(n):
-                fn()
-            b.record(stream); b.synchronize()
-            return a.elapsed_time(b) / n * 1e-3
+        timeit = steady_time
 
         qkv = dev_bf16(1, T.Q, (N, 3 * nh * dh), 1.0); dqkv = torch.zeros_like(qkv)
         o = torch.zeros((N, nh * dh), dtype=torch.bfloat16, device=dev); do = dev_bf16(1, T.DO, (N, nh * dh), 1.0)
@@ -394,15 +396,7 @@ def main():
         return res
 
     if args.moe_only:
-        def timeit(fn, n=10):
-            for _ in range(2):
-                fn()
-            a = torch.cuda.Event(enable_timing=True); b = torch.cuda.Event(enable_timing=True)
-            a.record(stream)
-            for _ in range(n):
-                fn()
-            b.record(stream); b.synchronize()
-            return a.elapsed_time(b) / n * 1e-3
+        timeit = steady_time
         res = {}
         moe_rows(res, timeit)
         print(json.dumps(res))
