@@ -56,3 +56,13 @@ def assemble(pieces, offsets, dim):
         else:
             out[:, o[j]:o[j + 1]] = p[:, :s]
     return out
+
+
+def reducescatter_split(full, offsets, dim, cap=None):
+    """Before a padded Reduce-Scatter (Sec. 2.3.1: the collective needs equal shards): the device's full partial tensor cut
+    into m slots of capacity cap = max_j s_j along dim, slot j = the range of shard j followed by ZEROS (they take part in
+    the element-wise sums and must not change them).  Returns the list of slots."""
+    o = _offsets(offsets)
+    sizes = [b - a for a, b in zip(o, o[1:])]
+    cap = max(sizes) if cap is None else cap
+    return [pad(shard(full, o, j, dim), cap, dim, fill=0) for j in range(len(sizes))]

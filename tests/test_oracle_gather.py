@@ -49,3 +49,42 @@ def test_bad_offsets_rejected():
         gather.assemble([_full(2, 2)], [1, 3], 0)
     with pytest.raises(ValueError):
         gather.assemble([_full(2, 2)], [0, 2, 4], 0)
+
+
+@pytest.mark.parametrize("dim", [0, 1])
+def test_reducescatter_slots_brute_force_and_round_trip(dim):
+    """Slot j holds the range of shard j, then zeros up to the capacity; putting the slots' valid parts back gives the tensor."""
+    full = _full(7, 6)
+    offs = [0, 3, 3, 7] if dim == 0 else [0, 1, 1, 6]
+    sizes = [b - a for a, b in zip(offs, offs[1:])]
+    cap = max(sizes)
+    slots = gather.reducescatter_split(full, offs, dim)
+    assert len(slots) == 3
+    for j, s in enumerate(slots):
+        assert s.shape == ((cap, 6) if dim == 0 else (7, cap)) and s.dtype == full.dtype
+        for r in range(s.shape[0]):
+            for c in range(s.shape[1]):
+                k = r if dim == 0 else c                                  # position along the sharded axis
+                want = (full[offs[j] + r, c] if dim == 0 else full[r, offs[j] + c]) if k < sizes[j] else 0
+                assert s[r, c] == want
+    assert not slots[1].any()                                             # the empty shard's slot is all zeros
+    assert np.array_equal(gather.assemble(slots, offs, dim), full)
+
+
+@pytest.mark.parametrize("dim", [0, 1])
+def test_padded_reduce_scatter_equals_shard_of_the_sum(dim):
+    """What the padding must guarantee: summing slot j over the devices (the collective's reduction) and trimming it gives
+    shard j of the summed tensor, and the padding sums to exactly zero - for LP + rounding ranges over unequal devices."""
+    rng = np.random.default_rng(4)
+    parts = [rng.integers(-50, 50, (12, 10)).astype(np.float64) for _ in range(3)]          # three devices' partial tensors
+    n = parts[0].shape[dim]
+    ratios, _ = lp.shard_ratios((1.0, 0.6, 0.35), [(1.0, 0, 0, 0)])
+    sizes, offs = rounding.round_shards(ratios, n, 1)
+    cap = max(sizes)
+    total = sum(parts)
+    for j in range(3):
+        reduced = sum(gather.reducescatter_split(p, offs, dim)[j] for p in parts)               # the slot device j ends up with
+        valid = reduced[:sizes[j]] if dim == 0 else reduced[:, :sizes[j]]
+        rest = reduced[sizes[j]:] if dim == 0 else reduced[:, sizes[j]:]
+        assert np.array_equal(valid, gather.shard(total, offs, j, dim)) and not rest.any()
+        assert reduced.shape[dim] == cap
