@@ -378,9 +378,11 @@ def main():
             outg = torch.empty((rows_, cols_), dtype=torch.bfloat16, device=dev)
             ptrs = [slots[j_].data_ptr() for j_ in range(m_)]
             t_ = timeit(lambda: hap.hap_allgather_assemble(gd, ptrs, [shp[1]] * m_, outg, cols_))
-            return round(2.0 * rows_ * cols_ * 2 / t_ / 1e9)
-        res["allgather_trim_cfg2_hidden_dim1_gbs"] = gather_row(Tn, F, 1, offsets)
-        res["allgather_trim_cfg5_tokens_dim0_gbs"] = gather_row(256 * 197, 1024, 0, [197 * b for b in (0, 79, 142, 205, 236, 256)])
+            # the reverse before a padded Reduce-Scatter: the full tensor read once, m capacity-sized slots (zeros included) written
+            t2_ = timeit(lambda: hap.hap_reducescatter_split(gd, outg, cols_, ptrs, [shp[1]] * m_))
+            return round(2.0 * rows_ * cols_ * 2 / t_ / 1e9), round((rows_ * cols_ + m_ * shp[0] * shp[1]) * 2 / t2_ / 1e9)
+        res["allgather_trim_cfg2_hidden_dim1_gbs"], res["reducescatter_split_cfg2_hidden_dim1_gbs"] = gather_row(Tn, F, 1, offsets)
+        res["allgather_trim_cfg5_tokens_dim0_gbs"], res["reducescatter_split_cfg5_tokens_dim0_gbs"] = gather_row(256 * 197, 1024, 0, [197 * b for b in (0, 79, 142, 205, 236, 256)])
         moe_rows(res, timeit)
         # config 3 the naive way (Fig. "sfb"(b)): every device's own fp32 dW_i, then their sum (what the All-Reduce delivers)
         inf, outf = w3.dims["in_features"], w3.dims["out_features"]

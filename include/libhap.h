@@ -350,6 +350,14 @@ int hap_allgather_pad(const hap_gather_desc* d, int shard_index, const void* sha
  * any piece.                                                                                        */
 int hap_allgather_assemble(const hap_gather_desc* d, const void* const* pieces, const int64_t* ld_pieces,
                            void* out, int64_t ld_out, void* stream);
+/* The collective libraries' Reduce-Scatter wants equal shards too (Sec. 2.3.1, first paragraph): before it, a device
+ * cuts its full [rows x cols] partial tensor (device, ld_full elements) into m slots of capacity size along dim -
+ * slot j = the range of shard j followed by zeros, which add nothing to the sums.  slots: host array of m device
+ * pointers, slot j [capacity x cols] (dim 0) or [rows x capacity] (dim 1) with ld_slots[j] elements per row; columns
+ * beyond the slot's width are not written.  One launch.  After the collective the device's own slot is trimmed with
+ * hap_allgather_assemble on a one-piece descriptor.                                                             */
+int hap_reducescatter_split(const hap_gather_desc* d, const void* full, int64_t ld_full, void* const* slots,
+                            const int64_t* ld_slots, void* stream);
 
 /* ------------------------------------------------------------------ diagnostics --- */
 

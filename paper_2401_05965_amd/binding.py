@@ -418,6 +418,13 @@ def hap_allgather_assemble(desc: GatherDesc, pieces, ld_pieces, out, ld_out, str
                                       _stream(stream)), "hap_allgather_assemble")
 
 
+def hap_reducescatter_split(desc: GatherDesc, full, ld_full, slots, ld_slots, stream=None):
+    m = desc.m
+    pp = (C.c_void_p * m)(*[_ptr(t) for t in slots])
+    _check(lib.hap_reducescatter_split(C.byref(desc.c), _ptr(full), C.c_int64(ld_full), pp, (C.c_int64 * m)(*map(int, ld_slots)),
+                                       _stream(stream)), "hap_reducescatter_split")
+
+
 def hap_attn_bwd_workspace(desc: AttnDesc, shard_index: int) -> int:
     return int(lib.hap_attn_bwd_workspace(C.byref(desc.c), C.c_int(shard_index)))
 

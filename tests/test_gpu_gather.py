@@ -75,6 +75,20 @@ def run_case(hap, rows, cols, dim, speeds, eb, ld_extra=0, base_shift=0):
     out2 = dev(np.zeros((rows, cols), dtype=NP[eb]))
     hap.hap_allgather_assemble(desc, shard_d, [max(s.shape[1], 1) for s in shards], out2, cols)
     assert np.array_equal(back(out2, NP[eb], (rows, cols)), og.assemble(shards, offs, dim)), "grouped"
+    # ---- the reverse, before a padded Reduce-Scatter: the full tensor (odd base, wide leading dimension) cut into m slots
+    # of capacity size, shard range first, zeros behind; bytes past a slot's width keep their poison
+    src_raw = dev(np.full((rows * ld_out * eb + 64,), 0x5A, dtype=np.uint8))
+    src_h = np.full((rows, ld_out), NP[eb](0x33), dtype=NP[eb]); src_h[:, :cols] = full
+    src_raw[base_shift * eb: base_shift * eb + rows * ld_out * eb] = torch.from_numpy(src_h.view(np.uint8).reshape(-1).copy()).cuda()
+    rs = dev(np.full((m,) + slot_shape, POISON, dtype=NP[eb]))
+    hap.hap_reducescatter_split(desc, src_raw.data_ptr() + base_shift * eb, ld_out, [rs.data_ptr() + j * slot_bytes for j in range(m)],
+                                [slot_shape[1]] * m)
+    got_rs = back(rs, NP[eb], (m,) + slot_shape)
+    want_rs = og.reducescatter_split(full, offs, dim)
+    for j in range(m):
+        w = want_rs[j].shape[1]
+        assert np.array_equal(got_rs[j][:, :w], want_rs[j]), f"reduce-scatter slot {j}"
+        assert (got_rs[j][:, w:] == POISON).all()
 
 
 @pytest.mark.parametrize("eb", [2, 4])

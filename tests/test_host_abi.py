@@ -166,6 +166,13 @@ def test_allgather_host_side_argument_errors(hap):
     assert hap.lib.hap_allgather_assemble(C.byref(d1.c), ptrs, lds, one, C.c_int64(100), z) == 2    # piece 2: ld 89 < its 90 columns
     assert hap.lib.hap_allgather_assemble(C.byref(d1.c), ptrs, lds, one, C.c_int64(99), z) == 2     # ld_out below cols
     assert hap.lib.hap_allgather_assemble(C.byref(d1.c), z, lds, one, C.c_int64(100), z) == 1
+    # the reverse movement before a padded Reduce-Scatter: slots of capacity 90 columns each
+    slots = (C.c_void_p * 3)(256, 256, 256)
+    assert hap.lib.hap_reducescatter_split(C.byref(d1.c), one, C.c_int64(99), slots, (C.c_int64 * 3)(90, 90, 90), z) == 2    # ld_full below cols
+    assert hap.lib.hap_reducescatter_split(C.byref(d1.c), one, C.c_int64(100), slots, (C.c_int64 * 3)(90, 89, 90), z) == 2   # slot 1 narrower than the capacity
+    assert hap.lib.hap_reducescatter_split(C.byref(d1.c), z, C.c_int64(100), slots, (C.c_int64 * 3)(90, 90, 90), z) == 1     # full is NULL
+    assert hap.lib.hap_reducescatter_split(C.byref(d1.c), one, C.c_int64(100), (C.c_void_p * 3)(256, 0, 256), (C.c_int64 * 3)(90, 90, 90), z) == 1   # the empty shard still has a slot
+    assert hap.lib.hap_reducescatter_split(C.byref(d1.c), one, C.c_int64(100), z, z, z) == 1
 
 
 def test_segment_ratios_match_oracle(hap):
