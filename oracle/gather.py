@@ -66,3 +66,10 @@ def reducescatter_split(full, offsets, dim, cap=None):
     sizes = [b - a for a, b in zip(o, o[1:])]
     cap = max(sizes) if cap is None else cap
     return [pad(shard(full, o, j, dim), cap, dim, fill=0) for j in range(len(sizes))]
+
+
+def all_to_all(shards, offsets_from, dim_from, offsets_to, dim_to):
+    """All-To-All(e, d, d') of Sec. 2.2 / Sec. 5.2 as the definition: the devices' slices of e along dim_from (ranges
+    offsets_from) become the devices' slices of e along dim_to (ranges offsets_to).  Returns the new list of shards."""
+    full = assemble(shards, offsets_from, dim_from)
+    return [shard(full, offsets_to, j, dim_to) for j in range(len(_offsets(offsets_to)) - 1)]

@@ -117,3 +117,38 @@ def test_gather_many_devices(hap):
 def test_gather_cfg2_full_size(hap):
     """The size bench.py times: config 2's [8192 x 16384] bf16 activations from three padded column slots, every byte compared."""
     run_case(hap, 8192, 16384, 1, (1.0, 0.6, 0.35), 2)
+
+
+@pytest.mark.parametrize("eb", [2, 4])
+def test_all_to_all_reshard_from_rows_to_columns(hap, eb):
+    """All-To-All at a segment boundary (Sec. 5.2): rows sharded with one set of ratios become columns sharded with another.
+    Every virtual device cuts its row shard into m zero-padded column pieces (hap_reducescatter_split on the shard), piece j
+    goes to device j, which stacks what arrives by the old row ranges (hap_allgather_assemble).  Bit-exact against the definition."""
+    torch = torch_mod()
+    rows, cols = 333, 470
+    full = pattern(rows, cols, eb)
+    r_from, _ = hap.hap_shard_ratios((1.0, 0.6, 0.35, 0.001), [(1.0, 0, 0, 0)])
+    r_to, _ = hap.hap_shard_ratios((0.4, 1.0, 0.9, 0.7), [(1.0, 0, 0, 0)])
+    _, offs_rows = hap.hap_round_shards(r_from, rows, 1)
+    sizes_to, offs_cols = hap.hap_round_shards(r_to, cols, 1)
+    m, cap = 4, max(sizes_to)
+    shards = [np.ascontiguousarray(og.shard(full, offs_rows, i, 0)) for i in range(m)]
+    want = og.all_to_all(shards, offs_rows, 0, offs_cols, 1)
+    # send side: device i's pieces, [m][rows_i x cap]
+    sent = []
+    for i in range(m):
+        ri = shards[i].shape[0]
+        buf = dev(np.full((m, max(ri, 1), cap), NP[eb](0xA5), dtype=NP[eb]))
+        if ri:
+            d = hap.GatherDesc(ri, cols, 1, offs_cols, eb)
+            hap.hap_reducescatter_split(d, dev(shards[i]), cols, [buf.data_ptr() + j * max(ri, 1) * cap * eb for j in range(m)], [cap] * m)
+        sent.append(buf)
+    # receive side: device j stacks piece (i -> j) of every i along the rows
+    dj = hap.GatherDesc(rows, cap, 0, offs_rows, eb)
+    for j in range(m):
+        out = dev(np.zeros((rows, cap), dtype=NP[eb]))
+        pieces = [sent[i].data_ptr() + j * max(shards[i].shape[0], 1) * cap * eb for i in range(m)]
+        hap.hap_allgather_assemble(dj, pieces, [cap] * m, out, cap)
+        got = back(out, NP[eb], (rows, cap))
+        assert np.array_equal(got[:, :sizes_to[j]], want[j]), f"device {j}"
+        assert not got[:, sizes_to[j]:].any()                     # the padding arrives as zeros

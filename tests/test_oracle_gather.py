@@ -88,3 +88,22 @@ def test_padded_reduce_scatter_equals_shard_of_the_sum(dim):
         rest = reduced[sizes[j]:] if dim == 0 else reduced[:, sizes[j]:]
         assert np.array_equal(valid, gather.shard(total, offs, j, dim)) and not rest.any()
         assert reduced.shape[dim] == cap
+
+
+def test_all_to_all_is_split_exchange_assemble():
+    """All-To-All(e, 0, 1) re-shards a row-sharded tensor by columns (the segment boundary of Sec. 5.2, with different
+    ratios on the two sides).  Its definition must equal the movement a device actually performs: cut the own row shard into m
+    column pieces (zero-padded to the new capacity), hand piece j to device j, stack what arrives by the old row ranges."""
+    full = _full(11, 9)
+    offs_rows, offs_cols = [0, 5, 5, 11], [0, 2, 6, 9]
+    m = 3
+    shards = [gather.shard(full, offs_rows, i, 0) for i in range(m)]
+    want = gather.all_to_all(shards, offs_rows, 0, offs_cols, 1)
+    for j in range(m):
+        assert np.array_equal(want[j], full[:, offs_cols[j]:offs_cols[j + 1]])
+    sent = [gather.reducescatter_split(shards[i], offs_cols, 1) for i in range(m)]       # sent[i][j]: device i's piece for device j
+    cap = max(b - a for a, b in zip(offs_cols, offs_cols[1:]))
+    for j in range(m):
+        got = gather.assemble([sent[i][j] for i in range(m)], offs_rows, 0)               # [11 x cap], valid columns first
+        assert got.shape == (11, cap)
+        assert np.array_equal(got[:, :offs_cols[j + 1] - offs_cols[j]], want[j])
