@@ -15,12 +15,12 @@ def attn_fwd(Q, K, V):
     """Returns (O, lse) with lse = log sum_k exp(S) per query row."""
     Q, K, V = (np.asarray(t, dtype=np.float64) for t in (Q, K, V))
     scale = 1.0 / np.sqrt(Q.shape[-1])
-    S = np.einsum("bhqd,bhkd->bhqk", Q, K) * scale
+    S = (Q @ K.swapaxes(-1, -2)) * scale          # [b, h, query, key]; matmul acts on the last two axes
     mx = S.max(axis=-1, keepdims=True)
     E = np.exp(S - mx)
     den = E.sum(axis=-1, keepdims=True)
     P = E / den
-    O = np.einsum("bhqk,bhkd->bhqd", P, V)
+    O = P @ V
     return O, (mx + np.log(den))[..., 0]
 
 
@@ -28,14 +28,14 @@ def attn_bwd(Q, K, V, dO):
     """Returns (dQ, dK, dV)."""
     Q, K, V, dO = (np.asarray(t, dtype=np.float64) for t in (Q, K, V, dO))
     scale = 1.0 / np.sqrt(Q.shape[-1])
-    S = np.einsum("bhqd,bhkd->bhqk", Q, K) * scale
+    S = (Q @ K.swapaxes(-1, -2)) * scale
     E = np.exp(S - S.max(axis=-1, keepdims=True))
     P = E / E.sum(axis=-1, keepdims=True)
-    dV = np.einsum("bhqk,bhqd->bhkd", P, dO)
-    dP = np.einsum("bhqd,bhkd->bhqk", dO, V)
+    dV = P.swapaxes(-1, -2) @ dO
+    dP = dO @ V.swapaxes(-1, -2)
     dS = P * (dP - (dP * P).sum(axis=-1, keepdims=True))
-    dQ = np.einsum("bhqk,bhkd->bhqd", dS, K) * scale
-    dK = np.einsum("bhqk,bhqd->bhkd", dS, Q) * scale
+    dQ = (dS @ K) * scale
+    dK = (dS.swapaxes(-1, -2) @ Q) * scale
     return dQ, dK, dV
 
 
