@@ -298,7 +298,8 @@ size_t hap_attn_bwd_workspace(const hap_attn_desc* d, int shard_index);
  * 16-byte aligned pointers with n a multiple of 16 / sizeof(element) take the vector path.          */
 int hap_layernorm_fwd(int64_t rows, int64_t n, int io_dtype, const void* x, const void* gamma, const void* beta,
                       void* y, float* mean, float* rstd, void* stream);
-/* dx in io_dtype; dgamma, dbeta fp32 [n], overwritten.  ws from hap_layernorm_bwd_workspace.
+/* dx in io_dtype; dgamma, dbeta fp32 [n], overwritten (with zeros when rows == 0: the partial sums of a device
+ * whose shard is empty).  ws from hap_layernorm_bwd_workspace.
  * dresidual: NULL, or [rows x n] in io_dtype that is added to dx before the one rounding to io_dtype (a
  * pre-LayerNorm layer's gradient on the residual path, which bypasses the normalisation); it may be dx
  * itself, no other aliasing.                                                                        */
@@ -370,13 +371,6 @@ int hap_probe_mfma_bf16(int random_operands, int iters, float* scratch, double* 
 /* Compute units and peak engine clock (kHz) of the current device, for the report's derivation of the roofline
  * (units x clock x 4096 bf16 flop per clock and unit).  Either pointer may be NULL.                        */
 int hap_device_info(int* compute_units, int* clock_khz);
-
-/* Testing aid.  The tiled GEMM kernels address an operand with 32-bit offsets, so the engine cuts a product whose
- * operand view reaches 2 GiB into row blocks (K-contiguous operand: separate launches) or contraction segments
- * (M- / N-contiguous operand: one launch).  This lowers that threshold so that the cutting can be exercised on
- * small inputs; bytes <= 0 (or above the hardware reach) restores the default.  Returns how many products the
- * engine has run in pieces so far in this process.  Process-wide, not thread-safe.                             */
-int64_t hap_debug_set_gemm_view_limit(int64_t bytes);
 
 #ifdef __cplusplus
 }

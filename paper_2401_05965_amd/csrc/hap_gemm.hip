@@ -36,7 +36,6 @@ typedef int i32x4_t __attribute__((ext_vector_type(4)));
 
 #define LDS_PTR(T, p) ((__attribute__((address_space(3))) T*)(p))
 
-constexpr int kCUs = 256;                     // compute units of MI355X
 constexpr unsigned kOobOffset = 0x80000000u;  // beyond any num_records we pass: reads as zero
 constexpr int64_t kViewLimitBytes = 2147483000;  // reach of the tiled kernels' 32-bit buffer offsets: operand views stay below it
 constexpr int kRsrcFlags = 0x00020000;        // raw buffer, 32-bit data format
@@ -989,18 +988,17 @@ __global__ __launch_bounds__(256) void gemm_generic_kernel(const GenericArgs g) 
   store_c<TC>(dst, acc);
 }
 
-/* Kernel variant for large bf16 problems; HAP_GEMM_KERNEL=staged|dma2 overrides the default (tuning aid). */
-int dma_variant() {
-  static int v = -1;
-  if (v < 0) {
-    const char* e = getenv("HAP_GEMM_KERNEL");
-    v = 1;
-    if (e) {
-      if (!strcmp(e, "staged")) v = 0;
-      else if (!strcmp(e, "dma2")) v = 1;
-    }
+/* Compute units of the current device (256 on MI355X), asked once per device; the planner's round arithmetic uses it. */
+int cu_count() {
+  static int cached[64] = {};
+  int device = 0;
+  if (hipGetDevice(&device) != hipSuccess || device < 0 || device >= 64) return 256;
+  if (cached[device] == 0) {     // benign race: every thread stores the same value
+    int n = 0;
+    if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, device) != hipSuccess || n < 8) n = 256;
+    cached[device] = n;
   }
-  return v;
+  return cached[device];
 }
 
 struct Plan {
@@ -1008,7 +1006,7 @@ struct Plan {
   int skewM, skewN, skewK;
   int bm, bn;       // tile
   const char* name;
-  int dma;          // 0: register-staged kernel; 1: direct-to-LDS kernel (2 stages x BK 64)
+  int dma;          // 1: bf16, direct-to-LDS kernel; 0: fp32, register-staged kernel
 };
 
 inline int esize(int dtype) { return dtype == HAP_BF16 ? 2 : 4; }
@@ -1044,6 +1042,7 @@ Plan make_plan(const hap_gemm_problem* p) {
   else {
     bool big = p->tile ? p->tile == 256 : (p->M + pl.skewM > 128 && p->N + pl.skewN > 128);
     if (big && !p->tile && (p->groups > 1 || p->group_len)) {
+      const int kCUs = cu_count();
       // A grouped launch is not cut into strips: compare whole rounds of big tiles (one per CU, time 1 each) with rounds
       // of small ones (two per CU, a quarter of the work each at lower efficiency: 0.6 per round, 0.3 when half empty).
       const long long g = p->groups > 1 ? p->groups : 1;
@@ -1055,9 +1054,8 @@ Plan make_plan(const hap_gemm_problem* p) {
       big = tb <= ts;
     }
     pl.bm = pl.bn = big ? 256 : 128;
-    pl.dma = dma_variant();
-    static const char* names[2][2] = {{"bf16_128x128x64_staged", "bf16_128x128x64_dma2"}, {"bf16_256x256x64_staged", "bf16_256x256x64_dma2"}};
-    pl.name = names[big][pl.dma ? 1 : 0];
+    pl.dma = 1;
+    pl.name = big ? "bf16_256x256x64_dma2" : "bf16_128x128x64_dma2";
   }
   return pl;
 }
@@ -1125,10 +1123,8 @@ int dispatch_tile(const hap_gemm_problem* p, const Plan& pl, const GemmArgs& a, 
   if constexpr (sizeof(T) == 4) {
     return dispatch_layout<T, TC, 64, 64, 64, 2, 2>(p, a, groups, st);
   } else {
-    if (pl.bm == 256 && pl.dma >= 1) return dispatch_dma<TC, 256, 256, 64, 2, 2, 4>(p, a, groups, st);
-    if (pl.bm == 128 && pl.dma >= 1) return dispatch_dma<TC, 128, 128, 64, 2, 2, 2>(p, a, groups, st);
-    if (pl.bm == 256) return dispatch_layout<T, TC, 256, 256, 64, 2, 4>(p, a, groups, st);
-    return dispatch_layout<T, TC, 128, 128, 64, 2, 2>(p, a, groups, st);
+    if (pl.bm == 256) return dispatch_dma<TC, 256, 256, 64, 2, 2, 4>(p, a, groups, st);
+    return dispatch_dma<TC, 128, 128, 64, 2, 2, 2>(p, a, groups, st);
   }
 }
 
@@ -1144,6 +1140,7 @@ namespace {
  * quarter of the work at lower efficiency, and two of them share a CU. */
 double small_tiles_time(long long n) {
   if (n <= 0) return 0.0;
+  const int kCUs = cu_count();
   // measured: a round of 512 small tiles takes 0.58 of a round of 256 big ones; a last round that leaves every CU at
   // most one small tile 0.36 (the tile has the CU to itself)
   const long long full = n / (2 * kCUs), rest = n % (2 * kCUs);
@@ -1172,6 +1169,8 @@ hap_gemm_problem sub_problem(const hap_gemm_problem* p, int64_t m_lo, int64_t m_
 static int64_t g_view_limit = kViewLimitBytes;
 static int64_t g_cut_products = 0;      // products run in pieces so far (testing aid, not synchronised)
 
+/* Test hook (declared in hap_internal.h, not part of the public interface): lowers the reach at which operand views are
+ * cut so the cutting can be exercised on small inputs; returns how many products have run in pieces so far. */
 extern "C" int64_t hap_debug_set_gemm_view_limit(int64_t bytes) {
   g_view_limit = bytes > 0 && bytes < kViewLimitBytes ? bytes : kViewLimitBytes;
   return g_cut_products;
@@ -1245,6 +1244,7 @@ static bool run_large(const hap_gemm_problem* p, void* stream, int* rc) {
  * 5.  The engine therefore cuts the output into a part whose big tiles fill whole rounds and a
  * remainder strip computed with 128x128 tiles, when its cost model says that is faster. */
 static int run_auto_tiled(const hap_gemm_problem* p, const Plan& pl, void* stream) {
+  const int kCUs = cu_count();
   const long long Mp = p->M + pl.skewM, Np = p->N + pl.skewN;
   const long long tm = cdiv(Mp, 256), tn = cdiv(Np, 256);
   const long long sm = cdiv(Mp, 128), sn = cdiv(Np, 128);
@@ -1350,10 +1350,7 @@ int hap_gemm_run(const hap_gemm_problem* p, void* stream) {
     if (run_large(p, stream, &rc)) return rc;
   }
   const Plan pl = make_plan(p);
-  static const bool split_ok = !(getenv("HAP_GEMM_SPLIT") && !strcmp(getenv("HAP_GEMM_SPLIT"), "0"));   // tuning aid
-  static const int forced_tile = getenv("HAP_GEMM_TILE") ? atoi(getenv("HAP_GEMM_TILE")) : 0;             // tuning aid
-  if (forced_tile && p->tile == 0 && pl.tiled && pl.dma && !grouped) { hap_gemm_problem q = *p; q.tile = forced_tile; return hap_gemm_run(&q, stream); }
-  if (pl.tiled && pl.dma && p->tile == 0 && pl.bm == 256 && split_ok && !grouped) return run_auto_tiled(p, pl, stream);
+  if (pl.tiled && pl.dma && p->tile == 0 && pl.bm == 256 && !grouped) return run_auto_tiled(p, pl, stream);
 
   if (!pl.tiled) {
     GenericArgs g;
@@ -1427,6 +1424,7 @@ int hap_gemm_run(const hap_gemm_problem* p, void* stream) {
     // keeping at least 4 K tiles per workgroup (2 for the small fp32 tiles, whose loop is bound by one load
     // latency per tile), as far as the caller's workspace allows.
     const long long out_tiles = (long long)a.tiles_m * a.tiles_n * groups;
+    const int kCUs = cu_count();
     const long long slots = pl.bm == 256 ? kCUs : (pl.bm == 128 ? 2 * kCUs : 4 * kCUs);
     const int min_tiles = pl.bm == 64 ? 2 : 4;
     long long g = slots / out_tiles;

@@ -29,6 +29,13 @@ int hap_colsum_grouped(int groups, int64_t rows, int64_t cols, int io_dtype, con
 int hap_gelu_bwd_grouped(int groups, int64_t rows, int64_t cols, int io_dtype, const void* preact, int64_t ldp, const void* dy,
                          int64_t lddy, void* out, int64_t ldo, const int32_t* group_len, void* stream);
 
+/* Test hook, not part of the public interface.  The tiled GEMM kernels address an operand with 32-bit offsets, so the
+ * engine cuts a product whose operand view reaches 2 GiB into row blocks (K-contiguous operand: separate launches) or
+ * contraction segments (M- / N-contiguous operand: one launch).  This lowers that threshold so that the cutting can be
+ * exercised on small inputs; bytes <= 0 (or above the hardware reach) restores the default.  Returns how many products
+ * the engine has run in pieces so far in this process.  Process-wide, not thread-safe. */
+int64_t hap_debug_set_gemm_view_limit(int64_t bytes);
+
 #ifdef __cplusplus
 }
 #endif

@@ -566,7 +566,15 @@ int hap_layernorm_bwd(int64_t rows, int64_t n, int io_dtype, const void* x, cons
                       void* ws, size_t ws_bytes, void* stream) {
   hap_clear_error();
   if (rows < 0 || n < 1) return hap_fail(HAP_EINVAL, "bad size");
-  if (rows == 0) return HAP_OK;
+  if (rows == 0) {
+    // A device whose batch shard is empty (B_j = 0 is feasible in Eq. (opt_B)) still contributes its partial parameter
+    // gradients to the all-reduce: they are empty sums, written as zeros (the column-sum fold over zero partial rows).
+    if (!dgamma || !dbeta) return hap_fail(HAP_EINVAL, "NULL pointer");
+    const dim3 fgrid((unsigned)((n + 15) / 16), 1);
+    hipLaunchKernelGGL(colsum_final_kernel, fgrid, dim3(256), 0, (hipStream_t)stream, n, 0, (const float*)dgamma, dgamma, n);
+    hipLaunchKernelGGL(colsum_final_kernel, fgrid, dim3(256), 0, (hipStream_t)stream, n, 0, (const float*)dbeta, dbeta, n);
+    return check_launch("layernorm_bwd (empty)");
+  }
   if (!x || !gamma || !mean || !rstd || !dy || !dx || !dgamma || !dbeta) return hap_fail(HAP_EINVAL, "NULL pointer");
   const size_t need = hap_layernorm_bwd_workspace(rows, n);
   if (!ws || ws_bytes < need) return hap_fail(HAP_EWORKSPACE, "layernorm_bwd needs %zu workspace bytes", need);

@@ -38,7 +38,7 @@ static int add_triple(triple* T, int* n, uint64_t pre, uint64_t post, int kind, 
   return 0;
 }
 
-/* Matches the rules on the graph (Sec. 4.2: "enumerating all rules and finding matches"). */
+/* Builds the background theory: every rule is matched against every node of the graph (Sec. 4.2). */
 static int build_theory(int n_nodes, const hap_graph_node* g, const hap_synth_rules* r, triple* T, int* nt) {
   *nt = 0;
   int bad = 0;

@@ -217,7 +217,7 @@ class EncoderShard:
         self.d_fc2 = L(N, max(self.f, 1), hidden, hap.REPLICATED, one, io, ldx=ldf, ldw=hidden, ldy=hidden, m=1)
         # Q|K|V are column blocks of the [N x 3hd] projection output; O and dO are [N x hd]
         self.d_attn = hap.AttnDesc(self.B, max(self.nh, 1), S, d, True, [0, max(self.nh, 1)], stride_b=S * 3 * hd, stride_s=3 * hd, stride_h=d,
-                                   o_strides=(S * hd, hd, d)) if hd else None
+                                   o_strides=(S * hd, hd, d)) if hd and self.B else None    # no (batch entry, head) pair: no attention call
         nws = max([hap.hap_linear_bwd_workspace(x, 0) for x in (self.d_qkv, self.d_wo, self.d_fc1, self.d_fc2)] +
                   [hap.hap_layernorm_bwd_workspace(N, hidden), hap.hap_colsum_workspace(N, hidden),
                    hap.hap_attn_bwd_workspace(self.d_attn, 0) if hd else 0, 256])
@@ -242,7 +242,8 @@ class EncoderShard:
             return
         _call(timer, "qkv_fwd", lambda: hap.hap_sharded_linear_fwd(self.d_qkv, 0, self.ln1, self.Wqkv, self.bqkv, self.qkv, None, self.ws))
         q = self.qkv.data_ptr()
-        _call(timer, "attn_fwd", lambda: hap.hap_sharded_attn_fwd(self.d_attn, 0, q, q + hd * 2, q + 2 * hd * 2, self.o, self.lse))
+        if self.d_attn is not None:
+            _call(timer, "attn_fwd", lambda: hap.hap_sharded_attn_fwd(self.d_attn, 0, q, q + hd * 2, q + 2 * hd * 2, self.o, self.lse))
         _call(timer, "wo_fwd", lambda: hap.hap_sharded_linear_fwd(self.d_wo, 0, self.o, self.Wo, None, self.attn_part, None, self.ws))
 
     def mlp_forward(self, x1, timer=None):
@@ -275,8 +276,9 @@ class EncoderShard:
             return
         _call(timer, "wo_bwd", lambda: hap.hap_sharded_linear_bwd(self.d_wo, 0, self.o, self.Wo, None, dx1, self.do, self.dWo, self.io, None, self.ws))
         q, dq = self.qkv.data_ptr(), self.dqkv.data_ptr()
-        _call(timer, "attn_bwd", lambda: hap.hap_sharded_attn_bwd(self.d_attn, 0, q, q + hd * 2, q + 2 * hd * 2, self.o, self.lse, self.do,
-                                                                  dq, dq + hd * 2, dq + 2 * hd * 2, self.ws))
+        if self.d_attn is not None:
+            _call(timer, "attn_bwd", lambda: hap.hap_sharded_attn_bwd(self.d_attn, 0, q, q + hd * 2, q + 2 * hd * 2, self.o, self.lse, self.do,
+                                                                      dq, dq + hd * 2, dq + 2 * hd * 2, self.ws))
         _call(timer, "qkv_bwd", lambda: hap.hap_sharded_linear_bwd(self.d_qkv, 0, self.ln1, self.Wqkv, None, self.dqkv, self.dln1_part, self.dWqkv,
                                                                    self.io, self.dbqkv, self.ws))
 
@@ -344,9 +346,7 @@ class EncoderLayerProgram:
             self._reduce([s.mlp_part for s in self.shards], self.red)
             self._add(N, self.x1, self.red, p["b2"], self.y)
         else:
-            for s in self.shards:
-                if s.N == 0:
-                    continue
+            for s in self.shards:      # a device with an empty batch shard runs the same calls on zero rows
                 xr, x1r, yr = s.rows(self.x), s.rows(self.x1), s.rows(self.y)
                 s.attn_forward(xr)
                 self._add(s.N, xr, s.attn_part, p["bo"], x1r)
@@ -366,9 +366,7 @@ class EncoderLayerProgram:
             self._reduce([s.dln1_part for s in self.shards], self.red)
             s0.ln1_backward(self.x, self.red, self.dx1, self.dx)
         else:
-            for s in self.shards:
-                if s.N == 0:
-                    continue
+            for s in self.shards:      # an empty shard's weight-gradient partials come out as zeros (empty sums)
                 xr, x1r, dyr, dx1r, dxr = (s.rows(t) for t in (self.x, self.x1, self.dy, self.dx1, self.dx))
                 s.mlp_backward(dyr)
                 s.ln2_backward(x1r, s.dln2_part, dyr, dx1r)

@@ -48,17 +48,18 @@ def test_attention_slices_fwd_bwd(hap, B, H, S, D, over_heads, offsets):
     Oo, lseo = oatt.attn_fwd(tr(Qh), tr(Kh), tr(Vh))
     # backward oracle from exact O; the device uses its own bf16 O for D = rowsum(dO * O)
     dQo, dKo, dVo = oatt.attn_bwd(tr(Qh), tr(Kh), tr(Vh), tr(dOh))
-    # dS = P * (dP - D) subtracts two sums that the device forms from bf16 data in different orders (D from its
-    # own bf16 O); where they cancel (one key: dP == D exactly) the exact dQ, dK are ~0 and only this absolute
-    # error is left:  |err dS| <= 2^-8 P (|dP| + |D|),  carried through dQ = scale dS K,  dK = scale dS^T Q.
+    # The bar is max|err| <= 2e-2 * max|ref| per tensor.  Only where the reference is exactly zero (a single key:
+    # P = 1, dP == D, so dS = dQ = dK = 0 and a relative metric is undefined) an absolute bound takes its place:
+    # the device forms dP and D from bf16 data in different summation orders, which leaves
+    # |err dS| <= 2^-8 P (|dP| + |D|), carried through dQ = scale dS K and dK = scale dS^T Q.
     sc = 1.0 / np.sqrt(D)
-    P = np.exp(np.einsum("bhqd,bhkd->bhqk", tr(Qh), tr(Kh)) * sc - lseo[..., None])
-    dPa = np.abs(np.einsum("bhqd,bhkd->bhqk", tr(dOh), tr(Vh)))
-    Da = np.abs((tr(dOh) * Oo).sum(-1))[..., None]
-    eS = 2.0 ** -8 * P * (dPa + Da)
-    floors = {"O": np.zeros_like(Oo), "dV": np.zeros_like(Oo),
-              "dQ": sc * np.einsum("bhqk,bhkd->bhqd", eS, np.abs(tr(Kh))),
-              "dK": sc * np.einsum("bhqk,bhqd->bhkd", eS, np.abs(tr(Qh)))}
+    zero_floor = {}
+    if S == 1:
+        dPa = np.abs(np.einsum("bhqd,bhkd->bhqk", tr(dOh), tr(Vh)))
+        Da = np.abs((tr(dOh) * Oo).sum(-1))[..., None]
+        eS = 2.0 ** -8 * (dPa + Da)
+        zero_floor = {"dQ": sc * np.einsum("bhqk,bhkd->bhqd", eS, np.abs(tr(Kh))),
+                      "dK": sc * np.einsum("bhqk,bhqd->bhkd", eS, np.abs(tr(Qh)))}
     for j in range(len(offsets) - 1):
         lo, hi = offsets[j], offsets[j + 1]
         O.zero_(); lse.zero_(); dQ.zero_(); dK.zero_(); dV.zero_()
@@ -71,8 +72,14 @@ def test_attention_slices_fwd_bwd(hap, B, H, S, D, over_heads, offsets):
         for n, ref in (("O", Oo), ("dQ", dQo), ("dK", dKo), ("dV", dVo)):
             if hi > lo:
                 err = np.abs(got[n][sl] - ref[sl]).max()
+                scale_ref = np.abs(ref[sl]).max()
                 assert np.isfinite(got[n][sl]).all()
-                assert err <= TOL["bf16"] * np.abs(ref[sl]).max() + floors[n][sl].max(), f"attn shard{j} {n}: {err:.3e}"
+                if scale_ref == 0.0:
+                    assert n in zero_floor and err <= zero_floor[n][sl].max(), f"attn shard{j} {n}: |err| {err:.3e} against an all-zero reference"
+                    print(f"attn B{B} H{H} S{S} D{D} shard{j} {n}: reference is exactly zero, |err| = {err:.3e}")
+                    continue
+                print(f"attn B{B} H{H} S{S} D{D} shard{j} {n}: max|err|/max|ref| = {err / scale_ref:.3e}")
+                assert err <= TOL["bf16"] * scale_ref, f"attn shard{j} {n}: max|err|/max|ref| = {err / scale_ref:.3e} > {TOL['bf16']:.0e}"
             assert not got[n][~mask].any(), f"{n}: (batch, head) pairs outside the slice were written"
         if hi > lo:
             assert np.abs(got_lse[sl] - lseo[sl]).max() <= 2e-2
@@ -196,6 +203,10 @@ def test_row_ops_degenerate_sizes(hap):
         hap.hap_colsum(0, 9, io, keep, 9, s, ws)
         assert not host(s).any()
         hap.hap_layernorm_fwd(0, 9, io, keep, keep, keep, keep, mean, rstd)
+        # LayerNorm backward of an empty shard: dx has no rows, the partial parameter gradients are empty sums = zeros
+        dg9 = empty((9,), "f32", float("nan")); db9 = empty((9,), "f32", float("nan"))
+        hap.hap_layernorm_bwd(0, 9, io, keep, keep, mean, rstd, keep, keep, dg9, db9, ws)
+        assert not host(dg9).any() and not host(db9).any()
         hap.hap_gelu_bwd(0, 9, io, keep, 9, keep, 9, keep, 9)
         hap.hap_add(0, 9, io, keep, 9, keep, 9, None, keep, 9)
         hap.hap_add(4, 0, io, keep, 9, keep, 9, None, keep, 9)

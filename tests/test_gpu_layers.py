@@ -76,6 +76,10 @@ def _check_layer(hap, style, B, S, hidden, heads, d, ffn, speeds):
     _, foffs = ratios_offsets(hap, speeds, ffn)
     _, boffs = ratios_offsets(hap, speeds, B)
     prog = EncoderLayerProgram(style, B, S, hidden, heads, d, ffn, hoffs, foffs, boffs, pd, xd, dyd)
+    for s in prog.shards:
+        if s.N == 0:      # an empty batch shard: its partial gradients must be WRITTEN as zeros, not left as they were
+            for t in (s.dWqkv, s.dWo, s.dW1, s.dW2, s.dbqkv, s.db1, s.dg1, s.dbe1, s.dg2, s.dbe2):
+                t.fill_(float("nan"))
     prog.forward(); prog.backward()
     ref = olay.encoder_layer(xh, ph, dyh, B, S, heads, d)
     for n, t in (("x1", prog.x1), ("y", prog.y), ("dx1", prog.dx1), ("dx", prog.dx), ("db2", prog.db2), ("dbo", prog.dbo)):
@@ -104,8 +108,6 @@ def _check_layer(hap, style, B, S, hidden, heads, d, ffn, speeds):
                 check(f"db1_{j}", host(s.db1)[:f], ref["db1"][fc], "bf16")
                 check(f"dW2_{j}", host(s.dW2)[:f], ref["dW2"][fc], "bf16")
         else:
-            if s.N == 0:
-                continue
             H = hidden
             got = host(s.dWqkv)
             parts = {"dWq": got[:, :H], "dWk": got[:, H:2 * H], "dWv": got[:, 2 * H:3 * H], "dWo": host(s.dWo), "dW1": host(s.dW1)[:, :ffn],
@@ -135,6 +137,14 @@ def test_encoder_layer_heads_and_ffn_sharded(hap):
 def test_vit_layer_batch_sharded(hap):
     """cfg5 at reduced size: 5 devices with speeds (1,.8,.8,.4,.25): batch slices, seq 197, head_dim 64."""
     _check_layer(hap, "data", B=13, S=197, hidden=256, heads=4, d=64, ffn=520, speeds=(1.0, 0.8, 0.8, 0.4, 0.25))
+
+
+def test_vit_layer_batch_sharded_with_an_empty_device(hap):
+    """Four samples over five devices (1, .8, .8, .4, .25) round to (1, 1, 1, 1, 0): the last device owns no rows, runs the
+    same calls on zero rows and contributes all-zero partial weight gradients (its buffers are NaN-filled beforehand)."""
+    sizes, _ = ratios_offsets(hap, (1.0, 0.8, 0.8, 0.4, 0.25), 4)
+    assert sizes == [1, 1, 1, 1, 0]
+    _check_layer(hap, "data", B=4, S=197, hidden=256, heads=4, d=64, ffn=520, speeds=(1.0, 0.8, 0.8, 0.4, 0.25))
 
 
 def test_vit_mlp_sfb_weight_gradients(hap):
