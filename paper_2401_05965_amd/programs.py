@@ -220,7 +220,7 @@ class EncoderShard:
                                    o_strides=(S * hd, hd, d)) if hd and self.B else None    # no (batch entry, head) pair: no attention call
         nws = max([hap.hap_linear_bwd_workspace(x, 0) for x in (self.d_qkv, self.d_wo, self.d_fc1, self.d_fc2)] +
                   [hap.hap_layernorm_bwd_workspace(N, hidden), hap.hap_colsum_workspace(N, hidden),
-                   hap.hap_attn_bwd_workspace(self.d_attn, 0) if hd else 0, 256])
+                   hap.hap_attn_bwd_workspace(self.d_attn, 0) if self.d_attn is not None else 0, 256])
         self.ws = torch.empty((nws,), dtype=torch.uint8, device=dev)
 
     # ---- token rows of this device inside whole [tokens x hidden] tensors

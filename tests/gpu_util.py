@@ -61,5 +61,6 @@ def relerr(got, ref):
 
 def check(name, got, ref, dtype):
     e = relerr(got, ref)
+    print(f"parity {name}: max|err|/max|ref| = {e:.3e} (bar {TOL[dtype]:.0e})")
     assert e <= TOL[dtype], f"{name}: max|err|/max|ref| = {e:.3e} > {TOL[dtype]:.0e}"
     return e

@@ -7,7 +7,7 @@ import pytest
 
 import hapgen
 from hapgen import TensorId as T
-from oracle import pointwise as opw, lp as olp, rounding as ornd
+from oracle import layers as olay, lp as olp, rounding as ornd, sfb as osfb
 
 pytestmark = pytest.mark.gpu
 
@@ -52,22 +52,21 @@ def test_cfg2_mlp_shard_full_size_sampled(hap, cfg2, j):
     rows = np.unique(np.concatenate([[0, 255, 256, Tn - 1], rng.integers(0, Tn, 28)]))
     X, dO = cfg2["Xh"], cfg2["dOh"]
     W1, b1, W2 = cfg2["W1h"][:, lo:hi], cfg2["b1h"][lo:hi], cfg2["W2h"][lo:hi]
-    # sampled token rows: forward and bwd-data are row-wise
-    pre = X[rows] @ W1 + b1
-    H = opw.gelu(pre)
-    check("H rows", host(s.H[rows])[:, :f], H, "bf16")
-    check("pre rows", host(s.pre[rows])[:, :f], pre, "bf16")
-    check("P rows", host(s.P[rows]), H @ W2, "bf16")
-    dH = dO[rows] @ W2.T
-    check("dH rows", host(s.dH[rows])[:, :f], dH, "bf16")
-    check("dX rows", host(s.dX[rows]), (dH * opw.gelu_grad(pre)) @ W1.T, "bf16")
-    # sampled ffn columns (first, last, tile edges, random): weight gradients are column-wise in the ffn index
+    # sampled token rows: forward and bwd-data are row-wise, so the block restricted to those rows is an exact sub-problem
+    zero_b2 = np.zeros(h)
+    r = olay.mlp_block(X[rows], W1, b1, W2, zero_b2, dO[rows])
+    check("H rows", host(s.H[rows])[:, :f], r["H"], "bf16")
+    check("pre rows", host(s.pre[rows])[:, :f], r["pre"], "bf16")
+    check("P rows", host(s.P[rows]), r["out"], "bf16")
+    check("dH rows", host(s.dH[rows])[:, :f], r["dH"], "bf16")
+    check("dX rows", host(s.dX[rows]), r["dX"], "bf16")
+    # sampled ffn columns (first, last, tile edges, random): the weight gradients of an ffn column depend on that column only,
+    # so the block restricted to those columns of W1 / rows of W2, over ALL tokens, is an exact sub-problem as well
     cols = np.unique(np.concatenate([[0, 255, 256, f - 1, (f // 256) * 256 % f], rng.integers(0, f, 11)]))
-    pre_c = X @ W1[:, cols] + b1[cols]
-    dP_c = (dO @ W2[cols].T) * opw.gelu_grad(pre_c)
-    check("dW1 cols", host(s.dW1)[:, cols], X.T @ dP_c, "bf16")
-    check("db1 cols", host(s.db1)[cols], dP_c.sum(0), "bf16")
-    check("dW2 rows", host(s.dW2)[cols], opw.gelu(pre_c).T @ dO, "bf16")
+    c = olay.mlp_block(X, W1[:, cols], b1[cols], W2[cols], zero_b2, dO)
+    check("dW1 cols", host(s.dW1)[:, cols], c["dW1"], "bf16")
+    check("db1 cols", host(s.db1)[cols], c["db1"], "bf16")
+    check("dW2 rows", host(s.dW2)[cols], c["dW2"], "bf16")
     # padding columns of the compact buffers stay untouched (they were zero-initialised)
     assert not host(s.H)[:, f:].any() and not host(s.dW1)[:, f:].any()
 
@@ -88,11 +87,9 @@ def test_cfg3_sfb_full_size_sampled(hap):
     assert np.isfinite(got).all()
     rng = np.random.default_rng(3)
     ri = np.unique(np.concatenate([[0, 255, 256, inf - 1], rng.integers(0, inf, 12)]))
-    ref = sum(Xh[i][:rows[i]][:, ri].T @ Yh[i][:rows[i]] for i in range(len(rows)))
-    check("sfb dW rows", got[ri], ref, "bf16")
+    check("sfb dW rows", got[ri], osfb.sfb_grad([x[:, ri] for x in Xh], Yh, rows), "bf16")      # rows of dW <-> columns of the X factors
     ci = np.unique(np.concatenate([[0, 255, 256, outf - 1], rng.integers(0, outf, 12)]))
-    ref = sum(Xh[i][:rows[i]].T @ Yh[i][:rows[i]][:, ci] for i in range(len(rows)))
-    check("sfb dW cols", got[:, ci], ref, "bf16")
+    check("sfb dW cols", got[:, ci], osfb.sfb_grad(Xh, [y[:, ci] for y in Yh], rows), "bf16")
     # property that holds at any size: the rebuild equals the sum of per-device local gradients (Fig. sfb(b) vs (c))
     torch = torch_mod()
     naive = torch.zeros_like(prog.dW)
@@ -104,7 +101,6 @@ def test_cfg3_sfb_full_size_sampled(hap):
 def test_moe_expert_block_full_size_sampled(hap):
     """The MoE row at the size bench.py times (device 0 of `moe_experts_bf16`: 10 experts x 2048 rows, hidden 768, ffn 3072), with
     ragged token counts; sampled token rows (forward, bwd-data) and sampled ffn columns (weight / bias gradients) of three experts."""
-    from oracle import pointwise as opw
     from paper_2401_05965_amd.programs import MoeExpertShard
     torch = torch_mod()
     w = hapgen.WORKLOADS["moe_experts_bf16"]
@@ -123,20 +119,17 @@ def test_moe_expert_block_full_size_sampled(hap):
     for e in (0, 3, n - 1):
         ne = int(rows[e])
         r = np.unique(np.concatenate([[0, ne - 1, min(255, ne - 1), min(256, ne - 1)], rng.integers(0, ne, 12)]))
-        pre = Xh[e][r] @ W1h[e] + b1h[e]
-        H = opw.gelu(pre)
-        check(f"H e{e}", host(sh.H[e][r]), H, "bf16")
-        check(f"out e{e}", host(sh.Out[e][r]), H @ W2h[e] + b2h[e], "bf16")
-        dH = dOh[e][r] @ W2h[e].T
-        check(f"dH e{e}", host(sh.dH[e][r]), dH, "bf16")
-        check(f"dX e{e}", host(sh.dX[e][r]), (dH * opw.gelu_grad(pre)) @ W1h[e].T, "bf16")
+        one = lambda a: a[None]        # the oracle's expert block on ONE expert restricted to sampled token rows / ffn columns
+        ref = olay.moe_ffn_block(one(Xh[e][r]), one(W1h[e]), one(b1h[e]), one(W2h[e]), one(b2h[e]), one(dOh[e][r]))
+        check(f"H e{e}", host(sh.H[e][r]), ref["H"][0], "bf16")
+        check(f"out e{e}", host(sh.Out[e][r]), ref["out"][0], "bf16")
+        check(f"dH e{e}", host(sh.dH[e][r]), ref["dH"][0], "bf16")
+        check(f"dX e{e}", host(sh.dX[e][r]), ref["dX"][0], "bf16")
         cols = np.unique(np.concatenate([[0, 255, 256, F - 1], rng.integers(0, F, 8)]))
-        Xe, dOe = Xh[e][:ne], dOh[e][:ne]
-        pre_c = Xe @ W1h[e][:, cols] + b1h[e][cols]
-        dP_c = (dOe @ W2h[e][cols].T) * opw.gelu_grad(pre_c)
-        check(f"dW1 e{e}", host(sh.dW1[e])[:, cols], Xe.T @ dP_c, "bf16")
-        check(f"db1 e{e}", host(sh.db1[e])[cols], dP_c.sum(0), "bf16")
-        check(f"dW2 e{e}", host(sh.dW2[e])[cols], opw.gelu(pre_c).T @ dOe, "bf16")
-        check(f"db2 e{e}", host(sh.db2[e]), dOe.sum(0), "bf16")
+        refc = olay.moe_ffn_block(one(Xh[e]), one(W1h[e][:, cols]), one(b1h[e][cols]), one(W2h[e][cols]), one(b2h[e]), one(dOh[e]), rows=[ne])
+        check(f"dW1 e{e}", host(sh.dW1[e])[:, cols], refc["dW1"][0], "bf16")
+        check(f"db1 e{e}", host(sh.db1[e])[cols], refc["db1"][0], "bf16")
+        check(f"dW2 e{e}", host(sh.dW2[e])[cols], refc["dW2"][0], "bf16")
+        check(f"db2 e{e}", host(sh.db2[e]), refc["db2"][0], "bf16")
         if ne < C:      # rows without a token stay as allocated (zero)
             assert not host(sh.H[e][ne:]).any() and not host(sh.dX[e][ne:]).any()
