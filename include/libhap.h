@@ -217,6 +217,20 @@ int hap_sfb_grad(int m, const void* const* X, const void* const* dY, const int64
                  float* dW, int64_t lddw, int accumulate, void* ws, size_t ws_bytes, void* stream);
 size_t hap_sfb_workspace(int m, const int64_t* rows, int64_t in_features, int64_t out_features);
 
+/* hap_sfb_grad for callers that cannot allocate device memory or hand over a workspace: code under HIP graph capture,
+ * tight serving / training loops, harnesses that forbid hipMalloc.  Same arguments and same results as hap_sfb_grad
+ * given a workspace of HAP_SFB_STATIC_SCRATCH_BYTES, but the split-K partial tiles live in an array that is part of
+ * the library's device image (each GPU the library runs on holds HAP_SFB_STATIC_SCRATCH_BYTES of it until the process
+ * ends); the call allocates and frees nothing.  Limit: in_features * out_features <= HAP_SFB_STATIC_MAX_ELEMS
+ * (HAP_EUNSUPPORTED beyond it, nothing launched).  All calls on one GPU share that GPU's array: calls that may run
+ * concurrently on one GPU (different streams, different threads) race on it and must be serialised by the caller; the
+ * array needs no clearing between calls (every partial tile is written before it is read).                          */
+#define HAP_SFB_STATIC_SCRATCH_BYTES ((size_t)64 << 20)
+#define HAP_SFB_STATIC_MAX_ELEMS ((int64_t)8 << 20)
+int hap_sfb_grad_static(int m, const void* const* X, const void* const* dY, const int64_t* rows,
+                        int64_t in_features, int64_t out_features, int64_t ldx, int64_t ldy, int in_dtype,
+                        float* dW, int64_t lddw, int accumulate, void* stream);
+
 /* ------------------------------------------------------------------ device: MoE experts --- */
 
 /* One fully-connected layer per expert of a Mixture-of-Experts layer whose EXPERT axis is sharded

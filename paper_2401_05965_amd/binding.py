@@ -378,6 +378,15 @@ def hap_sfb_grad(Xs, dYs, rows, in_features, out_features, ldx, ldy, in_dtype, d
                             wp, wb, _stream(stream)), "hap_sfb_grad")
 
 
+def hap_sfb_grad_static(Xs, dYs, rows, in_features, out_features, ldx, ldy, in_dtype, dW, lddw, accumulate=False, stream=None):
+    m = len(rows)
+    xp = (C.c_void_p * m)(*[_ptr(t) for t in Xs])
+    yp = (C.c_void_p * m)(*[_ptr(t) for t in dYs])
+    _check(lib.hap_sfb_grad_static(C.c_int(m), xp, yp, (C.c_int64 * m)(*map(int, rows)), C.c_int64(in_features), C.c_int64(out_features),
+                                   C.c_int64(ldx), C.c_int64(ldy), C.c_int(in_dtype), _ptr(dW), C.c_int64(lddw), C.c_int(int(accumulate)),
+                                   _stream(stream)), "hap_sfb_grad_static")
+
+
 def hap_sfb_workspace(m, rows, in_features, out_features) -> int:
     return int(lib.hap_sfb_workspace(C.c_int(m), (C.c_int64 * m)(*map(int, rows)), C.c_int64(in_features), C.c_int64(out_features)))
 

@@ -210,10 +210,47 @@ int hap_sharded_linear_bwd(const hap_linear_desc* d, int shard_index, const void
 
 size_t hap_sfb_workspace(int, const int64_t*, int64_t, int64_t) { return HAP_GEMM_WS_BYTES; }   // optional: split-K partial tiles
 
+static int sfb_grad_impl(int m, const void* const* X, const void* const* dY, const int64_t* rows,
+                         int64_t in_features, int64_t out_features, int64_t ldx, int64_t ldy, int in_dtype,
+                         float* dW, int64_t lddw, int accumulate, void* ws, size_t ws_bytes, void* stream);
+
 int hap_sfb_grad(int m, const void* const* X, const void* const* dY, const int64_t* rows,
                  int64_t in_features, int64_t out_features, int64_t ldx, int64_t ldy, int in_dtype,
                  float* dW, int64_t lddw, int accumulate, void* ws, size_t ws_bytes, void* stream) {
   hap_clear_error();
+  return sfb_grad_impl(m, X, dY, rows, in_features, out_features, ldx, ldy, in_dtype, dW, lddw, accumulate, ws, ws_bytes, stream);
+}
+
+/* Split-K partial tiles of hap_sfb_grad_static: one array per GPU, held until the process ends.  In host code the
+ * array's name is only a handle for hipGetSymbolAddress; kernels get the device address resolved below. */
+static __device__ __align__(256) unsigned char scratch[HAP_SFB_STATIC_SCRATCH_BYTES];
+
+int hap_sfb_grad_static(int m, const void* const* X, const void* const* dY, const int64_t* rows,
+                        int64_t in_features, int64_t out_features, int64_t ldx, int64_t ldy, int in_dtype,
+                        float* dW, int64_t lddw, int accumulate, void* stream) {
+  hap_clear_error();
+  if (in_features < 1 || out_features < 1) return hap_fail(HAP_EINVAL, "bad feature sizes");
+  if (in_features > HAP_SFB_STATIC_MAX_ELEMS / out_features)
+    return hap_fail(HAP_EUNSUPPORTED, "hap_sfb_grad_static: dW of %lld x %lld exceeds the %lld elements its fixed scratch is sized for; "
+                    "use hap_sfb_grad with a caller workspace", (long long)in_features, (long long)out_features, (long long)HAP_SFB_STATIC_MAX_ELEMS);
+  // each GPU holds its own copy of the array at its own address: resolve it once per device, with that device current
+  static void* resolved[64] = {};
+  int device = -1;
+  if (hipGetDevice(&device) != hipSuccess || device < 0 || device >= 64) return hap_fail(HAP_EDEVICE, "cannot identify the current device");
+  void* ptr = __atomic_load_n(&resolved[device], __ATOMIC_ACQUIRE);
+  if (!ptr) {
+    const hipError_t e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+    if (e != hipSuccess || !ptr) return hap_fail(HAP_EDEVICE, "cannot resolve the static scratch array: %s", hipGetErrorString(e));
+    __atomic_store_n(&resolved[device], ptr, __ATOMIC_RELEASE);     // every thread resolves the same address
+  }
+  // The partial tiles are written in full before the reduction reads them, so nothing has to be cleared between calls.
+  return sfb_grad_impl(m, X, dY, rows, in_features, out_features, ldx, ldy, in_dtype, dW, lddw, accumulate, ptr,
+                       (size_t)HAP_SFB_STATIC_SCRATCH_BYTES, stream);
+}
+
+static int sfb_grad_impl(int m, const void* const* X, const void* const* dY, const int64_t* rows,
+                         int64_t in_features, int64_t out_features, int64_t ldx, int64_t ldy, int in_dtype,
+                         float* dW, int64_t lddw, int accumulate, void* ws, size_t ws_bytes, void* stream) {
   if (m < 1 || m > HAP_SFB_MAX_DEVICES) return hap_fail(HAP_EINVAL, "m = %d outside [1, %d]", m, HAP_SFB_MAX_DEVICES);
   if (!X || !dY || !rows || !dW) return hap_fail(HAP_EINVAL, "NULL argument");
   if (in_features < 1 || out_features < 1) return hap_fail(HAP_EINVAL, "bad feature sizes");
