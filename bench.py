@@ -440,7 +440,7 @@ def main():
         "config": {"workload": "cfg2_mlp_bf16 shards 0 and 2 fwd+bwd + cfg3_sfb_bf16 rebuild", "tokens": Tn, "hidden": h, "ffn": F,
                    "speeds": list(w2.speeds), "shard_sizes": sizes, "sfb_rows": list(rows), "step_gflop": round(step_flops / 1e9, 1),
                    "pct_of_bf16_mfma_peak": round(100 * value / PEAK_BF16_TFLOPS, 2)},
-        "roofline": {"bound": "mfma", "kernel": "gemm_dma_kernel<bf16,256x256x64> (" + dom + ": M=8192 N=4096 K=8402)",
+        "roofline": {"bound": "mfma", "kernel": "gemm_pp_kernel<bf16,256x256x32,4 stages> (" + dom + ": M=8192 N=4096 K=8402)",
                      "achieved": round(achieved, 1), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                      "frac": round(achieved / PEAK_BF16_TFLOPS, 4), "traffic": traffic_bytes,
                      "algorithmic_bytes": int(2 * (big.T * big.f + big.f * big.h + big.T * big.h)),

@@ -101,6 +101,15 @@ __device__ __forceinline__ GemmArgs group_outputs(const GemmArgs& args, const Gr
   return e;
 }
 
+/* Compile-time loop: f(std::integral_constant<int, 0>) ... f(std::integral_constant<int, N-1>). */
+template <int N, int I = 0, typename F>
+__device__ __forceinline__ void static_for(F&& f) {
+  if constexpr (I < N) {
+    f(std::integral_constant<int, I>());
+    static_for<N, I + 1>(f);
+  }
+}
+
 /* Values that are the same in every lane but that the compiler cannot prove uniform (they depend on
  * a table entry picked by a loop-carried index) are pinned to scalar registers; otherwise every
  * buffer instruction using them is wrapped in a per-lane "waterfall" loop. */
@@ -273,6 +282,27 @@ struct Frag<__bf16, KC, ROWS, BK> {
   }
 };
 
+/* The same two fragment fetches as FragReader::read, written as instructions of their own.  The compiler treats every
+ * LDS read it knows about as possibly aliasing the direct-to-LDS loads in flight and waits for ALL of them (vmcnt 0)
+ * in front of it, which would drain a ring of several tiles on every tile.  These reads are ordered by hand instead:
+ * the kernel waits for the awaited tile's loads (vmcnt) and a barrier before it reads a slot, and for the LDS counter
+ * before it uses the values.  `off` is a compile-time byte offset (below 65536). */
+template <int OFF>
+__device__ __forceinline__ bf16x8_t lds_read_b128_at(unsigned addr) {
+  i32x4_t v;
+  asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(v) : "v"(addr), "n"(OFF));
+  return __builtin_bit_cast(bf16x8_t, v);
+}
+template <int OFF_LO, int OFF_HI>
+__device__ __forceinline__ bf16x8_t lds_read_tr_pair_at(unsigned addr) {
+  typedef int i32x2_t __attribute__((ext_vector_type(2)));
+  i32x2_t lo, hi;
+  asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(lo) : "v"(addr), "n"(OFF_LO));
+  asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(hi) : "v"(addr), "n"(OFF_HI));
+  i32x4_t v = {lo[0], lo[1], hi[0], hi[1]};
+  return __builtin_bit_cast(bf16x8_t, v);
+}
+
 /* The same bf16 fragment fetch with the address arithmetic folded.  The swizzles are XORs, so the byte
  * address of the fragment of 32-row block i (rows wave_mn + 32 i ..) at k-step kk of a tile is
  *   K-contiguous:    ((lane constant + tile address) ^ (kk << 5)) + i * 32 rows
@@ -296,6 +326,12 @@ struct FragReader {
 #pragma unroll
       for (int b = 0; b < NBLK; ++b) at[b] = lc ^ (unsigned)(((wave_mn >> 5) + b) << 6);
     }
+  }
+  /* read() with the hand-ordered LDS instructions (see lds_read_b128_at); BLK and KKI fold into the offset field. */
+  template <int BLK, int KKI>
+  __device__ __forceinline__ bf16x8_t read_unordered(unsigned tile) const {
+    if constexpr (KC) return lds_read_b128_at<BLK * 32 * ROWB>((at[0] + tile) ^ (unsigned)(KKI << 5));
+    else return lds_read_tr_pair_at<KKI * 16 * ROWB, KKI * 16 * ROWB + 4 * ROWB>(at[BLK] + tile);
   }
   __device__ __forceinline__ bf16x8_t read(unsigned tile, int blk, int kk) const {
     if constexpr (KC) {
@@ -675,7 +711,7 @@ struct DmaLoader {
   /* Interior tile: every k of the tile is inside the logical range; soff = tile_offset() >= 0 goes in
    * the instruction's scalar offset. */
   __device__ __forceinline__ void issue(__amdgpu_buffer_rsrc_t rsrc, char* lds, int tid, unsigned soff) const {
-    const int wave_first = (tid & ~63);
+    const int wave_first = uni(tid & ~63);      // pinned to a scalar register: it feeds M0, the LDS address of the direct load
 #pragma unroll
     for (int i = 0; i < CPT; ++i) dma16(rsrc, lds + (wave_first + i * NT) * 16, base[i], soff);
   }
@@ -907,6 +943,232 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_dma_kernel(const GemmArgs
   epilogue_transposed<T, TC, TM, TN>(group_outputs(args, gv, bp.grp), acc, m0 + wm0, n0 + wn0, lane, smem + wave * (32 * (TN * 32 * (int)sizeof(TC) + 16)));
 }
 
+/* ---------------------------------------------------------------------------------------------
+ * bf16 main kernel for 256 x 256 output tiles: the same direct-to-LDS loads, swizzles and fragment
+ * addressing as gemm_dma_kernel, with the eight waves run as two groups that alternate between a
+ * memory phase and a matrix phase, half a K tile apart ("ping-pong").
+ *
+ * A SIMD hosts one wave of each group (waves w and w + 4).  For K tile u a wave first runs
+ *   Mem(u): fetch ALL of its fragments of tile u from LDS into registers, request the tile STAGES-1
+ *           ahead from global memory, wait for its own chunks of tile u+1 (zeroing ragged k ends),
+ * then, after a barrier,
+ *   Cmp(u): nothing but the tile's MFMAs, at raised priority,
+ * and another barrier.  Group 1 enters the loop one barrier later than group 0, so whenever one wave
+ * of a SIMD is in Cmp the other is in Mem: the matrix unit always has a wave that issues nothing but
+ * MFMAs, and the LDS reads and load issue of the other wave hide behind them instead of delaying
+ * every wave's first MFMA after a common barrier.
+ *
+ * Ring discipline (phase p = interval between consecutive barriers; group 0 runs Mem(u) in phase 2u,
+ * group 1 in phase 2u+1):
+ *   - tile v is first read in phase 2v; every wave has waited for its own chunks of tile v in its
+ *     Mem(v-1), i.e. by the barrier that ends phase 2v-1 (tile 0: before the first barrier);
+ *   - the request issued in Mem(u) overwrites the slot of tile u-1, which both groups finished
+ *     reading (LDS counter waited) by the barrier that ends phase 2u-1.
+ * ------------------------------------------------------------------------------------------- */
+#if !defined(HAP_PP_PRIO)
+#define HAP_PP_PRIO 1
+#endif
+constexpr bool kPingPongPrio = HAP_PP_PRIO != 0;    // raise the wave's priority for its matrix phase
+template <int N> __device__ __forceinline__ void wait_vmcnt() { asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory"); }
+
+/* Fragment addressing of the ping-pong kernel: every address is (a register computed once before the K loop) +
+ * (a compile-time offset in the instruction), so fetching a tile's fragments costs no vector ALU work at all - the
+ * other wave of the SIMD owns the vector ALU port with its MFMAs meanwhile.  The ring lies at byte `ring` of LDS and
+ * is wider than the 16-bit offset field reaches, hence one base register per 64 KiB of it. */
+template <bool KC, int ROWS, int BK, int NBLK, int NH>
+struct PinnedFrag {
+  static constexpr int KK = BK / 16;
+  static constexpr int CPR = (KC ? BK : ROWS) / 8;
+  static constexpr int ROWB = CPR * 16;
+  static constexpr int NB = KC ? KK : NBLK;      // K-contiguous: one base per k-step (the swizzle XOR); M/N-contiguous: one per 32-column block
+  unsigned base[NB][NH];
+  __device__ __forceinline__ void init(int lane, int wave_mn, unsigned ring) {
+    FragReader<KC, ROWS, BK, NBLK> fr;
+    fr.init(lane, wave_mn);
+#pragma unroll
+    for (int b = 0; b < NB; ++b)
+#pragma unroll
+      for (int h = 0; h < NH; ++h) base[b][h] = (KC ? (fr.at[0] ^ (unsigned)(b << 5)) : fr.at[b]) + ring + (unsigned)h * 65536u;
+  }
+  /* Fragment of 32-row block BLK at k-step KKI of the tile that starts OFF bytes into the ring. */
+  template <int OFF, int BLK, int KKI>
+  __device__ __forceinline__ bf16x8_t read() const {
+    constexpr int H = OFF >> 16, LO = OFF & 0xffff;
+    if constexpr (KC) {
+      static_assert(LO + BLK * 32 * ROWB < 65536, "offset field");
+      return lds_read_b128_at<LO + BLK * 32 * ROWB>(base[KKI][H]);
+    } else {
+      static_assert(LO + KKI * 16 * ROWB + 4 * ROWB < 65536, "offset field");
+      return lds_read_tr_pair_at<LO + KKI * 16 * ROWB, LO + KKI * 16 * ROWB + 4 * ROWB>(base[BLK][H]);
+    }
+  }
+};
+
+template <typename TC, bool AKC, bool BKC, int BM, int BN, int BK, int WGM, int WGN, int STAGES>
+__global__ __launch_bounds__(64 * WGM * WGN) void gemm_pp_kernel(const GemmArgs args) {
+  typedef __bf16 T;
+  constexpr int NT = 64 * WGM * WGN;
+  constexpr int NW = WGM * WGN;
+  constexpr int WTM = BM / WGM, WTN = BN / WGN;
+  constexpr int TM = WTM / 32, TN = WTN / 32;
+  constexpr int A_BYTES = BM * BK * 2, B_BYTES = BN * BK * 2, STAGE_BYTES = A_BYTES + B_BYTES;
+  constexpr int NH = (STAGES * STAGE_BYTES + 65535) / 65536;
+  typedef DmaLoader<AKC, BM, BK, NT> LA;
+  typedef DmaLoader<BKC, BN, BK, NT> LB;
+  constexpr int LPT = LA::CPT + LB::CPT;            // loads per thread and tile
+  constexpr int KK = BK / 16;
+  static_assert(STAGES >= 2 && STAGES <= 5 && (STAGES - 1) * LPT < 64, "ring depth");
+
+  extern __shared__ __attribute__((aligned(1024))) char smem[];
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = uni(tid >> 6);
+  const int wm0 = (wave / WGN) * WTM, wn0 = (wave % WGN) * WTN;
+  const bool late_group = wave >= NW / 2;            // waves w and w + NW/2 share a SIMD
+  const BlockPos bp = block_pos(args);
+  const int ksplit = args.ksplit, out_tile = bp.out_tile, split = bp.split, tm = bp.tm, tn = bp.tn;
+  const int m0 = tm * BM, n0 = tn * BN;
+  const GroupView gv = group_view(args, bp.grp);
+  const int m_lim = args.skewM + gv.M, n_lim = args.skewN + args.N;
+  if (args.ragged == 1 && (gv.M == 0 || m0 >= m_lim)) return;
+  const int all_tiles = gv.k >= 0 ? (args.skewK + gv.k + BK - 1 >= BK ? (args.skewK + gv.k + BK - 1) / BK : 1) : args.ntiles;
+
+  LA la; LB lb;
+  la.init(tid, m0, m_lim, args.lda);
+  lb.init(tid, n0, n_lim, args.ldb);
+  PinnedFrag<AKC, BM, BK, TM, NH> fra;
+  PinnedFrag<BKC, BN, BK, TN, NH> frb;
+  fra.init(lane, wm0, lds_addr(smem));
+  frb.init(lane, wn0, lds_addr(smem));
+
+  f32x16_t acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
+
+  const int first = (int)((long long)all_tiles * split / ksplit);
+  const int ntiles = (int)((long long)all_tiles * (split + 1) / ksplit) - first;
+  int seg0 = 0, skip = first;
+  while (seg0 + 1 < args.nseg) {
+    const int in_seg = (args.skewK + args.seg[seg0].k + BK - 1) / BK;
+    if (skip < in_seg) break;
+    skip -= in_seg;
+    seg0 = uni(seg0 + 1);
+  }
+  // request cursor (runs STAGES-1 tiles ahead) and landing cursor (the next tile whose arrival is awaited); tile v lives in slot v % STAGES
+  int pseg = seg0, pk0 = skip * BK, pkend = uni(args.skewK + (gv.k >= 0 ? gv.k : args.seg[seg0].k)), issued = 0;
+  __amdgpu_buffer_rsrc_t ra = make_rsrc(static_cast<const char*>(args.seg[seg0].a) + gv.oa, args.seg[seg0].a_bytes);
+  __amdgpu_buffer_rsrc_t rb = make_rsrc(static_cast<const char*>(args.seg[seg0].b) + gv.ob, args.seg[seg0].b_bytes);
+  int lseg = seg0, lk0 = pk0, lkend = pkend;
+
+  auto request = [&](auto slot_tag) {
+    constexpr int SLOT = decltype(slot_tag)::value;
+    char* pa = smem + SLOT * STAGE_BYTES;
+    char* pb = pa + A_BYTES;
+    const unsigned soa = LA::tile_offset(pk0, args.skewK, args.lda), sob = LB::tile_offset(pk0, args.skewK, args.ldb);
+    if (pk0 < args.skewK || pk0 + BK > pkend) {      // first / last tile of a segment: validity per chunk
+      la.issue_edge(ra, pa, tid, soa, pk0, args.skewK, pkend);
+      lb.issue_edge(rb, pb, tid, sob, pk0, args.skewK, pkend);
+    } else {
+      la.issue(ra, pa, wave << 6, soa);          // (issue() needs only the wave's first thread id, here already a scalar)
+      lb.issue(rb, pb, wave << 6, sob);
+    }
+    pk0 += BK;
+    ++issued;
+    if (pk0 >= pkend && pseg + 1 < args.nseg) {
+      pseg = uni(pseg + 1);
+      pk0 = 0;
+      pkend = uni(args.skewK + args.seg[pseg].k);
+      ra = make_rsrc(static_cast<const char*>(args.seg[pseg].a) + gv.oa, args.seg[pseg].a_bytes);
+      rb = make_rsrc(static_cast<const char*>(args.seg[pseg].b) + gv.ob, args.seg[pseg].b_bytes);
+    }
+  };
+  // Waits until at most `newer` tiles requested after the awaited one are still in flight, then zeroes the awaited
+  // tile's k elements outside the logical range (own chunks only) and moves the landing cursor on.
+  auto land = [&](auto slot_tag, int newer) {
+    constexpr int SLOT = decltype(slot_tag)::value;
+    if (newer >= STAGES - 2) wait_vmcnt<(STAGES - 2) * LPT>();          // the steady state
+    else if (STAGES > 3 && newer == 2) wait_vmcnt<(STAGES > 3 ? 2 : 0) * LPT>();
+    else if (STAGES > 2 && newer == 1) wait_vmcnt<(STAGES > 2 ? 1 : 0) * LPT>();
+    else wait_vmcnt<0>();
+    if (lk0 < args.skewK || lk0 + BK > lkend) {
+      char* sa = smem + SLOT * STAGE_BYTES;
+      la.fixup(sa, tid, lk0, args.skewK, lkend);
+      lb.fixup(sa + A_BYTES, tid, lk0, args.skewK, lkend);
+    }
+    lk0 += BK;
+    if (lk0 >= lkend && lseg + 1 < args.nseg) { lseg = uni(lseg + 1); lk0 = 0; lkend = uni(args.skewK + args.seg[lseg].k); }
+  };
+
+  static_for<STAGES - 1>([&](auto s) { if (s < ntiles) request(s); });
+  if (ntiles > 0) land(std::integral_constant<int, 0>(), issued - 1);
+  __builtin_amdgcn_s_barrier();                      // tile 0 is in LDS for everybody
+  if (late_group) __builtin_amdgcn_s_barrier();      // group 1 runs one phase behind group 0
+
+  // one K tile whose ring slot is known at compile time
+  // FAST: the tile requested and the tile awaited are interior tiles of their segments and both cursors stay inside their
+  // segments, a request is due and a tile follows - no per-chunk validity, no fix-up, no data-dependent branch at all.
+  // (The two forms share ONE copy of the matrix phase: two copies of the tile body made the compiler shuffle the 128
+  // accumulator registers between them through scratch memory.)
+  auto tile = [&](auto slot_tag, const bool fast, int u) __attribute__((always_inline)) {
+    constexpr int SLOT = decltype(slot_tag)::value;
+    constexpr int PREV = (SLOT + STAGES - 1) % STAGES, NEXT = (SLOT + 1) % STAGES;
+    // ---- Mem(u): all fragments of the tile, the request STAGES-1 tiles ahead (into the slot of tile u-1), arrival of tile u+1
+    bf16x8_t fa[KK][TM], fb[KK][TN];
+    static_for<KK>([&](auto kk) {
+      static_for<TN>([&](auto j) { fb[kk][j] = frb.template read<SLOT * STAGE_BYTES + A_BYTES, j, kk>(); });
+      static_for<TM>([&](auto i) { fa[kk][i] = fra.template read<SLOT * STAGE_BYTES, i, kk>(); });
+    });
+    if (fast) {
+      char* pa = smem + PREV * STAGE_BYTES;
+      la.issue(ra, pa, wave << 6, LA::tile_offset(pk0, args.skewK, args.lda));
+      lb.issue(rb, pa + A_BYTES, wave << 6, LB::tile_offset(pk0, args.skewK, args.ldb));
+      pk0 += BK;
+      ++issued;
+    } else {
+      if (issued < ntiles) request(std::integral_constant<int, PREV>());
+    }
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");     // this wave's reads of tile u are done (its slot is refilled two phases on)
+    if (fast) {
+      wait_vmcnt<(STAGES - 2) * LPT>();
+      lk0 += BK;
+    } else {
+      if (u + 1 < ntiles) land(std::integral_constant<int, NEXT>(), issued - (u + 2));
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_sched_barrier(0);
+    // ---- Cmp(u)
+    if (kPingPongPrio) __builtin_amdgcn_s_setprio(1);
+#pragma unroll
+    for (int kk = 0; kk < KK; ++kk)
+#pragma unroll
+      for (int x = 0; x < TM * TN; ++x) acc[x / TN][x % TN] = mfma(fb[kk][x % TN], fa[kk][x / TN], acc[x / TN][x % TN]);
+    if (kPingPongPrio) __builtin_amdgcn_s_setprio(0);
+    __builtin_amdgcn_sched_barrier(0);
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_sched_barrier(0);
+  };
+  for (int u0 = 0; u0 < ntiles; u0 += STAGES) {
+    const bool fast = issued + STAGES <= ntiles && pk0 >= args.skewK && pk0 + STAGES * BK < pkend &&
+                      lk0 >= args.skewK && lk0 + STAGES * BK < lkend;
+    static_for<STAGES>([&](auto s) { if (fast || u0 + s < ntiles) tile(s, fast, u0 + s); });
+  }
+  if (!late_group) __builtin_amdgcn_s_barrier();     // group 1's last matrix phase: after it nobody reads the ring any more
+
+  if (ksplit > 1) {
+    GemmArgs pa = args;
+    pa.c = args.partial + (((long long)bp.grp * (gridDim.x / ksplit) + out_tile) * ksplit + split) * (BM * BN);
+    pa.ldc = BN; pa.M = BM; pa.N = BN; pa.skewM = 0; pa.skewN = 0;
+    pa.preact = nullptr; pa.bias = nullptr; pa.act = HAP_ACT_NONE; pa.accumulate = 0; pa.vec_store = 1;
+    epilogue_transposed<T, float, TM, TN>(pa, acc, wm0, wn0, lane, smem + wave * (32 * (TN * 32 * 4 + 16)));
+    return;
+  }
+  epilogue_transposed<T, TC, TM, TN>(group_outputs(args, gv, bp.grp), acc, m0 + wm0, n0 + wn0, lane, smem + wave * (32 * (TN * 32 * (int)sizeof(TC) + 16)));
+}
+
 /* Split-K reduction: sums the ksplit fp32 partial tiles of every output tile and applies what the
  * one-pass epilogue would have (bias, pre-activation copy, activation, accumulation, conversion),
  * storing only the logical rows / columns.  One thread per 4 consecutive columns. */
@@ -1001,19 +1263,31 @@ int cu_count() {
   return cached[device];
 }
 
+#if defined(HAP_GEMM_EXPERIMENT)
+int hap_exp_variant = 0;          // experiment builds only: 0 = ping-pong BK 32 x 4 stages, 1 = BK 32 x 5, 2 = BK 64 x 2, 3 = the two-stage kernel
+#define kPingPongBK (hap_exp_variant == 2 || hap_exp_variant == 3 ? 64 : 32)
+#define kPingPongSkipsKK false
+#else
+constexpr int kPingPongBK = 32;   // K step and ring depth of the 256 x 256 kernel: 4 stages of 32 KiB
+constexpr bool kPingPongSkipsKK = true;
+#endif
+constexpr int kPingPongStages = 4;
+
 struct Plan {
   bool tiled;
   int skewM, skewN, skewK;
   int bm, bn;       // tile
+  int bk;           // K step of the kernel that will run (the K-tile counts handed to it are in this unit)
   const char* name;
   int dma;          // 1: bf16, direct-to-LDS kernel; 0: fp32, register-staged kernel
+  bool pingpong;    // 256 x 256 tiles run by gemm_pp_kernel
 };
 
 inline int esize(int dtype) { return dtype == HAP_BF16 ? 2 : 4; }
 
 /* Decides whether the aligned-chunk kernel can address the operands and with which skews. */
 Plan make_plan(const hap_gemm_problem* p) {
-  Plan pl = {false, 0, 0, 0, 0, 0, "generic", 0};
+  Plan pl = {false, 0, 0, 0, 0, 0, 64, "generic", 0, false};
   if (p->force_generic) return pl;
   const int es = esize(p->in_dtype);
   if ((p->lda * es) % 16 || (p->ldb * es) % 16) return pl;
@@ -1055,7 +1329,11 @@ Plan make_plan(const hap_gemm_problem* p) {
     }
     pl.bm = pl.bn = big ? 256 : 128;
     pl.dma = 1;
-    pl.name = big ? "bf16_256x256x64_dma2" : "bf16_128x128x64_dma2";
+    // 256-tiles: the ping-pong kernel, except when both operands are K-contiguous (bwd-data), where the two-stage kernel
+    // with 128-byte rows per K tile is the faster one
+    pl.pingpong = big && !(p->a_kcontig && p->b_kcontig && kPingPongSkipsKK);
+    pl.bk = pl.pingpong ? kPingPongBK : 64;
+    pl.name = pl.pingpong ? "bf16_256x256x32_pingpong4" : (big ? "bf16_256x256x64_dma2" : "bf16_128x128x64_dma2");
   }
   return pl;
 }
@@ -1110,6 +1388,41 @@ int dispatch_dma(const hap_gemm_problem* p, const GemmArgs& a, int groups, hipSt
   return launch_dma<TC, false, true, BM, BN, BK, STAGES, WGM, WGN>(a, groups, st);
 }
 
+template <typename TC, bool AKC, bool BKC, int BM, int BN, int BK, int STAGES, int WGM, int WGN>
+int launch_pp(const GemmArgs& a, int groups, hipStream_t st) {
+  constexpr size_t smem = (size_t)STAGES * (BM + BN) * BK * 2;
+  void (*kernel)(const GemmArgs) = &gemm_pp_kernel<TC, AKC, BKC, BM, BN, BK, WGM, WGN, STAGES>;
+  // the attribute belongs to the kernel's copy on the current device (benign race: the call is idempotent)
+  static bool configured[64] = {};
+  int device = 0;
+  if (hipGetDevice(&device) != hipSuccess || device < 0 || device >= 64) device = -1;
+  if (device < 0 || !configured[device]) {
+    const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
+                                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+    if (e != hipSuccess) return hap_fail(HAP_EDEVICE, "cannot reserve %zu bytes of LDS: %s", smem, hipGetErrorString(e));
+    if (device >= 0) configured[device] = true;
+  }
+  const int out_tiles = a.tiles_m * a.tiles_n;
+  hipLaunchKernelGGL(kernel, dim3(out_tiles * a.ksplit, groups), dim3(64 * WGM * WGN), smem, st, a);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return hap_fail(HAP_EDEVICE, "gemm launch: %s", hipGetErrorString(e));
+  if (a.ksplit > 1) {
+    const long long threads = (long long)out_tiles * (BM * BN / 4);
+    hipLaunchKernelGGL((splitk_reduce_kernel<__bf16, TC, BM, BN>), dim3((unsigned)((threads + 255) / 256), groups), dim3(256), 0, st, a, out_tiles);
+    e = hipGetLastError();
+    if (e != hipSuccess) return hap_fail(HAP_EDEVICE, "split-K reduce launch: %s", hipGetErrorString(e));
+  }
+  return HAP_OK;
+}
+
+template <typename TC, int BM, int BN, int BK, int STAGES, int WGM, int WGN>
+int dispatch_pp(const hap_gemm_problem* p, const GemmArgs& a, int groups, hipStream_t st) {
+  if (p->a_kcontig && p->b_kcontig) return launch_pp<TC, true, true, BM, BN, BK, STAGES, WGM, WGN>(a, groups, st);
+  if (p->a_kcontig && !p->b_kcontig) return launch_pp<TC, true, false, BM, BN, BK, STAGES, WGM, WGN>(a, groups, st);
+  if (!p->a_kcontig && !p->b_kcontig) return launch_pp<TC, false, false, BM, BN, BK, STAGES, WGM, WGN>(a, groups, st);
+  return launch_pp<TC, false, true, BM, BN, BK, STAGES, WGM, WGN>(a, groups, st);
+}
+
 template <typename T, typename TC, int BM, int BN, int BK, int WGM, int WGN>
 int dispatch_layout(const hap_gemm_problem* p, const GemmArgs& a, int groups, hipStream_t st) {
   if (p->a_kcontig && p->b_kcontig) return launch_tiled<T, TC, true, true, BM, BN, BK, WGM, WGN>(a, groups, st);
@@ -1123,6 +1436,12 @@ int dispatch_tile(const hap_gemm_problem* p, const Plan& pl, const GemmArgs& a, 
   if constexpr (sizeof(T) == 4) {
     return dispatch_layout<T, TC, 64, 64, 64, 2, 2>(p, a, groups, st);
   } else {
+#if defined(HAP_GEMM_EXPERIMENT)
+    if (pl.bm == 256 && hap_exp_variant == 1) return dispatch_pp<TC, 256, 256, 32, 5, 2, 4>(p, a, groups, st);
+    if (pl.bm == 256 && hap_exp_variant == 2) return dispatch_pp<TC, 256, 256, 64, 2, 2, 4>(p, a, groups, st);
+    if (pl.bm == 256 && hap_exp_variant == 3) return dispatch_dma<TC, 256, 256, 64, 2, 2, 4>(p, a, groups, st);
+#endif
+    if (pl.pingpong) return dispatch_pp<TC, 256, 256, 32, kPingPongStages, 2, 4>(p, a, groups, st);
     if (pl.bm == 256) return dispatch_dma<TC, 256, 256, 64, 2, 2, 4>(p, a, groups, st);
     return dispatch_dma<TC, 128, 128, 64, 2, 2, 2>(p, a, groups, st);
   }
@@ -1415,7 +1734,7 @@ int hap_gemm_run(const hap_gemm_problem* p, void* stream) {
   a.ksplit = 1;
   a.partial = nullptr;
   {
-    const int bk = 64;                   // every tiled kernel steps K by 64
+    const int bk = pl.bk;                // the chosen kernel's K step
     for (int s = 0; s < a.nseg; ++s) a.ntiles += (pl.skewK + a.seg[s].k + bk - 1) / bk;
     if (a.ntiles == 0) a.ntiles = 1;     // empty contraction still runs one (all-zero) tile
   }
@@ -1426,7 +1745,7 @@ int hap_gemm_run(const hap_gemm_problem* p, void* stream) {
     const long long out_tiles = (long long)a.tiles_m * a.tiles_n * groups;
     const int kCUs = cu_count();
     const long long slots = pl.bm == 256 ? kCUs : (pl.bm == 128 ? 2 * kCUs : 4 * kCUs);
-    const int min_tiles = pl.bm == 64 ? 2 : 4;
+    const int min_tiles = pl.bm == 64 ? 2 : 4 * (64 / pl.bk);      // in K steps of the chosen kernel
     long long g = slots / out_tiles;
     if (g > a.ntiles / min_tiles) g = a.ntiles / min_tiles;
     if (g > 16) g = 16;
