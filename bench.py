@@ -46,7 +46,7 @@ def main():
     import hapgen
     from hapgen import TensorId as T
     import paper_2401_05965_amd as hap
-    from paper_2401_05965_amd.programs import EncoderShard, MlpShard, MoeExpertShard, SfbRebuild
+    from paper_2401_05965_amd.programs import EncoderLayerProgram, MlpShard, MoeExpertShard, SfbRebuild
 
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
@@ -91,6 +91,7 @@ def main():
 
     stream = torch.cuda.current_stream()
     marks = {}
+    held = {}      # device results of the untimed rows, kept for the parity leg
 
     def steady_time(fn, n=10):
         """Seconds per call of fn in steady state.  The GPU drops its clocks while the host prepares inputs and needs tens of
@@ -273,61 +274,85 @@ def main():
         t = timeit(lambda: hap.hap_sharded_attn_bwd(ad5, 0, p5, p5 + w5, p5 + 2 * w5, o5, lse5, do5, g5, g5 + w5, g5 + 2 * w5, aws5))
         res["cfg5_attn_bwd_tflops_2.5x_fwd_flops"] = round(2.5 * fl5 / t / 1e12, 1)
         del q5, dq5, o5, do5
-        rows5 = [197 * b for b in (79, 63, 63, 31, 20)]
-        X5 = [dev_bf16(3, T.SFB_X + i, (r, 1024), 1.0) for i, r in enumerate(rows5)]
-        dY5 = [dev_bf16(3, T.SFB_DY + i, (r, 4096), 1.0) for i, r in enumerate(rows5)]
-        dW5 = torch.zeros((1024, 4096), dtype=torch.float32, device=dev)
-        ws5 = torch.empty((max(16, hap.hap_sfb_workspace(len(rows5), rows5, 1024, 4096)),), dtype=torch.uint8, device=dev)
-        t = timeit(lambda: hap.hap_sfb_grad(X5, dY5, rows5, 1024, 4096, 1024, 4096, hap.BF16, dW5, 4096, ws=ws5))
-        res["cfg5_sfb_dW1_tflops"] = round(2.0 * 1024 * 4096 * sum(rows5) / t / 1e12, 1)
+        # ---- configs 5, 4 and 1 below run on hapgen's seeded inputs and keep their device results in `held`: the parity leg compares them
+        # with the oracle, tensor by tensor, after the timed part (max |gpu - oracle| / max |oracle| over all elements).
+        w5 = hapgen.WORKLOADS["cfg5_vit_bf16"]; d5 = w5.dims
+        r5, _ = hap.hap_shard_ratios(list(w5.speeds), [(1.0, 0.0, 0.0, 0.0)])
+        b5sizes, b5offs = hap.hap_round_shards(r5, d5["batch"])
+        s5, o5f = hap.hap_round_shards(r5, d5["ffn"])
+        assert b5sizes == [79, 63, 63, 31, 20] and s5 == [1261, 1008, 1008, 504, 315], (b5sizes, s5)
+        T5, h5, F5 = d5["batch"] * d5["seq"], d5["hidden"], d5["ffn"]
+        # SFB rebuild of both MLP weight gradients from five devices' gathered factors: K = 50432 in ragged segments 197 * b_j (split-K)
+        rows5 = [d5["seq"] * b for b in b5sizes]
+        X5 = [dev_bf16(5, T.SFB_X + i, (r, h5), 1.0) for i, r in enumerate(rows5)]
+        dY5 = [dev_bf16(5, T.SFB_DY + i, (r, F5), 1.0) for i, r in enumerate(rows5)]
+        dW5 = torch.zeros((h5, F5), dtype=torch.float32, device=dev)
+        ws5 = torch.empty((max(16, hap.hap_sfb_workspace(len(rows5), rows5, h5, F5)),), dtype=torch.uint8, device=dev)
+        t = timeit(lambda: hap.hap_sfb_grad(X5, dY5, rows5, h5, F5, h5, F5, hap.BF16, dW5, F5, ws=ws5))
+        res["cfg5_sfb_dW1_tflops"] = round(2.0 * h5 * F5 * sum(rows5) / t / 1e12, 1)
         # dW2 [4096 x 1024]: the factors swap roles (hidden activations [rows x 4096], output gradients [rows x 1024])
-        dW5b = torch.zeros((4096, 1024), dtype=torch.float32, device=dev)
-        t = timeit(lambda: hap.hap_sfb_grad(dY5, X5, rows5, 4096, 1024, 4096, 1024, hap.BF16, dW5b, 1024, ws=ws5))
-        res["cfg5_sfb_dW2_tflops"] = round(2.0 * 1024 * 4096 * sum(rows5) / t / 1e12, 1)
-        del X5, dY5, dW5, dW5b, ws5
+        dW5b = torch.zeros((F5, h5), dtype=torch.float32, device=dev)
+        t = timeit(lambda: hap.hap_sfb_grad(dY5, X5, rows5, F5, h5, F5, h5, hap.BF16, dW5b, h5, ws=ws5))
+        res["cfg5_sfb_dW2_tflops"] = round(2.0 * h5 * F5 * sum(rows5) / t / 1e12, 1)
+        held["cfg5_sfb"] = dict(rows=rows5, dW1=dW5, dW2=dW5b)
+        del X5, dY5, ws5
         # config 5's MLP with the ffn axis sharded (1261 | 1008 | 1008 | 504 | 315 of 4096) over all 50432 tokens: devices 0 and 4
-        T5, h5, F5 = 256 * 197, 1024, 4096
-        r5, _ = hap.hap_shard_ratios([1.0, 0.8, 0.8, 0.4, 0.25], [(1.0, 0.0, 0.0, 0.0)])
-        s5, o5f = hap.hap_round_shards(r5, F5)
-        gen5 = torch.Generator(device=dev); gen5.manual_seed(6)
-        rnd5 = lambda shp, sg: (torch.randn(shp, generator=gen5, device=dev) * sg).to(torch.bfloat16)
-        Xm, dOm = rnd5((T5, h5), 1.0), rnd5((T5, h5), 1.0)
-        W1m, b1m, W2m = rnd5((h5, F5), 0.02), rnd5((F5,), 0.02), rnd5((F5, h5), 0.02)
+        Xm, dOm = dev_bf16(5, T.X, (T5, h5), 1.0), dev_bf16(5, T.DY, (T5, h5), 1.0)
+        W1m, b1m, W2m = dev_bf16(5, T.W, (h5, F5), 0.02), dev_bf16(5, T.BIAS, (F5,), 0.02), dev_bf16(5, T.W2, (F5, h5), 0.02)
+        held["cfg5_mlp"] = dict(offs=o5f, shards={})
         for j5 in (0, 4):
             sh5 = MlpShard(T5, h5, F5, o5f, j5, Xm, W1m, b1m, W2m, dOm)
             t = timeit(lambda: (sh5.forward(), sh5.backward()), n=5)
             f5, b5 = sh5.flops()
             res[f"cfg5_mlp_fwd_bwd_device{j5}_ffn{s5[j5]}"] = {"ms": round(t * 1e3, 3), "gflop": round((f5 + b5) / 1e9, 1), "tflops": round((f5 + b5) / t / 1e12, 1)}
-            del sh5
+            held["cfg5_mlp"]["shards"][j5] = sh5
         del Xm, dOm, W1m, W2m
-        # whole encoder layer, forward + backward, as one device runs it (every GEMM, attention and row kernel in order):
-        # config 4 sharded over heads / ffn (devices 0 and 2), config 5's batch shard of device 0
-        def layer(style, j, B, S, hid, heads, d, ffn, hoffs, foffs, boffs):
-            gen4 = torch.Generator(device=dev); gen4.manual_seed(4)       # same distributions as hapgen's, drawn on the device to keep set-up short
-            sw = lambda tid, shp, sg: (torch.randn(shp, generator=gen4, device=dev) * sg).to(torch.bfloat16)
-            prm = {"Wq": sw(T.WQ, (hid, hid), 0.02), "Wk": sw(T.WK, (hid, hid), 0.02), "Wv": sw(T.WV, (hid, hid), 0.02), "Wo": sw(T.WO, (hid, hid), 0.02),
-                   "W1": sw(T.W, (hid, ffn), 0.02), "W2": sw(T.W2, (ffn, hid), 0.02), "b1": sw(T.BIAS, (ffn,), 0.02)}
-            for i, n in enumerate(("bq", "bk", "bv", "bo", "b2", "be1", "be2")):
-                prm[n] = sw(T.MISC + i, (hid,), 0.02)
-            prm["g1"] = torch.ones((hid,), dtype=torch.bfloat16, device=dev); prm["g2"] = prm["g1"].clone()
-            sh = EncoderShard(style, j, B, S, hid, heads, d, ffn, hoffs, foffs, boffs, prm)
-            xs = sw(T.X, (sh.N, hid), 1.0); dys = sw(T.DY, (sh.N, hid), 1.0)
-            buf = {n: torch.zeros_like(xs) for n in ("x1", "y", "dx1", "dx")}
-            buf["dbo"] = torch.zeros((hid,), dtype=torch.float32, device=dev); buf["db2"] = torch.zeros_like(buf["dbo"])
-            t = timeit(lambda: sh.device_step(xs, dys, buf, prm["bo"], prm["b2"]), n=5)
-            f, b = sh.flops()
-            return {"ms": round(t * 1e3, 3), "gflop": round((f + b) / 1e9, 1), "tflops": round((f + b) / t / 1e12, 1)}
-        c4 = (16, 1024, 2048, 16, 128, 8192, [0, 5, 10, 13, 16], [0, 2731, 5462, 6827, 8192], [0, 16])
-        res["cfg4_layer_fwd_bwd_device0_5heads_ffn2731"] = layer("tensor", 0, *c4)
-        res["cfg4_layer_fwd_bwd_device2_3heads_ffn1365"] = layer("tensor", 2, *c4)
-        res["cfg5_layer_fwd_bwd_device0_79samples"] = layer("data", 0, 256, 197, 1024, 16, 64, 4096, [0, 16], [0, 4096], [0, 79, 142, 205, 236, 256])
+        # Whole layers, forward + backward.  Every virtual device's shard is built from the same seeded parameters; the rows time ONE device's
+        # instruction list (every GEMM, attention and row kernel in order, its own partial products standing in for what the All-Reduce would
+        # deliver); afterwards the whole program (all devices in turn, partial tensors summed) runs once for the parity leg.
+        def layer_params(seed, hid, ffn):
+            prm = {"Wq": dev_bf16(seed, T.WQ, (hid, hid), 0.02), "Wk": dev_bf16(seed, T.WK, (hid, hid), 0.02), "Wv": dev_bf16(seed, T.WV, (hid, hid), 0.02),
+                   "Wo": dev_bf16(seed, T.WO, (hid, hid), 0.02), "W1": dev_bf16(seed, T.W, (hid, ffn), 0.02), "W2": dev_bf16(seed, T.W2, (ffn, hid), 0.02)}
+            for i, (n, sz) in enumerate((("bq", hid), ("bk", hid), ("bv", hid), ("bo", hid), ("b1", ffn), ("b2", hid), ("be1", hid), ("be2", hid))):
+                prm[n] = dev_bf16(seed, T.MISC + i, (sz,), 0.1)
+            for i, n in enumerate(("g1", "g2")):      # gamma = 1 + small, snapped to bf16
+                g = 1.0 + hapgen.normal_bf16(seed, T.MISC + 20 + i, (hid,), 0.1)[0]
+                prm[n] = torch.from_numpy(hapgen.to_bf16_bits(g.astype(np.float32)).view(np.int16)).view(torch.bfloat16).to(dev)
+            return prm
+
+        def layer_rows(tag, style, seed, w, hoffs, foffs, boffs, which, names):
+            d = w.dims
+            B, S, hid, heads, dh, ffn = d["batch"], d["seq"], d["hidden"], d["heads"], d["head_dim"], d["ffn"]
+            prm = layer_params(seed, hid, ffn)
+            x = dev_bf16(seed, T.X, (B * S, hid), 1.0); dy = dev_bf16(seed, T.DY, (B * S, hid), 1.0)
+            prog = EncoderLayerProgram(style, B, S, hid, heads, dh, ffn, hoffs, foffs, boffs, prm, x, dy)
+            for j, name in zip(which, names):
+                sh = prog.shards[j]
+                xs, dys = (x, dy) if style == "tensor" else (sh.rows(x), sh.rows(dy))
+                buf = {n: torch.zeros_like(xs) for n in ("x1", "y", "dx1", "dx")}
+                buf["dbo"] = torch.zeros((hid,), dtype=torch.float32, device=dev); buf["db2"] = torch.zeros_like(buf["dbo"])
+                t = timeit(lambda: sh.device_step(xs, dys, buf, prm["bo"], prm["b2"]), n=5)
+                f, b = sh.flops()
+                res[name] = {"ms": round(t * 1e3, 3), "gflop": round((f + b) / 1e9, 1), "tflops": round((f + b) / t / 1e12, 1)}
+                del buf
+            prog.forward(); prog.backward()
+            torch.cuda.synchronize()
+            held[tag] = dict(prog=prog, seed=seed, style=style, w=w, hoffs=hoffs, foffs=foffs, boffs=boffs)
+        w4 = hapgen.WORKLOADS["cfg4_encoder_bf16"]; d4 = w4.dims
+        r4, _ = hap.hap_shard_ratios(list(w4.speeds), [(1.0, 0.0, 0.0, 0.0)])
+        h4sizes, h4offs = hap.hap_round_shards(r4, d4["heads"]); f4sizes, f4offs = hap.hap_round_shards(r4, d4["ffn"])
+        assert h4sizes == [5, 5, 3, 3] and f4sizes == [2731, 2731, 1365, 1365], (h4sizes, f4sizes)
+        layer_rows("cfg4", "tensor", 4, w4, h4offs, f4offs, [0, d4["batch"]], (0, 2),
+                   ("cfg4_layer_fwd_bwd_device0_5heads_ffn2731", "cfg4_layer_fwd_bwd_device2_3heads_ffn1365"))
+        layer_rows("cfg5_layer", "data", 5, w5, [0, d5["heads"]], [0, d5["ffn"]], b5offs, (0, 4),
+                   ("cfg5_layer_fwd_bwd_device0_79samples", "cfg5_layer_fwd_bwd_device4_20samples"))
         # config 1: one fp32 fully-connected layer, 64 x 1024 x 1024, rows split (38, 26): latency-bound, reported in microseconds (warm)
         w1 = hapgen.WORKLOADS["cfg1_fc_f32"]
         r1, _ = hap.hap_shard_ratios(list(w1.speeds), [(1.0, 0.0, 0.0, 0.0)])
         s1, o1 = hap.hap_round_shards(r1, w1.dims["tokens"])
-        gen1 = torch.Generator(device=dev); gen1.manual_seed(1)
-        X1 = torch.randn((64, 1024), generator=gen1, device=dev); W1c = torch.randn((1024, 1024), generator=gen1, device=dev) * 0.02
-        dY1 = torch.randn((64, 1024), generator=gen1, device=dev)
+        assert s1 == [38, 26], s1
+        dev_f32 = lambda tid, shape, sigma: torch.from_numpy(hapgen.normal(1, tid, shape, sigma, dtype=np.float32)).to(dev)
+        X1 = dev_f32(T.X, (64, 1024), 1.0); W1c = dev_f32(T.W, (1024, 1024), 0.02); dY1 = dev_f32(T.DY, (64, 1024), 1.0)
         Y1 = torch.zeros_like(dY1); dX1 = torch.zeros_like(X1); dW1c = torch.zeros_like(W1c)
         d1 = hap.LinearDesc(64, 1024, 1024, hap.SHARD_BATCH, o1, hap.F32)
         ws1 = torch.empty((hap.hap_linear_bwd_workspace(d1, 0),), dtype=torch.uint8, device=dev)
@@ -367,6 +392,15 @@ def main():
             step1()
         c1["step_hip_graph_us"] = round(timeit(graph1.replay, n=50) * 1e6, 1)
         res["cfg1_fc_f32_latency"] = c1
+        # one more pass of config 1 with every device's results kept apart (for the parity leg): rows of Y and dX, the devices' partial dW, the rebuild
+        dWp = [torch.zeros_like(W1c) for _ in range(2)]; dWs = torch.zeros_like(W1c)
+        Y1.zero_(); dX1.zero_()
+        for j1 in range(2):
+            hap.hap_sharded_linear_fwd(d1, j1, X1, W1c, None, Y1, None, ws1)
+            hap.hap_sharded_linear_bwd(d1, j1, X1, W1c, None, dY1, dX1, dWp[j1], hap.F32, None, ws1)
+        hap.hap_sfb_grad([X1[:s1[0]], X1[s1[0]:]], [dY1[:s1[0]], dY1[s1[0]:]], s1, 1024, 1024, 1024, 1024, hap.F32, dWs, 1024, ws=ws1)
+        torch.cuda.synchronize()
+        held["cfg1"] = dict(Y=Y1, dX=dX1, dW_partials=dWp, dW_sfb=dWs, rows=s1)
         # uneven All-Gather data movement (Sec. 2.3.1): the padded slots of config 2's hidden activations (8402 | 5041 | 2941 of 16384
         # columns: byte offsets 16804 and 26886, nothing 16-byte aligned) and of config 5's token rows (batch 79 | 63 | 63 | 31 | 20 x 197)
         def gather_row(rows_, cols_, dim_, offs_):
@@ -475,9 +509,105 @@ def main():
 
         out["cpu_baseline"] = cpu_baseline(np, hapgen, T, w2, offsets, compare)
         tol = 2e-2
+        fmt = lambda e: {k: float(f"{v:.3g}") for k, v in e.items()}
         out["parity"] = {"against": "oracle, all elements of both timed shards' tensors and of the SFB gradient", "tolerance": tol,
-                         "max_rel_err": {k: float(f"{v:.3g}") for k, v in errs.items()}, "pass": bool(max(errs.values()) <= tol)}
+                         "max_rel_err": fmt(errs), "pass": bool(max(errs.values()) <= tol)}
+        # every configuration at its stated size: what the untimed rows left on the device against the oracle (same seeded inputs), per tensor
+        per_cfg = {"cfg2_mlp_bf16 + cfg3_sfb_bf16 (the timed step)": {"tolerance": tol, "max_rel_err": fmt(errs), "pass": out["parity"]["pass"]}}
+        for name, (e, t_) in config_parity(np, hapgen, T, held).items():
+            per_cfg[name] = {"tolerance": t_, "max_rel_err": fmt(e), "pass": bool(max(e.values()) <= t_)}
+        out["parity"]["configs"] = per_cfg
+        out["parity"]["all_configs_pass"] = bool(all(v["pass"] for v in per_cfg.values()))
     print(json.dumps(out))
+
+
+def config_parity(np, hapgen, T, held):
+    """Configs 1, 4 and 5 at their stated sizes: the device results the untimed rows kept (`held`) against the float64 oracle on the same
+    seeded inputs, max |gpu - oracle| / max |oracle| per tensor over all elements.  Returns {config: (errors, tolerance)}."""
+    from oracle import layers, sfb
+    res = {}
+
+    def host(t):
+        return t.detach().float().cpu().numpy().astype(np.float64)
+
+    def rel(got, ref):
+        ref = np.asarray(ref, dtype=np.float64)
+        return float(np.abs(got - ref).max() / max(np.abs(ref).max(), 1e-30)) if np.isfinite(got).all() else float("inf")
+
+    if "cfg1" in held:
+        h = held["cfg1"]
+        X = hapgen.normal(1, T.X, (64, 1024), 1.0, dtype=np.float32).astype(np.float64)
+        W = hapgen.normal(1, T.W, (1024, 1024), 0.02, dtype=np.float32).astype(np.float64)
+        dY = hapgen.normal(1, T.DY, (64, 1024), 1.0, dtype=np.float32).astype(np.float64)
+        dWo = X.T @ dY
+        res["cfg1_fc_f32"] = ({"Y": rel(host(h["Y"]), X @ W), "dX": rel(host(h["dX"]), dY @ W.T),
+                               "dW (sum of the devices' partials)": rel(sum(host(t) for t in h["dW_partials"]), dWo),
+                               "dW (SFB rebuild)": rel(host(h["dW_sfb"]), dWo)}, 1e-5)
+    if "cfg5_sfb" in held:
+        h = held["cfg5_sfb"]
+        Xs = [hapgen.normal_bf16(5, T.SFB_X + i, (r, 1024), 1.0)[0] for i, r in enumerate(h["rows"])]
+        Ys = [hapgen.normal_bf16(5, T.SFB_DY + i, (r, 4096), 1.0)[0] for i, r in enumerate(h["rows"])]
+        res["cfg5_vit_bf16: SFB rebuild of dW1, dW2 (K = 50432)"] = ({"dW1": rel(host(h["dW1"]), sfb.sfb_grad(Xs, Ys, h["rows"])),
+                                                                      "dW2": rel(host(h["dW2"]), sfb.sfb_grad(Ys, Xs, h["rows"]))}, 2e-2)
+        del Xs, Ys
+    if "cfg5_mlp" in held:
+        h = held["cfg5_mlp"]
+        any_shard = next(iter(h["shards"].values()))
+        tok, hid, F = any_shard.T, any_shard.h, any_shard.F
+        X = hapgen.normal_bf16(5, T.X, (tok, hid), 1.0)[0]; dO = hapgen.normal_bf16(5, T.DY, (tok, hid), 1.0)[0]
+        W1 = hapgen.normal_bf16(5, T.W, (hid, F), 0.02)[0]; b1 = hapgen.normal_bf16(5, T.BIAS, (F,), 0.02)[0]; W2 = hapgen.normal_bf16(5, T.W2, (F, hid), 0.02)[0]
+        e = {}
+        for j, sh in h["shards"].items():     # the block restricted to the device's ffn columns IS the device's program: its out / dX are the partial sums
+            lo, hi = h["offs"][j], h["offs"][j + 1]
+            ref = layers.mlp_block(X, np.ascontiguousarray(W1[:, lo:hi]), b1[lo:hi], np.ascontiguousarray(W2[lo:hi]), np.zeros(hid), dO)
+            f = sh.f
+            for n, got, want in (("H", sh.H[:, :f], "H"), ("P", sh.P, "out"), ("dH", sh.dH[:, :f], "dH"), ("dX", sh.dX, "dX"),
+                                 ("dW1", sh.dW1[:, :f], "dW1"), ("db1", sh.db1[:f], "db1"), ("dW2", sh.dW2[:f], "dW2")):
+                e[f"{n}[device {j}, ffn {f}]"] = rel(host(got), ref[want])
+            del ref
+        res["cfg5_vit_bf16: ffn-sharded MLP over 50432 tokens"] = (e, 2e-2)
+        del X, dO, W1, W2
+    for tag, title in (("cfg4", "cfg4_encoder_bf16: whole layer, 4 devices (heads 5|5|3|3, ffn 2731|2731|1365|1365)"),
+                       ("cfg5_layer", "cfg5_vit_bf16: whole layer, 5 devices (batch 79|63|63|31|20)")):
+        if tag not in held:
+            continue
+        h = held[tag]; prog = h["prog"]; d = h["w"].dims; seed = h["seed"]
+        B, S, hid, heads, dh, ffn = d["batch"], d["seq"], d["hidden"], d["heads"], d["head_dim"], d["ffn"]
+        nb = hapgen.normal_bf16
+        ph = {"Wq": nb(seed, T.WQ, (hid, hid), 0.02)[0], "Wk": nb(seed, T.WK, (hid, hid), 0.02)[0], "Wv": nb(seed, T.WV, (hid, hid), 0.02)[0],
+              "Wo": nb(seed, T.WO, (hid, hid), 0.02)[0], "W1": nb(seed, T.W, (hid, ffn), 0.02)[0], "W2": nb(seed, T.W2, (ffn, hid), 0.02)[0]}
+        for i, (n, sz) in enumerate((("bq", hid), ("bk", hid), ("bv", hid), ("bo", hid), ("b1", ffn), ("b2", hid), ("be1", hid), ("be2", hid))):
+            ph[n] = nb(seed, T.MISC + i, (sz,), 0.1)[0]
+        for i, n in enumerate(("g1", "g2")):
+            g = 1.0 + nb(seed, T.MISC + 20 + i, (hid,), 0.1)[0]
+            ph[n] = hapgen.from_bf16_bits(hapgen.to_bf16_bits(g.astype(np.float32)))
+        ref = layers.encoder_layer(nb(seed, T.X, (B * S, hid), 1.0)[0], ph, nb(seed, T.DY, (B * S, hid), 1.0)[0], B, S, heads, dh)
+        e = {n: rel(host(t), ref[n]) for n, t in (("x1", prog.x1), ("y", prog.y), ("dx1", prog.dx1), ("dx", prog.dx), ("db2", prog.db2), ("dbo", prog.dbo))}
+        if h["style"] == "tensor":      # every device's exact slices of the weight gradients; the worst device is reported per tensor
+            worst = {}
+            for j, sh in enumerate(prog.shards):
+                c = slice(h["hoffs"][j] * dh, h["hoffs"][j + 1] * dh); fc = slice(h["foffs"][j], h["foffs"][j + 1]); hd, f = sh.hd, sh.f
+                got = host(sh.dWqkv)
+                pairs = [("dWq", got[:, :hd], ref["dWq"][:, c]), ("dWk", got[:, hd:2 * hd], ref["dWk"][:, c]), ("dWv", got[:, 2 * hd:3 * hd], ref["dWv"][:, c]),
+                         ("dWo", host(sh.dWo)[:hd], ref["dWo"][c]), ("o", host(sh.o)[:, :hd], ref["o"][:, c]),
+                         ("dW1", host(sh.dW1)[:, :f], ref["dW1"][:, fc]), ("db1", host(sh.db1)[:f], ref["db1"][fc]), ("dW2", host(sh.dW2)[:f], ref["dW2"][fc])]
+                for n, g_, r_ in pairs:
+                    worst[n] = max(worst.get(n, 0.0), rel(g_, r_))
+            e.update({f"{n} (worst device)": v for n, v in worst.items()})
+            s0 = prog.shards[0]
+            e.update({n: rel(host(t), ref[n]) for n, t in (("dg1", s0.dg1), ("dbe1", s0.dbe1), ("dg2", s0.dg2), ("dbe2", s0.dbe2))})
+        else:                           # batch shards: the devices' partial weight gradients summed = the all-reduced gradient
+            acc = {}
+            for sh in prog.shards:
+                got = host(sh.dWqkv)
+                parts = {"dWq": got[:, :hid], "dWk": got[:, hid:2 * hid], "dWv": got[:, 2 * hid:3 * hid], "dWo": host(sh.dWo), "dW1": host(sh.dW1)[:, :ffn],
+                         "dW2": host(sh.dW2), "db1": host(sh.db1), "dg1": host(sh.dg1), "dbe1": host(sh.dbe1), "dg2": host(sh.dg2), "dbe2": host(sh.dbe2)}
+                for n, v in parts.items():
+                    acc[n] = acc.get(n, 0) + v
+            e.update({f"{n} (sum over devices)": rel(v, ref[n]) for n, v in acc.items()})
+        res[title] = (e, 2e-2)
+        del ref, ph
+    return res
 
 
 def cpu_baseline(np, hapgen, T, w2, offsets, compare=None):
