@@ -205,14 +205,19 @@ def main():
         W2r = (torch.randn((F, h), generator=gen7, device=dev) * 0.02).to(torch.bfloat16)
         b1r = torch.zeros((F,), dtype=torch.bfloat16, device=dev)
         mid = MlpShard(Tn, h, F, offsets, 1, X, W1r, b1r, W2r, dOut)
-        del W1r, W2r
         t0, t2, t1 = t_block(shards[0]), t_block(shards[1]), t_block(mid)
+        # the same shard with whole tensors handed over (operands_are_full = 1): its columns start at byte 16804 of a row, so every view
+        # is skewed and the epilogues store through chunks aligned in the destination's own address space
+        whole = MlpShard(Tn, h, F, offsets, 1, X, W1r, b1r, W2r, dOut, whole_tensors=True)
+        t1_whole = t_block(whole)
+        del W1r, W2r, whole
         B0, B1, B2 = (sizes[j] / F for j in range(3))
         alpha = (t0 - t2) / (B0 - B2); beta = t0 - alpha * B0
         pred1 = alpha * B1 + beta
         out = {"block_fwd_bwd_ms_by_shard": {str(sizes[0]): round(t0 * 1e3, 3), str(sizes[1]): round(t1 * 1e3, 3), str(sizes[2]): round(t2 * 1e3, 3)},
                "fit_seconds": {"per_unit_ratio": round(alpha, 6), "fixed": round(beta, 6)},
-               "middle_shard_predicted_ms": round(pred1 * 1e3, 3), "middle_shard_error_pct": round(100 * (pred1 - t1) / t1, 2)}
+               "middle_shard_predicted_ms": round(pred1 * 1e3, 3), "middle_shard_error_pct": round(100 * (pred1 - t1) / t1, 2),
+               "middle_shard_whole_tensor_operands_ms": round(t1_whole * 1e3, 3), "whole_vs_compact_pct": round(100 * (t1_whole - t1) / t1, 2)}
         # one stage: compute = (alpha * B_j + beta) / relative speed_j; communication = one All-Gather forward and one
         # Reduce-Scatter backward of the block's [tokens x hidden] bf16 activations, time = bytes / bandwidth * max_j B_j
         act_bytes = 2.0 * Tn * h * 2

@@ -55,6 +55,8 @@ struct GemmArgs {
   int nseg;
   int tiles_m, tiles_n;
   int vec_store;       // C (and preact) rows are 16-byte addressable: whole-chunk stores allowed
+  int cdelta;          // columns by which tile columns are shifted in the store patch so that its 16-byte chunks coincide with
+                       // 16-byte chunks of C's address space (0 when C has the B operand's phase; see epilogue_transposed)
   int ksplit;          // >1: each output tile is computed by ksplit workgroups over disjoint K-tile ranges, fp32 partials go to `partial`
   float* partial;      // [group][tile][ksplit][BM][BN] fp32 workspace when ksplit > 1
   int ntiles;          // K tiles (of 64) over all segments
@@ -557,7 +559,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(const GemmArgs arg
     GemmArgs pa = args;
     pa.c = args.partial + (((long long)bp.grp * (gridDim.x / ksplit) + out_tile) * ksplit + split) * (BM * BN);
     pa.ldc = BN; pa.M = BM; pa.N = BN; pa.skewM = 0; pa.skewN = 0;
-    pa.preact = nullptr; pa.bias = nullptr; pa.act = HAP_ACT_NONE; pa.accumulate = 0; pa.vec_store = 1;
+    pa.preact = nullptr; pa.bias = nullptr; pa.act = HAP_ACT_NONE; pa.accumulate = 0; pa.vec_store = 1; pa.cdelta = 0;
     epilogue<T, float, TM, TN>(pa, acc, wm0, wn0, lane);
     return;
   }
@@ -575,8 +577,8 @@ template <typename TC> struct Vec16;
 template <> struct Vec16<__bf16> { typedef __bf16 type __attribute__((ext_vector_type(8))); };
 template <> struct Vec16<float> { typedef float type __attribute__((ext_vector_type(4))); };
 
-template <typename T, typename TC, int TM, int TN>
-__device__ __forceinline__ void epilogue_transposed(const GemmArgs& args, f32x16_t (&acc)[TM][TN], int row0, int col0, int lane, char* patch) {
+template <typename T, typename TC, int TM, int TN, bool SHIFTED>
+__device__ __forceinline__ void epilogue_transposed_impl(const GemmArgs& args, f32x16_t (&acc)[TM][TN], int row0, int col0, int lane, char* patch) {
   constexpr int ES = sizeof(TC);
   constexpr int EPC = 16 / ES;
   constexpr int COLS = TN * 32;
@@ -588,6 +590,11 @@ __device__ __forceinline__ void epilogue_transposed(const GemmArgs& args, f32x16
   const T* bias = static_cast<const T*>(args.bias);
   const int h = lane >> 5, ml = lane & 31;
   const bool vec_ok = args.vec_store != 0;
+  // A shard's columns start anywhere (column 8402 of a bf16 matrix is byte 16804), so C's 16-byte chunks need not coincide with the
+  // tile's: the tile is written into the patch `delta` columns to the right (the row padding takes the overflow), which makes patch
+  // chunk c the destination chunk that starts at tile column c * EPC - delta; only row ends are then stored element by element.
+  const int delta = SHIFTED ? args.cdelta : 0;
+  constexpr int nchunks = SHIFTED ? CH + 1 : CH;
   // this lane's bias values: the same 4 consecutive columns of every 8-column group, for all row blocks and passes
   float bv[TN][4][4];
 #pragma unroll
@@ -619,7 +626,13 @@ __device__ __forceinline__ void epilogue_transposed(const GemmArgs& args, f32x16
             if (pass == 1 && args.act == HAP_ACT_GELU_ERF) f = gelu_erf(f);
             v[x] = (TC)f;
           }
-          __builtin_memcpy(patch + ml * ROWB + cl * ES, v, 4 * ES);
+          if constexpr (!SHIFTED) {
+            __builtin_memcpy(patch + ml * ROWB + cl * ES, v, 4 * ES);
+          } else {
+            TC* q = reinterpret_cast<TC*>(patch + ml * ROWB) + cl + delta;
+#pragma unroll
+            for (int x = 0; x < 4; ++x) q[x] = v[x];
+          }
         }
       // Order the patch accesses of this wave only: LDS operations of a wave execute in order, so a
       // wait on the LDS counter is enough (a fence would also drain the global stores in flight).
@@ -627,15 +640,18 @@ __device__ __forceinline__ void epilogue_transposed(const GemmArgs& args, f32x16
       __builtin_amdgcn_wave_barrier();
       // LDS patch -> global, 16 bytes per lane
 #pragma unroll
-      for (int it = 0; it < 32 * CH / 64; ++it) {
+      for (int it = 0; it < (32 * nchunks + 63) / 64; ++it) {
         const int idx = it * 64 + lane;
-        const int r = idx / CH, c = idx % CH;
+        if (SHIFTED && idx >= 32 * nchunks) break;
+        const int r = idx / nchunks, c = idx % nchunks;
         const int m = row0 + i * 32 + r - args.skewM;
-        const int n = col0 + c * EPC - args.skewN;
-        if (m < 0 || m >= args.M || n >= args.N || n + EPC <= 0) continue;
+        const int n = col0 + c * EPC - delta - args.skewN;
+        // (a patch chunk also ends where the tile's columns end: what lies beyond was not written in this pass)
+        const int t_lo = c * EPC - delta < 0 ? delta - c * EPC : 0, t_hi = c * EPC - delta + EPC > COLS ? COLS - (c * EPC - delta) : EPC;
+        if (m < 0 || m >= args.M || n + t_lo >= args.N || n + t_hi <= 0) continue;
         vec_t val = *reinterpret_cast<const vec_t*>(patch + r * ROWB + c * 16);
         TC* dst = dst_base + (long long)m * ldd + n;
-        if (vec_ok && n >= 0 && n + EPC <= args.N) {
+        if (vec_ok && n >= 0 && n + EPC <= args.N && t_lo == 0 && t_hi == EPC) {
           if (pass == 1 && args.accumulate) {
             const vec_t old = *reinterpret_cast<const vec_t*>(dst);
 #pragma unroll
@@ -645,7 +661,7 @@ __device__ __forceinline__ void epilogue_transposed(const GemmArgs& args, f32x16
         } else {
 #pragma unroll
           for (int x = 0; x < EPC; ++x)
-            if (n + x >= 0 && n + x < args.N) {
+            if (x >= t_lo && x < t_hi && n + x >= 0 && n + x < args.N) {
               float f = (float)val[x];
               if (pass == 1 && args.accumulate) f += load_s<TC>(dst + x);
               store_c<TC>(dst + x, f);
@@ -658,6 +674,12 @@ __device__ __forceinline__ void epilogue_transposed(const GemmArgs& args, f32x16
       __builtin_amdgcn_wave_barrier();
     }
   }
+}
+
+template <typename T, typename TC, int TM, int TN>
+__device__ __forceinline__ void epilogue_transposed(const GemmArgs& args, f32x16_t (&acc)[TM][TN], int row0, int col0, int lane, char* patch) {
+  if (args.cdelta) epilogue_transposed_impl<T, TC, TM, TN, true>(args, acc, row0, col0, lane, patch);
+  else epilogue_transposed_impl<T, TC, TM, TN, false>(args, acc, row0, col0, lane, patch);
 }
 
 /* ---------------------------------------------------------------------------------------------
@@ -936,7 +958,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_dma_kernel(const GemmArgs
     GemmArgs pa = args;
     pa.c = args.partial + (((long long)bp.grp * (gridDim.x / ksplit) + out_tile) * ksplit + split) * (BM * BN);
     pa.ldc = BN; pa.M = BM; pa.N = BN; pa.skewM = 0; pa.skewN = 0;
-    pa.preact = nullptr; pa.bias = nullptr; pa.act = HAP_ACT_NONE; pa.accumulate = 0; pa.vec_store = 1;
+    pa.preact = nullptr; pa.bias = nullptr; pa.act = HAP_ACT_NONE; pa.accumulate = 0; pa.vec_store = 1; pa.cdelta = 0;
     epilogue_transposed<T, float, TM, TN>(pa, acc, wm0, wn0, lane, smem + wave * (32 * (TN * 32 * 4 + 16)));
     return;
   }
@@ -1162,7 +1184,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_pp_kernel(const GemmArgs 
     GemmArgs pa = args;
     pa.c = args.partial + (((long long)bp.grp * (gridDim.x / ksplit) + out_tile) * ksplit + split) * (BM * BN);
     pa.ldc = BN; pa.M = BM; pa.N = BN; pa.skewM = 0; pa.skewN = 0;
-    pa.preact = nullptr; pa.bias = nullptr; pa.act = HAP_ACT_NONE; pa.accumulate = 0; pa.vec_store = 1;
+    pa.preact = nullptr; pa.bias = nullptr; pa.act = HAP_ACT_NONE; pa.accumulate = 0; pa.vec_store = 1; pa.cdelta = 0;
     epilogue_transposed<T, float, TM, TN>(pa, acc, wm0, wn0, lane, smem + wave * (32 * (TN * 32 * 4 + 16)));
     return;
   }
@@ -1725,10 +1747,14 @@ int hap_gemm_run(const hap_gemm_problem* p, void* stream) {
     a.seg[0].a = p->c; a.seg[0].b = p->c; a.seg[0].k = 0; a.seg[0].a_bytes = 0; a.seg[0].b_bytes = 0; a.seg[0].pad = 0;
   }
   {
+    // Whole-chunk stores need rows of C (and of the pre-activation copy, with C's phase) that start on the same 16-byte phase;
+    // the phase itself is arbitrary: cdelta shifts the tile inside the store patch onto C's chunk grid.
     const int ces = esize(p->c_dtype), cepc = 16 / ces;
-    a.vec_store = pl.skewN == 0 && ((uintptr_t)p->c % 16) == 0 && p->ldc % cepc == 0 &&
-                  (!p->preact || (((uintptr_t)p->preact % 16) == 0 && p->ldp % cepc == 0)) &&
+    a.vec_store = ((uintptr_t)p->c % ces) == 0 && p->ldc % cepc == 0 &&
+                  (!p->preact || (((uintptr_t)p->preact % 16) == ((uintptr_t)p->c % 16) && p->ldp % cepc == 0)) &&
                   (groups == 1 || (p->gc % cepc == 0 && (!p->preact || p->gp % cepc == 0)));
+    const int skew_c = (int)(((uintptr_t)p->c % 16) / ces);       // columns of C's 16-byte chunk that precede logical column 0
+    a.cdelta = a.vec_store ? ((skew_c - pl.skewN) % cepc + cepc) % cepc : 0;
   }
   a.ntiles = 0;
   a.ksplit = 1;

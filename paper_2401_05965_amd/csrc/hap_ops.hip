@@ -44,9 +44,13 @@ template <typename T, int V> struct Pack { T v[V]; } __attribute__((aligned(size
  * its valid elements are stored. */
 /* blockIdx.y: one of several row groups of `rows` rows each, stacked in the same buffers; with group_len only the first
  * group_len[g] rows of group g are processed (the experts of an MoE layer and their token counts). */
+/* skew (RAGGED only): the three views start `skew` elements past a 16-byte boundary (a column range of whole tensors, e.g.
+ * columns 8402.. of a bf16 matrix); the pointers passed are the views' bases moved down to that boundary, chunks are
+ * aligned in the buffers' own address space and the first chunk of a row is ragged as well. */
 template <typename T, int V, bool RAGGED>
 __global__ __launch_bounds__(256) void gelu_bwd_kernel(int64_t rows, int64_t cols, const T* pre, int64_t ldp,
-                                                       const T* dy, int64_t lddy, T* out, int64_t ldo, const int* group_len) {
+                                                       const T* dy, int64_t lddy, T* out, int64_t ldo, const int* group_len, int skew) {
+  cols += skew;      // physical columns counted from the aligned base; logical column = physical - skew
   const int64_t cv = (cols + V - 1) / V;
   pre += (int64_t)blockIdx.y * rows * ldp; dy += (int64_t)blockIdx.y * rows * lddy; out += (int64_t)blockIdx.y * rows * ldo;
   if (group_len) {
@@ -61,12 +65,12 @@ __global__ __launch_bounds__(256) void gelu_bwd_kernel(int64_t rows, int64_t col
     Pack<T, V> o;
 #pragma unroll
     for (int e = 0; e < V; ++e) o.v[e] = (T)((float)g.v[e] * gelu_grad((float)p.v[e]));
-    if (!RAGGED || c + V <= cols) {
+    if (!RAGGED || (c + V <= cols && c >= skew)) {
       *reinterpret_cast<Pack<T, V>*>(out + r * ldo + c) = o;
     } else {
 #pragma unroll
       for (int e = 0; e < V; ++e)
-        if (c + e < cols) out[r * ldo + c + e] = o.v[e];
+        if (c + e < cols && c + e >= skew) out[r * ldo + c + e] = o.v[e];
     }
   }
 }
@@ -368,11 +372,17 @@ template <typename T>
 int gelu_bwd_t(int groups, int64_t rows, int64_t cols, const void* pre, int64_t ldp, const void* dy, int64_t lddy, void* out, int64_t ldo,
                const int* group_len, hipStream_t s) {
   constexpr int V = 16 / sizeof(T);
-  const bool vec = ldp % V == 0 && lddy % V == 0 && ldo % V == 0 && aligned16(pre) && aligned16(dy) && aligned16(out);
+  // 16-byte accesses need pitches of whole chunks and views that share one phase inside their chunks (any phase: a skewed view is
+  // read and written through chunks aligned in the buffers' own address space)
+  const uintptr_t ph = (uintptr_t)pre % 16;
+  const bool vec = ldp % V == 0 && lddy % V == 0 && ldo % V == 0 && ph % sizeof(T) == 0 && (uintptr_t)dy % 16 == ph && (uintptr_t)out % 16 == ph &&
+                   (groups == 1 || ph == 0 || (rows * ldp) % V == 0);
+  const int skew = vec ? (int)(ph / sizeof(T)) : 0;
+  const T* pre_a = (const T*)pre - skew; const T* dy_a = (const T*)dy - skew; T* out_a = (T*)out - skew;
   const unsigned gy = (unsigned)groups;
-  if (vec && cols % V == 0) hipLaunchKernelGGL((gelu_bwd_kernel<T, V, false>), dim3(grid_for(rows * (cols / V)), gy), dim3(256), 0, s, rows, cols, (const T*)pre, ldp, (const T*)dy, lddy, (T*)out, ldo, group_len);
-  else if (vec) hipLaunchKernelGGL((gelu_bwd_kernel<T, V, true>), dim3(grid_for(rows * ((cols + V - 1) / V)), gy), dim3(256), 0, s, rows, cols, (const T*)pre, ldp, (const T*)dy, lddy, (T*)out, ldo, group_len);
-  else hipLaunchKernelGGL((gelu_bwd_kernel<T, 1, false>), dim3(grid_for(rows * cols), gy), dim3(256), 0, s, rows, cols, (const T*)pre, ldp, (const T*)dy, lddy, (T*)out, ldo, group_len);
+  if (vec && skew == 0 && cols % V == 0) hipLaunchKernelGGL((gelu_bwd_kernel<T, V, false>), dim3(grid_for(rows * (cols / V)), gy), dim3(256), 0, s, rows, cols, pre_a, ldp, dy_a, lddy, out_a, ldo, group_len, 0);
+  else if (vec) hipLaunchKernelGGL((gelu_bwd_kernel<T, V, true>), dim3(grid_for(rows * ((cols + skew + V - 1) / V)), gy), dim3(256), 0, s, rows, cols, pre_a, ldp, dy_a, lddy, out_a, ldo, group_len, skew);
+  else hipLaunchKernelGGL((gelu_bwd_kernel<T, 1, false>), dim3(grid_for(rows * cols), gy), dim3(256), 0, s, rows, cols, (const T*)pre, ldp, (const T*)dy, lddy, (T*)out, ldo, group_len, 0);
   return check_launch("gelu_bwd");
 }
 

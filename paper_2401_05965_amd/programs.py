@@ -33,13 +33,34 @@ class MlpShard:
     dimension of W1_j rounded up to a multiple of 8 elements.
     """
 
-    def __init__(self, tokens, hidden, ffn, offsets, j, X, W1, b1, W2, dOut, dtype=torch.bfloat16):
+    def __init__(self, tokens, hidden, ffn, offsets, j, X, W1, b1, W2, dOut, dtype=torch.bfloat16, whole_tensors=False):
         self.T, self.h, self.F, self.j = tokens, hidden, ffn, j
         lo, hi = offsets[j], offsets[j + 1]
         self.f = f = hi - lo
-        self.ld = ld = max(_pad8(f), 8)
         dev = X.device
         self.X, self.dOut = X, dOut
+        io = hap.BF16 if dtype == torch.bfloat16 else hap.F32
+        self.io = io
+        if whole_tensors:
+            # The other way to hand a shard to the library (operands_are_full = 1): every tensor is passed whole and the library
+            # applies the device's range [lo, hi) itself - zero-copy views that start at arbitrary elements.  Results land in the
+            # device's columns / rows of whole-size buffers; `cols` is that range.
+            self.ld = ld = ffn
+            self.cols = slice(lo, hi)
+            self.W1, self.b1, self.W2 = W1, b1, W2
+            z = lambda *shape, dt=dtype: torch.zeros(shape, dtype=dt, device=dev)
+            self.H, self.pre, self.dH = z(tokens, ffn), z(tokens, ffn), z(tokens, ffn)
+            self.P, self.dX = z(tokens, hidden), z(tokens, hidden)
+            self.dW1, self.dW2, self.db1 = z(hidden, ffn), z(ffn, hidden), z(ffn, dt=torch.float32)
+            self.fc1 = hap.LinearDesc(tokens, hidden, ffn, hap.SHARD_FEATURE, offsets, io, act=hap.ACT_GELU_ERF, has_bias=True,
+                                      ldx=hidden, ldw=ffn, ldy=ffn, operands_are_full=True)
+            self.fc2 = hap.LinearDesc(tokens, ffn, hidden, hap.SHARD_REDUCTION, offsets, io, ldx=ffn, ldw=hidden, ldy=hidden,
+                                      operands_are_full=True)
+            nws = max(hap.hap_linear_bwd_workspace(self.fc1, j), hap.hap_linear_bwd_workspace(self.fc2, j), 256)
+            self.ws = torch.empty((nws,), dtype=torch.uint8, device=dev)
+            return
+        self.ld = ld = max(_pad8(f), 8)
+        self.cols = slice(0, f)
         self.W1 = torch.zeros((hidden, ld), dtype=dtype, device=dev); self.W1[:, :f] = W1[:, lo:hi]
         self.b1 = b1[lo:hi].clone() if f else torch.zeros((8,), dtype=dtype, device=dev)
         self.W2 = W2[lo:hi].clone() if f else torch.zeros((8, hidden), dtype=dtype, device=dev)
@@ -51,8 +72,6 @@ class MlpShard:
         self.dW1 = torch.zeros((hidden, ld), dtype=dtype, device=dev)
         self.dW2 = torch.zeros((max(f, 1), hidden), dtype=dtype, device=dev)
         self.db1 = torch.zeros((max(f, 1),), dtype=torch.float32, device=dev)
-        io = hap.BF16 if dtype == torch.bfloat16 else hap.F32
-        self.io = io
         self.fc1 = hap.LinearDesc(tokens, hidden, ffn, hap.SHARD_FEATURE, offsets, io, act=hap.ACT_GELU_ERF, has_bias=True,
                                   ldx=hidden, ldw=ld, ldy=ld, operands_are_full=False)
         self.fc2 = hap.LinearDesc(tokens, ffn, hidden, hap.SHARD_REDUCTION, offsets, io, ldx=ld, ldw=hidden, ldy=hidden,

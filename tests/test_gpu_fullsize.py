@@ -71,6 +71,49 @@ def test_cfg2_mlp_shard_full_size_sampled(hap, cfg2, j):
     assert not host(s.H)[:, f:].any() and not host(s.dW1)[:, f:].any()
 
 
+def test_cfg2_whole_tensor_operands_shard1_full_size(hap, cfg2):
+    """The library's other way of taking a shard (operands_are_full = 1): whole tensors in, the device's range applied inside.  Shard 1 owns
+    ffn columns 8402..13442 - byte offset 16804 in a row, nothing 16-byte aligned - so every view is skewed: W1's and Y's columns (feature
+    rule), H's columns and W2's rows (reduction rule), and the column ranges of dH, dW1, db1 the backward writes.  Sampled rows / columns
+    against the oracle's block on the sub-problem; everything outside the device's range must stay as it was (NaN sentinel)."""
+    from paper_2401_05965_amd.programs import MlpShard
+    Tn, h, F = cfg2["dims"]
+    offs = cfg2["offs"]; j = 1
+    lo, hi = offs[j], offs[j + 1]
+    f = hi - lo
+    assert (lo * 2) % 16 != 0
+    s = MlpShard(Tn, h, F, offs, j, cfg2["X"], cfg2["W1"], cfg2["b1"], cfg2["W2"], cfg2["dO"], whole_tensors=True)
+    nan = float("nan")
+    for t in (s.H, s.pre, s.dH, s.dW1, s.dW2, s.db1):
+        t.fill_(nan)
+    s.forward(); s.backward()
+    rng = np.random.default_rng(11)
+    rows = np.unique(np.concatenate([[0, 255, 256, Tn - 1], rng.integers(0, Tn, 20)]))
+    X, dO = cfg2["Xh"], cfg2["dOh"]
+    W1, b1, W2 = cfg2["W1h"][:, lo:hi], cfg2["b1h"][lo:hi], cfg2["W2h"][lo:hi]
+    zero_b2 = np.zeros(h)
+    r = olay.mlp_block(X[rows], W1, b1, W2, zero_b2, dO[rows])
+    check("whole H rows", host(s.H[rows])[:, lo:hi], r["H"], "bf16")
+    check("whole pre rows", host(s.pre[rows])[:, lo:hi], r["pre"], "bf16")
+    check("whole P rows", host(s.P[rows]), r["out"], "bf16")
+    check("whole dH rows", host(s.dH[rows])[:, lo:hi], r["dH"], "bf16")
+    check("whole dX rows", host(s.dX[rows]), r["dX"], "bf16")
+    cols = np.unique(np.concatenate([[0, 1, 5, 6, 7, 8, 255, 256, f - 9, f - 8, f - 2, f - 1], rng.integers(0, f, 8)]))     # both ragged ends chunk by chunk
+    c = olay.mlp_block(X, W1[:, cols], b1[cols], W2[cols], zero_b2, dO)
+    check("whole dW1 cols", host(s.dW1[:, lo:hi])[:, cols], c["dW1"], "bf16")
+    check("whole db1 cols", host(s.db1[lo:hi])[cols], c["db1"], "bf16")
+    check("whole dW2 rows", host(s.dW2[lo:hi])[cols], c["dW2"], "bf16")
+    check("whole H cols", host(s.H[:, lo:hi])[:, cols], c["H"], "bf16")
+    check("whole dH cols", host(s.dH[:, lo:hi])[:, cols], c["dH"], "bf16")
+    # nothing outside the device's range was written
+    torch = torch_mod()
+    for name, t in (("H", s.H), ("pre", s.pre), ("dH", s.dH), ("dW1", s.dW1)):
+        assert bool(torch.isnan(t[:, :lo]).all()) and bool(torch.isnan(t[:, hi:]).all()), name
+        assert not bool(torch.isnan(t[:, lo:hi]).any()), name
+    assert bool(torch.isnan(s.dW2[:lo]).all()) and bool(torch.isnan(s.dW2[hi:]).all()) and not bool(torch.isnan(s.dW2[lo:hi]).any())
+    assert bool(torch.isnan(s.db1[:lo]).all()) and bool(torch.isnan(s.db1[hi:]).all()) and not bool(torch.isnan(s.db1[lo:hi]).any())
+
+
 def test_cfg3_sfb_full_size_sampled(hap):
     from paper_2401_05965_amd.programs import SfbRebuild
     w = hapgen.WORKLOADS["cfg3_sfb_bf16"]
