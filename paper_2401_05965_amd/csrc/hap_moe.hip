@@ -38,7 +38,9 @@ int resolve(const hap_moe_desc* d, int j, int64_t* lo, int64_t* n) {
   return HAP_OK;
 }
 
-inline int64_t lddp_of(const hap_moe_desc* d) { return round_up(d->out_features, 8) + 8; }
+/* Row pitch of the dP copy: a multiple of 128 bytes (it is the K-contiguous operand of the bwd-data products, whose row fetches
+ * should not straddle cache sectors), with 8 spare elements for the 16-byte phase of W's slice. */
+inline int64_t lddp_of(const hap_moe_desc* d) { return round_up(d->out_features + 8, 128 / esize(d->io_dtype)); }
 
 size_t dp_bytes(const hap_moe_desc* d, int64_t n) {
   return d->act == HAP_ACT_NONE ? 0 : (size_t)round_up((n * d->capacity * lddp_of(d) + 8) * esize(d->io_dtype), 256);
