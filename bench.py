@@ -506,8 +506,8 @@ def main():
             else:
                 sj = shards[0] if tag == sizes[0] else shards[1]
                 assert sj.f == tag
-                got = {"H": sj.H[:, :sj.f], "P": sj.P, "dH": sj.dH[:, :sj.f], "dX": sj.dX, "dW1": sj.dW1[:, :sj.f], "db1": sj.db1, "dW2": sj.dW2}
-                want = {"H": ref["H"], "P": ref["out"], "dH": ref["dH"], "dX": ref["dX"], "dW1": ref["dW1"], "db1": ref["db1"], "dW2": ref["dW2"]}
+                got = {"H": sj.H[:, :sj.f], "P": sj.P, sj.dH_holds: sj.dH[:, :sj.f], "dX": sj.dX, "dW1": sj.dW1[:, :sj.f], "db1": sj.db1, "dW2": sj.dW2}
+                want = {"H": ref["H"], "P": ref["out"], sj.dH_holds: ref[sj.dH_holds], "dX": ref["dX"], "dW1": ref["dW1"], "db1": ref["db1"], "dW2": ref["dW2"]}
             for k in got:
                 g = got[k].float().cpu().numpy().astype(np.float64)
                 errs[f"{k}[f={tag}]" if tag != "sfb" else k] = float(np.abs(g - want[k]).max() / np.abs(want[k]).max())
@@ -566,7 +566,7 @@ def config_parity(np, hapgen, T, held):
             lo, hi = h["offs"][j], h["offs"][j + 1]
             ref = layers.mlp_block(X, np.ascontiguousarray(W1[:, lo:hi]), b1[lo:hi], np.ascontiguousarray(W2[lo:hi]), np.zeros(hid), dO)
             f = sh.f
-            for n, got, want in (("H", sh.H[:, :f], "H"), ("P", sh.P, "out"), ("dH", sh.dH[:, :f], "dH"), ("dX", sh.dX, "dX"),
+            for n, got, want in (("H", sh.H[:, :f], "H"), ("P", sh.P, "out"), (sh.dH_holds, sh.dH[:, :f], sh.dH_holds), ("dX", sh.dX, "dX"),
                                  ("dW1", sh.dW1[:, :f], "dW1"), ("db1", sh.db1[:f], "db1"), ("dW2", sh.dW2[:f], "dW2")):
                 e[f"{n}[device {j}, ffn {f}]"] = rel(host(got), ref[want])
             del ref

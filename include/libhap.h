@@ -194,6 +194,20 @@ int hap_sharded_linear_bwd(const hap_linear_desc* d, int shard_index, const void
                            const void* preact, const void* dY, void* dX, void* dW, int dW_dtype,
                            float* dbias, void* ws, size_t ws_bytes, void* stream);
 
+/* hap_sharded_linear_bwd with the activation backward of the layer that PRODUCED X folded into the dX product's
+ * epilogue (Sec. 2.3.1: the chain fc1 -> GeLU -> fc2 of a transformer MLP; the backward of fc2 hands fc1 its dP):
+ *     dX <- (dP W^T) * x_act'(x_preact)
+ * x_preact (device, io_dtype) is that layer's saved pre-activation and has X's shape, layout and leading dimension
+ * ldx (whole or compact exactly as X is); x_act is its hap_act.  The returned dX is then that layer's dP, and its own
+ * backward is called with a descriptor whose act is NONE.  Defined only where dX is complete on the device (BATCH,
+ * REDUCTION, REPLICATED): in FEATURE mode dX is a partial sum, the activation backward belongs after its All-Reduce,
+ * and the call returns HAP_EINVAL.  x_act = HAP_ACT_NONE makes the call identical to hap_sharded_linear_bwd.
+ * The result equals hap_sharded_linear_bwd followed by hap_gelu_bwd in place, rounding included (dX is rounded to
+ * io_dtype before the multiplication in both); it saves that pass's read and write of dX.  Same workspace.          */
+int hap_sharded_linear_bwd_dact(const hap_linear_desc* d, int shard_index, const void* X, const void* W,
+                                const void* preact, const void* dY, void* dX, void* dW, int dW_dtype,
+                                float* dbias, const void* x_preact, int x_act, void* ws, size_t ws_bytes, void* stream);
+
 /* Workspace sizes.  The forward needs none; what hap_linear_fwd_workspace() reports (and the last 64 MiB of what
  * hap_linear_bwd_workspace() / hap_sfb_workspace() report) is OPTIONAL scratch that lets the GEMM engine split the
  * contracted axis over idle compute units when an output has too few tiles to fill the chip.  With a smaller

@@ -368,6 +368,14 @@ def hap_sharded_linear_bwd(desc: LinearDesc, shard_index, X, W, preact, dY, dX, 
            "hap_sharded_linear_bwd")
 
 
+def hap_sharded_linear_bwd_dact(desc: LinearDesc, shard_index, X, W, preact, dY, dX, dW, dW_dtype, dbias, x_preact, x_act,
+                                ws=None, stream=None):
+    wp, wb = _ws(ws)
+    _check(lib.hap_sharded_linear_bwd_dact(C.byref(desc.c), C.c_int(shard_index), _ptr(X), _ptr(W), _ptr(preact), _ptr(dY),
+                                           _ptr(dX), _ptr(dW), C.c_int(dW_dtype), _ptr(dbias), _ptr(x_preact), C.c_int(x_act),
+                                           wp, wb, _stream(stream)), "hap_sharded_linear_bwd_dact")
+
+
 def hap_sfb_grad(Xs, dYs, rows, in_features, out_features, ldx, ldy, in_dtype, dW, lddw, accumulate=False, ws=None, stream=None):
     m = len(rows)
     xp = (C.c_void_p * m)(*[_ptr(t) for t in Xs])

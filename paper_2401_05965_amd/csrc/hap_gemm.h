@@ -33,6 +33,10 @@ struct hap_gemm_problem {
   const void* bias;                    /* [N] in in_dtype or NULL, added before the activation    */
   void* preact; int64_t ldp;           /* optional copy of (product + bias) in c_dtype            */
   int act;                             /* hap_act                                                 */
+  const void* dact_preact; int64_t ldd; /* optional, in c_dtype: the result is multiplied by act'(dact_preact[m][n]) before it is
+                                           stored (the activation backward of the layer that produced the output's tensor,
+                                           folded into this product's epilogue); dact = the hap_act in question            */
+  int dact;
   int force_generic;                   /* testing aid: take the scalar fallback kernel            */
   void* ws; size_t ws_bytes;           /* optional device scratch for split-K partial tiles (NULL: never split K)   */
   int tile;                            /* 0: engine chooses (and may split the problem); 128 / 256: fixed output tile */

@@ -65,6 +65,8 @@ struct GemmArgs {
   void* preact;
   const void* bias;
   int act, accumulate;
+  const void* dact_preact;   // optional [M x N] in C's dtype, leading dimension ldd: C = (product + bias) * act'(dact_preact)
+  long long ldd;
   // Grouped launch (gridDim.y groups): a workgroup works on one of `groups` independent products that differ only in their base
   // addresses (byte strides below) and, when group_len is given, in the valid length of one axis.
   int ragged;              // 0: every group is M x N x k;  1: group_len bounds M;  2: group_len bounds the contraction (nseg == 1)
@@ -150,6 +152,18 @@ __device__ __forceinline__ float erf_fast(float x) {
   return copysignf(1.0f - p * t * e, x);
 }
 __device__ __forceinline__ float gelu_erf(float x) { return 0.5f * x * (1.0f + erf_fast(x * 0.70710678118654752f)); }
+/* d gelu / dx = Phi(x) + x phi(x); exp(-x^2/2) serves both the erf approximation (its argument is x/sqrt 2) and phi */
+__device__ __forceinline__ float gelu_erf_grad(float x) {
+  const float ax = fabsf(x) * 0.70710678118654752f;
+  const float t = __builtin_amdgcn_rcpf(fmaf(0.3275911f, ax, 1.0f));
+  float p = fmaf(1.061405429f, t, -1.453152027f);
+  p = fmaf(p, t, 1.421413741f);
+  p = fmaf(p, t, -0.284496736f);
+  p = fmaf(p, t, 0.254829592f);
+  const float e = __builtin_amdgcn_exp2f(x * x * -0.7213475204444817f);
+  const float half_erf = copysignf(fmaf(p * t, -0.5f * e, 0.5f), x);      // erf(x / sqrt 2) / 2
+  return fmaf(x, 0.3989422804014327f * e, 0.5f + half_erf);
+}
 
 template <typename T> struct Elem;
 template <> struct Elem<__bf16> {
@@ -444,6 +458,7 @@ __device__ __forceinline__ void epilogue(const GemmArgs& args, f32x16_t (&acc)[T
           float v = acc[i][j][e] + bv;
           if (P) store_c<TC>(P + (long long)m * args.ldp + n, v);
           if (args.act == HAP_ACT_GELU_ERF) v = gelu_erf(v);
+          if (args.dact_preact) v *= gelu_erf_grad(load_s<TC>(static_cast<const TC*>(args.dact_preact) + (long long)m * args.ldd + n));
           TC* dst = C + (long long)m * args.ldc + n;
           if (args.accumulate) v += load_s<TC>(dst);
           store_c<TC>(dst, v);
@@ -559,7 +574,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(const GemmArgs arg
     GemmArgs pa = args;
     pa.c = args.partial + (((long long)bp.grp * (gridDim.x / ksplit) + out_tile) * ksplit + split) * (BM * BN);
     pa.ldc = BN; pa.M = BM; pa.N = BN; pa.skewM = 0; pa.skewN = 0;
-    pa.preact = nullptr; pa.bias = nullptr; pa.act = HAP_ACT_NONE; pa.accumulate = 0; pa.vec_store = 1; pa.cdelta = 0;
+    pa.preact = nullptr; pa.bias = nullptr; pa.act = HAP_ACT_NONE; pa.accumulate = 0; pa.vec_store = 1; pa.cdelta = 0; pa.dact_preact = nullptr;
     epilogue<T, float, TM, TN>(pa, acc, wm0, wn0, lane);
     return;
   }
@@ -577,7 +592,7 @@ template <typename TC> struct Vec16;
 template <> struct Vec16<__bf16> { typedef __bf16 type __attribute__((ext_vector_type(8))); };
 template <> struct Vec16<float> { typedef float type __attribute__((ext_vector_type(4))); };
 
-template <typename T, typename TC, int TM, int TN, bool SHIFTED>
+template <typename T, typename TC, int TM, int TN, bool SHIFTED, bool DACT>
 __device__ __forceinline__ void epilogue_transposed_impl(const GemmArgs& args, f32x16_t (&acc)[TM][TN], int row0, int col0, int lane, char* patch) {
   constexpr int ES = sizeof(TC);
   constexpr int EPC = 16 / ES;
@@ -596,21 +611,55 @@ __device__ __forceinline__ void epilogue_transposed_impl(const GemmArgs& args, f
   const int delta = SHIFTED ? args.cdelta : 0;
   constexpr int nchunks = SHIFTED ? CH + 1 : CH;
   // this lane's bias values: the same 4 consecutive columns of every 8-column group, for all row blocks and passes
-  float bv[TN][4][4];
+  // (DACT: the host admits no bias either, which frees these registers for the pre-activation chunks below)
+  float bv[DACT ? 1 : TN][4][4];
+  if constexpr (!DACT) {
 #pragma unroll
-  for (int j = 0; j < TN; ++j)
+    for (int j = 0; j < TN; ++j)
 #pragma unroll
-    for (int g = 0; g < 4; ++g)
+      for (int g = 0; g < 4; ++g)
 #pragma unroll
-      for (int x = 0; x < 4; ++x) {
-        const int n = col0 + j * 32 + g * 8 + h * 4 + x - args.skewN;
-        bv[j][g][x] = (bias && n >= 0 && n < args.N) ? load_s<T>(bias + n) : 0.0f;
-      }
+        for (int x = 0; x < 4; ++x) {
+          const int n = col0 + j * 32 + g * 8 + h * 4 + x - args.skewN;
+          bv[j][g][x] = (bias && n >= 0 && n < args.N) ? load_s<T>(bias + n) : 0.0f;
+        }
+  }
+  constexpr int ITS = (32 * nchunks + 63) / 64;          // 16-byte chunks of one 32-row block per lane
+  // (row, column, valid part) of the chunk this lane stores in iteration `it` of row block i
+  auto chunk_at = [&](int i, int it, int* m, int* n, int* t_lo, int* t_hi) -> bool {
+    const int idx = it * 64 + lane;
+    const int r = idx / nchunks, c = idx % nchunks;
+    *m = row0 + i * 32 + r - args.skewM;
+    *n = col0 + c * EPC - delta - args.skewN;
+    // (a patch chunk also ends where the tile's columns end: what lies beyond was not written in this pass)
+    *t_lo = c * EPC - delta < 0 ? delta - c * EPC : 0;
+    *t_hi = c * EPC - delta + EPC > COLS ? COLS - (c * EPC - delta) : EPC;
+    return (!SHIFTED || idx < 32 * nchunks) && *m >= 0 && *m < args.M && *n + *t_lo < args.N && *n + *t_hi > 0;
+  };
+  // DACT: all pre-activation chunks of the wave's tile are requested now, in one burst, so that the stores below wait for one
+  // memory round trip instead of one per chunk
+  // (an fp32 tile has twice the chunks: there the requests go out one row block at a time, ahead of that block's patch traffic)
+  constexpr int BURST = !DACT ? 0 : ES == 2 ? TM : 1;
+  vec_t pvs[DACT ? BURST : 1][DACT ? ITS : 1];
+  auto request_preact = [&](int i, int slot) {
+#pragma unroll
+    for (int it = 0; it < ITS; ++it) {
+      int m, n, t_lo, t_hi;
+      // (a chunk that this wave stores only part of - its other columns belong to the neighbouring wave's tile - is still read whole)
+      if (chunk_at(i, it, &m, &n, &t_lo, &t_hi) && vec_ok && n >= 0 && n + EPC <= args.N)
+        pvs[slot][it] = *reinterpret_cast<const vec_t*>(static_cast<const TC*>(args.dact_preact) + (long long)m * args.ldd + n);
+    }
+  };
+  if constexpr (BURST == TM) {
+#pragma unroll
+    for (int i = 0; i < TM; ++i) request_preact(i, i);
+  }
 #pragma unroll
   for (int i = 0; i < TM; ++i) {
 #pragma unroll
     for (int pass = 0; pass < 2; ++pass) {
-      if (pass == 0 && !P) continue;
+      if (pass == 0 && (DACT || !P)) continue;       // (DACT: the host admits neither a pre-activation copy, an activation nor accumulation)
+      if constexpr (BURST == 1) request_preact(i, 0);
       TC* dst_base = pass == 0 ? P : C;
       const long long ldd = pass == 0 ? args.ldp : args.ldc;
       // registers -> LDS patch [32 rows][COLS]
@@ -622,8 +671,9 @@ __device__ __forceinline__ void epilogue_transposed_impl(const GemmArgs& args, f
           TC v[4];
 #pragma unroll
           for (int x = 0; x < 4; ++x) {
-            float f = acc[i][j][g * 4 + x] + bv[j][g][x];
-            if (pass == 1 && args.act == HAP_ACT_GELU_ERF) f = gelu_erf(f);
+            float f = acc[i][j][g * 4 + x];
+            if constexpr (!DACT) f += bv[j][g][x];
+            if (!DACT && pass == 1 && args.act == HAP_ACT_GELU_ERF) f = gelu_erf(f);
             v[x] = (TC)f;
           }
           if constexpr (!SHIFTED) {
@@ -640,19 +690,27 @@ __device__ __forceinline__ void epilogue_transposed_impl(const GemmArgs& args, f
       __builtin_amdgcn_wave_barrier();
       // LDS patch -> global, 16 bytes per lane
 #pragma unroll
-      for (int it = 0; it < (32 * nchunks + 63) / 64; ++it) {
+      for (int it = 0; it < ITS; ++it) {
+        int m, n, t_lo, t_hi;
+        if (!chunk_at(i, it, &m, &n, &t_lo, &t_hi)) continue;
         const int idx = it * 64 + lane;
-        if (SHIFTED && idx >= 32 * nchunks) break;
         const int r = idx / nchunks, c = idx % nchunks;
-        const int m = row0 + i * 32 + r - args.skewM;
-        const int n = col0 + c * EPC - delta - args.skewN;
-        // (a patch chunk also ends where the tile's columns end: what lies beyond was not written in this pass)
-        const int t_lo = c * EPC - delta < 0 ? delta - c * EPC : 0, t_hi = c * EPC - delta + EPC > COLS ? COLS - (c * EPC - delta) : EPC;
-        if (m < 0 || m >= args.M || n + t_lo >= args.N || n + t_hi <= 0) continue;
         vec_t val = *reinterpret_cast<const vec_t*>(patch + r * ROWB + c * 16);
         TC* dst = dst_base + (long long)m * ldd + n;
+        const TC* dpre = DACT ? static_cast<const TC*>(args.dact_preact) + (long long)m * args.ldd + n : nullptr;
+        // (vec_ok implies that dact_preact shares C's 16-byte phase and pitch rule.)  The multiplication is done once, for whole
+        // chunks, before the lanes part into chunk stores and element stores; elements of a partly stored chunk that lie outside
+        // this wave's columns hold patch leftovers and are dropped below.
+        const bool pv_ok = DACT && vec_ok && n >= 0 && n + EPC <= args.N;
+        if constexpr (DACT) {
+          if (pv_ok) {
+            const vec_t pv = pvs[BURST == TM ? i : 0][it];
+#pragma unroll
+            for (int x = 0; x < EPC; ++x) val[x] = (TC)((float)val[x] * gelu_erf_grad((float)pv[x]));
+          }
+        }
         if (vec_ok && n >= 0 && n + EPC <= args.N && t_lo == 0 && t_hi == EPC) {
-          if (pass == 1 && args.accumulate) {
+          if (!DACT && pass == 1 && args.accumulate) {
             const vec_t old = *reinterpret_cast<const vec_t*>(dst);
 #pragma unroll
             for (int x = 0; x < EPC; ++x) val[x] = (TC)((float)val[x] + (float)old[x]);
@@ -663,7 +721,8 @@ __device__ __forceinline__ void epilogue_transposed_impl(const GemmArgs& args, f
           for (int x = 0; x < EPC; ++x)
             if (x >= t_lo && x < t_hi && n + x >= 0 && n + x < args.N) {
               float f = (float)val[x];
-              if (pass == 1 && args.accumulate) f += load_s<TC>(dst + x);
+              if constexpr (DACT) { if (!pv_ok) f *= gelu_erf_grad(load_s<TC>(dpre + x)); }
+              if (!DACT && pass == 1 && args.accumulate) f += load_s<TC>(dst + x);
               store_c<TC>(dst + x, f);
             }
         }
@@ -678,8 +737,11 @@ __device__ __forceinline__ void epilogue_transposed_impl(const GemmArgs& args, f
 
 template <typename T, typename TC, int TM, int TN>
 __device__ __forceinline__ void epilogue_transposed(const GemmArgs& args, f32x16_t (&acc)[TM][TN], int row0, int col0, int lane, char* patch) {
-  if (args.cdelta) epilogue_transposed_impl<T, TC, TM, TN, true>(args, acc, row0, col0, lane, patch);
-  else epilogue_transposed_impl<T, TC, TM, TN, false>(args, acc, row0, col0, lane, patch);
+  if (args.dact_preact) {
+    if (args.cdelta) epilogue_transposed_impl<T, TC, TM, TN, true, true>(args, acc, row0, col0, lane, patch);
+    else epilogue_transposed_impl<T, TC, TM, TN, false, true>(args, acc, row0, col0, lane, patch);
+  } else if (args.cdelta) epilogue_transposed_impl<T, TC, TM, TN, true, false>(args, acc, row0, col0, lane, patch);
+  else epilogue_transposed_impl<T, TC, TM, TN, false, false>(args, acc, row0, col0, lane, patch);
 }
 
 /* ---------------------------------------------------------------------------------------------
@@ -958,7 +1020,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_dma_kernel(const GemmArgs
     GemmArgs pa = args;
     pa.c = args.partial + (((long long)bp.grp * (gridDim.x / ksplit) + out_tile) * ksplit + split) * (BM * BN);
     pa.ldc = BN; pa.M = BM; pa.N = BN; pa.skewM = 0; pa.skewN = 0;
-    pa.preact = nullptr; pa.bias = nullptr; pa.act = HAP_ACT_NONE; pa.accumulate = 0; pa.vec_store = 1; pa.cdelta = 0;
+    pa.preact = nullptr; pa.bias = nullptr; pa.act = HAP_ACT_NONE; pa.accumulate = 0; pa.vec_store = 1; pa.cdelta = 0; pa.dact_preact = nullptr;
     epilogue_transposed<T, float, TM, TN>(pa, acc, wm0, wn0, lane, smem + wave * (32 * (TN * 32 * 4 + 16)));
     return;
   }
@@ -1184,7 +1246,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_pp_kernel(const GemmArgs 
     GemmArgs pa = args;
     pa.c = args.partial + (((long long)bp.grp * (gridDim.x / ksplit) + out_tile) * ksplit + split) * (BM * BN);
     pa.ldc = BN; pa.M = BM; pa.N = BN; pa.skewM = 0; pa.skewN = 0;
-    pa.preact = nullptr; pa.bias = nullptr; pa.act = HAP_ACT_NONE; pa.accumulate = 0; pa.vec_store = 1; pa.cdelta = 0;
+    pa.preact = nullptr; pa.bias = nullptr; pa.act = HAP_ACT_NONE; pa.accumulate = 0; pa.vec_store = 1; pa.cdelta = 0; pa.dact_preact = nullptr;
     epilogue_transposed<T, float, TM, TN>(pa, acc, wm0, wn0, lane, smem + wave * (32 * (TN * 32 * 4 + 16)));
     return;
   }
@@ -1222,6 +1284,7 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(const GemmArgs args_
     if (bias) v += load_s<T>(bias + nn);
     if (P) store_c<TC>(P + (long long)m * args.ldp + nn, v);
     if (args.act == HAP_ACT_GELU_ERF) v = gelu_erf(v);
+    if (args.dact_preact) v *= gelu_erf_grad(load_s<TC>(static_cast<const TC*>(args.dact_preact) + (long long)m * args.ldd + nn));
     TC* dst = C + (long long)m * args.ldc + nn;
     if (args.accumulate) v += load_s<TC>(dst);
     store_c<TC>(dst, v);
@@ -1236,6 +1299,7 @@ struct GenericArgs {
   int a_kcontig, b_kcontig;
   void* c; void* preact; const void* bias;
   int act, accumulate;
+  const void* dact_preact; long long ldd;
   int ragged;                        // as in GemmArgs; blockIdx.z is the group
   const int* group_len;
   long long ga, gb, gc, gp, gbias;   // byte strides between groups
@@ -1267,6 +1331,7 @@ __global__ __launch_bounds__(256) void gemm_generic_kernel(const GenericArgs g) 
   if (g.bias) acc += load_s<T>(reinterpret_cast<const T*>(static_cast<const char*>(g.bias) + grp * g.gbias) + n);
   if (g.preact) store_c<TC>(reinterpret_cast<TC*>(static_cast<char*>(g.preact) + grp * g.gp) + (long long)m * g.ldp + n, acc);
   if (g.act == HAP_ACT_GELU_ERF) acc = gelu_erf(acc);
+  if (g.dact_preact) acc *= gelu_erf_grad(load_s<TC>(static_cast<const TC*>(g.dact_preact) + (long long)m * g.ldd + n));
   TC* dst = reinterpret_cast<TC*>(static_cast<char*>(g.c) + grp * g.gc) + (long long)m * g.ldc + n;
   if (g.accumulate) acc += load_s<TC>(dst);
   store_c<TC>(dst, acc);
@@ -1479,8 +1544,10 @@ int dispatch_tile(const hap_gemm_problem* p, const Plan& pl, const GemmArgs& a, 
     return dispatch_layout<T, TC, 64, 64, 64, 2, 2>(p, a, groups, st);
   } else {
 #if defined(HAP_GEMM_EXPERIMENT)
+#if defined(HAP_GEMM_EXPERIMENT_ALL)
     if (pl.bm == 256 && hap_exp_variant == 1) return dispatch_pp<TC, 256, 256, 32, 5, 2, 4>(p, a, groups, st);
     if (pl.bm == 256 && hap_exp_variant == 2) return dispatch_pp<TC, 256, 256, 64, 2, 2, 4>(p, a, groups, st);
+#endif
     if (pl.bm == 256 && hap_exp_variant == 3) return dispatch_dma<TC, 256, 256, 64, 2, 2, 4>(p, a, groups, st);
 #endif
     if (pl.pingpong) return dispatch_pp<TC, 256, 256, 32, kPingPongStages, 2, 4>(p, a, groups, st);
@@ -1521,6 +1588,7 @@ hap_gemm_problem sub_problem(const hap_gemm_problem* p, int64_t m_lo, int64_t m_
   }
   q.c = static_cast<char*>(p->c) + (m_lo * p->ldc + n_lo) * ces;
   if (p->preact) q.preact = static_cast<char*>(p->preact) + (m_lo * p->ldp + n_lo) * ces;
+  if (p->dact_preact) q.dact_preact = static_cast<const char*>(p->dact_preact) + (m_lo * p->ldd + n_lo) * ces;
   if (p->bias) q.bias = static_cast<const char*>(p->bias) + n_lo * es;
   return q;
 }
@@ -1696,6 +1764,11 @@ int hap_gemm_run(const hap_gemm_problem* p, void* stream) {
   if (p->M > 0x7fffffff || p->N > 0x7fffffff) return hap_fail(HAP_EUNSUPPORTED, "GEMM extent exceeds 2^31");
   if (p->accumulate && p->c_dtype != HAP_F32) return hap_fail(HAP_EINVAL, "accumulate needs an fp32 output");
   if (p->in_dtype == HAP_F32 && p->c_dtype != HAP_F32) return hap_fail(HAP_EUNSUPPORTED, "fp32 inputs need fp32 output");
+  if (p->dact != HAP_ACT_NONE) {
+    if (p->dact != HAP_ACT_GELU_ERF || !p->dact_preact) return hap_fail(HAP_EINVAL, "bad activation backward in the epilogue (dact %d)", p->dact);
+    if (p->act != HAP_ACT_NONE || p->accumulate || p->preact || p->groups > 1 || p->group_len)
+      return hap_fail(HAP_EINVAL, "an epilogue with an activation backward has no activation, pre-activation copy, accumulation or groups");
+  }
   const int es = esize(p->in_dtype), ces_out = esize(p->c_dtype);
   const int groups = p->groups > 1 ? p->groups : 1;
   const bool grouped = groups > 1 || p->group_len;
@@ -1719,6 +1792,7 @@ int hap_gemm_run(const hap_gemm_problem* p, void* stream) {
     g.lda = p->lda; g.ldb = p->ldb; g.ldc = p->ldc; g.ldp = p->ldp;
     g.a_kcontig = p->a_kcontig; g.b_kcontig = p->b_kcontig;
     g.c = p->c; g.preact = p->preact; g.bias = p->bias; g.act = p->act; g.accumulate = p->accumulate;
+    g.dact_preact = p->dact ? p->dact_preact : nullptr; g.ldd = p->ldd;
     g.ragged = ragged; g.group_len = p->group_len;
     g.ga = p->ga * es; g.gb = p->gb * es; g.gc = p->gc * ces_out; g.gp = p->gp * ces_out; g.gbias = p->gbias * es;
     for (int s = 0; s < p->nseg; ++s) {
@@ -1741,6 +1815,7 @@ int hap_gemm_run(const hap_gemm_problem* p, void* stream) {
   a.skewM = pl.skewM; a.skewN = pl.skewN; a.skewK = pl.skewK;
   a.lda = p->lda; a.ldb = p->ldb; a.ldc = p->ldc; a.ldp = p->ldp;
   a.c = p->c; a.preact = p->preact; a.bias = p->bias; a.act = p->act; a.accumulate = p->accumulate;
+  a.dact_preact = p->dact ? p->dact_preact : nullptr; a.ldd = p->ldd;
   a.ragged = ragged; a.group_len = p->group_len;
   a.ga = p->ga * es; a.gb = p->gb * es; a.gc = p->gc * ces_out; a.gp = p->gp * ces_out; a.gbias = p->gbias * es;
   a.tiles_m = (int)((p->M + pl.skewM + pl.bm - 1) / pl.bm);
@@ -1772,7 +1847,8 @@ int hap_gemm_run(const hap_gemm_problem* p, void* stream) {
     const int ces = esize(p->c_dtype), cepc = 16 / ces;
     a.vec_store = ((uintptr_t)p->c % ces) == 0 && p->ldc % cepc == 0 &&
                   (!p->preact || (((uintptr_t)p->preact % 16) == ((uintptr_t)p->c % 16) && p->ldp % cepc == 0)) &&
-                  (groups == 1 || (p->gc % cepc == 0 && (!p->preact || p->gp % cepc == 0)));
+                  (groups == 1 || (p->gc % cepc == 0 && (!p->preact || p->gp % cepc == 0))) &&
+                  (!(p->dact && p->dact_preact) || (((uintptr_t)p->dact_preact % 16) == ((uintptr_t)p->c % 16) && p->ldd % cepc == 0));
     const int skew_c = (int)(((uintptr_t)p->c % 16) / ces);       // columns of C's 16-byte chunk that precede logical column 0
     a.cdelta = a.vec_store ? ((skew_c - pl.skewN) % cepc + cepc) % cepc : 0;
   }

@@ -138,15 +138,40 @@ int hap_sharded_linear_fwd(const hap_linear_desc* d, int shard_index, const void
   return hap_gemm_run(&p, stream);
 }
 
+static int linear_bwd_impl(const hap_linear_desc* d, int shard_index, const void* X, const void* W,
+                           const void* preact, const void* dY, void* dX, void* dW, int dW_dtype,
+                           float* dbias, const void* x_preact, int x_act, void* ws, size_t ws_bytes, void* stream);
+
 int hap_sharded_linear_bwd(const hap_linear_desc* d, int shard_index, const void* X, const void* W,
                            const void* preact, const void* dY, void* dX, void* dW, int dW_dtype,
                            float* dbias, void* ws, size_t ws_bytes, void* stream) {
   hap_clear_error();
+  return linear_bwd_impl(d, shard_index, X, W, preact, dY, dX, dW, dW_dtype, dbias, NULL, HAP_ACT_NONE, ws, ws_bytes, stream);
+}
+
+int hap_sharded_linear_bwd_dact(const hap_linear_desc* d, int shard_index, const void* X, const void* W,
+                                const void* preact, const void* dY, void* dX, void* dW, int dW_dtype,
+                                float* dbias, const void* x_preact, int x_act, void* ws, size_t ws_bytes, void* stream) {
+  hap_clear_error();
+  if (x_act != HAP_ACT_NONE && x_act != HAP_ACT_GELU_ERF) return hap_fail(HAP_EINVAL, "bad x_act %d", x_act);
+  if (x_act != HAP_ACT_NONE) {
+    if (!d) return hap_fail(HAP_EINVAL, "descriptor is NULL");
+    // act' is applied to a complete dX only: the feature rule yields a partial sum that is all-reduced first
+    if (d->mode == HAP_SHARD_FEATURE) return hap_fail(HAP_EINVAL, "dX of a feature-sharded layer is a partial sum: the producer's activation backward comes after its All-Reduce");
+  }
+  return linear_bwd_impl(d, shard_index, X, W, preact, dY, dX, dW, dW_dtype, dbias, x_preact, x_act, ws, ws_bytes, stream);
+}
+
+static int linear_bwd_impl(const hap_linear_desc* d, int shard_index, const void* X, const void* W,
+                           const void* preact, const void* dY, void* dX, void* dW, int dW_dtype,
+                           float* dbias, const void* x_preact, int x_act, void* ws, size_t ws_bytes, void* stream) {
   View v;
   int rc = resolve(d, shard_index, &v);
   if (rc) return rc;
   // pointers to slices the device owns nothing of may be NULL (a compact slice of size 0)
   const bool has_dp = v.tok_n > 0 && v.out_n > 0;
+  if (x_act != HAP_ACT_NONE && v.tok_n > 0 && v.in_n > 0 && (!dX || !x_preact)) return hap_fail(HAP_EINVAL, "x_act given but dX or x_preact is NULL");
+  if (x_act == HAP_ACT_NONE) x_preact = NULL;
   if (!dY && has_dp) return hap_fail(HAP_EINVAL, "dY is NULL");
   if (dX && !W && has_dp && v.in_n > 0) return hap_fail(HAP_EINVAL, "dX requested but W is NULL");
   if (dW && !X && has_dp && v.in_n > 0) return hap_fail(HAP_EINVAL, "dW requested but X is NULL");
@@ -190,6 +215,7 @@ int hap_sharded_linear_bwd(const hap_linear_desc* d, int shard_index, const void
     p.b[0] = at(W, o.w, es); p.ldb = d->ldw; p.b_kcontig = 1;   // B(k = out, n = in) = W[n*ldw + k]
     p.in_dtype = d->io_dtype;
     p.c = at(dX, o.x, es); p.ldc = d->ldx; p.c_dtype = d->io_dtype;
+    if (x_preact) { p.dact_preact = at(x_preact, o.x, es); p.ldd = d->ldx; p.dact = x_act; }
     p.ws = gemm_ws_bytes ? gemm_ws : NULL; p.ws_bytes = gemm_ws_bytes;
     rc = hap_gemm_run(&p, stream);
     if (rc) return rc;

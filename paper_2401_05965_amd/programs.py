@@ -36,8 +36,17 @@ class MlpShard:
     dimension of W1_j rounded up to a multiple of 64 elements (128 bytes).
     """
 
-    def __init__(self, tokens, hidden, ffn, offsets, j, X, W1, b1, W2, dOut, dtype=torch.bfloat16, whole_tensors=False):
+    def __init__(self, tokens, hidden, ffn, offsets, j, X, W1, b1, W2, dOut, dtype=torch.bfloat16, whole_tensors=False, fuse_act_bwd=None):
         self.T, self.h, self.F, self.j = tokens, hidden, ffn, j
+        # fuse_act_bwd: fc2's backward multiplies its dX product by gelu'(pre) in the epilogue, so the buffer `dH` receives
+        # dP = dH * gelu'(pre) directly (`dH_holds` names which of the two it holds) and fc1's backward skips that pass.
+        # Default: on for compact slices (measured -3 % of the backward), off for whole tensors: there a shard's columns start off the
+        # 16-byte grid, every wave's strip of the tile has partly stored chunks at both ends, and the multiplication in front of those
+        # element stores costs more than the separate pass it replaces.
+        if fuse_act_bwd is None:
+            fuse_act_bwd = not whole_tensors
+        self.fuse_act_bwd = fuse_act_bwd
+        self.dH_holds = "dP" if fuse_act_bwd else "dH"
         lo, hi = offsets[j], offsets[j + 1]
         self.f = f = hi - lo
         dev = X.device
@@ -59,6 +68,8 @@ class MlpShard:
                                       ldx=hidden, ldw=ffn, ldy=ffn, operands_are_full=True)
             self.fc2 = hap.LinearDesc(tokens, ffn, hidden, hap.SHARD_REDUCTION, offsets, io, ldx=ffn, ldw=hidden, ldy=hidden,
                                       operands_are_full=True)
+            self.fc1_lin = hap.LinearDesc(tokens, hidden, ffn, hap.SHARD_FEATURE, offsets, io, has_bias=True,
+                                          ldx=hidden, ldw=ffn, ldy=ffn, operands_are_full=True)
             nws = max(hap.hap_linear_bwd_workspace(self.fc1, j), hap.hap_linear_bwd_workspace(self.fc2, j), 256)
             self.ws = torch.empty((nws,), dtype=torch.uint8, device=dev)
             return
@@ -79,6 +90,8 @@ class MlpShard:
                                   ldx=hidden, ldw=ld, ldy=ld, operands_are_full=False)
         self.fc2 = hap.LinearDesc(tokens, ffn, hidden, hap.SHARD_REDUCTION, offsets, io, ldx=ld, ldw=hidden, ldy=hidden,
                                   operands_are_full=False)
+        self.fc1_lin = hap.LinearDesc(tokens, hidden, ffn, hap.SHARD_FEATURE, offsets, io, has_bias=True,
+                                      ldx=hidden, ldw=ld, ldy=ld, operands_are_full=False)    # fc1 with its activation already differentiated
         nws = max(hap.hap_linear_bwd_workspace(self.fc1, j), hap.hap_linear_bwd_workspace(self.fc2, j), 256)
         self.ws = torch.empty((nws,), dtype=torch.uint8, device=dev)      # also serves the forward's optional split-K scratch
 
@@ -94,6 +107,14 @@ class MlpShard:
 
     def backward(self, timer=None):
         j = self.j
+        if self.fuse_act_bwd:
+            # fc2 (reduction rule): dP_j = (dOut W2[c_j,:]^T) * gelu'(pre_j) in one product, dW2[c_j,:] = H_j^T dOut
+            _call(timer, "fc2_bwd", lambda: hap.hap_sharded_linear_bwd_dact(self.fc2, j, self.H, self.W2, None, self.dOut, self.dH, self.dW2,
+                                                                            self.io, None, self.pre, hap.ACT_GELU_ERF, self.ws))
+            # fc1 (feature rule) on dP: dX_j = dP W1_j^T (partial), dW1_j = X^T dP, db1_j = colsum(dP)
+            _call(timer, "fc1_bwd", lambda: hap.hap_sharded_linear_bwd(self.fc1_lin, j, self.X, self.W1, None, self.dH, self.dX, self.dW1,
+                                                                       self.io, self.db1, self.ws))
+            return
         # fc2 (reduction rule): dH_j = dOut W2[c_j,:]^T, dW2[c_j,:] = H_j^T dOut
         _call(timer, "fc2_bwd", lambda: hap.hap_sharded_linear_bwd(self.fc2, j, self.H, self.W2, None, self.dOut, self.dH, self.dW2,
                                                                    self.io, None, self.ws))
@@ -237,6 +258,7 @@ class EncoderShard:
         self.d_wo = L(N, max(hd, 1), hidden, hap.REPLICATED, one, io, ldx=max(hd, 8), ldw=hidden, ldy=hidden, m=1)
         self.d_fc1 = L(N, hidden, max(self.f, 1), hap.REPLICATED, one, io, act=hap.ACT_GELU_ERF, has_bias=True, ldx=hidden, ldw=ldf, ldy=ldf, m=1)
         self.d_fc2 = L(N, max(self.f, 1), hidden, hap.REPLICATED, one, io, ldx=ldf, ldw=hidden, ldy=hidden, m=1)
+        self.d_fc1_lin = L(N, hidden, max(self.f, 1), hap.REPLICATED, one, io, has_bias=True, ldx=hidden, ldw=ldf, ldy=ldf, m=1)
         # Q|K|V are column blocks of the [N x 3hd] projection output; O and dO are [N x hd]
         self.d_attn = hap.AttnDesc(self.B, max(self.nh, 1), S, d, True, [0, max(self.nh, 1)], stride_b=S * 3 * hd, stride_s=3 * hd, stride_h=d,
                                    o_strides=(S * hd, hd, d)) if hd and self.B else None    # no (batch entry, head) pair: no attention call
@@ -282,8 +304,10 @@ class EncoderShard:
         if self.f == 0:
             self.dln2_part.zero_()
             return
-        _call(timer, "fc2_bwd", lambda: hap.hap_sharded_linear_bwd(self.d_fc2, 0, self.H, self.W2, None, dy, self.dH, self.dW2, self.io, None, self.ws))
-        _call(timer, "fc1_bwd", lambda: hap.hap_sharded_linear_bwd(self.d_fc1, 0, self.ln2, self.W1, self.pre, self.dH, self.dln2_part, self.dW1, self.io, self.db1, self.ws))
+        # fc2's backward hands fc1 its dP: the GeLU backward rides in the epilogue of the dH product (dH then holds dP)
+        _call(timer, "fc2_bwd", lambda: hap.hap_sharded_linear_bwd_dact(self.d_fc2, 0, self.H, self.W2, None, dy, self.dH, self.dW2, self.io, None,
+                                                                        self.pre, hap.ACT_GELU_ERF, self.ws))
+        _call(timer, "fc1_bwd", lambda: hap.hap_sharded_linear_bwd(self.d_fc1_lin, 0, self.ln2, self.W1, None, self.dH, self.dln2_part, self.dW1, self.io, self.db1, self.ws))
 
     def ln2_backward(self, x1, dln2, dres, dx1, timer=None):
         """dx1 = dres + LayerNorm2-backward(dln2): the residual path's gradient joins in the same kernel."""

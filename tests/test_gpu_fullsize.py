@@ -58,7 +58,7 @@ def test_cfg2_mlp_shard_full_size_sampled(hap, cfg2, j):
     check("H rows", host(s.H[rows])[:, :f], r["H"], "bf16")
     check("pre rows", host(s.pre[rows])[:, :f], r["pre"], "bf16")
     check("P rows", host(s.P[rows]), r["out"], "bf16")
-    check("dH rows", host(s.dH[rows])[:, :f], r["dH"], "bf16")
+    check(f"{s.dH_holds} rows", host(s.dH[rows])[:, :f], r[s.dH_holds], "bf16")
     check("dX rows", host(s.dX[rows]), r["dX"], "bf16")
     # sampled ffn columns (first, last, tile edges, random): the weight gradients of an ffn column depend on that column only,
     # so the block restricted to those columns of W1 / rows of W2, over ALL tokens, is an exact sub-problem as well
@@ -71,18 +71,21 @@ def test_cfg2_mlp_shard_full_size_sampled(hap, cfg2, j):
     assert not host(s.H)[:, f:].any() and not host(s.dW1)[:, f:].any()
 
 
-def test_cfg2_whole_tensor_operands_shard1_full_size(hap, cfg2):
+@pytest.mark.parametrize("fuse_act_bwd", [False, True])
+def test_cfg2_whole_tensor_operands_shard1_full_size(hap, cfg2, fuse_act_bwd):
     """The library's other way of taking a shard (operands_are_full = 1): whole tensors in, the device's range applied inside.  Shard 1 owns
     ffn columns 8402..13442 - byte offset 16804 in a row, nothing 16-byte aligned - so every view is skewed: W1's and Y's columns (feature
     rule), H's columns and W2's rows (reduction rule), and the column ranges of dH, dW1, db1 the backward writes.  Sampled rows / columns
-    against the oracle's block on the sub-problem; everything outside the device's range must stay as it was (NaN sentinel)."""
+    against the oracle's block on the sub-problem; everything outside the device's range must stay as it was (NaN sentinel).  Both with the
+    GeLU backward as a pass of its own (the default for whole tensors) and folded into the epilogue of fc2's dX product, whose stores then
+    go through the shifted patch with the pre-activation read at the same skew."""
     from paper_2401_05965_amd.programs import MlpShard
     Tn, h, F = cfg2["dims"]
     offs = cfg2["offs"]; j = 1
     lo, hi = offs[j], offs[j + 1]
     f = hi - lo
     assert (lo * 2) % 16 != 0
-    s = MlpShard(Tn, h, F, offs, j, cfg2["X"], cfg2["W1"], cfg2["b1"], cfg2["W2"], cfg2["dO"], whole_tensors=True)
+    s = MlpShard(Tn, h, F, offs, j, cfg2["X"], cfg2["W1"], cfg2["b1"], cfg2["W2"], cfg2["dO"], whole_tensors=True, fuse_act_bwd=fuse_act_bwd)
     nan = float("nan")
     for t in (s.H, s.pre, s.dH, s.dW1, s.dW2, s.db1):
         t.fill_(nan)
@@ -96,7 +99,7 @@ def test_cfg2_whole_tensor_operands_shard1_full_size(hap, cfg2):
     check("whole H rows", host(s.H[rows])[:, lo:hi], r["H"], "bf16")
     check("whole pre rows", host(s.pre[rows])[:, lo:hi], r["pre"], "bf16")
     check("whole P rows", host(s.P[rows]), r["out"], "bf16")
-    check("whole dH rows", host(s.dH[rows])[:, lo:hi], r["dH"], "bf16")
+    check(f"whole {s.dH_holds} rows", host(s.dH[rows])[:, lo:hi], r[s.dH_holds], "bf16")
     check("whole dX rows", host(s.dX[rows]), r["dX"], "bf16")
     cols = np.unique(np.concatenate([[0, 1, 5, 6, 7, 8, 255, 256, f - 9, f - 8, f - 2, f - 1], rng.integers(0, f, 8)]))     # both ragged ends chunk by chunk
     c = olay.mlp_block(X, W1[:, cols], b1[cols], W2[cols], zero_b2, dO)
@@ -104,7 +107,7 @@ def test_cfg2_whole_tensor_operands_shard1_full_size(hap, cfg2):
     check("whole db1 cols", host(s.db1[lo:hi])[cols], c["db1"], "bf16")
     check("whole dW2 rows", host(s.dW2[lo:hi])[cols], c["dW2"], "bf16")
     check("whole H cols", host(s.H[:, lo:hi])[:, cols], c["H"], "bf16")
-    check("whole dH cols", host(s.dH[:, lo:hi])[:, cols], c["dH"], "bf16")
+    check(f"whole {s.dH_holds} cols", host(s.dH[:, lo:hi])[:, cols], c[s.dH_holds], "bf16")
     # nothing outside the device's range was written
     torch = torch_mod()
     for name, t in (("H", s.H), ("pre", s.pre), ("dH", s.dH), ("dW1", s.dW1)):

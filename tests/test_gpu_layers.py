@@ -45,8 +45,10 @@ def ratios_offsets(hap, speeds, n, granule=1):
     return sizes, offs
 
 
-def test_mlp_block_ffn_sharded_three_devices(hap):
-    """cfg2 at reduced size: ffn sharded by speeds (1, 0.6, 0.35); partial outputs summed = unsharded block."""
+@pytest.mark.parametrize("fuse_act_bwd", [True, False])
+def test_mlp_block_ffn_sharded_three_devices(hap, fuse_act_bwd):
+    """cfg2 at reduced size: ffn sharded by speeds (1, 0.6, 0.35); partial outputs summed = unsharded block.  With the GeLU
+    backward folded into fc2's bwd-data epilogue (the buffer dH then holds dP = dH * gelu'(pre)) and as a pass of its own."""
     from paper_2401_05965_amd.programs import MlpShard
     tokens, hidden, ffn = 640, 384, 1111
     sizes, offs = ratios_offsets(hap, (1.0, 0.6, 0.35), ffn)
@@ -56,11 +58,11 @@ def test_mlp_block_ffn_sharded_three_devices(hap):
     ref = olay.mlp_block(Xh, W1h, b1h, W2h, np.zeros(hidden), dOh)
     out = np.zeros((tokens, hidden)); dX = np.zeros((tokens, hidden))
     for j in range(3):
-        s = MlpShard(tokens, hidden, ffn, offs, j, Xd, W1d, b1d, W2d, dOd)
+        s = MlpShard(tokens, hidden, ffn, offs, j, Xd, W1d, b1d, W2d, dOd, fuse_act_bwd=fuse_act_bwd)
         s.forward(); s.backward()
         c = slice(offs[j], offs[j + 1]); f = s.f
         check(f"H_{j}", host(s.H)[:, :f], ref["H"][:, c], "bf16")
-        check(f"dH_{j}", host(s.dH)[:, :f], ref["dH"][:, c], "bf16")
+        check(f"{s.dH_holds}_{j}", host(s.dH)[:, :f], ref[s.dH_holds][:, c], "bf16")
         check(f"dW1_{j}", host(s.dW1)[:, :f], ref["dW1"][:, c], "bf16")
         check(f"db1_{j}", host(s.db1)[:f], ref["db1"][c], "bf16")
         check(f"dW2_{j}", host(s.dW2)[:f], ref["dW2"][c], "bf16")

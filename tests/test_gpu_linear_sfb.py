@@ -354,3 +354,73 @@ def test_cfg1_step_replays_from_a_hip_graph(hap):
             assert torch.equal(out[k], want[k]), (rep, k)
         step()                                           # and an eager step in between
         torch.cuda.synchronize()
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("mode,full", [("batch", True), ("batch", False), ("reduction", True), ("reduction", False), ("replicated", False)])
+@pytest.mark.parametrize("shape", [(300, 200, 130), (64, 96, 4200), (1031, 517, 263)])
+def test_linear_bwd_with_producer_activation_backward(hap, dtype, mode, full, shape):
+    """hap_sharded_linear_bwd_dact: dX * gelu'(x_preact) in the dX product's epilogue equals the oracle's dX times the oracle's
+    gelu', for every shard of the modes whose dX is complete on the device; shapes take the tiled kernels, the split
+    contraction (64 x 96 outputs over 4200) and ragged tiles with odd leading dimensions (the element-wise stores)."""
+    from oracle import pointwise as opw
+    tokens, in_f, out_f = shape
+    code = {"batch": olin.BATCH, "reduction": olin.REDUCTION, "replicated": olin.REPLICATED}[mode]
+    axis = {"batch": tokens, "reduction": in_f, "replicated": 1}[mode]
+    offsets = [0, axis * 2 // 5, axis * 2 // 5, axis] if mode != "replicated" else [0, 1]
+    Xh, Xd = gen(11, T.X, (tokens, in_f), 1.0, dtype); Wh, Wd = gen(11, T.W, (in_f, out_f), 0.05, dtype)
+    dYh, dYd = gen(11, T.DY, (tokens, out_f), 1.0, dtype); Ph, Pd = gen(11, T.MISC, (tokens, in_f), 1.5, dtype)   # the producer's pre-activation
+    for j in range(len(offsets) - 1):
+        lo, hi = offsets[j], offsets[j + 1]
+        dXo, dWo, _ = olin.sharded_linear_bwd(code, offsets, j, Xh, Wh, None, dYh, False)
+        rs = slice(lo, hi) if mode == "batch" else slice(None)
+        cs = slice(lo, hi) if mode == "reduction" else slice(None)
+        want = dXo * opw.gelu_grad(Ph[rs, cs])
+        if full or mode == "replicated":
+            Xj, Wj, dYj, Pj = Xd, Wd, dYd, Pd
+            ldx, ldw, ldy = in_f, out_f, out_f
+            dXj = empty((tokens, in_f), dtype, float("nan"))
+        else:
+            Xj, Pj = Xd[rs, cs].contiguous(), Pd[rs, cs].contiguous()
+            Wj = Wd[cs].contiguous() if mode == "reduction" else Wd
+            dYj = dYd[rs].contiguous()
+            ldx, ldw, ldy = Xj.shape[1], out_f, out_f
+            dXj = empty(tuple(Xj.shape), dtype, float("nan"))
+        if Xj.numel() == 0:
+            Xj = Pj = dXj = empty((8, max(ldx, 8)), dtype, 0); ldx = max(ldx, 8)
+        desc = hap.LinearDesc(tokens, in_f, out_f, code, offsets, DT[dtype], ldx=ldx, ldw=ldw, ldy=ldy, operands_are_full=full, m=len(offsets) - 1)
+        ws = empty((max(hap.hap_linear_bwd_workspace(desc, j), 16),), "u8")
+        dWj = empty((Wj.shape[0], ldw), "f32", 0)
+        hap.hap_sharded_linear_bwd_dact(desc, j, Xj, Wj, None, dYj, dXj, dWj, hap.F32, None, Pj, hap.ACT_GELU_ERF, ws)
+        got = host(dXj)
+        if full and mode != "replicated":
+            inside = got[rs, cs]
+            outside = np.ones(got.shape, bool); outside[rs, cs] = False
+            assert np.isnan(got[outside]).all(), "elements outside the shard were written"
+            got = inside
+        elif hi == lo and mode != "replicated":
+            continue
+        if want.size:
+            e = check(f"{dtype} {mode} full{int(full)} shard {j} dX*gelu'", got, want, dtype)
+            # and it is the two-step result: the plain backward followed by the element-wise pass, same roundings
+            dX2 = empty(tuple(dXj.shape), dtype, float("nan"))
+            hap.hap_sharded_linear_bwd(desc, j, Xj, Wj, None, dYj, dX2, None, hap.F32, None, ws)
+            if full and mode != "replicated":
+                v2, vp = dX2[rs, cs].contiguous(), Pd[rs, cs].contiguous()
+            else:
+                v2, vp = dX2, Pj
+            two = empty(tuple(v2.shape), dtype, 0)
+            hap.hap_gelu_bwd(v2.shape[0], v2.shape[1], DT[dtype], vp, vp.stride(0), v2, v2.stride(0), two, two.stride(0))
+            assert relerr(got, host(two)) <= (1e-2 if dtype == "bf16" else 1e-5)
+
+
+def test_linear_bwd_dact_rejects_partial_sums(hap):
+    """In feature mode dX is a partial sum: an activation backward applied before the All-Reduce would be wrong, so the call refuses."""
+    desc = hap.LinearDesc(64, 32, 48, olin.FEATURE, [0, 20, 48], hap.F32, ldx=32, ldw=48, ldy=48, operands_are_full=True)
+    X, W, dY, dX, P = (empty(s, "f32", 0) for s in ((64, 32), (32, 48), (64, 48), (64, 32), (64, 32)))
+    ws = empty((hap.hap_linear_bwd_workspace(desc, 0),), "u8")
+    with pytest.raises(hap.HapError):
+        hap.hap_sharded_linear_bwd_dact(desc, 0, X, W, None, dY, dX, None, hap.F32, None, P, hap.ACT_GELU_ERF, ws)
+    with pytest.raises(hap.HapError):
+        d2 = hap.LinearDesc(64, 32, 48, olin.BATCH, [0, 20, 64], hap.F32, ldx=32, ldw=48, ldy=48, operands_are_full=True)
+        hap.hap_sharded_linear_bwd_dact(d2, 0, X, W, None, dY, dX, None, hap.F32, None, None, hap.ACT_GELU_ERF, ws)
