@@ -467,9 +467,18 @@ def main():
     # (M = 8192 tokens, N = 4096, K = 8402: 512 output tiles, no remainder strip), bracketed by events above.
     dom = f"fc2_fwd[f={big.f}]"
     achieved = call_flops[dom] / (per[dom] * 1e-3) / 1e12
-    # HBM-side bytes of that launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (KiB), scaled by the factors a
-    # plain 256 MiB copy gives (2.000 and 1.000); see profiles/gemm_dma_256x256x64_cfg2_cfg3.md
-    traffic_bytes = int((404685 * 2.000 + 65536 * 1.000) * 1024)
+    # HBM-side bytes of that launch: rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (KiB per dispatch) scaled by the factors a plain
+    # 256 MiB copy gives.  Counters cannot be read from inside this process, so the figure comes from the committed summary of the
+    # profiler runs (profiles/roofline_traffic.json: counter values, factors, the commands and the library commit they were taken
+    # on) and is reported with that source; null when the file is not there.
+    traffic_bytes, traffic_source = None, None
+    tj = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles", "roofline_traffic.json")
+    if os.path.exists(tj):
+        with open(tj) as fh:
+            t = json.load(fh)
+        traffic_bytes = int((t["fetch_size_kib_per_dispatch"] * t["copy_calibration_factor_fetch"] +
+                             t["write_size_kib_per_dispatch"] * t["copy_calibration_factor_write"]) * 1024)
+        traffic_source = {"file": "profiles/roofline_traffic.json", "summary": t["source"], "library_commit": t["library_commit"]}
     out = {
         "metric": "TFLOP/s of sharded fwd+bwd + SFB dW at uneven ratios; % of MFMA peak",
         "value": round(value, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -481,7 +490,7 @@ def main():
                    "pct_of_bf16_mfma_peak": round(100 * value / PEAK_BF16_TFLOPS, 2)},
         "roofline": {"bound": "mfma", "kernel": "gemm_pp_kernel<bf16,256x256x32,4 stages> (" + dom + ": M=8192 N=4096 K=8402)",
                      "achieved": round(achieved, 1), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                     "frac": round(achieved / PEAK_BF16_TFLOPS, 4), "traffic": traffic_bytes,
+                     "frac": round(achieved / PEAK_BF16_TFLOPS, 4), "traffic": traffic_bytes, "traffic_source": traffic_source,
                      "algorithmic_bytes": int(2 * (big.T * big.f + big.f * big.h + big.T * big.h)),
                      "launch_ms": round(per[dom], 4)},
         "calls_ms": {k: round(v, 4) for k, v in sorted(per.items())},
