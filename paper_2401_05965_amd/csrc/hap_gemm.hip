@@ -1291,6 +1291,97 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(const GemmArgs args_
   }
 }
 
+/* ---------------------------------------------------------------------------------------------
+ * fp32 products with at most 64 output rows (a layer whose batch shard is a few dozen samples: the single fully-connected layer
+ * of the smallest workload, 38 / 26 rows of 64).  Such a product has far too few output tiles for the chip, and splitting its
+ * contraction over workgroups costs a second, dependent launch for the reduction - on this machine about as long as the product
+ * itself.  Here the split happens INSIDE a workgroup: one workgroup owns all (<= 64) rows of 16 output columns, its 16 waves each
+ * contract 1/16 of K with v_mfma_f32_16x16x4_f32, and their partial tiles are summed through LDS in a fixed order (deterministic).
+ *   A (K-contiguous): lane (row r = lane % 16, k-quad q = lane / 16) fetches the 4 consecutive k values 16c + 4q .. + 3 of a
+ *   16-wide chunk c as one 16-byte load and feeds element s to step s; B's lane (k-quad q, column) supplies the same k, so the
+ *   order in which a chunk's k values are consumed is a permutation that both operands share.
+ * ------------------------------------------------------------------------------------------- */
+struct SkinnyArgs {
+  int M, N, K;
+  long long lda, ldb, ldc, ldp;
+  const float* a; const float* b; float* c; float* preact; const float* bias;
+  int act, accumulate;
+};
+
+typedef float f32x4_t __attribute__((ext_vector_type(4)));
+
+template <bool BKC>
+__global__ __launch_bounds__(1024) void gemm_skinny_f32_kernel(const SkinnyArgs g) {
+  __shared__ float red[16][64][16];                  // one partial [rows][columns] tile per wave: 64 KB
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, r = lane & 15, kq = lane >> 4;
+  const int n0 = blockIdx.x * 16, col = n0 + r;
+  const int rb = (g.M + 15) >> 4;                    // 16-row blocks in use
+  const int kslice = ((g.K + 255) >> 8) << 4;        // k values per wave, a multiple of 16
+  const int kb0 = wave * kslice;
+  const int kb1 = kb0 + kslice < g.K ? kb0 + kslice : g.K;      // (K is a multiple of 4: a lane's quad is inside or outside as a whole)
+  f32x4_t acc[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) acc[i] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+  for (int kb = kb0; kb < kb1; kb += 64) {
+    f32x4_t av[4][4], bv[4];
+    // all loads of four chunks first, then their MFMAs
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+      const int kk = kb + 16 * c + 4 * kq;
+      const bool kin = kk < kb1;
+      bv[c] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+      if (kin && col < g.N) {
+        if constexpr (BKC) bv[c] = *reinterpret_cast<const f32x4_t*>(g.b + (long long)col * g.ldb + kk);
+        else {
+#pragma unroll
+          for (int x = 0; x < 4; ++x) bv[c][x] = g.b[(long long)(kk + x) * g.ldb + col];
+        }
+      }
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int row = i * 16 + r;
+        av[c][i] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+        if (i < rb && kin && row < g.M) av[c][i] = *reinterpret_cast<const f32x4_t*>(g.a + (long long)row * g.lda + kk);
+      }
+    }
+#pragma unroll
+    for (int c = 0; c < 4; ++c)
+#pragma unroll
+      for (int x = 0; x < 4; ++x)
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+          if (i < rb) acc[i] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[c][i][x], bv[c][x], acc[i], 0, 0, 0);
+  }
+  // accumulator element v of lane l is output (row 4 * (l / 16) + v, column l % 16) of its 16-row block
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int v = 0; v < 4; ++v) red[wave][i * 16 + 4 * kq + v][r] = acc[i][v];
+  __syncthreads();
+  const int row = tid >> 4, c = tid & 15, n = n0 + c;
+  if (row >= g.M || n >= g.N) return;
+  float v = 0.f;
+#pragma unroll
+  for (int w = 0; w < 16; ++w) v += red[w][row][c];
+  if (g.bias) v += g.bias[n];
+  if (g.preact) g.preact[(long long)row * g.ldp + n] = v;
+  if (g.act == HAP_ACT_GELU_ERF) v = gelu_erf(v);
+  float* dst = g.c + (long long)row * g.ldc + n;
+  if (g.accumulate) v += *dst;
+  *dst = v;
+}
+
+/* Whether hap_gemm_run hands the product to gemm_skinny_f32_kernel (see there). */
+static bool skinny_f32_applies(const hap_gemm_problem* p) {
+  if (p->in_dtype != HAP_F32 || p->c_dtype != HAP_F32 || p->M > 64 || !p->a_kcontig || p->nseg != 1) return false;
+  if (p->groups > 1 || p->group_len || p->force_generic || p->tile || p->dact) return false;
+  const int64_t K = p->k[0];
+  if (K < 256 || K % 4 || K > 0x7fffffff || (p->N + 63) / 64 >= 128) return false;      // enough 64-wide tiles: the tiled kernel fills the chip by itself
+  if (p->lda % 4 || (uintptr_t)p->a[0] % 16) return false;
+  if (p->b_kcontig && (p->ldb % 4 || (uintptr_t)p->b[0] % 16)) return false;
+  return true;
+}
+
 /* Scalar fallback for operand views the tiled kernel cannot address with aligned 16-byte chunks
  * (leading dimension not a multiple of 16 bytes, or differently skewed K-contiguous operands). */
 struct GenericArgs {
@@ -1782,6 +1873,20 @@ int hap_gemm_run(const hap_gemm_problem* p, void* stream) {
   if (!grouped && !p->force_generic) {
     int rc;
     if (run_large(p, stream, &rc)) return rc;
+  }
+  if (skinny_f32_applies(p)) {
+    SkinnyArgs g;
+    g.M = (int)p->M; g.N = (int)p->N; g.K = (int)p->k[0];
+    g.lda = p->lda; g.ldb = p->ldb; g.ldc = p->ldc; g.ldp = p->ldp;
+    g.a = static_cast<const float*>(p->a[0]); g.b = static_cast<const float*>(p->b[0]);
+    g.c = static_cast<float*>(p->c); g.preact = static_cast<float*>(p->preact); g.bias = static_cast<const float*>(p->bias);
+    g.act = p->act; g.accumulate = p->accumulate;
+    const dim3 grid((unsigned)((p->N + 15) / 16));
+    if (p->b_kcontig) hipLaunchKernelGGL(gemm_skinny_f32_kernel<true>, grid, dim3(1024), 0, st, g);
+    else hipLaunchKernelGGL(gemm_skinny_f32_kernel<false>, grid, dim3(1024), 0, st, g);
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return hap_fail(HAP_EDEVICE, "skinny fp32 gemm launch: %s", hipGetErrorString(e));
+    return HAP_OK;
   }
   const Plan pl = make_plan(p);
   if (pl.tiled && pl.dma && p->tile == 0 && pl.bm == 256 && !grouped) return run_auto_tiled(p, pl, stream);

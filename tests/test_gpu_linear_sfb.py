@@ -424,3 +424,24 @@ def test_linear_bwd_dact_rejects_partial_sums(hap):
     with pytest.raises(hap.HapError):
         d2 = hap.LinearDesc(64, 32, 48, olin.BATCH, [0, 20, 64], hap.F32, ldx=32, ldw=48, ldy=48, operands_are_full=True)
         hap.hap_sharded_linear_bwd_dact(d2, 0, X, W, None, dY, dX, None, hap.F32, None, None, hap.ACT_GELU_ERF, ws)
+
+
+@pytest.mark.parametrize("tokens", [1, 16, 38, 64])
+@pytest.mark.parametrize("in_f,out_f", [(1024, 1024), (256, 1000), (4100, 17), (2048, 8000)])
+def test_fp32_layer_with_few_rows(hap, tokens, in_f, out_f):
+    """fp32 layers of at most 64 rows (config 1's shards are 38 and 26 rows) run forward and bwd-data in a kernel that splits the
+    contraction over the waves of a workgroup and sums the partial tiles through LDS: all row-block counts, ragged column tiles,
+    contractions that do not divide by the 16 waves, bias + GeLU + saved pre-activation, and dX through the K-contiguous weight.
+    (8000 columns are 125 tiles of 64: just below where the tiled kernel takes over.)"""
+    Xh, Xd = gen(3, T.X, (tokens, in_f), 1.0, "f32"); Wh, Wd = gen(3, T.W, (in_f, out_f), 0.05, "f32")
+    bh, bd = gen(3, T.BIAS, (out_f,), 0.5, "f32"); dYh, dYd = gen(3, T.DY, (tokens, out_f), 1.0, "f32")
+    desc = hap.LinearDesc(tokens, in_f, out_f, olin.REPLICATED, [0, 1], hap.F32, act=hap.ACT_GELU_ERF, has_bias=True, m=1)
+    Y = empty((tokens, out_f), "f32", float("nan")); P = empty((tokens, out_f), "f32", float("nan"))
+    ws = empty((max(hap.hap_linear_bwd_workspace(desc, 0), 16),), "u8")
+    hap.hap_sharded_linear_fwd(desc, 0, Xd, Wd, bd, Y, P, ws)
+    Yo, preo = olin.linear_fwd(Xh, Wh, bh, True)
+    check("Y", host(Y), Yo, "f32"); check("preact", host(P), preo, "f32")
+    dX = empty((tokens, in_f), "f32", float("nan")); dW = empty((in_f, out_f), "f32", float("nan")); db = empty((out_f,), "f32", float("nan"))
+    hap.hap_sharded_linear_bwd(desc, 0, Xd, Wd, P, dYd, dX, dW, hap.F32, db, ws)
+    dXo, dWo, dbo = olin.linear_bwd(Xh, Wh, preo, dYh, True)
+    check("dX", host(dX), dXo, "f32"); check("dW", host(dW), dWo, "f32"); check("db", host(db), dbo, "f32")
