@@ -1088,6 +1088,14 @@ struct PinnedFrag {
   }
 };
 
+#if defined(HAP_GEMM_EXPERIMENT)
+// (development harness only) wall-clock stamps of every workgroup: start, main loop start, main loop end, end
+__device__ unsigned long long hap_exp_stamps[4 * 2048];
+#define HAP_EXP_STAMP(i) do { if (threadIdx.x == 0 && blockIdx.x < 2048) hap_exp_stamps[blockIdx.x * 4 + (i)] = __builtin_amdgcn_s_memrealtime(); } while (0)
+#else
+#define HAP_EXP_STAMP(i) do { } while (0)
+#endif
+
 template <typename TC, bool AKC, bool BKC, int BM, int BN, int BK, int WGM, int WGN, int STAGES>
 __global__ __launch_bounds__(64 * WGM * WGN) void gemm_pp_kernel(const GemmArgs args) {
   typedef __bf16 T;
@@ -1104,6 +1112,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_pp_kernel(const GemmArgs 
   static_assert(STAGES >= 2 && STAGES <= 5 && (STAGES - 1) * LPT < 64, "ring depth");
 
   extern __shared__ __attribute__((aligned(1024))) char smem[];
+  HAP_EXP_STAMP(0);
 
   const int tid = threadIdx.x, lane = tid & 63, wave = uni(tid >> 6);
   const int wm0 = (wave / WGN) * WTM, wn0 = (wave % WGN) * WTN;
@@ -1189,6 +1198,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_pp_kernel(const GemmArgs 
   static_for<STAGES - 1>([&](auto s) { if (s < ntiles) request(s); });
   if (ntiles > 0) land(std::integral_constant<int, 0>(), issued - 1);
   __builtin_amdgcn_s_barrier();                      // tile 0 is in LDS for everybody
+  HAP_EXP_STAMP(1);
   if (late_group) __builtin_amdgcn_s_barrier();      // group 1 runs one phase behind group 0
 
   // one K tile whose ring slot is known at compile time
@@ -1241,6 +1251,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_pp_kernel(const GemmArgs 
     static_for<STAGES>([&](auto s) { if (fast || u0 + s < ntiles) tile(s, fast, u0 + s); });
   }
   if (!late_group) __builtin_amdgcn_s_barrier();     // group 1's last matrix phase: after it nobody reads the ring any more
+  HAP_EXP_STAMP(2);
 
   if (ksplit > 1) {
     GemmArgs pa = args;
@@ -1251,6 +1262,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_pp_kernel(const GemmArgs 
     return;
   }
   epilogue_transposed<T, TC, TM, TN>(group_outputs(args, gv, bp.grp), acc, m0 + wm0, n0 + wn0, lane, smem + wave * (32 * (TN * 32 * (int)sizeof(TC) + 16)));
+  HAP_EXP_STAMP(3);
 }
 
 /* Split-K reduction: sums the ksplit fp32 partial tiles of every output tile and applies what the
