@@ -1053,6 +1053,10 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_dma_kernel(const GemmArgs
 #define HAP_PP_PRIO 1
 #endif
 constexpr bool kPingPongPrio = HAP_PP_PRIO != 0;    // raise the wave's priority for its matrix phase
+#if !defined(HAP_PP_DEFER)
+#define HAP_PP_DEFER 1
+#endif
+constexpr bool kPingPongDefer = HAP_PP_DEFER != 0;  // group 0 awaits the next tile behind its MFMAs instead of in its memory phase
 template <int N> __device__ __forceinline__ void wait_vmcnt() { asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory"); }
 
 /* Fragment addressing of the ping-pong kernel: every address is (a register computed once before the K loop) +
@@ -1226,7 +1230,10 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_pp_kernel(const GemmArgs 
     }
     asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");     // this wave's reads of tile u are done (its slot is refilled two phases on)
     if (fast) {
-      wait_vmcnt<(STAGES - 2) * LPT>();
+      // Tile u+1 is first read by group 0, in its memory phase behind the NEXT barrier but one (group 0's matrix phase lies
+      // between).  Group 1 is one phase behind: the barrier that ends this memory phase is already the last one before that read,
+      // so it waits here; group 0 has its whole matrix phase to go and waits behind its MFMAs.
+      if (late_group || !kPingPongDefer) wait_vmcnt<(STAGES - 2) * LPT>();
       lk0 += BK;
     } else {
       if (u + 1 < ntiles) land(std::integral_constant<int, NEXT>(), issued - (u + 2));
@@ -1242,6 +1249,9 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_pp_kernel(const GemmArgs 
       for (int x = 0; x < TM * TN; ++x) acc[x / TN][x % TN] = mfma(fb[kk][x % TN], fa[kk][x / TN], acc[x / TN][x % TN]);
     if (kPingPongPrio) __builtin_amdgcn_s_setprio(0);
     __builtin_amdgcn_sched_barrier(0);
+    // group 0 awaits its share of tile u+1 here: one more phase for the loads to arrive, and the wait is out of the memory phase
+    // that group 1's MFMAs run against
+    if (kPingPongDefer && fast && !late_group) wait_vmcnt<(STAGES - 2) * LPT>();
     __builtin_amdgcn_s_barrier();
     __builtin_amdgcn_sched_barrier(0);
   };
