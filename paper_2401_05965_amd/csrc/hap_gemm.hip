@@ -771,14 +771,18 @@ struct DmaLoader {
     *c = swz<KC, CPR>(*row, id % CPR);
   }
 
-  __device__ __forceinline__ void init(int tid, int mn0, int mn_lim, long long ld) {
+  /* mn0: the tile's first physical row / column; [mn_lo, mn_lim): the physical range that holds the operand's logical rows /
+   * columns.  A K-contiguous operand's rows may be placed mn_lo rows into the tile grid (so that the OUTPUT's columns fall on
+   * its 16-byte chunks): grid rows below mn_lo do not exist and read as zero.  mn_lo is 0 for an M-/N-contiguous operand,
+   * whose skew is part of its aligned-down base address. */
+  __device__ __forceinline__ void init(int tid, int mn0, int mn_lo, int mn_lim, long long ld) {
 #pragma unroll
     for (int i = 0; i < CPT; ++i) {
       int row, c;
       where(tid + i * NT, &row, &c);
       if constexpr (KC) {
         const int mn = mn0 + row;
-        base[i] = mn < mn_lim ? (unsigned)(((long long)mn * ld + c * EPC) * 2) : kOobOffset;
+        base[i] = (mn >= mn_lo && mn < mn_lim) ? (unsigned)(((long long)(mn - mn_lo) * ld + c * EPC) * 2) : kOobOffset;
       } else {
         const int mn = mn0 + c * EPC;
         base[i] = mn < mn_lim ? (unsigned)(((long long)row * ld + mn) * 2) : kOobOffset;
@@ -872,8 +876,8 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_dma_kernel(const GemmArgs
   const int all_tiles = gv.k >= 0 ? (args.skewK + gv.k + BK - 1 >= BK ? (args.skewK + gv.k + BK - 1) / BK : 1) : args.ntiles;
 
   LA la; LB lb;
-  la.init(tid, m0, m_lim, args.lda);
-  lb.init(tid, n0, n_lim, args.ldb);
+  la.init(tid, m0, AKC ? args.skewM : 0, m_lim, args.lda);
+  lb.init(tid, n0, BKC ? args.skewN : 0, n_lim, args.ldb);
   FragReader<AKC, BM, BK, TM> fra;
   FragReader<BKC, BN, BK, TN> frb;
   fra.init(lane, wm0);
@@ -1130,8 +1134,8 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_pp_kernel(const GemmArgs 
   const int all_tiles = gv.k >= 0 ? (args.skewK + gv.k + BK - 1 >= BK ? (args.skewK + gv.k + BK - 1) / BK : 1) : args.ntiles;
 
   LA la; LB lb;
-  la.init(tid, m0, m_lim, args.lda);
-  lb.init(tid, n0, n_lim, args.ldb);
+  la.init(tid, m0, AKC ? args.skewM : 0, m_lim, args.lda);
+  lb.init(tid, n0, BKC ? args.skewN : 0, n_lim, args.ldb);
   PinnedFrag<AKC, BM, BK, TM, NH> fra;
   PinnedFrag<BKC, BN, BK, TN, NH> frb;
   fra.init(lane, wm0, lds_addr(smem));
@@ -1525,6 +1529,13 @@ Plan make_plan(const hap_gemm_problem* p) {
   pl.skewK = p->a_kcontig ? sa : (p->b_kcontig ? sb : 0);
   pl.skewM = p->a_kcontig ? 0 : sa;
   pl.skewN = p->b_kcontig ? 0 : sb;
+  // A K-contiguous B has no preferred column origin of its own (its rows are the output's columns), so the tile grid is laid on
+  // the 16-byte chunks of the OUTPUT instead: the reduction rule's dX[:, k_j] of a whole tensor starts at an arbitrary column, and
+  // with the grid on its chunks the epilogue stores whole chunks everywhere but at the matrix's two ends.
+  if (p->b_kcontig && p->in_dtype == HAP_BF16 && !(p->groups > 1) && !p->group_len) {
+    const int ces = esize(p->c_dtype), cepc = 16 / ces;
+    if ((uintptr_t)p->c % ces == 0 && p->ldc % cepc == 0) pl.skewN = (int)(((uintptr_t)p->c % 16) / ces);
+  }
   // operand views must stay below 2 GiB so 32-bit buffer offsets and the out-of-range marker work
   for (int s = 0; s < p->nseg; ++s) {
     const double ea = p->a_kcontig ? ((double)(p->M - 1) * p->lda + pl.skewK + p->k[s]) : ((double)(p->k[s] - 1) * p->lda + pl.skewM + p->M);

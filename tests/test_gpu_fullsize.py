@@ -77,8 +77,8 @@ def test_cfg2_whole_tensor_operands_shard1_full_size(hap, cfg2, fuse_act_bwd):
     ffn columns 8402..13442 - byte offset 16804 in a row, nothing 16-byte aligned - so every view is skewed: W1's and Y's columns (feature
     rule), H's columns and W2's rows (reduction rule), and the column ranges of dH, dW1, db1 the backward writes.  Sampled rows / columns
     against the oracle's block on the sub-problem; everything outside the device's range must stay as it was (NaN sentinel).  Both with the
-    GeLU backward as a pass of its own (the default for whole tensors) and folded into the epilogue of fc2's dX product, whose stores then
-    go through the shifted patch with the pre-activation read at the same skew."""
+    GeLU backward as a pass of its own and folded into the epilogue of fc2's dX product (the default), whose tile grid is laid on the
+    16-byte chunks of dH's column range with the pre-activation read at the same skew."""
     from paper_2401_05965_amd.programs import MlpShard
     Tn, h, F = cfg2["dims"]
     offs = cfg2["offs"]; j = 1
