@@ -456,7 +456,7 @@ __device__ __forceinline__ void epilogue(const GemmArgs& args, f32x16_t (&acc)[T
         const int m = row0 + i * 32 + (e >> 2) * 8 + (lane >> 5) * 4 + (e & 3) - args.skewM;
         if (n_ok && m >= 0 && m < args.M) {
           float v = acc[i][j][e] + bv;
-          if (P) store_c<TC>(P + (long long)m * args.ldp + n, v);
+          if (P) { store_c<TC>(P + (long long)m * args.ldp + n, v); v = (float)(TC)v; }     // the activation sees the stored value
           if (args.act == HAP_ACT_GELU_ERF) v = gelu_erf(v);
           if (args.dact_preact) v *= gelu_erf_grad(load_s<TC>(static_cast<const TC*>(args.dact_preact) + (long long)m * args.ldd + n));
           TC* dst = C + (long long)m * args.ldc + n;
@@ -592,8 +592,15 @@ template <typename TC> struct Vec16;
 template <> struct Vec16<__bf16> { typedef __bf16 type __attribute__((ext_vector_type(8))); };
 template <> struct Vec16<float> { typedef float type __attribute__((ext_vector_type(4))); };
 
-template <typename T, typename TC, int TM, int TN, bool SHIFTED, bool DACT>
+/* MODE 0: bias, optional activation, optional pre-activation copy (a pass of its own), optional accumulation.
+ * MODE 1 (DACT): the product times act'(dact_preact); no bias, activation, copy or accumulation (the host sees to that).
+ * MODE 2 (ACTP): activation AND pre-activation copy in ONE pass through the patch: the pre-activation chunk is stored as it comes
+ *         out of the patch and the activation is applied to those same, already rounded values, H = act(round(P)) - what a
+ *         framework computes that stores P and then applies the activation to the stored tensor, and the point at which the
+ *         backward evaluates act'.  Every other epilogue of the engine rounds the same way when it writes a copy. */
+template <typename T, typename TC, int TM, int TN, bool SHIFTED, int MODE>
 __device__ __forceinline__ void epilogue_transposed_impl(const GemmArgs& args, f32x16_t (&acc)[TM][TN], int row0, int col0, int lane, char* patch) {
+  constexpr bool DACT = MODE == 1, ACTP = MODE == 2;
   constexpr int ES = sizeof(TC);
   constexpr int EPC = 16 / ES;
   constexpr int COLS = TN * 32;
@@ -658,7 +665,7 @@ __device__ __forceinline__ void epilogue_transposed_impl(const GemmArgs& args, f
   for (int i = 0; i < TM; ++i) {
 #pragma unroll
     for (int pass = 0; pass < 2; ++pass) {
-      if (pass == 0 && (DACT || !P)) continue;       // (DACT: the host admits neither a pre-activation copy, an activation nor accumulation)
+      if (pass == 0 && (DACT || ACTP || !P)) continue;
       if constexpr (BURST == 1) request_preact(i, 0);
       TC* dst_base = pass == 0 ? P : C;
       const long long ldd = pass == 0 ? args.ldp : args.ldc;
@@ -673,7 +680,7 @@ __device__ __forceinline__ void epilogue_transposed_impl(const GemmArgs& args, f
           for (int x = 0; x < 4; ++x) {
             float f = acc[i][j][g * 4 + x];
             if constexpr (!DACT) f += bv[j][g][x];
-            if (!DACT && pass == 1 && args.act == HAP_ACT_GELU_ERF) f = gelu_erf(f);
+            if (!DACT && !ACTP && pass == 1 && args.act == HAP_ACT_GELU_ERF) f = gelu_erf(f);
             v[x] = (TC)f;
           }
           if constexpr (!SHIFTED) {
@@ -709,7 +716,15 @@ __device__ __forceinline__ void epilogue_transposed_impl(const GemmArgs& args, f
             for (int x = 0; x < EPC; ++x) val[x] = (TC)((float)val[x] * gelu_erf_grad((float)pv[x]));
           }
         }
+        // ACTP: keep the pre-activation chunk, apply the activation to the whole chunk once (leftover elements are dropped below)
+        vec_t pre = val;
+        TC* pdst = ACTP ? P + (long long)m * args.ldp + n : nullptr;
+        if constexpr (ACTP) {
+#pragma unroll
+          for (int x = 0; x < EPC; ++x) val[x] = (TC)gelu_erf((float)val[x]);
+        }
         if (vec_ok && n >= 0 && n + EPC <= args.N && t_lo == 0 && t_hi == EPC) {
+          if constexpr (ACTP) *reinterpret_cast<vec_t*>(pdst) = pre;
           if (!DACT && pass == 1 && args.accumulate) {
             const vec_t old = *reinterpret_cast<const vec_t*>(dst);
 #pragma unroll
@@ -721,6 +736,7 @@ __device__ __forceinline__ void epilogue_transposed_impl(const GemmArgs& args, f
           for (int x = 0; x < EPC; ++x)
             if (x >= t_lo && x < t_hi && n + x >= 0 && n + x < args.N) {
               float f = (float)val[x];
+              if constexpr (ACTP) store_c<TC>(pdst + x, (float)pre[x]);
               if constexpr (DACT) { if (!pv_ok) f *= gelu_erf_grad(load_s<TC>(dpre + x)); }
               if (!DACT && pass == 1 && args.accumulate) f += load_s<TC>(dst + x);
               store_c<TC>(dst + x, f);
@@ -738,10 +754,13 @@ __device__ __forceinline__ void epilogue_transposed_impl(const GemmArgs& args, f
 template <typename T, typename TC, int TM, int TN>
 __device__ __forceinline__ void epilogue_transposed(const GemmArgs& args, f32x16_t (&acc)[TM][TN], int row0, int col0, int lane, char* patch) {
   if (args.dact_preact) {
-    if (args.cdelta) epilogue_transposed_impl<T, TC, TM, TN, true, true>(args, acc, row0, col0, lane, patch);
-    else epilogue_transposed_impl<T, TC, TM, TN, false, true>(args, acc, row0, col0, lane, patch);
-  } else if (args.cdelta) epilogue_transposed_impl<T, TC, TM, TN, true, false>(args, acc, row0, col0, lane, patch);
-  else epilogue_transposed_impl<T, TC, TM, TN, false, false>(args, acc, row0, col0, lane, patch);
+    if (args.cdelta) epilogue_transposed_impl<T, TC, TM, TN, true, 1>(args, acc, row0, col0, lane, patch);
+    else epilogue_transposed_impl<T, TC, TM, TN, false, 1>(args, acc, row0, col0, lane, patch);
+  } else if (args.preact && args.act == HAP_ACT_GELU_ERF) {
+    if (args.cdelta) epilogue_transposed_impl<T, TC, TM, TN, true, 2>(args, acc, row0, col0, lane, patch);
+    else epilogue_transposed_impl<T, TC, TM, TN, false, 2>(args, acc, row0, col0, lane, patch);
+  } else if (args.cdelta) epilogue_transposed_impl<T, TC, TM, TN, true, 0>(args, acc, row0, col0, lane, patch);
+  else epilogue_transposed_impl<T, TC, TM, TN, false, 0>(args, acc, row0, col0, lane, patch);
 }
 
 /* ---------------------------------------------------------------------------------------------
@@ -1308,7 +1327,7 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(const GemmArgs args_
     if (nn < 0 || nn >= args.N) continue;
     float v = sum[x];
     if (bias) v += load_s<T>(bias + nn);
-    if (P) store_c<TC>(P + (long long)m * args.ldp + nn, v);
+    if (P) { store_c<TC>(P + (long long)m * args.ldp + nn, v); v = (float)(TC)v; }     // the activation sees the stored value
     if (args.act == HAP_ACT_GELU_ERF) v = gelu_erf(v);
     if (args.dact_preact) v *= gelu_erf_grad(load_s<TC>(static_cast<const TC*>(args.dact_preact) + (long long)m * args.ldd + nn));
     TC* dst = C + (long long)m * args.ldc + nn;
@@ -1446,7 +1465,10 @@ __global__ __launch_bounds__(256) void gemm_generic_kernel(const GenericArgs g) 
     }
   }
   if (g.bias) acc += load_s<T>(reinterpret_cast<const T*>(static_cast<const char*>(g.bias) + grp * g.gbias) + n);
-  if (g.preact) store_c<TC>(reinterpret_cast<TC*>(static_cast<char*>(g.preact) + grp * g.gp) + (long long)m * g.ldp + n, acc);
+  if (g.preact) {
+    store_c<TC>(reinterpret_cast<TC*>(static_cast<char*>(g.preact) + grp * g.gp) + (long long)m * g.ldp + n, acc);
+    acc = (float)(TC)acc;                                // the activation sees the stored value
+  }
   if (g.act == HAP_ACT_GELU_ERF) acc = gelu_erf(acc);
   if (g.dact_preact) acc *= gelu_erf_grad(load_s<TC>(static_cast<const TC*>(g.dact_preact) + (long long)m * g.ldd + n));
   TC* dst = reinterpret_cast<TC*>(static_cast<char*>(g.c) + grp * g.gc) + (long long)m * g.ldc + n;
@@ -1675,7 +1697,16 @@ int dispatch_tile(const hap_gemm_problem* p, const Plan& pl, const GemmArgs& a, 
     if (pl.bm == 256 && hap_exp_variant == 3) return dispatch_dma<TC, 256, 256, 64, 2, 2, 4>(p, a, groups, st);
 #endif
     if (pl.pingpong) return dispatch_pp<TC, 256, 256, 32, kPingPongStages, 2, 4>(p, a, groups, st);
+#if defined(HAP_GEMM_EXPERIMENT)
     if (pl.bm == 256) return dispatch_dma<TC, 256, 256, 64, 2, 2, 4>(p, a, groups, st);
+#else
+    // 256-tiles outside the ping-pong kernel: only products with both operands K-contiguous (the other three layouts of the
+    // two-stage kernel at this size are never launched, so they are not built)
+    if (pl.bm == 256) {
+      if (!(p->a_kcontig && p->b_kcontig)) return hap_fail(HAP_EDEVICE, "internal: no 256-tile two-stage kernel for this layout");
+      return launch_dma<TC, true, true, 256, 256, 64, 2, 2, 4>(a, groups, st);
+    }
+#endif
     return dispatch_dma<TC, 128, 128, 64, 2, 2, 2>(p, a, groups, st);
   }
 }
