@@ -283,6 +283,14 @@ int hap_moe_linear_fwd(const hap_moe_desc* d, int shard_index, const void* X, co
 int hap_moe_linear_bwd(const hap_moe_desc* d, int shard_index, const void* X, const void* W, const void* preact,
                        const void* dY, const int32_t* rows, void* dX, void* dW, int dW_dtype, float* dbias,
                        void* ws, size_t ws_bytes, void* stream);
+/* hap_moe_linear_bwd with the activation backward of the expert layer that PRODUCED X folded into the dX products' epilogue
+ * (the experts' fc1 -> GeLU -> fc2 chain, Sec. 7.6): dX_e <- (dP_e W_e^T) * x_act'(x_preact_e) on the expert's token rows.
+ * x_preact (device, io_dtype) has X's shape and layout [experts x capacity x ldx]; the returned dX is that layer's dP and its
+ * own backward is called with a descriptor whose act is NONE.  Expert parallelism shards the expert axis, so dX is always
+ * complete on the device.  x_act = HAP_ACT_NONE makes the call identical to hap_moe_linear_bwd.  Same workspace.              */
+int hap_moe_linear_bwd_dact(const hap_moe_desc* d, int shard_index, const void* X, const void* W, const void* preact,
+                            const void* dY, const int32_t* rows, void* dX, void* dW, int dW_dtype, float* dbias,
+                            const void* x_preact, int x_act, void* ws, size_t ws_bytes, void* stream);
 size_t hap_moe_linear_fwd_workspace(const hap_moe_desc* d, int shard_index);
 size_t hap_moe_linear_bwd_workspace(const hap_moe_desc* d, int shard_index);
 

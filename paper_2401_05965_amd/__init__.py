@@ -12,7 +12,7 @@ from .binding import (  # noqa: F401
     hap_sharded_linear_fwd, hap_sharded_linear_bwd, hap_sharded_linear_bwd_dact, hap_linear_fwd_workspace, hap_linear_bwd_workspace,
     hap_sfb_grad, hap_sfb_grad_static, hap_sfb_workspace, hap_sharded_attn_fwd, hap_sharded_attn_bwd, hap_attn_bwd_workspace,
     hap_layernorm_fwd, hap_layernorm_bwd, hap_layernorm_bwd_workspace,
-    hap_moe_linear_fwd, hap_moe_linear_bwd, hap_moe_linear_fwd_workspace, hap_moe_linear_bwd_workspace,
+    hap_moe_linear_fwd, hap_moe_linear_bwd, hap_moe_linear_bwd_dact, hap_moe_linear_fwd_workspace, hap_moe_linear_bwd_workspace,
     hap_allgather_capacity, hap_allgather_pad, hap_allgather_assemble, hap_reducescatter_split,
     hap_gelu_bwd, hap_add, hap_colsum, hap_colsum_workspace, hap_probe_mfma_bf16, hap_debug_set_gemm_view_limit, hap_device_info,
 )

@@ -419,6 +419,13 @@ def hap_moe_linear_bwd(desc: MoeDesc, shard_index, X, W, preact, dY, rows, dX, d
                                   _ptr(dX), _ptr(dW), C.c_int(dW_dtype), _ptr(dbias), wp, wb, _stream(stream)), "hap_moe_linear_bwd")
 
 
+def hap_moe_linear_bwd_dact(desc: MoeDesc, shard_index, X, W, preact, dY, rows, dX, dW, dW_dtype, dbias, x_preact, x_act, ws=None, stream=None):
+    wp, wb = _ws(ws)
+    _check(lib.hap_moe_linear_bwd_dact(C.byref(desc.c), C.c_int(shard_index), _ptr(X), _ptr(W), _ptr(preact), _ptr(dY), _ptr(rows),
+                                       _ptr(dX), _ptr(dW), C.c_int(dW_dtype), _ptr(dbias), _ptr(x_preact), C.c_int(x_act), wp, wb,
+                                       _stream(stream)), "hap_moe_linear_bwd_dact")
+
+
 def hap_allgather_capacity(desc: GatherDesc) -> int:
     return int(lib.hap_allgather_capacity(C.byref(desc.c)))
 

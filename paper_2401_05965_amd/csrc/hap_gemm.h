@@ -47,7 +47,7 @@ struct hap_gemm_problem {
    * (rows of A and C beyond it are neither read nor written), 2 bounds the contraction k[0]. */
   int groups;                          /* 0 or 1: a single product                               */
   int64_t ga, gb, gbias;               /* strides between groups, in in_dtype elements           */
-  int64_t gc, gp;                      /* ... of C and preact, in c_dtype elements               */
+  int64_t gc, gp, gd;                  /* ... of C, preact and dact_preact, in c_dtype elements  */
   const int32_t* group_len;
   int group_ragged;
 };

@@ -71,7 +71,7 @@ struct GemmArgs {
   // addresses (byte strides below) and, when group_len is given, in the valid length of one axis.
   int ragged;              // 0: every group is M x N x k;  1: group_len bounds M;  2: group_len bounds the contraction (nseg == 1)
   const int* group_len;    // device array [groups], or nullptr
-  long long ga, gb, gc, gp, gbias;
+  long long ga, gb, gc, gp, gbias, gd;
   SegArg seg[HAP_GEMM_MAX_SEG];
 };
 
@@ -102,6 +102,7 @@ __device__ __forceinline__ GemmArgs group_outputs(const GemmArgs& args, const Gr
   e.c = static_cast<char*>(args.c) + grp * args.gc;
   if (args.preact) e.preact = static_cast<char*>(args.preact) + grp * args.gp;
   if (args.bias) e.bias = static_cast<const char*>(args.bias) + grp * args.gbias;
+  if (args.dact_preact) e.dact_preact = static_cast<const char*>(args.dact_preact) + grp * args.gd;
   return e;
 }
 
@@ -1438,7 +1439,7 @@ struct GenericArgs {
   const void* dact_preact; long long ldd;
   int ragged;                        // as in GemmArgs; blockIdx.z is the group
   const int* group_len;
-  long long ga, gb, gc, gp, gbias;   // byte strides between groups
+  long long ga, gb, gc, gp, gbias, gd;   // byte strides between groups
   const void* a[HAP_GEMM_MAX_SEG];
   const void* b[HAP_GEMM_MAX_SEG];
   int k[HAP_GEMM_MAX_SEG];
@@ -1470,7 +1471,7 @@ __global__ __launch_bounds__(256) void gemm_generic_kernel(const GenericArgs g) 
     acc = (float)(TC)acc;                                // the activation sees the stored value
   }
   if (g.act == HAP_ACT_GELU_ERF) acc = gelu_erf(acc);
-  if (g.dact_preact) acc *= gelu_erf_grad(load_s<TC>(static_cast<const TC*>(g.dact_preact) + (long long)m * g.ldd + n));
+  if (g.dact_preact) acc *= gelu_erf_grad(load_s<TC>(reinterpret_cast<const TC*>(static_cast<const char*>(g.dact_preact) + grp * g.gd) + (long long)m * g.ldd + n));
   TC* dst = reinterpret_cast<TC*>(static_cast<char*>(g.c) + grp * g.gc) + (long long)m * g.ldc + n;
   if (g.accumulate) acc += load_s<TC>(dst);
   store_c<TC>(dst, acc);
@@ -1921,8 +1922,8 @@ int hap_gemm_run(const hap_gemm_problem* p, void* stream) {
   if (p->in_dtype == HAP_F32 && p->c_dtype != HAP_F32) return hap_fail(HAP_EUNSUPPORTED, "fp32 inputs need fp32 output");
   if (p->dact != HAP_ACT_NONE) {
     if (p->dact != HAP_ACT_GELU_ERF || !p->dact_preact) return hap_fail(HAP_EINVAL, "bad activation backward in the epilogue (dact %d)", p->dact);
-    if (p->act != HAP_ACT_NONE || p->accumulate || p->preact || p->groups > 1 || p->group_len)
-      return hap_fail(HAP_EINVAL, "an epilogue with an activation backward has no activation, pre-activation copy, accumulation or groups");
+    if (p->act != HAP_ACT_NONE || p->accumulate || p->preact || p->bias)
+      return hap_fail(HAP_EINVAL, "an epilogue with an activation backward has no bias, activation, pre-activation copy or accumulation");
   }
   const int es = esize(p->in_dtype), ces_out = esize(p->c_dtype);
   const int groups = p->groups > 1 ? p->groups : 1;
@@ -1963,7 +1964,7 @@ int hap_gemm_run(const hap_gemm_problem* p, void* stream) {
     g.c = p->c; g.preact = p->preact; g.bias = p->bias; g.act = p->act; g.accumulate = p->accumulate;
     g.dact_preact = p->dact ? p->dact_preact : nullptr; g.ldd = p->ldd;
     g.ragged = ragged; g.group_len = p->group_len;
-    g.ga = p->ga * es; g.gb = p->gb * es; g.gc = p->gc * ces_out; g.gp = p->gp * ces_out; g.gbias = p->gbias * es;
+    g.ga = p->ga * es; g.gb = p->gb * es; g.gc = p->gc * ces_out; g.gp = p->gp * ces_out; g.gbias = p->gbias * es; g.gd = p->gd * ces_out;
     for (int s = 0; s < p->nseg; ++s) {
       if (p->k[s] <= 0) continue;
       if (p->k[s] > 0x7fffffff) return hap_fail(HAP_EUNSUPPORTED, "segment longer than 2^31");
@@ -1986,7 +1987,7 @@ int hap_gemm_run(const hap_gemm_problem* p, void* stream) {
   a.c = p->c; a.preact = p->preact; a.bias = p->bias; a.act = p->act; a.accumulate = p->accumulate;
   a.dact_preact = p->dact ? p->dact_preact : nullptr; a.ldd = p->ldd;
   a.ragged = ragged; a.group_len = p->group_len;
-  a.ga = p->ga * es; a.gb = p->gb * es; a.gc = p->gc * ces_out; a.gp = p->gp * ces_out; a.gbias = p->gbias * es;
+  a.ga = p->ga * es; a.gb = p->gb * es; a.gc = p->gc * ces_out; a.gp = p->gp * ces_out; a.gbias = p->gbias * es; a.gd = p->gd * ces_out;
   a.tiles_m = (int)((p->M + pl.skewM + pl.bm - 1) / pl.bm);
   a.tiles_n = (int)((p->N + pl.skewN + pl.bn - 1) / pl.bn);
   a.nseg = 0;
@@ -2017,7 +2018,8 @@ int hap_gemm_run(const hap_gemm_problem* p, void* stream) {
     a.vec_store = ((uintptr_t)p->c % ces) == 0 && p->ldc % cepc == 0 &&
                   (!p->preact || (((uintptr_t)p->preact % 16) == ((uintptr_t)p->c % 16) && p->ldp % cepc == 0)) &&
                   (groups == 1 || (p->gc % cepc == 0 && (!p->preact || p->gp % cepc == 0))) &&
-                  (!(p->dact && p->dact_preact) || (((uintptr_t)p->dact_preact % 16) == ((uintptr_t)p->c % 16) && p->ldd % cepc == 0));
+                  (!(p->dact && p->dact_preact) || (((uintptr_t)p->dact_preact % 16) == ((uintptr_t)p->c % 16) && p->ldd % cepc == 0 &&
+                                                    (groups == 1 || p->gd % cepc == 0)));
     const int skew_c = (int)(((uintptr_t)p->c % 16) / ces);       // columns of C's 16-byte chunk that precede logical column 0
     a.cdelta = a.vec_store ? ((skew_c - pl.skewN) % cepc + cepc) % cepc : 0;
   }

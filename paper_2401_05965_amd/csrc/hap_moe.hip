@@ -101,10 +101,29 @@ int hap_moe_linear_fwd(const hap_moe_desc* d, int shard_index, const void* X, co
   return hap_gemm_run(&p, stream);
 }
 
+static int moe_linear_bwd_impl(const hap_moe_desc* d, int shard_index, const void* X, const void* W, const void* preact,
+                               const void* dY, const int32_t* rows, void* dX, void* dW, int dW_dtype, float* dbias,
+                               const void* x_preact, int x_act, void* ws, size_t ws_bytes, void* stream);
+
 int hap_moe_linear_bwd(const hap_moe_desc* d, int shard_index, const void* X, const void* W, const void* preact,
                        const void* dY, const int32_t* rows, void* dX, void* dW, int dW_dtype, float* dbias,
                        void* ws, size_t ws_bytes, void* stream) {
   hap_clear_error();
+  return moe_linear_bwd_impl(d, shard_index, X, W, preact, dY, rows, dX, dW, dW_dtype, dbias, NULL, HAP_ACT_NONE, ws, ws_bytes, stream);
+}
+
+int hap_moe_linear_bwd_dact(const hap_moe_desc* d, int shard_index, const void* X, const void* W, const void* preact,
+                            const void* dY, const int32_t* rows, void* dX, void* dW, int dW_dtype, float* dbias,
+                            const void* x_preact, int x_act, void* ws, size_t ws_bytes, void* stream) {
+  hap_clear_error();
+  if (x_act != HAP_ACT_NONE && x_act != HAP_ACT_GELU_ERF) return hap_fail(HAP_EINVAL, "bad x_act %d", x_act);
+  return moe_linear_bwd_impl(d, shard_index, X, W, preact, dY, rows, dX, dW, dW_dtype, dbias, x_act != HAP_ACT_NONE ? x_preact : NULL, x_act,
+                             ws, ws_bytes, stream);
+}
+
+static int moe_linear_bwd_impl(const hap_moe_desc* d, int shard_index, const void* X, const void* W, const void* preact,
+                               const void* dY, const int32_t* rows, void* dX, void* dW, int dW_dtype, float* dbias,
+                               const void* x_preact, int x_act, void* ws, size_t ws_bytes, void* stream) {
   int64_t lo, n;
   int rc = resolve(d, shard_index, &lo, &n);
   if (rc) return rc;
@@ -116,6 +135,7 @@ int hap_moe_linear_bwd(const hap_moe_desc* d, int shard_index, const void* X, co
   if (live && dX && !W) return hap_fail(HAP_EINVAL, "dX requested but W is NULL");
   if (live && dW && !X) return hap_fail(HAP_EINVAL, "dW requested but X is NULL");
   if (live && d->act != HAP_ACT_NONE && !preact) return hap_fail(HAP_EINVAL, "activation backward needs the saved pre-activation");
+  if (live && x_act != HAP_ACT_NONE && (!dX || !x_preact)) return hap_fail(HAP_EINVAL, "x_act given but dX or x_preact is NULL");
   const size_t need = required_bwd_bytes(d, n, dbias != NULL);
   if (live && need && (!ws || ws_bytes < need)) return hap_fail(HAP_EWORKSPACE, "moe_linear_bwd needs %zu workspace bytes", need);
   // [dP][column-sum scratch][optional split-K scratch for the GEMM engine]
@@ -147,6 +167,7 @@ int hap_moe_linear_bwd(const hap_moe_desc* d, int shard_index, const void* X, co
     p.a[0] = dP; p.lda = lddp; p.a_kcontig = 1; p.ga = gdp;
     p.b[0] = at(W, first * gw, es); p.ldb = d->ldw; p.b_kcontig = 1; p.gb = gw;     // B(k = out, n = in) = W_e[n*ldw + k]
     p.c = at(dX, first * gx, es); p.ldc = d->ldx; p.c_dtype = d->io_dtype; p.gc = gx;
+    if (x_preact) { p.dact_preact = at(x_preact, first * gx, es); p.ldd = d->ldx; p.gd = gx; p.dact = x_act; }
     p.ws = gemm_ws_bytes ? gemm_ws : NULL; p.ws_bytes = gemm_ws_bytes;
     if ((rc = hap_gemm_run(&p, stream))) return rc;
   }

@@ -132,8 +132,11 @@ class MoeExpertShard:
     `rows` (int32, on the device) holds the token count of every expert buffer.
     """
 
-    def __init__(self, experts, capacity, hidden, ffn, offsets, j, X, W1, b1, W2, b2, rows, dOut, dtype=torch.bfloat16):
+    def __init__(self, experts, capacity, hidden, ffn, offsets, j, X, W1, b1, W2, b2, rows, dOut, dtype=torch.bfloat16, fuse_act_bwd=True):
         self.j, self.C, self.h, self.f = j, capacity, hidden, ffn
+        # fuse_act_bwd: fc2's backward multiplies its dX products by gelu'(pre) in the epilogue; `dH` then holds dP (see MlpShard)
+        self.fuse_act_bwd = fuse_act_bwd
+        self.dH_holds = "dP" if fuse_act_bwd else "dH"
         lo, hi = offsets[j], offsets[j + 1]
         self.n = n = hi - lo
         dev = X.device
@@ -151,6 +154,7 @@ class MoeExpertShard:
         self.db2 = torch.zeros((m, hidden), dtype=torch.float32, device=dev)
         self.fc1 = hap.MoeDesc(experts, capacity, hidden, ffn, offsets, io, act=hap.ACT_GELU_ERF, has_bias=True, operands_are_full=False)
         self.fc2 = hap.MoeDesc(experts, capacity, ffn, hidden, offsets, io, has_bias=True, operands_are_full=False)
+        self.fc1_lin = hap.MoeDesc(experts, capacity, hidden, ffn, offsets, io, has_bias=True, operands_are_full=False)
         nws = max(hap.hap_moe_linear_bwd_workspace(self.fc1, j), hap.hap_moe_linear_bwd_workspace(self.fc2, j), 256)
         self.ws = torch.empty((nws,), dtype=torch.uint8, device=dev)
 
@@ -167,6 +171,12 @@ class MoeExpertShard:
 
     def backward(self, timer=None):
         j = self.j
+        if self.fuse_act_bwd:
+            _call(timer, "moe_fc2_bwd", lambda: hap.hap_moe_linear_bwd_dact(self.fc2, j, self.H, self.W2, None, self.dOut, self.rows, self.dH, self.dW2,
+                                                                            self.io, self.db2, self.pre, hap.ACT_GELU_ERF, self.ws))
+            _call(timer, "moe_fc1_bwd", lambda: hap.hap_moe_linear_bwd(self.fc1_lin, j, self.X, self.W1, None, self.dH, self.rows, self.dX, self.dW1,
+                                                                       self.io, self.db1, self.ws))
+            return
         _call(timer, "moe_fc2_bwd", lambda: hap.hap_moe_linear_bwd(self.fc2, j, self.H, self.W2, None, self.dOut, self.rows, self.dH, self.dW2,
                                                                    self.io, self.db2, self.ws))
         _call(timer, "moe_fc1_bwd", lambda: hap.hap_moe_linear_bwd(self.fc1, j, self.X, self.W1, self.pre, self.dH, self.rows, self.dX, self.dW1,

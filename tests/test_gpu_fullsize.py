@@ -169,7 +169,9 @@ def test_moe_expert_block_full_size_sampled(hap):
         ref = olay.moe_ffn_block(one(Xh[e][r]), one(W1h[e]), one(b1h[e]), one(W2h[e]), one(b2h[e]), one(dOh[e][r]))
         check(f"H e{e}", host(sh.H[e][r]), ref["H"][0], "bf16")
         check(f"out e{e}", host(sh.Out[e][r]), ref["out"][0], "bf16")
-        check(f"dH e{e}", host(sh.dH[e][r]), ref["dH"][0], "bf16")
+        from oracle import pointwise as opw
+        ref["dP"] = ref["dH"] * opw.gelu_grad(ref["pre"])
+        check(f"{sh.dH_holds} e{e}", host(sh.dH[e][r]), ref[sh.dH_holds][0], "bf16")
         check(f"dX e{e}", host(sh.dX[e][r]), ref["dX"][0], "bf16")
         cols = np.unique(np.concatenate([[0, 255, 256, F - 1], rng.integers(0, F, 8)]))
         refc = olay.moe_ffn_block(one(Xh[e]), one(W1h[e][:, cols]), one(b1h[e][cols]), one(W2h[e][cols]), one(b2h[e]), one(dOh[e]), rows=[ne])

@@ -155,10 +155,12 @@ def test_moe_single_expert_device_equals_linear_layer(hap):
     assert torch.equal(Y[0], Y2) and torch.equal(P[0], P2)
 
 
-def test_moe_expert_ffn_block_uneven_devices(hap):
+@pytest.mark.parametrize("fuse_act_bwd", [True, False])
+def test_moe_expert_ffn_block_uneven_devices(hap, fuse_act_bwd):
     """Whole expert feed-forward block (fc1 + GeLU + fc2, forward and backward) for 11 experts placed (4, 4, 2, 1) on devices of
-    speeds (1, 1, 0.5, 0.3): every device's slice against the unsharded oracle block."""
-    from oracle import layers as olay
+    speeds (1, 1, 0.5, 0.3): every device's slice against the unsharded oracle block; with the GeLU backward folded into the
+    grouped dH products (the buffer dH then holds dP = dH * gelu'(pre) on the experts' token rows) and as a pass of its own."""
+    from oracle import layers as olay, pointwise as opw
     from paper_2401_05965_amd.programs import MoeExpertShard
     torch = torch_mod()
     E, C, Hd, F = 11, 200, 192, 456
@@ -170,13 +172,14 @@ def test_moe_expert_ffn_block_uneven_devices(hap):
     rows = np.array([200, 150, 0, 200, 37, 128, 129, 64, 199, 1, 200])
     rows_d = torch.from_numpy(rows.astype(np.int32)).cuda()
     ref = olay.moe_ffn_block(Xh, W1h, b1h, W2h, b2h, dOh, rows)
+    ref["dP"] = ref["dH"] * opw.gelu_grad(ref["pre"])
     live = np.arange(C)[None, :] < rows[:, None]
     for j in range(4):
         s = slice(offs[j], offs[j + 1])
-        sh = MoeExpertShard(E, C, Hd, F, offs, j, Xd, W1d, b1d, W2d, b2d, rows_d, dOd)
+        sh = MoeExpertShard(E, C, Hd, F, offs, j, Xd, W1d, b1d, W2d, b2d, rows_d, dOd, fuse_act_bwd=fuse_act_bwd)
         sh.forward(); sh.backward()
         lv = live[s]
-        for name, t in (("H", sh.H), ("out", sh.Out), ("dH", sh.dH), ("dX", sh.dX)):
+        for name, t in (("H", sh.H), ("out", sh.Out), (sh.dH_holds, sh.dH), ("dX", sh.dX)):
             check(f"{name} dev{j}", host(t)[lv], ref[name][s][lv], "bf16")
         for name, t in (("dW1", sh.dW1), ("db1", sh.db1), ("dW2", sh.dW2), ("db2", sh.db2)):
             check(f"{name} dev{j}", host(t), ref[name][s], "bf16")
