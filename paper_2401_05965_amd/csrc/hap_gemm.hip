@@ -16,6 +16,14 @@
  * launcher aligns every operand base DOWN to 16 bytes and passes the number of leading elements
  * (skew) that do not belong to the shard.  Leading / trailing elements along k are zeroed in
  * registers before they reach LDS; leading / trailing rows and columns of C are simply not stored.
+ *
+ * Kernels.  gemm_pp_kernel: bf16, 256 x 256 tiles, two wave groups that alternate a memory phase and a matrix phase over a
+ * 4-stage ring of direct-to-LDS K tiles (all layouts but "both operands K-contiguous").  gemm_dma_kernel: bf16, two-stage ring,
+ * 256 x 256 (both operands K-contiguous) and 128 x 128 (small outputs, remainder strips).  gemm_kernel: register-staged, fp32
+ * and what the direct kernels cannot address.  gemm_skinny_f32_kernel: fp32 products of at most 64 rows, contraction split over
+ * the waves of a workgroup.  gemm_generic_kernel: scalar fallback.  Epilogues: bias, GeLU, pre-activation copy, fp32
+ * accumulation, or the product times gelu'(saved pre-activation) - the activation backward of the layer that produced the
+ * output's tensor.
  */
 #include <hip/hip_runtime.h>
 
@@ -50,7 +58,8 @@ struct SegArg {
 
 struct GemmArgs {
   int M, N;            // logical extent of C
-  int skewM, skewN;    // physical columns preceding logical 0 in an M-/N-contiguous operand
+  int skewM, skewN;    // physical columns preceding logical 0 in an M-/N-contiguous operand; for a K-contiguous B, skewN rows of the
+                       // tile grid precede its first row (the grid then sits on C's 16-byte chunks)
   int skewK;           // physical k preceding logical 0 in a K-contiguous operand
   int nseg;
   int tiles_m, tiles_n;
