@@ -1594,7 +1594,12 @@ Plan make_plan(const hap_gemm_problem* p) {
     pl.dma = 1;
     // 256-tiles: the ping-pong kernel, except when both operands are K-contiguous (bwd-data), where the two-stage kernel
     // with 128-byte rows per K tile is the faster one
-    pl.pingpong = big && !(p->a_kcontig && p->b_kcontig && kPingPongSkipsKK);
+    // ... and except short contractions: below about 20 K tiles of 64 the four-stage ring's fill does not pay off (measured at
+    // K = 512 / 768 / 1024: the two-stage kernel is 7 / 4 / 1 % faster, from K = 1536 on the ping-pong kernel wins)
+    long long nk64 = 0;
+    for (int s = 0; s < p->nseg; ++s) nk64 += p->k[s] > 0 ? (pl.skewK + p->k[s] + 63) / 64 : 0;
+    const bool short_k = kPingPongSkipsKK && nk64 < 20 && !(!p->a_kcontig && p->b_kcontig);
+    pl.pingpong = big && !(p->a_kcontig && p->b_kcontig && kPingPongSkipsKK) && !short_k;
     pl.bk = pl.pingpong ? kPingPongBK : 64;
     pl.name = pl.pingpong ? "bf16_256x256x32_pingpong4" : (big ? "bf16_256x256x64_dma2" : "bf16_128x128x64_dma2");
   }
@@ -1710,11 +1715,13 @@ int dispatch_tile(const hap_gemm_problem* p, const Plan& pl, const GemmArgs& a, 
 #if defined(HAP_GEMM_EXPERIMENT)
     if (pl.bm == 256) return dispatch_dma<TC, 256, 256, 64, 2, 2, 4>(p, a, groups, st);
 #else
-    // 256-tiles outside the ping-pong kernel: only products with both operands K-contiguous (the other three layouts of the
-    // two-stage kernel at this size are never launched, so they are not built)
+    // 256-tiles outside the ping-pong kernel: both operands K-contiguous, or a short contraction (A M-contiguous with B
+    // K-contiguous always takes the ping-pong kernel, so that layout of the two-stage kernel is not built at this size)
     if (pl.bm == 256) {
-      if (!(p->a_kcontig && p->b_kcontig)) return hap_fail(HAP_EDEVICE, "internal: no 256-tile two-stage kernel for this layout");
-      return launch_dma<TC, true, true, 256, 256, 64, 2, 2, 4>(a, groups, st);
+      if (p->a_kcontig && p->b_kcontig) return launch_dma<TC, true, true, 256, 256, 64, 2, 2, 4>(a, groups, st);
+      if (p->a_kcontig) return launch_dma<TC, true, false, 256, 256, 64, 2, 2, 4>(a, groups, st);
+      if (!p->b_kcontig) return launch_dma<TC, false, false, 256, 256, 64, 2, 2, 4>(a, groups, st);
+      return hap_fail(HAP_EDEVICE, "internal: no 256-tile two-stage kernel for this layout");
     }
 #endif
     return dispatch_dma<TC, 128, 128, 64, 2, 2, 2>(p, a, groups, st);
