@@ -44,6 +44,16 @@ typedef int i32x4_t __attribute__((ext_vector_type(4)));
 
 #define LDS_PTR(T, p) ((__attribute__((address_space(3))) T*)(p))
 
+#if defined(HAP_GEMM_EXPERIMENT)
+// (development harness only) wall-clock stamps of every workgroup: 0 start, 1 main loop start, 2 main loop end, 3 end, 4..7 after each
+// 32-row block of the epilogue
+__device__ unsigned long long hap_exp_stamps[8 * 2048];
+#define HAP_EXP_STAMP(i) do { if (threadIdx.x == 0 && blockIdx.x < 2048) hap_exp_stamps[blockIdx.x * 8 + (i)] = __builtin_amdgcn_s_memrealtime(); } while (0)
+#else
+#define HAP_EXP_STAMP(i) do { } while (0)
+#endif
+
+
 constexpr unsigned kOobOffset = 0x80000000u;  // beyond any num_records we pass: reads as zero
 constexpr int64_t kViewLimitBytes = 2147483000;  // reach of the tiled kernels' 32-bit buffer offsets: operand views stay below it
 constexpr int kRsrcFlags = 0x00020000;        // raw buffer, 32-bit data format
@@ -742,15 +752,21 @@ __device__ __forceinline__ void epilogue_transposed_impl(const GemmArgs& args, f
           }
           *reinterpret_cast<vec_t*>(dst) = val;
         } else {
-#pragma unroll
-          for (int x = 0; x < EPC; ++x)
-            if (x >= t_lo && x < t_hi && n + x >= 0 && n + x < args.N) {
-              float f = (float)val[x];
-              if constexpr (ACTP) store_c<TC>(pdst + x, (float)pre[x]);
-              if constexpr (DACT) { if (!pv_ok) f *= gelu_erf_grad(load_s<TC>(dpre + x)); }
-              if (!DACT && pass == 1 && args.accumulate) f += load_s<TC>(dst + x);
-              store_c<TC>(dst + x, f);
-            }
+          // Rare (a chunk cut by a row end or by the wave's strip, or a destination that is not 16-byte addressable): element by
+          // element, straight from the patch, as a real loop - unrolled eight-fold into every iteration above it made the epilogue
+          // several times the size of the instruction cache, and the waves waited for code, not for data.
+          // (read through an LDS-space pointer: a generic one makes the load a flat instruction, which counts on the memory
+          // counter as well and makes every later wait for patch data a wait for the global stores in flight)
+          const unsigned pe = lds_addr(patch + r * ROWB + c * 16);
+#pragma unroll 1
+          for (int x = t_lo; x < t_hi; ++x) {
+            if (n + x < 0 || n + x >= args.N) continue;
+            float f = (float)*LDS_PTR(const TC, (unsigned long)(pe + x * ES));
+            if constexpr (ACTP) { store_c<TC>(pdst + x, f); f = gelu_erf(f); }
+            if constexpr (DACT) f = (float)(TC)f * gelu_erf_grad(load_s<TC>(dpre + x));
+            if (!DACT && pass == 1 && args.accumulate) f += load_s<TC>(dst + x);
+            store_c<TC>(dst + x, f);
+          }
         }
       }
       // Order the patch accesses of this wave only: LDS operations of a wave execute in order, so a
@@ -758,6 +774,7 @@ __device__ __forceinline__ void epilogue_transposed_impl(const GemmArgs& args, f
       asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
       __builtin_amdgcn_wave_barrier();
     }
+    HAP_EXP_STAMP(4 + (i & 3));
   }
 }
 
@@ -881,7 +898,7 @@ struct DmaLoader {
 };
 
 template <typename TC, bool AKC, bool BKC, int BM, int BN, int BK, int WGM, int WGN, int STAGES>
-__global__ __launch_bounds__(64 * WGM * WGN) void gemm_dma_kernel(const GemmArgs args) {
+__global__ __launch_bounds__(64 * WGM * WGN, (WGM * WGN <= 4 ? 2 : 1))   /* the 4-wave kernel is built to share a compute unit with a second workgroup: two waves per SIMD */ void gemm_dma_kernel(const GemmArgs args) {
   typedef __bf16 T;
   constexpr int NT = 64 * WGM * WGN;
   constexpr int WTM = BM / WGM, WTN = BN / WGN;
@@ -1124,14 +1141,6 @@ struct PinnedFrag {
     }
   }
 };
-
-#if defined(HAP_GEMM_EXPERIMENT)
-// (development harness only) wall-clock stamps of every workgroup: start, main loop start, main loop end, end
-__device__ unsigned long long hap_exp_stamps[4 * 2048];
-#define HAP_EXP_STAMP(i) do { if (threadIdx.x == 0 && blockIdx.x < 2048) hap_exp_stamps[blockIdx.x * 4 + (i)] = __builtin_amdgcn_s_memrealtime(); } while (0)
-#else
-#define HAP_EXP_STAMP(i) do { } while (0)
-#endif
 
 template <typename TC, bool AKC, bool BKC, int BM, int BN, int BK, int WGM, int WGN, int STAGES>
 __global__ __launch_bounds__(64 * WGM * WGN) void gemm_pp_kernel(const GemmArgs args) {
