@@ -179,9 +179,9 @@ typedef struct {
  *   FEATURE:   Y[:,c_j]  = act(X W[:,c_j] + b[c_j])     W,bias,Y(,preact) sharded on columns
  *   REDUCTION: P_j       = X[:,k_j] W[k_j,:]            X sharded on columns, W on rows; Y whole [tokens x out]
  * X, W, bias (NULL iff !has_bias), Y, preact (NULL = do not save) are device pointers.
- * preact has Y's shape/ld and is required by the backward only when act != NONE.  When preact is
- * given, the activation is applied to the value as stored there (Y = act(round_to_io_dtype(XW + b))),
- * the point at which the backward evaluates act'; without it, to the fp32 sum.                      */
+ * preact has Y's shape/ld and is required by the backward only when act != NONE.  The activation
+ * is applied to the pre-activation as preact stores it (Y = act(round_to_io_dtype(XW + b))), the
+ * point at which the backward evaluates act', whether or not the copy is kept.                     */
 int hap_sharded_linear_fwd(const hap_linear_desc* d, int shard_index, const void* X, const void* W,
                            const void* bias, void* Y, void* preact, void* ws, size_t ws_bytes, void* stream);
 

@@ -476,8 +476,8 @@ __device__ __forceinline__ void epilogue(const GemmArgs& args, f32x16_t (&acc)[T
         const int m = row0 + i * 32 + (e >> 2) * 8 + (lane >> 5) * 4 + (e & 3) - args.skewM;
         if (n_ok && m >= 0 && m < args.M) {
           float v = acc[i][j][e] + bv;
-          if (P) { store_c<TC>(P + (long long)m * args.ldp + n, v); v = (float)(TC)v; }     // the activation sees the stored value
-          if (args.act == HAP_ACT_GELU_ERF) v = gelu_erf(v);
+          if (P) store_c<TC>(P + (long long)m * args.ldp + n, v);
+          if (args.act == HAP_ACT_GELU_ERF) v = gelu_erf((float)(TC)v);     // the activation sees the value as stored
           if (args.dact_preact) v *= gelu_erf_grad(load_s<TC>(static_cast<const TC*>(args.dact_preact) + (long long)m * args.ldd + n));
           TC* dst = C + (long long)m * args.ldc + n;
           if (args.accumulate) v += load_s<TC>(dst);
@@ -612,12 +612,13 @@ template <typename TC> struct Vec16;
 template <> struct Vec16<__bf16> { typedef __bf16 type __attribute__((ext_vector_type(8))); };
 template <> struct Vec16<float> { typedef float type __attribute__((ext_vector_type(4))); };
 
-/* MODE 0: bias, optional activation, optional pre-activation copy (a pass of its own), optional accumulation.
+/* MODE 0: bias, optional pre-activation copy (a pass of its own), optional accumulation; no activation.
  * MODE 1 (DACT): the product times act'(dact_preact); no bias, activation, copy or accumulation (the host sees to that).
- * MODE 2 (ACTP): activation AND pre-activation copy in ONE pass through the patch: the pre-activation chunk is stored as it comes
- *         out of the patch and the activation is applied to those same, already rounded values, H = act(round(P)) - what a
- *         framework computes that stores P and then applies the activation to the stored tensor, and the point at which the
- *         backward evaluates act'.  Every other epilogue of the engine rounds the same way when it writes a copy. */
+ * MODE 2 (ACTP): activation, with the optional pre-activation copy in the SAME pass through the patch: the pre-activation chunk is
+ *         stored as it comes out of the patch and the activation is applied to those same, already rounded values,
+ *         H = act(round(P)) - what a framework computes that stores P and then applies the activation to the stored tensor, and
+ *         the point at which the backward evaluates act'.  Every epilogue of the engine rounds before the activation, with or
+ *         without a copy, so a layer's output does not depend on whether its pre-activation is kept. */
 template <typename T, typename TC, int TM, int TN, bool SHIFTED, int MODE>
 __device__ __forceinline__ void epilogue_transposed_impl(const GemmArgs& args, f32x16_t (&acc)[TM][TN], int row0, int col0, int lane, char* patch) {
   constexpr bool DACT = MODE == 1, ACTP = MODE == 2;
@@ -700,7 +701,6 @@ __device__ __forceinline__ void epilogue_transposed_impl(const GemmArgs& args, f
           for (int x = 0; x < 4; ++x) {
             float f = acc[i][j][g * 4 + x];
             if constexpr (!DACT) f += bv[j][g][x];
-            if (!DACT && !ACTP && pass == 1 && args.act == HAP_ACT_GELU_ERF) f = gelu_erf(f);
             v[x] = (TC)f;
           }
           if constexpr (!SHIFTED) {
@@ -744,7 +744,7 @@ __device__ __forceinline__ void epilogue_transposed_impl(const GemmArgs& args, f
           for (int x = 0; x < EPC; ++x) val[x] = (TC)gelu_erf((float)val[x]);
         }
         if (vec_ok && n >= 0 && n + EPC <= args.N && t_lo == 0 && t_hi == EPC) {
-          if constexpr (ACTP) *reinterpret_cast<vec_t*>(pdst) = pre;
+          if constexpr (ACTP) { if (P) *reinterpret_cast<vec_t*>(pdst) = pre; }
           if (!DACT && pass == 1 && args.accumulate) {
             const vec_t old = *reinterpret_cast<const vec_t*>(dst);
 #pragma unroll
@@ -762,7 +762,7 @@ __device__ __forceinline__ void epilogue_transposed_impl(const GemmArgs& args, f
           for (int x = t_lo; x < t_hi; ++x) {
             if (n + x < 0 || n + x >= args.N) continue;
             float f = (float)*LDS_PTR(const TC, (unsigned long)(pe + x * ES));
-            if constexpr (ACTP) { store_c<TC>(pdst + x, f); f = gelu_erf(f); }
+            if constexpr (ACTP) { if (P) store_c<TC>(pdst + x, f); f = gelu_erf(f); }
             if constexpr (DACT) f = (float)(TC)f * gelu_erf_grad(load_s<TC>(dpre + x));
             if (!DACT && pass == 1 && args.accumulate) f += load_s<TC>(dst + x);
             store_c<TC>(dst + x, f);
@@ -783,7 +783,7 @@ __device__ __forceinline__ void epilogue_transposed(const GemmArgs& args, f32x16
   if (args.dact_preact) {
     if (args.cdelta) epilogue_transposed_impl<T, TC, TM, TN, true, 1>(args, acc, row0, col0, lane, patch);
     else epilogue_transposed_impl<T, TC, TM, TN, false, 1>(args, acc, row0, col0, lane, patch);
-  } else if (args.preact && args.act == HAP_ACT_GELU_ERF) {
+  } else if (args.act == HAP_ACT_GELU_ERF) {
     if (args.cdelta) epilogue_transposed_impl<T, TC, TM, TN, true, 2>(args, acc, row0, col0, lane, patch);
     else epilogue_transposed_impl<T, TC, TM, TN, false, 2>(args, acc, row0, col0, lane, patch);
   } else if (args.cdelta) epilogue_transposed_impl<T, TC, TM, TN, true, 0>(args, acc, row0, col0, lane, patch);
@@ -1346,8 +1346,8 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(const GemmArgs args_
     if (nn < 0 || nn >= args.N) continue;
     float v = sum[x];
     if (bias) v += load_s<T>(bias + nn);
-    if (P) { store_c<TC>(P + (long long)m * args.ldp + nn, v); v = (float)(TC)v; }     // the activation sees the stored value
-    if (args.act == HAP_ACT_GELU_ERF) v = gelu_erf(v);
+    if (P) store_c<TC>(P + (long long)m * args.ldp + nn, v);
+    if (args.act == HAP_ACT_GELU_ERF) v = gelu_erf((float)(TC)v);     // the activation sees the value as stored
     if (args.dact_preact) v *= gelu_erf_grad(load_s<TC>(static_cast<const TC*>(args.dact_preact) + (long long)m * args.ldd + nn));
     TC* dst = C + (long long)m * args.ldc + nn;
     if (args.accumulate) v += load_s<TC>(dst);
@@ -1484,11 +1484,8 @@ __global__ __launch_bounds__(256) void gemm_generic_kernel(const GenericArgs g) 
     }
   }
   if (g.bias) acc += load_s<T>(reinterpret_cast<const T*>(static_cast<const char*>(g.bias) + grp * g.gbias) + n);
-  if (g.preact) {
-    store_c<TC>(reinterpret_cast<TC*>(static_cast<char*>(g.preact) + grp * g.gp) + (long long)m * g.ldp + n, acc);
-    acc = (float)(TC)acc;                                // the activation sees the stored value
-  }
-  if (g.act == HAP_ACT_GELU_ERF) acc = gelu_erf(acc);
+  if (g.preact) store_c<TC>(reinterpret_cast<TC*>(static_cast<char*>(g.preact) + grp * g.gp) + (long long)m * g.ldp + n, acc);
+  if (g.act == HAP_ACT_GELU_ERF) acc = gelu_erf((float)(TC)acc);     // the activation sees the value as stored
   if (g.dact_preact) acc *= gelu_erf_grad(load_s<TC>(reinterpret_cast<const TC*>(static_cast<const char*>(g.dact_preact) + grp * g.gd) + (long long)m * g.ldd + n));
   TC* dst = reinterpret_cast<TC*>(static_cast<char*>(g.c) + grp * g.gc) + (long long)m * g.ldc + n;
   if (g.accumulate) acc += load_s<TC>(dst);
