@@ -715,8 +715,10 @@ __device__ __forceinline__ void epilogue_transposed_impl(const GemmArgs& args, f
       // wait on the LDS counter is enough (a fence would also drain the global stores in flight).
       asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
       __builtin_amdgcn_wave_barrier();
-      // LDS patch -> global, 16 bytes per lane
-#pragma unroll
+      // LDS patch -> global, 16 bytes per lane.  (An fp32 tile has eight iterations per block; all of them in flight at once, each
+      // with its chunk, its address and - when accumulating - the old chunk, overflowed the registers the accumulators leave.)
+      constexpr int kStoreUnroll = (ES == 4 && !DACT) ? 2 : ITS;
+#pragma unroll kStoreUnroll
       for (int it = 0; it < ITS; ++it) {
         int m, n, t_lo, t_hi;
         if (!chunk_at(i, it, &m, &n, &t_lo, &t_hi)) continue;
